@@ -1,0 +1,191 @@
+/*
+ * thinkv.h -- C ABI of the ThinKV decode hot path for AMD MI355X (gfx950).
+ *
+ * A paged KV cache whose tokens are group-quantised at a precision chosen by their thought
+ * type, whose evicted tokens are only marked in a mask, and whose freed slots are reused in
+ * place by newly appended tokens of the same type (the paper's "Continuous Thinking" memory
+ * manager, Sec. 5.2, with thought-adaptive quantisation, Sec. 4.2), plus decode-step grouped-
+ * query attention computed directly over the packed pages (appendix "Decode", "Grouped-Query
+ * Attention"; physical slot order is irrelevant by the theorem "KV Permutation Invariance of
+ * Attention").
+ *
+ * Conventions
+ *   - Every pointer inside thinkv_view and every array argument marked DEVICE is device
+ *     memory owned by the caller; the library allocates nothing and keeps no global state.
+ *   - Every call enqueues work on the caller's HIP stream and returns without synchronising.
+ *     Calls on one view must be ordered by the stream(s) the caller uses.
+ *   - Return value: a thinkv_status for problems the host can see (null pointers, bad
+ *     geometry, workspace too small, launch failure).  Problems only the device can see set
+ *     bit flags in view->dev_status and skip the offending token / slot; nothing aborts.
+ *   - Thought types are numbered as in the paper's pseudocode: 0 = transition (T),
+ *     1 = execution (E), 2 = reasoning (R).  bits_of_class maps a type to 2, 4 or 8 bits.
+ */
+#ifndef THINKV_H
+#define THINKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { THINKV_F16 = 0, THINKV_BF16 = 1, THINKV_F32 = 2 } thinkv_dtype;
+
+typedef enum {
+  THINKV_OK = 0,
+  THINKV_E_INVALID_ARG = 1, /* null pointer, negative count, bad enum                      */
+  THINKV_E_SHAPE = 2,       /* geometry the kernels do not cover                            */
+  THINKV_E_UNSUPPORTED = 3, /* dtype / option combination not implemented                   */
+  THINKV_E_WORKSPACE = 4,   /* workspace_bytes smaller than thinkv_*_workspace_bytes()      */
+  THINKV_E_HIP = 5          /* a HIP call or kernel launch failed                           */
+} thinkv_status;
+
+/* bit flags in dev_status[seq * n_layers + layer]; the last word of dev_status
+ * (index max_seqs * n_layers) collects conditions that belong to no valid sequence. */
+#define THINKV_ST_NOPAGES 1u    /* page pool of the class empty, or the page list full       */
+#define THINKV_ST_BAD_CLASS 2u  /* tok_class > 2                                             */
+#define THINKV_ST_BAD_SLOT 4u   /* evict handle names no page of that sequence               */
+#define THINKV_ST_EVICT_DEAD 8u /* evict of a slot that holds no live token (ignored)        */
+#define THINKV_ST_BAD_SEQ 16u   /* sequence id outside [0, max_seqs)                         */
+
+#define THINKV_PAGE_SIZE 16
+#define THINKV_GROUP_SIZE 32
+
+/* Static geometry; host memory, passed by value inside thinkv_view. */
+typedef struct {
+  int32_t n_layers, n_q_heads, n_kv_heads;
+  int32_t head_dim;         /* 64 or 128                                                     */
+  int32_t page_size;        /* 16 slots per page                                             */
+  int32_t group_size;       /* 32 consecutive channels share a scale and zero-point          */
+  int32_t bits_of_class[3]; /* each 2, 4 or 8; index = thought type                          */
+  int32_t max_seqs;
+  int32_t max_pages;        /* capacity of each (sequence, layer, type) page list            */
+} thinkv_config;
+
+/*
+ * The cache.  The paper's block table (physical block #, # filled, thought type, eviction
+ * mask; Sec. 5.2 "Block Table") is kept as one page list per (sequence, layer, thought type)
+ * -- the table sorted by its thought-type column -- plus per-physical-page state:
+ *
+ *   arena[c]        packed pages of type c, page stride thinkv_page_bytes(cfg, bits_of_class[c])
+ *   free_stack[c]   [arena_pages[c]] LIFO pool; free_top[c] = number of free pages
+ *   block_table     [max_seqs][n_layers][3][max_pages] physical page numbers, -1 = unused
+ *   n_pages         [max_seqs][n_layers][3]
+ *   page_filled[c]  [arena_pages[c]] slots ever written, 0..16 (the paper's "# Filled")
+ *   page_mask[c]    [arena_pages[c]] bits 0..15: slot holds a live token;
+ *                                    bits 16..31: slot soft-evicted and reclaimable
+ *   slot_pos[c]     [arena_pages[c]][16] logical position of the token in the slot, -1 = none
+ *   n_live          [max_seqs][n_layers] live tokens
+ *   dev_status      [max_seqs * n_layers + 1] THINKV_ST_* flags
+ *
+ * Byte layout of one page: n_kv_heads blocks of thinkv_block_bytes(); a block is
+ * [K codes: 64 chunks of CB = (head_dim/32)*b bytes][K meta: 16*(head_dim/32) dwords]
+ * [V codes: 64 chunks][V meta].  A meta dword (slot*NG + group) holds the binary16 scale in
+ * bits 0..15 and the binary16 zero-point in bits 16..31.  Inside a chunk a b-bit code sits at
+ * bit 32*(f / FPH) + 16*h + b*(f % FPH), FPH = 16/b, with
+ *   K, slot t, channel c: chunk 16*((c%32)/8) + t, f = 4*(c/32) + (c%8)/2, h = c%2
+ *   V, slot t, channel c: chunk 16*(t/4) + c%16,   f = ((t%4)/2)*(head_dim/16) + c/16, h = t%2
+ */
+typedef struct {
+  thinkv_config cfg;
+  uint8_t* arena[3];        /* DEVICE */
+  int64_t arena_pages[3];
+  int32_t* free_stack[3];   /* DEVICE */
+  int32_t* free_top;        /* DEVICE [3] */
+  int32_t* block_table;     /* DEVICE */
+  int32_t* n_pages;         /* DEVICE */
+  uint8_t* page_filled[3];  /* DEVICE */
+  uint32_t* page_mask[3];   /* DEVICE */
+  int32_t* slot_pos[3];     /* DEVICE */
+  int32_t* n_live;          /* DEVICE */
+  uint32_t* dev_status;     /* DEVICE */
+} thinkv_view;
+
+/* A slot handle names a slot of one sequence and layer: (type << 28) | (index in that type's
+ * page list << 4) | slot.  thinkv_append_quantized reports the handle each token received. */
+#define THINKV_HANDLE(type, page_idx, slot) (((int32_t)(type) << 28) | ((int32_t)(page_idx) << 4) | (int32_t)(slot))
+
+/* Layout queries (host, pure).  Return 0 for unsupported geometry. */
+size_t thinkv_block_bytes(const thinkv_config* cfg, int bits); /* one (page, kv-head)        */
+size_t thinkv_page_bytes(const thinkv_config* cfg, int bits);  /* n_kv_heads blocks          */
+
+/* Bytes of scratch thinkv_append_quantized needs for a call with n_tok tokens. */
+size_t thinkv_append_workspace_bytes(const thinkv_config* cfg, int32_t n_tok);
+/* Bytes of scratch thinkv_decode_attention needs for B queries when no sequence holds more
+ * than max_ctx_pages pages (summed over the three types) in the layer attended. */
+size_t thinkv_decode_workspace_bytes(const thinkv_config* cfg, int32_t B, int32_t max_ctx_pages);
+
+/* Puts a view into the empty state: free stacks filled so that pages come out 0,1,2,...,
+ * tables -1, counters and flags 0, slot_pos -1.  Arena bytes are not touched. */
+int thinkv_init_view(const thinkv_view* view, void* stream /* hipStream_t */);
+
+/*
+ * Quantise-and-append (paper Sec. 4.2 Problem "Thought-Adaptive Quantization": each new KV
+ * entry is quantised at the precision of its thought type; Sec. 5.2 "Efficient Memory
+ * Management" and the appendix walkthrough, step d: the token goes to a reclaimable slot of an
+ * existing block of its type, else to the next unused slot of the last block of that type,
+ * else to a newly allocated block; never into a block of another type).
+ *
+ *   k_new, v_new  DEVICE [n_tok][n_kv_heads][head_dim] of in_dtype (post-RoPE keys)
+ *   tok_seq       DEVICE [n_tok] sequence ids, non-decreasing
+ *   tok_pos       DEVICE [n_tok] logical positions
+ *   tok_class     DEVICE [n_tok] thought types
+ *   tok_handle    DEVICE [n_tok] out, may be NULL: handle of each token, -1 if it was skipped
+ *
+ * Tokens of one sequence are applied in array order; among reclaimable slots the first page
+ * in list order and its lowest slot go first; new pages are popped in token order, so the
+ * result equals a one-token-at-a-time loop.  Quantiser: per group of 32 channels, zero-point =
+ * binary16(min), scale = smallest binary16 >= (max-min)/(2^b-1), code = clamp(rint((x-zp)/
+ * scale), 0, 2^b-1) in binary32 with IEEE division and round-half-even.
+ * Skipped tokens: invalid sequence or type, or no page available (flags in dev_status).
+ */
+int thinkv_append_quantized(const thinkv_view* view, int32_t layer, const void* k_new, const void* v_new,
+                            const int32_t* tok_seq, const int32_t* tok_pos, const uint8_t* tok_class,
+                            int32_t* tok_handle, int32_t n_tok, thinkv_dtype in_dtype, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/*
+ * Soft eviction (paper Sec. 5.2 "TBE with CT": evicted tokens are only marked in the
+ * eviction mask; removal is deferred until a new token overwrites the slot).
+ *   ev_seq, ev_handle  DEVICE [n_ev]
+ * Sets the slot's reclaimable bit, clears its live bit, decrements n_live.  A handle whose slot
+ * holds no live token is ignored (THINKV_ST_EVICT_DEAD); duplicates in one call count once.
+ */
+int thinkv_evict(const thinkv_view* view, int32_t layer, const int32_t* ev_seq, const int32_t* ev_handle,
+                 int32_t n_ev, void* stream);
+
+/*
+ * Decode attention (appendix "Decode": O = softmax(q K^T / sqrt(d)) V over every cached
+ * token; "Grouped-Query Attention": the n_q_heads / n_kv_heads query heads of a group share
+ * one K/V head, each with its own softmax).  K^ and V^ are zp + code * scale from the stored
+ * binary16 scale and zero-point; slots whose live bit is clear are not attended; with window
+ * W > 0 only slots with 0 <= q_pos - slot_pos < W are.
+ *
+ *   q        DEVICE [B][n_q_heads][head_dim] of q_dtype (F16 or BF16)
+ *   out      DEVICE [B][n_q_heads][head_dim] of out_dtype
+ *   lse      DEVICE [B][n_q_heads] float, may be NULL: log-sum-exp of the scaled scores
+ *   seq_ids  DEVICE [B] which sequence each query belongs to
+ *   q_pos    DEVICE [B] logical position of the query (used only when window > 0)
+ *   max_ctx_pages  host upper bound on pages (all types) any attended sequence holds
+ *
+ * A query with no visible token gets out = 0 and lse = -inf.  Accumulation is binary32.
+ */
+int thinkv_decode_attention(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
+                            const int32_t* seq_ids, const int32_t* q_pos, int32_t B, int32_t window,
+                            float softmax_scale, thinkv_dtype q_dtype, thinkv_dtype out_dtype,
+                            int32_t max_ctx_pages, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same contract and arguments as thinkv_decode_attention, computed by the plain vector-ALU
+ * kernel (binary32 dequantisation, no matrix cores).  Kept as a slow cross-check. */
+int thinkv_decode_attention_valu(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
+                                 const int32_t* seq_ids, const int32_t* q_pos, int32_t B, int32_t window,
+                                 float softmax_scale, thinkv_dtype q_dtype, thinkv_dtype out_dtype,
+                                 int32_t max_ctx_pages, void* workspace, size_t workspace_bytes, void* stream);
+
+const char* thinkv_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* THINKV_H */

@@ -202,6 +202,14 @@ class OracleCache:
                                     self.v_codes[c][:n], self.v_scale[c][:n], self.v_zp[c][:n], b)
         return img.reshape(n, -1)
 
+    def arena_image_pages(self, c, pids):
+        """uint8 [len(pids), page_bytes] image of the listed physical pages of class c"""
+        b = self.cfg.bits_of_class[c]
+        p = np.asarray(pids, dtype=np.int64)
+        img = layout.pack_page_head(self.k_codes[c][p], self.k_scale[c][p], self.k_zp[c][p],
+                                    self.v_codes[c][p], self.v_scale[c][p], self.v_zp[c][p], b)
+        return img.reshape(len(p), -1)
+
     def stored_bytes_live(self, s, layer):
         """K+V bytes the live tokens of (s, layer) occupy: per token and kv-head
         2*(D*b/8 + (D/32)*4)  (codes plus a binary16 scale and zero-point per group)."""

@@ -1,0 +1,193 @@
+"""ctypes binding of libthinkv.so (include/thinkv.h).  Argument marshalling only: every step
+of the path runs in the HIP kernels; torch supplies device memory and the current stream.
+There is no CPU fallback: a missing library raises."""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libthinkv.so")
+_lib = None
+
+F16, BF16, F32 = 0, 1, 2
+_DT = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
+ST_NOPAGES, ST_BAD_CLASS, ST_BAD_SLOT, ST_EVICT_DEAD, ST_BAD_SEQ = 1, 2, 4, 8, 16
+EXPORTS = ["thinkv_block_bytes", "thinkv_page_bytes", "thinkv_append_workspace_bytes",
+           "thinkv_decode_workspace_bytes", "thinkv_init_view", "thinkv_append_quantized", "thinkv_evict",
+           "thinkv_decode_attention", "thinkv_decode_attention_valu", "thinkv_status_string"]
+
+
+class Config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("page_size", C.c_int32), ("group_size", C.c_int32),
+                ("bits_of_class", C.c_int32 * 3), ("max_seqs", C.c_int32), ("max_pages", C.c_int32)]
+
+
+class View(C.Structure):
+    _fields_ = [("cfg", Config), ("arena", C.c_void_p * 3), ("arena_pages", C.c_int64 * 3),
+                ("free_stack", C.c_void_p * 3), ("free_top", C.c_void_p), ("block_table", C.c_void_p),
+                ("n_pages", C.c_void_p), ("page_filled", C.c_void_p * 3), ("page_mask", C.c_void_p * 3),
+                ("slot_pos", C.c_void_p * 3), ("n_live", C.c_void_p), ("dev_status", C.c_void_p)]
+
+
+def load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python __graft_entry__.py` (hipcc, gfx950)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    lib.thinkv_block_bytes.restype = sz
+    lib.thinkv_block_bytes.argtypes = [C.POINTER(Config), C.c_int]
+    lib.thinkv_page_bytes.restype = sz
+    lib.thinkv_page_bytes.argtypes = [C.POINTER(Config), C.c_int]
+    lib.thinkv_append_workspace_bytes.restype = sz
+    lib.thinkv_append_workspace_bytes.argtypes = [C.POINTER(Config), i32]
+    lib.thinkv_decode_workspace_bytes.restype = sz
+    lib.thinkv_decode_workspace_bytes.argtypes = [C.POINTER(Config), i32, i32]
+    lib.thinkv_init_view.restype = C.c_int
+    lib.thinkv_init_view.argtypes = [C.POINTER(View), vp]
+    lib.thinkv_append_quantized.restype = C.c_int
+    lib.thinkv_append_quantized.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, vp, vp, i32, C.c_int, vp, sz, vp]
+    lib.thinkv_evict.restype = C.c_int
+    lib.thinkv_evict.argtypes = [C.POINTER(View), i32, vp, vp, i32, vp]
+    for name in ("thinkv_decode_attention", "thinkv_decode_attention_valu"):
+        fn = getattr(lib, name)
+        fn.restype = C.c_int
+        fn.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, vp, i32, i32, C.c_float, C.c_int, C.c_int, i32, vp, sz, vp]
+    lib.thinkv_status_string.restype = C.c_char_p
+    lib.thinkv_status_string.argtypes = [C.c_int]
+    _lib = lib
+    return lib
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"{what}: {load().thinkv_status_string(rc).decode()} (status {rc})")
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def make_config(n_layers, n_q_heads, n_kv_heads, head_dim, bits_of_class, max_seqs, max_pages):
+    return Config(n_layers, n_q_heads, n_kv_heads, head_dim, 16, 32, (C.c_int32 * 3)(*bits_of_class), max_seqs, max_pages)
+
+
+def thinkv_block_bytes(cfg, bits):
+    return load().thinkv_block_bytes(C.byref(cfg), bits)
+
+
+def thinkv_page_bytes(cfg, bits):
+    return load().thinkv_page_bytes(C.byref(cfg), bits)
+
+
+def thinkv_append_workspace_bytes(cfg, n_tok):
+    return load().thinkv_append_workspace_bytes(C.byref(cfg), n_tok)
+
+
+def thinkv_decode_workspace_bytes(cfg, B, max_ctx_pages):
+    return load().thinkv_decode_workspace_bytes(C.byref(cfg), B, max_ctx_pages)
+
+
+class Cache:
+    """Device buffers of one cache (torch tensors) and the thinkv_view that points at them."""
+
+    def __init__(self, n_layers, n_q_heads, n_kv_heads, head_dim, bits_of_class, max_seqs, max_pages,
+                 arena_pages, device="cuda:0", zero_arena=True):
+        load()
+        self.device = torch.device(device)
+        self.cfg = make_config(n_layers, n_q_heads, n_kv_heads, head_dim, bits_of_class, max_seqs, max_pages)
+        self.bits_of_class = tuple(bits_of_class)
+        self.arena_pages = tuple(int(x) for x in arena_pages)
+        d = self.device
+        mk = torch.zeros if zero_arena else torch.empty
+        self.page_bytes = [thinkv_page_bytes(self.cfg, b) for b in bits_of_class]
+        if 0 in self.page_bytes:
+            raise RuntimeError("unsupported geometry")
+        self.arena = [mk(max(1, n) * pb, dtype=torch.uint8, device=d) for n, pb in zip(self.arena_pages, self.page_bytes)]
+        self.free_stack = [torch.empty(max(1, n), dtype=torch.int32, device=d) for n in self.arena_pages]
+        self.free_top = torch.empty(3, dtype=torch.int32, device=d)
+        self.block_table = torch.empty((max_seqs, n_layers, 3, max_pages), dtype=torch.int32, device=d)
+        self.n_pages = torch.empty((max_seqs, n_layers, 3), dtype=torch.int32, device=d)
+        self.page_filled = [torch.empty(max(1, n), dtype=torch.uint8, device=d) for n in self.arena_pages]
+        self.page_mask = [torch.empty(max(1, n), dtype=torch.int32, device=d) for n in self.arena_pages]
+        self.slot_pos = [torch.empty((max(1, n), 16), dtype=torch.int32, device=d) for n in self.arena_pages]
+        self.n_live = torch.empty((max_seqs, n_layers), dtype=torch.int32, device=d)
+        self.dev_status = torch.empty(max_seqs * n_layers + 1, dtype=torch.int32, device=d)
+        v = View()
+        v.cfg = self.cfg
+        for k in range(3):
+            v.arena[k] = self.arena[k].data_ptr()
+            v.arena_pages[k] = self.arena_pages[k]
+            v.free_stack[k] = self.free_stack[k].data_ptr()
+            v.page_filled[k] = self.page_filled[k].data_ptr()
+            v.page_mask[k] = self.page_mask[k].data_ptr()
+            v.slot_pos[k] = self.slot_pos[k].data_ptr()
+        v.free_top = self.free_top.data_ptr()
+        v.block_table = self.block_table.data_ptr()
+        v.n_pages = self.n_pages.data_ptr()
+        v.n_live = self.n_live.data_ptr()
+        v.dev_status = self.dev_status.data_ptr()
+        self.view = v
+        self._ws = None
+        thinkv_init_view(self)
+
+    def workspace(self, nbytes):
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = torch.empty(int(nbytes * 1.25) + 256, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+
+def thinkv_init_view(cache, stream=None):
+    _check(load().thinkv_init_view(C.byref(cache.view), _stream(stream)), "thinkv_init_view")
+
+
+def thinkv_append_quantized(cache, layer, k_new, v_new, tok_seq, tok_pos, tok_class, tok_handle=None, stream=None):
+    """k_new, v_new: [n_tok, Hkv, D] device tensors (f16/bf16/f32, contiguous); tok_seq/tok_pos int32,
+    tok_class uint8, tok_handle int32 (optional, out) device tensors."""
+    n_tok = int(tok_seq.numel())
+    assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.dtype == v_new.dtype
+    assert tok_seq.dtype == torch.int32 and tok_pos.dtype == torch.int32 and tok_class.dtype == torch.uint8
+    assert tuple(k_new.shape) == (n_tok, cache.cfg.n_kv_heads, cache.cfg.head_dim) == tuple(v_new.shape)
+    nb = thinkv_append_workspace_bytes(cache.cfg, n_tok)
+    ws = cache.workspace(nb)
+    _check(load().thinkv_append_quantized(C.byref(cache.view), layer, _ptr(k_new), _ptr(v_new), _ptr(tok_seq),
+                                          _ptr(tok_pos), _ptr(tok_class), _ptr(tok_handle), n_tok, _DT[k_new.dtype],
+                                          _ptr(ws), ws.numel(), _stream(stream)), "thinkv_append_quantized")
+
+
+def thinkv_evict(cache, layer, ev_seq, ev_handle, stream=None):
+    assert ev_seq.dtype == torch.int32 and ev_handle.dtype == torch.int32
+    _check(load().thinkv_evict(C.byref(cache.view), layer, _ptr(ev_seq), _ptr(ev_handle), int(ev_seq.numel()),
+                               _stream(stream)), "thinkv_evict")
+
+
+def _decode(fn, cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale, max_ctx_pages, stream):
+    B = int(q.shape[0])
+    assert q.is_contiguous() and out.is_contiguous() and tuple(q.shape) == tuple(out.shape)
+    assert tuple(q.shape[1:]) == (cache.cfg.n_q_heads, cache.cfg.head_dim)
+    assert seq_ids.dtype == torch.int32 and (q_pos is None or q_pos.dtype == torch.int32)
+    assert lse is None or (lse.dtype == torch.float32 and lse.numel() == B * cache.cfg.n_q_heads)
+    nb = thinkv_decode_workspace_bytes(cache.cfg, B, max_ctx_pages)
+    ws = cache.workspace(nb)
+    _check(fn(C.byref(cache.view), layer, _ptr(q), _ptr(out), _ptr(lse), _ptr(seq_ids), _ptr(q_pos), B, window,
+              float(softmax_scale), _DT[q.dtype], _DT[out.dtype], int(max_ctx_pages), _ptr(ws), ws.numel(),
+              _stream(stream)), "thinkv_decode_attention")
+
+
+def thinkv_decode_attention(cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale, max_ctx_pages, stream=None):
+    _decode(load().thinkv_decode_attention, cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale,
+            max_ctx_pages, stream)
+
+
+def thinkv_decode_attention_valu(cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale, max_ctx_pages, stream=None):
+    _decode(load().thinkv_decode_attention_valu, cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale,
+            max_ctx_pages, stream)

@@ -1,0 +1,171 @@
+// C ABI entry points: argument checks and kernel dispatch.  No allocation, no global state,
+// no synchronisation.
+#include "decode_common.h"
+
+namespace thinkv {
+size_t append_ws_bytes(const thinkv_config& c, int n_tok);
+int launch_append(const thinkv_view& v, int layer, const void* k_new, const void* v_new, const int32_t* tok_seq,
+                  const int32_t* tok_pos, const uint8_t* tok_class, int32_t* tok_handle, int n_tok, int in_dtype,
+                  void* workspace, hipStream_t st);
+int launch_evict(const thinkv_view& v, int layer, const int32_t* ev_seq, const int32_t* ev_handle, int n_ev, hipStream_t st);
+int launch_init(const thinkv_view& v, hipStream_t st);
+int launch_decode_simple(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
+int launch_decode_mfma(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
+int launch_decode_merge(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
+int decode_mfma_supported(const thinkv_config& c);
+
+constexpr int kPagesPerItemSimple = 64;
+constexpr int kPagesPerItemMfma = 32;
+
+static int check_config(const thinkv_config* c) {
+  if (!c) return THINKV_E_INVALID_ARG;
+  if (c->page_size != kPage || c->group_size != kGroup) return THINKV_E_SHAPE;
+  if (c->head_dim != 64 && c->head_dim != 128) return THINKV_E_SHAPE;
+  if (c->n_layers < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1 || c->max_seqs < 1 || c->max_pages < 1) return THINKV_E_SHAPE;
+  if (c->n_q_heads % c->n_kv_heads) return THINKV_E_SHAPE;
+  if (c->n_q_heads / c->n_kv_heads > 8) return THINKV_E_SHAPE;
+  if (c->max_pages >= (1 << 24)) return THINKV_E_SHAPE;
+  for (int k = 0; k < 3; ++k)
+    if (!bits_ok(c->bits_of_class[k])) return THINKV_E_SHAPE;
+  return THINKV_OK;
+}
+
+static int check_view(const thinkv_view* v) {
+  if (!v) return THINKV_E_INVALID_ARG;
+  int rc = check_config(&v->cfg);
+  if (rc) return rc;
+  for (int k = 0; k < 3; ++k) {
+    if (v->arena_pages[k] < 0 || v->arena_pages[k] > 0x7fffffff) return THINKV_E_INVALID_ARG;
+    if (v->arena_pages[k] > 0 && (!v->arena[k] || !v->free_stack[k] || !v->page_filled[k] || !v->page_mask[k] || !v->slot_pos[k]))
+      return THINKV_E_INVALID_ARG;
+  }
+  if (!v->free_top || !v->block_table || !v->n_pages || !v->n_live || !v->dev_status) return THINKV_E_INVALID_ARG;
+  return THINKV_OK;
+}
+
+static int max_split_for(int max_ctx_pages, int pages_per_item) {
+  int s = (max_ctx_pages + pages_per_item - 1) / pages_per_item;
+  return s < 1 ? 1 : s;
+}
+
+static int decode_common(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
+                         const int32_t* seq_ids, const int32_t* q_pos, int32_t B, int32_t window, float softmax_scale,
+                         int q_dtype, int out_dtype, int32_t max_ctx_pages, void* workspace, size_t workspace_bytes,
+                         void* stream, bool fast) {
+  int rc = check_view(view);
+  if (rc) return rc;
+  if (B < 0 || layer < 0 || layer >= view->cfg.n_layers || window < 0 || max_ctx_pages < 0) return THINKV_E_INVALID_ARG;
+  if (B == 0) return THINKV_OK;
+  if (!q || !out || !seq_ids || !workspace || (window > 0 && !q_pos)) return THINKV_E_INVALID_ARG;
+  if (q_dtype != THINKV_F16 && q_dtype != THINKV_BF16) return THINKV_E_UNSUPPORTED;
+  if (out_dtype != THINKV_F16 && out_dtype != THINKV_BF16 && out_dtype != THINKV_F32) return THINKV_E_UNSUPPORTED;
+  if (workspace_bytes < thinkv_decode_workspace_bytes(&view->cfg, B, max_ctx_pages)) return THINKV_E_WORKSPACE;
+  fast = fast && decode_mfma_supported(view->cfg);
+  DecodeArgs a;
+  a.q = q;
+  a.out = out;
+  a.lse = lse;
+  a.seq_ids = seq_ids;
+  a.q_pos = q_pos;
+  a.partial = (float*)workspace;
+  a.layer = layer;
+  a.B = B;
+  a.window = window;
+  a.q_dtype = q_dtype;
+  a.out_dtype = out_dtype;
+  a.pages_per_item = fast ? kPagesPerItemMfma : kPagesPerItemSimple;
+  a.max_split = max_split_for(max_ctx_pages, a.pages_per_item);
+  a.scale_log2e = softmax_scale * 1.4426950408889634f;
+  hipStream_t st = (hipStream_t)stream;
+  rc = fast ? launch_decode_mfma(*view, a, st) : launch_decode_simple(*view, a, st);
+  if (rc) return rc;
+  return launch_decode_merge(*view, a, st);
+}
+
+}  // namespace thinkv
+
+using namespace thinkv;
+
+extern "C" {
+
+size_t thinkv_block_bytes(const thinkv_config* cfg, int bits) {
+  if (check_config(cfg) || !bits_ok(bits)) return 0;
+  return (size_t)block_geom(bits, cfg->head_dim).block_bytes;
+}
+
+size_t thinkv_page_bytes(const thinkv_config* cfg, int bits) {
+  return thinkv_block_bytes(cfg, bits) * (cfg ? (size_t)cfg->n_kv_heads : 0);
+}
+
+size_t thinkv_append_workspace_bytes(const thinkv_config* cfg, int32_t n_tok) {
+  if (check_config(cfg) || n_tok < 0) return 0;
+  return append_ws_bytes(*cfg, n_tok);
+}
+
+size_t thinkv_decode_workspace_bytes(const thinkv_config* cfg, int32_t B, int32_t max_ctx_pages) {
+  if (check_config(cfg) || B < 0 || max_ctx_pages < 0) return 0;
+  // sized for the finer of the two split granularities
+  const int ms = max_split_for(max_ctx_pages, kPagesPerItemMfma < kPagesPerItemSimple ? kPagesPerItemMfma : kPagesPerItemSimple);
+  return (size_t)(B > 0 ? B : 1) * cfg->n_q_heads * ms * (cfg->head_dim + 2) * sizeof(float);
+}
+
+int thinkv_init_view(const thinkv_view* view, void* stream) {
+  int rc = check_view(view);
+  if (rc) return rc;
+  return launch_init(*view, (hipStream_t)stream);
+}
+
+int thinkv_append_quantized(const thinkv_view* view, int32_t layer, const void* k_new, const void* v_new,
+                            const int32_t* tok_seq, const int32_t* tok_pos, const uint8_t* tok_class,
+                            int32_t* tok_handle, int32_t n_tok, thinkv_dtype in_dtype, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  int rc = check_view(view);
+  if (rc) return rc;
+  if (n_tok < 0 || layer < 0 || layer >= view->cfg.n_layers) return THINKV_E_INVALID_ARG;
+  if (n_tok == 0) return THINKV_OK;
+  if (!k_new || !v_new || !tok_seq || !tok_pos || !tok_class || !workspace) return THINKV_E_INVALID_ARG;
+  if (in_dtype != THINKV_F16 && in_dtype != THINKV_BF16 && in_dtype != THINKV_F32) return THINKV_E_UNSUPPORTED;
+  if (workspace_bytes < append_ws_bytes(view->cfg, n_tok)) return THINKV_E_WORKSPACE;
+  return launch_append(*view, layer, k_new, v_new, tok_seq, tok_pos, tok_class, tok_handle, n_tok, (int)in_dtype,
+                       workspace, (hipStream_t)stream);
+}
+
+int thinkv_evict(const thinkv_view* view, int32_t layer, const int32_t* ev_seq, const int32_t* ev_handle, int32_t n_ev,
+                 void* stream) {
+  int rc = check_view(view);
+  if (rc) return rc;
+  if (n_ev < 0 || layer < 0 || layer >= view->cfg.n_layers) return THINKV_E_INVALID_ARG;
+  if (n_ev == 0) return THINKV_OK;
+  if (!ev_seq || !ev_handle) return THINKV_E_INVALID_ARG;
+  return launch_evict(*view, layer, ev_seq, ev_handle, n_ev, (hipStream_t)stream);
+}
+
+int thinkv_decode_attention(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
+                            const int32_t* seq_ids, const int32_t* q_pos, int32_t B, int32_t window,
+                            float softmax_scale, thinkv_dtype q_dtype, thinkv_dtype out_dtype, int32_t max_ctx_pages,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_common(view, layer, q, out, lse, seq_ids, q_pos, B, window, softmax_scale, (int)q_dtype, (int)out_dtype,
+                       max_ctx_pages, workspace, workspace_bytes, stream, true);
+}
+
+int thinkv_decode_attention_valu(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
+                                 const int32_t* seq_ids, const int32_t* q_pos, int32_t B, int32_t window,
+                                 float softmax_scale, thinkv_dtype q_dtype, thinkv_dtype out_dtype, int32_t max_ctx_pages,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  return decode_common(view, layer, q, out, lse, seq_ids, q_pos, B, window, softmax_scale, (int)q_dtype, (int)out_dtype,
+                       max_ctx_pages, workspace, workspace_bytes, stream, false);
+}
+
+const char* thinkv_status_string(int status) {
+  switch (status) {
+    case THINKV_OK: return "ok";
+    case THINKV_E_INVALID_ARG: return "invalid argument";
+    case THINKV_E_SHAPE: return "unsupported geometry";
+    case THINKV_E_UNSUPPORTED: return "unsupported dtype or option";
+    case THINKV_E_WORKSPACE: return "workspace too small";
+    case THINKV_E_HIP: return "HIP call failed";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

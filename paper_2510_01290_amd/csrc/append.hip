@@ -1,0 +1,397 @@
+// Quantise-and-append: slot selection with in-place reuse of evicted slots, group
+// quantisation of the new K/V rows, packing into the page layout, table updates.
+//
+// The result must equal a one-token-at-a-time loop (first reclaimable slot in list order,
+// else the tail of the last page, else a new page popped in token order).  Because eviction
+// never interleaves with an append call, that loop has a closed form per (sequence, type):
+// the k-th token of the type (k counted inside the call) takes
+//     k < R            the k-th reclaimable slot in (page, slot) order        (R = #reclaimable)
+//     k < R + tail     slot filled + (k - R) of the last page                  (tail = 16 - filled)
+//     otherwise        slot (k-R-tail) % 16 of the (k-R-tail)/16-th new page
+// and new pages are granted to sequences in ascending sequence id, which is token order.
+// Four kernels, all on the caller's stream:
+//   plan   (block per sequence)  token ranks per type, prefix popcounts of the reclaimable bits,
+//                                pages needed
+//   grant  (one block)           exclusive scan of the needs over sequences against the pools
+//   place  (block per token)     slot lookup, quantisation, packing, slot_pos, handle
+//   commit (block per sequence)  masks, fill counts, page lists, counters
+#include "common.h"
+
+namespace thinkv {
+
+struct SeqPlan {
+  int lo, hi;        // token range of the sequence inside the call
+  int n[3];          // tokens per type
+  int R[3];          // reclaimable slots per type before the call
+  int tail[3];       // never-used slots in the last page
+  int np_old[3];
+  int need[3];       // new pages wanted (already limited by the page-list capacity)
+  int grant[3];      // new pages granted
+  int base[3];       // offset of the first granted page in pop order
+  int pad;
+};
+static_assert(sizeof(SeqPlan) == 24 * 4, "SeqPlan layout");
+
+struct AppendWs {
+  SeqPlan* plan;     // [max_seqs]
+  int* avail_old;    // [4]
+  int* tok_rank;     // [n_tok]
+  int* pre;          // [max_seqs][3][max_pages]
+};
+
+__host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+size_t append_ws_bytes(const thinkv_config& c, int n_tok) {
+  return align256((size_t)c.max_seqs * sizeof(SeqPlan)) + 256 + align256((size_t)(n_tok > 0 ? n_tok : 1) * 4) +
+         align256((size_t)c.max_seqs * 3 * c.max_pages * 4);
+}
+
+static AppendWs carve(const thinkv_config& c, int n_tok, void* ws) {
+  char* p = (char*)ws;
+  AppendWs w;
+  w.plan = (SeqPlan*)p;
+  p += align256((size_t)c.max_seqs * sizeof(SeqPlan));
+  w.avail_old = (int*)p;
+  p += 256;
+  w.tok_rank = (int*)p;
+  p += align256((size_t)(n_tok > 0 ? n_tok : 1) * 4);
+  w.pre = (int*)p;
+  return w;
+}
+
+// exclusive scan of one int per thread over a 256-thread block; returns the block total
+__device__ inline int block_excl_scan(int v, int* excl, int* lds /*[5]*/) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    int o = __shfl_up(inc, d, 64);
+    if (lane >= d) inc += o;
+  }
+  __syncthreads();
+  if (lane == 63) lds[wave] = inc;
+  __syncthreads();
+  int off = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    int t = lds[w];
+    if (w < wave) off += t;
+    tot += t;
+  }
+  *excl = off + inc - v;
+  return tot;
+}
+
+__global__ __launch_bounds__(256) void append_plan_kernel(thinkv_view v, int layer, const int32_t* __restrict__ tok_seq,
+                                                          const uint8_t* __restrict__ tok_class, int n_tok, AppendWs ws) {
+  __shared__ int s_rng[2];
+  __shared__ int s_scan[5];
+  const thinkv_config& c = v.cfg;
+  const int s = blockIdx.x, tid = threadIdx.x;
+  if (tid == 0) {
+    int lo = 0, hi = n_tok;  // lower_bound(s)
+    while (lo < hi) {
+      int mid = (lo + hi) >> 1;
+      if (tok_seq[mid] < s) lo = mid + 1; else hi = mid;
+    }
+    int lo2 = lo, hi2 = n_tok;  // upper_bound(s)
+    while (lo2 < hi2) {
+      int mid = (lo2 + hi2) >> 1;
+      if (tok_seq[mid] <= s) lo2 = mid + 1; else hi2 = mid;
+    }
+    s_rng[0] = lo;
+    s_rng[1] = lo2;
+  }
+  __syncthreads();
+  const int lo = s_rng[0], hi = s_rng[1];
+  SeqPlan pl;
+  pl.lo = lo;
+  pl.hi = hi;
+  pl.pad = 0;
+  for (int k = 0; k < 3; ++k) {
+    pl.n[k] = pl.R[k] = pl.tail[k] = pl.need[k] = pl.grant[k] = pl.base[k] = 0;
+    pl.np_old[k] = 0;
+  }
+  if (lo < hi) {
+    for (int k = 0; k < 3; ++k) {
+      int running = 0;
+      for (int b0 = lo; b0 < hi; b0 += 256) {
+        int i = b0 + tid;
+        int is = (i < hi && tok_class[i] == k) ? 1 : 0;
+        int ex;
+        int tot = block_excl_scan(is, &ex, s_scan);
+        if (is) ws.tok_rank[i] = running + ex;
+        running += tot;
+      }
+      const int np = v.n_pages[npages_index(c, s, layer, k)];
+      const int32_t* tab = v.block_table + table_base(c, s, layer, k);
+      int* pre = ws.pre + ((int64_t)s * 3 + k) * c.max_pages;
+      int runR = 0;
+      for (int b0 = 0; b0 < np; b0 += 256) {
+        int pi = b0 + tid;
+        int cnt = 0;
+        if (pi < np) cnt = __popc(v.page_mask[k][tab[pi]] >> 16);
+        int ex;
+        int tot = block_excl_scan(cnt, &ex, s_scan);
+        if (pi < np) pre[pi] = runR + ex;
+        runR += tot;
+      }
+      int tail = np > 0 ? kPage - (int)v.page_filled[k][tab[np - 1]] : 0;
+      int need = running - runR - tail;
+      need = need > 0 ? (need + kPage - 1) / kPage : 0;
+      int room = c.max_pages - np;
+      need = need < room ? need : room;
+      pl.n[k] = running;
+      pl.R[k] = runR;
+      pl.tail[k] = tail;
+      pl.np_old[k] = np;
+      pl.need[k] = need;
+    }
+  }
+  if (tid == 0) ws.plan[s] = pl;
+}
+
+__global__ __launch_bounds__(256) void append_grant_kernel(thinkv_view v, AppendWs ws) {
+  __shared__ int s_scan[5];
+  const int tid = threadIdx.x, S = v.cfg.max_seqs;
+  for (int k = 0; k < 3; ++k) {
+    const int avail = v.free_top[k];
+    int running = 0;
+    for (int b0 = 0; b0 < S; b0 += 256) {
+      int s = b0 + tid;
+      int need = s < S ? ws.plan[s].need[k] : 0;
+      int ex;
+      int tot = block_excl_scan(need, &ex, s_scan);
+      if (s < S) {
+        int base = running + ex;
+        int left = avail - base;
+        int g = left < 0 ? 0 : (left < need ? left : need);
+        ws.plan[s].base[k] = base < avail ? base : avail;
+        ws.plan[s].grant[k] = g;
+      }
+      running += tot;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      ws.avail_old[k] = avail;
+      v.free_top[k] = avail - (running < avail ? running : avail);
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// place: one block per token.
+template <int D>
+__global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int layer, const void* __restrict__ k_new,
+                                                           const void* __restrict__ v_new, const int32_t* __restrict__ tok_seq,
+                                                           const int32_t* __restrict__ tok_pos, const uint8_t* __restrict__ tok_class,
+                                                           int32_t* __restrict__ tok_handle, int n_tok, int in_dtype, AppendWs ws) {
+  constexpr int NG = D / kGroup;        // groups per row
+  constexpr int NM = D / 16;            // 16-channel blocks per row
+  constexpr int HP = 256 / (2 * D);     // heads handled per pass
+  __shared__ int s_place[4];            // type, page id, slot, ok
+  __shared__ uint8_t s_codes[HP][2][D];
+  __shared__ uint32_t s_meta[HP][2][NG];
+  const thinkv_config& c = v.cfg;
+  const int i = blockIdx.x, tid = threadIdx.x;
+  if (tid == 0) {
+    int ok = 0, cls = 0, pid = 0, slot = 0, pi = 0;
+    const int s = tok_seq[i];
+    if (s < 0 || s >= c.max_seqs) {
+      atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEQ);
+    } else {
+      cls = tok_class[i];
+      const SeqPlan& pl = ws.plan[s];
+      if (cls > 2) {
+        atomicOr(&v.dev_status[sl_index(c, s, layer)], THINKV_ST_BAD_CLASS);
+      } else if (i >= pl.lo && i < pl.hi) {
+        const int k = ws.tok_rank[i];
+        const int32_t* tab = v.block_table + table_base(c, s, layer, cls);
+        const int R = pl.R[cls], tail = pl.tail[cls], np = pl.np_old[cls];
+        if (k < R) {
+          const int* pre = ws.pre + ((int64_t)s * 3 + cls) * c.max_pages;
+          int lo = 0, hi = np - 1;  // largest pi with pre[pi] <= k
+          while (lo < hi) {
+            int mid = (lo + hi + 1) >> 1;
+            if (pre[mid] <= k) lo = mid; else hi = mid - 1;
+          }
+          pi = lo;
+          pid = tab[pi];
+          uint32_t e = v.page_mask[cls][pid] >> 16;
+          for (int j = k - pre[pi]; j > 0; --j) e &= e - 1;
+          slot = __ffs(e) - 1;
+          ok = 1;
+        } else if (k < R + tail) {
+          pi = np - 1;
+          pid = tab[pi];
+          slot = (int)v.page_filled[cls][pid] + (k - R);
+          ok = 1;
+        } else {
+          const int kk = k - R - tail, npi = kk >> 4;
+          if (npi < pl.grant[cls]) {
+            pi = np + npi;
+            slot = kk & 15;
+            pid = v.free_stack[cls][ws.avail_old[cls] - 1 - (pl.base[cls] + npi)];
+            ok = 1;
+          }
+        }
+      }
+    }
+    if (ok) v.slot_pos[cls][(int64_t)pid * kPage + slot] = tok_pos[i];
+    if (tok_handle) tok_handle[i] = ok ? THINKV_HANDLE(cls, pi, slot) : -1;
+    s_place[0] = cls;
+    s_place[1] = pid;
+    s_place[2] = slot;
+    s_place[3] = ok;
+  }
+  __syncthreads();
+  if (!s_place[3]) return;
+  const int cls = s_place[0], pid = s_place[1], t = s_place[2];
+  const int bits = c.bits_of_class[cls];
+  const BlockGeom g = block_geom(bits, D);
+  const int H = c.n_kv_heads;
+  const float qmax = (float)((1 << bits) - 1);
+  uint8_t* page = v.arena[cls] + (int64_t)pid * H * g.block_bytes;
+  const int CB = g.chunk_bytes, FPH = 16 / bits, CPB = 8 / bits;  // codes per byte
+
+  const int hs = tid / (2 * D), r = tid % (2 * D), kind = r / D, ch = r % D;
+  for (int h0 = 0; h0 < H; h0 += HP) {
+    const int h = h0 + hs;
+    if (h < H) {
+      const void* src = kind ? v_new : k_new;
+      const float x = load_as_f32(src, ((int64_t)i * H + h) * D + ch, in_dtype);
+      float mn = x, mx = x;
+#pragma unroll
+      for (int d = 16; d >= 1; d >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, d, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, d, 64));
+      }
+      const _Float16 zp = (_Float16)(mn + 0.0f);
+      const float s32 = (mx - mn) / qmax;
+      _Float16 sc = (_Float16)s32;
+      if ((float)sc < s32) {
+        uint16_t u = __builtin_bit_cast(uint16_t, sc);
+        sc = __builtin_bit_cast(_Float16, (uint16_t)(u + 1));
+      }
+      const float sf = (float)sc, zf = (float)zp;
+      float code = 0.0f;
+      if (sf > 0.0f) {
+        code = rintf((x - zf) / sf);
+        code = fminf(fmaxf(code, 0.0f), qmax);
+      }
+      s_codes[hs][kind][ch] = (uint8_t)(int)code;
+      if ((ch & 31) == 0)
+        s_meta[hs][kind][ch >> 5] = (uint32_t)__builtin_bit_cast(uint16_t, sc) | ((uint32_t)__builtin_bit_cast(uint16_t, zp) << 16);
+    }
+    __syncthreads();
+    // pack: every destination byte the slot owns is assembled by one thread
+    const int per_head = 8 * CB;  // 4*CB bytes of K codes + 4*CB bytes of V codes
+    const int ph = tid / per_head, pr = tid % per_head;
+    if (ph < HP && h0 + ph < H) {
+      uint8_t* blk = page + (int64_t)(h0 + ph) * g.block_bytes;
+      uint32_t byte = 0;
+      if (pr < 4 * CB) {  // K: chunk 16*j + t, byte ob
+        const int j = pr / CB, ob = pr % CB;
+        const int w = ob >> 2, bo = (ob & 3) * 8, hh = bo >> 4, lf = (bo & 15) / bits;
+        for (int q = 0; q < CPB; ++q) {
+          const int f = w * FPH + lf + q;
+          const int chn = 32 * (f >> 2) + 8 * j + 2 * (f & 3) + hh;
+          byte |= (uint32_t)s_codes[ph][0][chn] << (q * bits);
+        }
+        blk[g.k_codes + (16 * j + t) * CB + ob] = (uint8_t)byte;
+      } else {            // V: chunk 16*(t/4) + m, fields u*NM .. u*NM+NM-1 of half t%2
+        const int vb = pr - 4 * CB, OB = CB / 4;
+        const int m = vb / OB, kk = vb % OB;
+        const int u = (t >> 1) & 1, hh = t & 1;
+        const int f0 = u * NM + kk * CPB;
+        const int off = 4 * (f0 / FPH) + 2 * hh + (bits * (f0 % FPH)) / 8;
+        for (int q = 0; q < CPB; ++q) {
+          const int mb = kk * CPB + q;
+          byte |= (uint32_t)s_codes[ph][1][16 * mb + m] << (q * bits);
+        }
+        blk[g.v_codes + (16 * (t >> 2) + m) * CB + off] = (uint8_t)byte;
+      }
+    }
+    if (tid < HP * 2 * NG) {
+      const int mh = tid / (2 * NG), mr = tid % (2 * NG), mk = mr / NG, mg = mr % NG;
+      if (h0 + mh < H) {
+        uint8_t* blk = page + (int64_t)(h0 + mh) * g.block_bytes;
+        ((uint32_t*)(blk + (mk ? g.v_meta : g.k_meta)))[t * NG + mg] = s_meta[mh][mk][mg];
+      }
+    }
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(256) void append_commit_kernel(thinkv_view v, int layer, AppendWs ws) {
+  const thinkv_config& c = v.cfg;
+  const int s = blockIdx.x, tid = threadIdx.x;
+  const SeqPlan pl = ws.plan[s];
+  if (pl.lo >= pl.hi) return;
+  int placed_all = 0, short_any = 0;
+  for (int k = 0; k < 3; ++k) {
+    const int n = pl.n[k], R = pl.R[k], tail = pl.tail[k], np = pl.np_old[k], grant = pl.grant[k];
+    if (n == 0) continue;
+    int32_t* tab = v.block_table + table_base(c, s, layer, k);
+    const int* pre = ws.pre + ((int64_t)s * 3 + k) * c.max_pages;
+    for (int pi = tid; pi < np; pi += 256) {
+      const int pid = tab[pi];
+      uint32_t m = v.page_mask[k][pid];
+      uint32_t e = m >> 16;
+      int take = n - pre[pi];
+      const int have = __popc(e);
+      take = take < 0 ? 0 : (take > have ? have : take);
+      uint32_t bits = 0;
+      for (int j = 0; j < take; ++j) {
+        uint32_t b = e & (0u - e);
+        bits |= b;
+        e ^= b;
+      }
+      m = (m | bits) & ~(bits << 16);
+      if (pi == np - 1 && tail > 0 && n > R) {
+        const int add = (n - R) < tail ? (n - R) : tail;
+        const int f = v.page_filled[k][pid];
+        m |= ((1u << add) - 1u) << f;
+        v.page_filled[k][pid] = (uint8_t)(f + add);
+      }
+      v.page_mask[k][pid] = m;
+    }
+    for (int i = tid; i < grant; i += 256) {
+      const int pid = v.free_stack[k][ws.avail_old[k] - 1 - (pl.base[k] + i)];
+      int cnt = n - R - tail - kPage * i;
+      cnt = cnt > kPage ? kPage : cnt;
+      tab[np + i] = pid;
+      v.page_filled[k][pid] = (uint8_t)cnt;
+      v.page_mask[k][pid] = (1u << cnt) - 1u;
+      for (int sl = cnt; sl < kPage; ++sl) v.slot_pos[k][(int64_t)pid * kPage + sl] = -1;
+    }
+    const int cap = R + tail + kPage * grant;
+    placed_all += n < cap ? n : cap;
+    if (n > cap) short_any = 1;
+    if (tid == 0) v.n_pages[npages_index(c, s, layer, k)] = np + grant;
+  }
+  if (tid == 0) {
+    v.n_live[sl_index(c, s, layer)] += placed_all;
+    if (short_any) atomicOr(&v.dev_status[sl_index(c, s, layer)], THINKV_ST_NOPAGES);
+  }
+}
+
+int launch_append(const thinkv_view& v, int layer, const void* k_new, const void* v_new, const int32_t* tok_seq,
+                  const int32_t* tok_pos, const uint8_t* tok_class, int32_t* tok_handle, int n_tok, int in_dtype,
+                  void* workspace, hipStream_t st) {
+  AppendWs ws = carve(v.cfg, n_tok, workspace);
+  const int S = v.cfg.max_seqs;
+  hipLaunchKernelGGL(append_plan_kernel, dim3(S), dim3(256), 0, st, v, layer, tok_seq, tok_class, n_tok, ws);
+  hipLaunchKernelGGL(append_grant_kernel, dim3(1), dim3(256), 0, st, v, ws);
+  if (v.cfg.head_dim == 128)
+    hipLaunchKernelGGL(append_place_kernel<128>, dim3(n_tok), dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
+                       tok_class, tok_handle, n_tok, in_dtype, ws);
+  else
+    hipLaunchKernelGGL(append_place_kernel<64>, dim3(n_tok), dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
+                       tok_class, tok_handle, n_tok, in_dtype, ws);
+  hipLaunchKernelGGL(append_commit_kernel, dim3(S), dim3(256), 0, st, v, layer, ws);
+  return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
+}
+
+}  // namespace thinkv

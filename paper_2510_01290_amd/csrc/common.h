@@ -1,0 +1,75 @@
+// Shared device/host helpers for the ThinKV kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/thinkv.h"
+
+namespace thinkv {
+
+constexpr int kPage = THINKV_PAGE_SIZE;   // slots per page
+constexpr int kGroup = THINKV_GROUP_SIZE; // channels per quantisation group
+constexpr int kWave = 64;
+
+// Geometry of one (page, kv-head) block for b-bit codes and head_dim D.
+struct BlockGeom {
+  int chunk_bytes;  // CB = (D/32)*b
+  int codes_bytes;  // 64*CB
+  int meta_bytes;   // 16*(D/32)*4
+  int k_codes, k_meta, v_codes, v_meta;  // region offsets
+  int block_bytes;
+};
+
+__host__ __device__ inline BlockGeom block_geom(int bits, int D) {
+  BlockGeom g;
+  g.chunk_bytes = (D / kGroup) * bits;
+  g.codes_bytes = 64 * g.chunk_bytes;
+  g.meta_bytes = kPage * (D / kGroup) * 4;
+  g.k_codes = 0;
+  g.k_meta = g.codes_bytes;
+  g.v_codes = g.codes_bytes + g.meta_bytes;
+  g.v_meta = 2 * g.codes_bytes + g.meta_bytes;
+  g.block_bytes = 2 * (g.codes_bytes + g.meta_bytes);
+  return g;
+}
+
+__host__ __device__ inline bool bits_ok(int b) { return b == 2 || b == 4 || b == 8; }
+
+// index helpers for the per-(sequence, layer[, type]) tables
+__device__ inline int64_t table_base(const thinkv_config& c, int seq, int layer, int cls) {
+  return (((int64_t)seq * c.n_layers + layer) * 3 + cls) * (int64_t)c.max_pages;
+}
+__device__ inline int npages_index(const thinkv_config& c, int seq, int layer, int cls) {
+  return (seq * c.n_layers + layer) * 3 + cls;
+}
+__device__ inline int sl_index(const thinkv_config& c, int seq, int layer) { return seq * c.n_layers + layer; }
+
+// widen one element of a 16/32-bit float array exactly to binary32
+__device__ inline float load_as_f32(const void* p, int64_t i, int dtype) {
+  if (dtype == THINKV_F16) {
+    return (float)(((const _Float16*)p)[i]);
+  } else if (dtype == THINKV_BF16) {
+    uint32_t u = ((uint32_t)((const uint16_t*)p)[i]) << 16;
+    return __builtin_bit_cast(float, u);
+  }
+  return ((const float*)p)[i];
+}
+
+__device__ inline uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ inline void store_from_f32(void* p, int64_t i, int dtype, float v) {
+  if (dtype == THINKV_F16) {
+    ((_Float16*)p)[i] = (_Float16)v;
+  } else if (dtype == THINKV_BF16) {
+    ((uint16_t*)p)[i] = f32_to_bf16_rne(v);
+  } else {
+    ((float*)p)[i] = v;
+  }
+}
+
+}  // namespace thinkv

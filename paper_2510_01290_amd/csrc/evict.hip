@@ -1,0 +1,70 @@
+// Soft eviction and view initialisation.
+#include "common.h"
+
+namespace thinkv {
+
+// One thread per handle.  The live bit is cleared with one atomic; only the thread that saw
+// it set goes on to mark the slot reclaimable, so duplicates and dead slots count once.
+__global__ __launch_bounds__(256) void evict_kernel(thinkv_view v, int layer, const int32_t* __restrict__ ev_seq,
+                                                    const int32_t* __restrict__ ev_handle, int n_ev) {
+  const thinkv_config& c = v.cfg;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_ev) return;
+  const int s = ev_seq[i];
+  if (s < 0 || s >= c.max_seqs) {
+    atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEQ);
+    return;
+  }
+  const int32_t h = ev_handle[i];
+  const uint32_t uh = (uint32_t)h;
+  const int cls = uh >> 28, pi = (uh >> 4) & 0xFFFFFF, slot = uh & 15;
+  uint32_t* status = &v.dev_status[sl_index(c, s, layer)];
+  if (h < 0 || cls > 2 || pi >= v.n_pages[npages_index(c, s, layer, cls)]) {
+    atomicOr(status, THINKV_ST_BAD_SLOT);
+    return;
+  }
+  const int pid = v.block_table[table_base(c, s, layer, cls) + pi];
+  const uint32_t bit = 1u << slot;
+  const uint32_t old = atomicAnd(&v.page_mask[cls][pid], ~bit);
+  if (old & bit) {
+    atomicOr(&v.page_mask[cls][pid], bit << 16);
+    atomicSub(&v.n_live[sl_index(c, s, layer)], 1);
+  } else {
+    atomicOr(status, THINKV_ST_EVICT_DEAD);
+  }
+}
+
+__global__ __launch_bounds__(256) void init_kernel(thinkv_view v) {
+  const thinkv_config& c = v.cfg;
+  const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int k = 0; k < 3; ++k) {
+    const int64_t n = v.arena_pages[k];
+    for (int64_t i = tid; i < n; i += stride) {
+      v.free_stack[k][i] = (int32_t)(n - 1 - i);
+      v.page_filled[k][i] = 0;
+      v.page_mask[k][i] = 0;
+    }
+    for (int64_t i = tid; i < n * kPage; i += stride) v.slot_pos[k][i] = -1;
+    if (tid == 0) v.free_top[k] = (int32_t)n;
+  }
+  const int64_t nt = (int64_t)c.max_seqs * c.n_layers * 3 * c.max_pages;
+  for (int64_t i = tid; i < nt; i += stride) v.block_table[i] = -1;
+  const int64_t nsl = (int64_t)c.max_seqs * c.n_layers;
+  for (int64_t i = tid; i < nsl * 3; i += stride) v.n_pages[i] = 0;
+  for (int64_t i = tid; i < nsl; i += stride) v.n_live[i] = 0;
+  for (int64_t i = tid; i < nsl + 1; i += stride) v.dev_status[i] = 0;
+}
+
+int launch_evict(const thinkv_view& v, int layer, const int32_t* ev_seq, const int32_t* ev_handle, int n_ev, hipStream_t st) {
+  if (n_ev == 0) return THINKV_OK;
+  hipLaunchKernelGGL(evict_kernel, dim3((n_ev + 255) / 256), dim3(256), 0, st, v, layer, ev_seq, ev_handle, n_ev);
+  return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
+}
+
+int launch_init(const thinkv_view& v, hipStream_t st) {
+  hipLaunchKernelGGL(init_kernel, dim3(1024), dim3(256), 0, st, v);
+  return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
+}
+
+}  // namespace thinkv

@@ -1,0 +1,195 @@
+"""GPU-vs-oracle parity harness (test helper; also used by __graft_entry__.smoke and bench.py's
+cpu_baseline leg).  The same seeded script is replayed on the HIP cache and on the CPU oracle;
+bookkeeping and packed bytes are compared bit for bit, attention within the stated tolerance."""
+import time
+from dataclasses import dataclass, field
+
+import numpy as np
+import torch
+
+from oracle import attention as oattn
+from oracle import cache as ocache
+from paper_2510_01290_amd import synth
+
+import backends
+
+TOL = 2e-3          # max-abs error of the attention output against the binary64 oracle (binary32 out)
+
+
+class GpuBackend:
+    def __init__(self, cache):
+        self.cache = cache
+        self.device = cache.device
+
+    def append(self, layer, k, v, tok_seq, tok_pos, tok_class):
+        from paper_2510_01290_amd import binding as B
+        d = self.device
+        ts = torch.from_numpy(np.ascontiguousarray(tok_seq, dtype=np.int32)).to(d)
+        tp = torch.from_numpy(np.ascontiguousarray(tok_pos, dtype=np.int32)).to(d)
+        tc = torch.from_numpy(np.ascontiguousarray(tok_class, dtype=np.uint8)).to(d)
+        h = torch.empty(len(tok_seq), dtype=torch.int32, device=d)
+        B.thinkv_append_quantized(self.cache, layer, k.contiguous(), v.contiguous(), ts, tp, tc, h)
+        return h.cpu().numpy()
+
+    def evict(self, layer, ev_seq, ev_handle):
+        from paper_2510_01290_amd import binding as B
+        d = self.device
+        B.thinkv_evict(self.cache, layer, torch.from_numpy(np.ascontiguousarray(ev_seq, dtype=np.int32)).to(d),
+                       torch.from_numpy(np.ascontiguousarray(ev_handle, dtype=np.int32)).to(d))
+
+
+def make_gpu_cache(wl, max_seqs=None, arena_pages=None, max_pages=None, device="cuda:0"):
+    from paper_2510_01290_amd import binding as B
+    g = wl.geom
+    return B.Cache(g.n_layers, g.n_q_heads, g.n_kv_heads, g.head_dim, g.bits_of_class,
+                   max_seqs or wl.n_seqs, max_pages or backends.max_pages_need(wl),
+                   arena_pages or backends.arena_need(wl), device=device)
+
+
+def make_oracle(wl, max_seqs=None, arena_pages=None, max_pages=None, store_data=True):
+    cfg = backends.oracle_config(wl.geom, max_seqs or wl.n_seqs, max_pages or backends.max_pages_need(wl),
+                                 arena_pages or backends.arena_need(wl))
+    return backends.OracleBackend(cfg, store_data=store_data)
+
+
+# ------------------------------------------------------------------------- comparisons
+def gpu_tables(gc):
+    """host copies of the device bookkeeping"""
+    t = dict(table=gc.block_table.cpu().numpy(), n_pages=gc.n_pages.cpu().numpy(), n_live=gc.n_live.cpu().numpy(),
+             status=gc.dev_status.cpu().numpy().view(np.uint32), free_top=gc.free_top.cpu().numpy())
+    t["filled"] = [x.cpu().numpy() for x in gc.page_filled]
+    t["mask"] = [x.cpu().numpy().view(np.uint32) for x in gc.page_mask]
+    t["slot_pos"] = [x.cpu().numpy() for x in gc.slot_pos]
+    t["free_stack"] = [x.cpu().numpy() for x in gc.free_stack]
+    return t
+
+
+def compare_bookkeeping_full(oc, gc):
+    """every table, mask, counter and the free pools, bit for bit (same physical page ids)"""
+    t = gpu_tables(gc)
+    assert np.array_equal(t["n_pages"], oc.n_pages), "n_pages"
+    assert np.array_equal(t["n_live"], oc.n_live), "n_live"
+    assert np.array_equal(t["status"], oc.status), ("dev_status", t["status"], oc.status)
+    assert np.array_equal(t["free_top"], oc.free_top), "free_top"
+    S, L = oc.n_pages.shape[:2]
+    for s in range(S):
+        for l in range(L):
+            for c in range(3):
+                n = int(oc.n_pages[s, l, c])
+                assert np.array_equal(t["table"][s, l, c, :n], oc.table[s, l, c, :n]), ("block_table", s, l, c)
+    for c in range(3):
+        n = int(oc.cfg.arena_pages[c])
+        top = int(oc.free_top[c])
+        assert np.array_equal(t["free_stack"][c][:top], oc.free_stack[c][:top]), "free_stack"
+        used = np.setdiff1d(np.arange(n), oc.free_stack[c][:top])
+        assert np.array_equal(t["filled"][c][used], oc.filled[c][used]), "filled"
+        assert np.array_equal(t["mask"][c][used] & 0xFFFF, oc.valid[c][used]), "live bits"
+        assert np.array_equal(t["mask"][c][used] >> 16, oc.evict[c][used]), "evict bits"
+        assert np.array_equal(t["slot_pos"][c][used], oc.slot_pos[c][used]), "slot_pos"
+
+
+def compare_sequences(oc, gc, pairs, check_bytes=True):
+    """per (oracle seq, gpu seq, layer): page lists compared page by page through the tables, so it
+    also works when the oracle replayed only a sample of the sequences (different physical ids)"""
+    t = gpu_tables(gc)
+    for so, sg, l in pairs:
+        assert np.array_equal(t["n_pages"][sg, l], oc.n_pages[so, l]), ("n_pages", sg, l)
+        assert t["n_live"][sg, l] == oc.n_live[so, l], ("n_live", sg, l)
+        for c in range(3):
+            n = int(oc.n_pages[so, l, c])
+            po = oc.table[so, l, c, :n]
+            pg = t["table"][sg, l, c, :n]
+            assert np.array_equal(t["filled"][c][pg], oc.filled[c][po]), ("filled", sg, l, c)
+            assert np.array_equal(t["mask"][c][pg] & 0xFFFF, oc.valid[c][po]), ("live bits", sg, l, c)
+            assert np.array_equal(t["mask"][c][pg] >> 16, oc.evict[c][po]), ("evict bits", sg, l, c)
+            assert np.array_equal(t["slot_pos"][c][pg], oc.slot_pos[c][po]), ("slot_pos", sg, l, c)
+            if check_bytes and n:
+                pb = gc.page_bytes[c]
+                idx = torch.from_numpy(pg.astype(np.int64)).to(gc.device)
+                img_g = gc.arena[c].view(-1, pb)[idx].cpu().numpy()
+                img_o = oc.arena_image_pages(c, po)
+                assert np.array_equal(img_g, img_o), ("page bytes", sg, l, c)
+
+
+def gpu_attention(gc, wl, runner, layer, out_dtype=torch.float32, variant="fast", seqs=None, max_ctx_pages=None):
+    from paper_2510_01290_amd import binding as B
+    g = wl.geom
+    seqs = list(range(wl.n_seqs)) if seqs is None else list(seqs)
+    q = torch.stack([synth.query_rows(wl.seed, layer, s, 0, g, gc.device) for s in seqs]).contiguous()
+    out = torch.empty(q.shape, dtype=out_dtype, device=gc.device)
+    lse = torch.empty((len(seqs), g.n_q_heads), dtype=torch.float32, device=gc.device)
+    sid = torch.tensor(seqs, dtype=torch.int32, device=gc.device)
+    qp = torch.from_numpy(wl.q_pos[seqs].astype(np.int32)).to(gc.device)
+    if max_ctx_pages is None:
+        max_ctx_pages = int(gc.n_pages[:, layer].sum(-1).max().item())
+    fn = B.thinkv_decode_attention if variant == "fast" else B.thinkv_decode_attention_valu
+    fn(gc, layer, q, out, lse, sid, qp, wl.window_of_layer[layer], g.head_dim ** -0.5, max_ctx_pages)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
+
+
+def oracle_attention(oc, wl, layer, seqs_oracle, seqs_workload):
+    g = wl.geom
+    q = torch.stack([synth.query_rows(wl.seed, layer, s, 0, g, torch.device("cpu")) for s in seqs_workload])
+    return oattn.decode_attention(oc, layer, q.float().numpy().astype(np.float64), seqs_oracle,
+                                  wl.q_pos[list(seqs_workload)], wl.window_of_layer[layer], g.head_dim ** -0.5)
+
+
+def half_ulp(ref, dtype):
+    """half a unit in the last place of `dtype` at |ref| (rounding allowance for 16-bit outputs)"""
+    mant = {torch.float16: 10, torch.bfloat16: 7}[dtype]
+    e = np.floor(np.log2(np.maximum(np.abs(ref), 2.0 ** -14)))
+    return 2.0 ** (e - mant - 1)
+
+
+# ------------------------------------------------------------------------------- cases
+@dataclass
+class Case:
+    wl: object
+    sample: list = None          # (seq, layer) pairs the oracle replays; None = everything
+    variants: tuple = ("fast", "valu")
+
+
+def case_tiny(seed=0, bits=(8, 2, 4)):
+    return Case(synth.config_tiny(seed, bits))
+
+
+def run_case(case, check_bytes=True, out_dtypes=(torch.float32,)):
+    wl = case.wl
+    gc = make_gpu_cache(wl)
+    gr = synth.ScriptRunner(wl, GpuBackend(gc)).run()
+    torch.cuda.synchronize()
+    res = {"workload": wl.name}
+    if case.sample is None:
+        ob = make_oracle(wl)
+        orr = synth.ScriptRunner(wl, ob).run()
+        for key in gr.handle:
+            assert np.array_equal(gr.handle[key], orr.handle[key]), ("handles", key)
+        compare_bookkeeping_full(ob.cache, gc)
+        pairs = [(s, s, l) for s in range(wl.n_seqs) for l in range(wl.geom.n_layers)]
+        compare_sequences(ob.cache, gc, pairs, check_bytes)
+        att = [(l, list(range(wl.n_seqs)), list(range(wl.n_seqs)), ob.cache) for l in range(wl.geom.n_layers)]
+    else:
+        att = []
+        for s, l in case.sample:
+            ob = make_oracle(wl)
+            orr = synth.ScriptRunner(wl, ob, layers=[l], seqs=[s]).run()
+            assert np.array_equal(gr.handle[(l, s)], orr.handle[(l, s)]), ("handles", s, l)
+            compare_sequences(ob.cache, gc, [(s, s, l)], check_bytes)
+            att.append((l, [s], [s], ob.cache))
+    worst = {}
+    for l, so, sw, oc in att:
+        ref, ref_lse = oracle_attention(oc, wl, l, so, sw)
+        for variant in case.variants:
+            for dt in out_dtypes:
+                got, lse = gpu_attention(gc, wl, gr, l, dt, variant, seqs=sw)
+                err = np.abs(got - ref)
+                allow = TOL + (half_ulp(ref, dt) if dt != torch.float32 else 0.0)
+                key = f"attn_max_abs_err_{'f32' if dt == torch.float32 else str(dt).split('.')[-1]}" + ("" if variant == "fast" else "_valu")
+                worst[key] = max(worst.get(key, 0.0), float(err.max()))
+                assert np.all(err <= allow), (key, l, float(err.max()))
+                fin = np.isfinite(ref_lse)
+                assert np.array_equal(np.isfinite(lse), fin)
+                assert np.all(np.abs(lse[fin] - ref_lse[fin]) <= 1e-3), ("lse", float(np.abs(lse[fin] - ref_lse[fin]).max()))
+    res.update(worst)
+    return res

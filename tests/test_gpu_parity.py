@@ -1,0 +1,119 @@
+"""HIP path vs CPU oracle on the same seeded inputs (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import backends
+import parity
+from oracle import cache as ocache
+from paper_2510_01290_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.mark.parametrize("bits", [(8, 2, 4), (2, 4, 8), (2, 4, 4)], ids=["T8E2R4", "paper-R8E4T2", "paper-R4E4T2"])
+def test_config1_tiny(bits):
+    _say(f"config 1 tiny, bits(T,E,R)={bits}")
+    res = parity.run_case(parity.case_tiny(0, bits), out_dtypes=(torch.float32, torch.float16))
+    _say(res)
+
+
+@pytest.mark.parametrize("D,dtype,G", [(128, "bf16", 4), (64, "bf16", 8), (128, "f16", 5), (64, "f16", 1)])
+def test_ragged_multi_sequence_multi_layer(D, dtype, G):
+    _say(f"ragged multi-seq D={D} {dtype} G={G}")
+    geom = synth.Geometry(2, 2 * G, 2, D, dtype, (8, 2, 4))
+    wl = synth.bulk_evict_refill("ragged", geom, 5, 4, np.array([300, 17, 1000, 1]), {synth.E: 0.3, synth.R: 0.1, synth.T: 0.05},
+                                 refill_chunk=3)
+    res = parity.run_case(parity.Case(wl), out_dtypes=(torch.float32, torch.bfloat16))
+    _say(res)
+
+
+def test_budgeted_decode_scrambles_slots():
+    _say("config-3-like budgeted decode, scaled down")
+    geom = synth.Geometry(1, 10, 2, 128, "bf16", (8, 2, 4))
+    wl = synth.budgeted_decode("budget-small", geom, 2, 3, 3000, 512, steps_per_call=8)
+    res = parity.run_case(parity.Case(wl))
+    _say(res)
+
+
+def test_sliding_window_layer():
+    _say("sliding window W=128 on layer 1")
+    geom = synth.Geometry(2, 16, 2, 64, "bf16", (8, 2, 4))
+    wl = synth.bulk_evict_refill("window", geom, 9, 3, np.array([700, 90, 2000]), {synth.T: 0.2, synth.E: 0.2, synth.R: 0.2},
+                                 refill_chunk=5, window_of_layer=[0, 128])
+    res = parity.run_case(parity.Case(wl))
+    _say(res)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_quantizer_every_binary16_value_in_range(bits):
+    """all binary16 values in [-8, 8] as group members next to a fixed minimum -8 and maximum 8:
+    codes, scales and zero-points from the device equal the oracle's, byte for byte"""
+    _say(f"exhaustive binary16 quantizer check, {bits} bits")
+    allv = np.arange(65536, dtype=np.uint16).view(np.float16)
+    vals = allv[np.isfinite(allv) & (np.abs(allv.astype(np.float32)) <= 8)]
+    n_grp = (len(vals) + 29) // 30
+    pad = np.zeros(n_grp * 30, dtype=np.float16)
+    pad[:len(vals)] = vals
+    rows = np.empty((n_grp, 32), dtype=np.float16)
+    rows[:, 0], rows[:, 1], rows[:, 2:] = -8, 8, pad.reshape(n_grp, 30)
+    n_tok = (n_grp + 3) // 4                       # D=64, Hkv=2: four groups per token
+    buf = np.zeros((n_tok * 4, 32), dtype=np.float16)
+    buf[:n_grp] = rows
+    k = torch.from_numpy(buf.reshape(n_tok, 2, 64))
+    v = torch.from_numpy(buf[::-1].copy().reshape(n_tok, 2, 64))
+    geom = synth.Geometry(1, 2, 2, 64, "f16", (bits, bits, bits))
+    wl = synth.Workload("exhaustive", geom, 0, 1, [np.ones(n_tok, np.uint8)], [])
+    gc = parity.make_gpu_cache(wl)
+    ob = parity.make_oracle(wl)
+    ts, tp, tc = np.zeros(n_tok, np.int32), np.arange(n_tok, dtype=np.int32), np.ones(n_tok, np.uint8)
+    hg = parity.GpuBackend(gc).append(0, k.cuda(), v.cuda(), ts, tp, tc)
+    ho = ob.append(0, k, v, ts, tp, tc)
+    assert np.array_equal(hg, ho)
+    parity.compare_bookkeeping_full(ob.cache, gc)
+    parity.compare_sequences(ob.cache, gc, [(0, 0, 0)], check_bytes=True)
+
+
+def test_flags_and_degenerate_cases():
+    _say("device-side flags, empty and fully evicted sequences, single token")
+    from paper_2510_01290_amd import binding as B
+    geom = synth.Geometry(1, 8, 2, 64, "f16", (8, 2, 4))
+    wl = synth.Workload("flags", geom, 0, 4, [np.zeros(64, np.uint8)] * 4, [], (0,), np.zeros(4, np.int32))
+    gc = parity.make_gpu_cache(wl, arena_pages=(2, 2, 2), max_pages=4)
+    ob = parity.make_oracle(wl, arena_pages=(2, 2, 2), max_pages=4)
+    gb = parity.GpuBackend(gc)
+    dev = gc.device
+
+    def both(seqs, pos, cls, seed):
+        n = len(seqs)
+        k = synth.normals((seed, 1), 0, n * 2 * 64, "cpu").view(n, 2, 64).to(torch.float16)
+        v = synth.normals((seed, 2), 0, n * 2 * 64, "cpu").view(n, 2, 64).to(torch.float16)
+        a = gb.append(0, k.to(dev), v.to(dev), np.array(seqs), np.array(pos), np.array(cls, dtype=np.uint8))
+        b = ob.append(0, k, v, np.array(seqs), np.array(pos), np.array(cls, dtype=np.uint8))
+        assert np.array_equal(a, b), (a, b)
+        return a
+
+    h0 = both([0] * 40, list(range(40)), [0] * 40, 1)            # type-0 pool (2 pages) runs dry at 32
+    assert (h0[32:] == -1).all()
+    h1 = both([1, 1, 1, 2, 9], [0, 1, 2, 0, 0], [1, 7, 2, 2, 1], 2)   # bad class 7, bad sequence 9
+    assert h1[1] == -1 and h1[4] == -1
+    for seqs, hs in ([[1, 1], [h1[0], h1[0]]], [[1], [ocache.make_handle(2, 3, 0)]], [[2], [h1[3]]], [[7], [0]]):
+        gb.evict(0, np.array(seqs), np.array(hs))
+        ob.evict(0, np.array(seqs), np.array(hs))
+    parity.compare_bookkeeping_full(ob.cache, gc)
+    st = gc.dev_status.cpu().numpy()
+    assert st[0] & B.ST_NOPAGES and st[1] & B.ST_BAD_CLASS and st[1] & B.ST_EVICT_DEAD and st[1] & B.ST_BAD_SLOT
+    assert st[-1] & B.ST_BAD_SEQ
+    # sequence 1 keeps a single live token (class R); sequence 2 is fully evicted; sequence 3 never used
+    wl.q_pos = np.array([39, 2, 0, 0], dtype=np.int32)
+    ref, ref_lse = parity.oracle_attention(ob.cache, wl, 0, [0, 1, 2, 3], [0, 1, 2, 3])
+    for variant in ("fast", "valu"):
+        got, lse = parity.gpu_attention(gc, wl, None, 0, torch.float32, variant, max_ctx_pages=4)
+        assert np.abs(got - ref).max() <= parity.TOL
+        assert not got[2].any() and not got[3].any() and np.all(np.isneginf(lse[2:]))
+        assert np.abs(got[1] - ref[1]).max() <= 1e-6               # one live token: its value row
+        assert np.abs(lse[:2] - ref_lse[:2]).max() <= 1e-3
