@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the ThinKV decode hot path on one MI355X.
+
+A step = one pass of the whole path over one batch: soft-evict one token per sequence,
+quantise-and-append one new token per sequence (reusing freed slots), decode attention for
+every sequence.  Workload: DeepSeek-R1-Distill-Llama-8B-shaped layer (32 query / 8 KV heads,
+head_dim 128, bf16), batch 16, 32,768 live tokens per sequence in 16-token pages at
+T8/R4/E2 bits, built by bulk append, class-wise eviction (30 % of E, 10 % of R) and refill.
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK = 8.0e12
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--ctx", type=int, default=32768, help="live tokens per sequence")
+    ap.add_argument("--batch", type=int, default=16)
+    ap.add_argument("--variant", default="fast", choices=["fast", "valu"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (one MI355X per box); --gpus must be 1")
+
+    import numpy as np
+    import torch
+    from paper_2510_01290_amd import binding as B
+    from paper_2510_01290_amd import synth
+    import backends
+    import parity
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    nsteps = args.steps + args.warmup
+    wl = synth.config_llama8b_layer(seed=1, n_seqs=args.batch, ctx=args.ctx, refill_chunk=64,
+                                    name=f"cfg2-shape B={args.batch} ctx={args.ctx}")
+    g = wl.geom
+    # room for the timed appends
+    arena = tuple(int(x + args.batch * (nsteps // 16 + 2)) for x in backends.arena_need(wl))
+    maxp = backends.max_pages_need(wl) + nsteps // 16 + 2
+    t0 = time.time()
+    gc = parity.make_gpu_cache(wl, arena_pages=arena, max_pages=maxp)
+    gr = synth.ScriptRunner(wl, parity.GpuBackend(gc)).run()
+    torch.cuda.synchronize()
+    build_s = time.time() - t0
+    assert int(gc.dev_status.abs().sum().item()) == 0, "device flags set while building the cache"
+
+    # ---- per-step inputs, resident on the device before timing starts
+    rng = np.random.default_rng(1234)
+    ev_handles = np.empty((nsteps, args.batch), dtype=np.int32)
+    new_cls = np.empty((nsteps, args.batch), dtype=np.uint8)
+    ntok0 = [len(c) for c in wl.classes]
+    for s in range(args.batch):
+        hs = gr.handle[(0, s)]
+        cls = wl.classes[s]
+        # positions still live: never evicted by the build script
+        dead = np.zeros(len(hs), dtype=bool)
+        for op in wl.ops:
+            if isinstance(op, synth.Evict):
+                dead[op.pos[op.seqs == s]] = True
+        cand = np.flatnonzero((~dead) & (cls == synth.E))
+        ev_handles[:, s] = hs[rng.choice(cand, size=nsteps, replace=False)]
+        new_cls[:, s] = synth.thought_classes(rng, nsteps)[0]
+    ev_seq = torch.arange(args.batch, dtype=torch.int32, device=dev)
+    ev_h = torch.from_numpy(ev_handles).to(dev)
+    t_cls = torch.from_numpy(new_cls).to(dev)
+    t_pos = torch.stack([torch.arange(ntok0[s], ntok0[s] + nsteps, dtype=torch.int32) for s in range(args.batch)], 1).contiguous().to(dev)
+    k_new = torch.stack([synth.kv_rows(wl.seed, 0, s, 0, ntok0[s], ntok0[s] + nsteps, g, dev) for s in range(args.batch)], 1).contiguous()
+    v_new = torch.stack([synth.kv_rows(wl.seed, 0, s, 1, ntok0[s], ntok0[s] + nsteps, g, dev) for s in range(args.batch)], 1).contiguous()
+    q_all = torch.stack([torch.stack([synth.query_rows(wl.seed, 0, s, st, g, dev) for s in range(args.batch)]) for st in range(nsteps)]).contiguous()
+    out = torch.empty((args.batch, g.n_q_heads, g.head_dim), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty((args.batch, g.n_q_heads), dtype=torch.float32, device=dev)
+    h_out = torch.empty(args.batch, dtype=torch.int32, device=dev)
+    max_ctx_pages = int(gc.n_pages[:, 0].sum(-1).max().item()) + nsteps // 16 + 3
+    scale = g.head_dim ** -0.5
+    decode = B.thinkv_decode_attention if args.variant == "fast" else B.thinkv_decode_attention_valu
+
+    def step(i, ev=None):
+        B.thinkv_evict(gc, 0, ev_seq, ev_h[i])
+        B.thinkv_append_quantized(gc, 0, k_new[i], v_new[i], ev_seq, t_pos[i], t_cls[i], h_out)
+        if ev is not None:
+            ev[0].record()
+        decode(gc, 0, q_all[i], out, lse, ev_seq, t_pos[i], 0, scale, max_ctx_pages)
+        if ev is not None:
+            ev[1].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        step(args.warmup + i, evs[i])
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = e0.elapsed_time(e1) / args.steps
+    attn_ms = np.array([a.elapsed_time(b) for a, b in evs])
+    assert int(gc.dev_status.abs().sum().item()) == 0, "device flags set during the timed steps"
+
+    # ---- algorithmic bytes of one step (from the tables as they stand after the run)
+    live_by_class = []
+    for c in range(3):
+        m = (gc.page_mask[c][:gc.arena_pages[c]] & 0xFFFF).cpu().numpy().astype(np.uint16)
+        live_by_class.append(int(np.unpackbits(m.view(np.uint8)).sum()))
+    pages_visited = int(gc.n_pages[:, 0].sum().item())
+    H, D, Hq = g.n_kv_heads, g.head_dim, g.n_q_heads
+    kv_bytes = sum(n * H * 2 * (D * b // 8 + D // 32 * 4) for n, b in zip(live_by_class, g.bits_of_class))
+    attn_bytes = kv_bytes + pages_visited * 8 + args.batch * Hq * D * (2 + 2)
+    append_bytes = args.batch * (2 * H * D * 2 + H * 2 * (D * 4 // 8 + D // 32 * 4) + 12)
+    step_bytes = attn_bytes + append_bytes + args.batch * 12
+    attn_s = float(attn_ms.mean()) * 1e-3
+    achieved = attn_bytes / attn_s / 1e9
+    line = {
+        "metric": "hybrid-quant paged decode attention, algorithmic HBM GB/s of one decode step at 32k ctx",
+        "value": step_bytes / (ms_step * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "us_per_step": ms_step * 1e3, "attn_us_mean": float(attn_ms.mean() * 1e3), "attn_us_min": float(attn_ms.min() * 1e3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 codes x f16 q on MFMA, f32 accumulate" if args.variant == "fast" else "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name + " (R1-Llama-8B layer: 32 q / 8 kv heads, head_dim 128, bf16; T8/R4/E2, 30% E + 10% R evicted and refilled)",
+                   "batch": args.batch, "live_tokens_per_seq": int(sum(live_by_class) / args.batch), "page_size": 16,
+                   "live_by_class_TER": live_by_class, "kernel": args.variant, "build_seconds": round(build_s, 1),
+                   "step": "evict 1 + append 1 + decode attention, per sequence"},
+        "roofline": {"bound": "hbm", "kernel": "decode attention (split-K kernel + merge)", "achieved": achieved, "peak": HBM_PEAK / 1e9,
+                     "unit": "GB/s", "frac": achieved * 1e9 / HBM_PEAK, "traffic": None, "algorithmic_bytes_per_launch": attn_bytes},
+        "host_wall_ms_per_step": wall / args.steps * 1e3,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl, args, nsteps, ev_handles, new_cls, np, torch, synth, parity)
+    print(json.dumps(line))
+
+
+def cpu_baseline(wl, args, nsteps, ev_handles, new_cls, np, torch, synth, parity):
+    """The oracle as it stands, timed on this machine's host cores on ONE sequence of the same
+    workload (sequence 0: its full build is replayed untimed, then whole steps are timed)."""
+    from oracle import attention as oattn
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = 1
+    g = wl.geom
+    ob = parity.make_oracle(wl, max_seqs=1, arena_pages=tuple(int(x) + 8 for x in parity.backends.arena_need(wl)),
+                            max_pages=parity.backends.max_pages_need(wl) + 8)
+    synth.ScriptRunner(wl, ob, seqs=[0]).run()
+    oc = ob.cache
+    n0 = len(wl.classes[0])
+    cpu = torch.device("cpu")
+    k = synth.kv_rows(wl.seed, 0, 0, 0, n0, n0 + nsteps, g, cpu).float().numpy()
+    v = synth.kv_rows(wl.seed, 0, 0, 1, n0, n0 + nsteps, g, cpu).float().numpy()
+    t0 = time.perf_counter()
+    done = 0
+    live = 0
+    while done < nsteps and (done < 1 or time.perf_counter() - t0 < args.cpu_seconds):
+        i = done
+        oc.evict_slots(0, [0], [ev_handles[i, 0]])
+        oc.append(0, k[i:i + 1], v[i:i + 1], [0], [n0 + i], [new_cls[i, 0]])
+        q = synth.query_rows(wl.seed, 0, 0, i, g, cpu).float().numpy().astype(np.float64)[None]
+        oattn.decode_attention(oc, 0, q, [0], [n0 + i], 0, g.head_dim ** -0.5)
+        live = oc.stored_bytes_live(0, 0)
+        done += 1
+    dt = time.perf_counter() - t0
+    return {"value": live * done / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "seconds_per_sequence_step": dt / done,
+            "sample": f"{done} whole steps (evict 1, append 1, binary64 attention) of sequence 0 of the same workload "
+                      f"({int(oc.n_live[0, 0])} live tokens); a batch step costs {args.batch}x this"}
+
+
+if __name__ == "__main__":
+    main()

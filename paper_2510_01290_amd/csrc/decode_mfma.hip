@@ -1,6 +1,451 @@
-// placeholder until the MFMA kernel lands
+// Decode attention on the matrix cores (gfx950).
+//
+// The affine dequantisation is distributed over the dot products so that the matrix cores
+// only ever see exact operands:
+//
+//   scores   q.k^_t = sum_g [ s_K(t,g) * (sum_{i in g} q_i c_K(t,i)) + zp_K(t,g) * (sum_{i in g} q_i) ]
+//   values   o_c    = sum_t [ (p_t s_V(t,g(c))) * c_V(t,c) ]  +  sum_t p_t zp_V(t,g(c))
+//
+// The integer codes c are fed to v_mfma_f32_16x16x32_f16 as binary16 numbers without any
+// conversion: a b-bit field masked in place inside a 16-bit half IS the binary16 (sub)normal
+// c * 2^(position-24); the power of two is folded into the query (for K) or into the output
+// scale (for V).  A quantisation group is 32 channels = the K extent of one MFMA, so group
+// scales multiply whole MFMA results in binary32.  Scores are computed transposed
+// (tokens x heads) so that their register layout is already the B-operand layout of the PV
+// product; the 16 MFMA columns carry the G query heads of the group, a duplicate of them
+// that takes the low half of a two-term binary16 split of p*s_V (22 significant bits), and
+// padding.  Per-token scales reach the lanes that need them through DPP row broadcasts.
+//
+// One workgroup of four waves per (query, kv-head, split); a wave walks page pairs of its
+// share, class by class (so the bit width is a compile-time constant of the inner loop);
+// the four waves are merged through LDS into one partial (m, l, acc) per query head.
 #include "decode_common.h"
+
 namespace thinkv {
-int decode_mfma_supported(const thinkv_config&) { return 0; }
-int launch_decode_mfma(const thinkv_view&, const DecodeArgs&, hipStream_t) { return THINKV_E_UNSUPPORTED; }
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef float float2v __attribute__((ext_vector_type(2)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+
+union H8 {
+  half8 h;
+  uint32_t u[4];
+};
+
+template <int N>
+__device__ __forceinline__ float bcast_row(float v) {
+  // value of lane N of this lane's row of 16
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x150 + N, 0xf, 0xf, false));
+}
+
+__device__ __forceinline__ uint32_t pack_rne(float a, float b) {
+  float2v f = {a, b};
+  half2v h = __builtin_convertvector(f, half2v);
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+__device__ __forceinline__ float half_lo(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u & 0xFFFFu)); }
+__device__ __forceinline__ float half_hi(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u >> 16)); }
+
+// Field geometry of a b-bit layout: FPH fields per 16-bit half-word.  The matrix core adds the
+// products of one instruction in a fixed-width window below the largest *nominal* product
+// exponent, and a subnormal operand keeps its nominal exponent (2^-14) however many leading
+// zeros it has -- so a code left at the bottom of the half-word would cost up to ten bits of the
+// sum.  Every field is therefore moved, by one shift shared with its neighbour field, to sit
+// just under bit 11 (offset OMIN or OMIN + BITS), and only the residual 2^REL is folded into
+// the other operand.  8-bit codes fill the low byte as they are.
+template <int BITS>
+struct Fld {
+  static constexpr int FPH = 16 / BITS;
+  static constexpr uint32_t MASK = ((1u << BITS) - 1u) * 0x00010001u;
+  static constexpr int OMIN = BITS == 2 ? 7 : (BITS == 4 ? 3 : 0);
+  __device__ static constexpr int rel_of(int f) { return BITS == 8 ? 0 : BITS * ((f % FPH) & 1); }
+  // operand register (two codes: low/high half) for field f of the chunk words w[]
+  __device__ static __forceinline__ uint32_t get(const uint32_t* w, int f) {
+    const int word = f / FPH, pos = f % FPH;
+    const uint32_t x = w[word];
+    if constexpr (BITS == 8) {
+      return (pos == 0 ? x : (x >> 8)) & MASK;
+    } else {
+      // field pair (pos & ~1, pos | 1) starts at bit BITS*(pos & ~1); bring it to bit OMIN
+      const int from = BITS * (pos & ~1);
+      const uint32_t y = from <= OMIN ? (x << (OMIN - from)) : (x >> (from - OMIN));
+      return y & (MASK << (OMIN + BITS * (pos & 1)));
+    }
+  }
+};
+
+template <int D, int BITS>
+struct PageRegs {
+  static constexpr int CW = (D / 32) * BITS / 4;  // chunk dwords
+  uint32_t kw[CW], vw[CW];
+  uint32_t kmeta, vmeta;
+};
+
+template <int D, int BITS>
+__device__ __forceinline__ void load_page(PageRegs<D, BITS>& r, const uint8_t* blk, int lane, int meta_idx) {
+  constexpr int CW = PageRegs<D, BITS>::CW;
+  const BlockGeom g = block_geom(BITS, D);
+  const uint32_t* kc = (const uint32_t*)(blk + g.k_codes) + lane * CW;
+  const uint32_t* vc = (const uint32_t*)(blk + g.v_codes) + lane * CW;
+  if constexpr (CW == 1) {
+    r.kw[0] = kc[0];
+    r.vw[0] = vc[0];
+  } else if constexpr (CW == 2) {
+    const uint2 a = *(const uint2*)kc, b = *(const uint2*)vc;
+    r.kw[0] = a.x; r.kw[1] = a.y;
+    r.vw[0] = b.x; r.vw[1] = b.y;
+  } else {
+#pragma unroll
+    for (int i = 0; i < CW; i += 4) {
+      const uint4 a = *(const uint4*)(kc + i), b = *(const uint4*)(vc + i);
+      r.kw[i] = a.x; r.kw[i + 1] = a.y; r.kw[i + 2] = a.z; r.kw[i + 3] = a.w;
+      r.vw[i] = b.x; r.vw[i + 1] = b.y; r.vw[i + 2] = b.z; r.vw[i + 3] = b.w;
+    }
+  }
+  r.kmeta = ((const uint32_t*)(blk + g.k_meta))[meta_idx];
+  r.vmeta = ((const uint32_t*)(blk + g.v_meta))[meta_idx];
+}
+
+template <int D>
+struct WaveState {
+  static constexpr int NG = D / 32, NM = D / 16;
+  float4v o[NM];   // o[mb][r]: channel 16*mb + 4*q + r, column n
+  float ozp[NG];   // zero-point part of the output, this lane's own tokens only
+  float m, l;      // running maximum (log2 domain) of column n; partial sum of p over own tokens
+};
+
+// One class (bit width) of one wave's share: pages tab[p0 + 2*wave_stride ...).
+template <int D, int BITS, int G>
+__device__ __forceinline__ void run_class(WaveState<D>& st, const thinkv_view& v, const DecodeArgs& a, int cls, const int32_t* tab,
+                                          int p0, int p1, int wave, int hkv, const _Float16* s_q, const float* s_qsum, int qpos) {
+  constexpr int NG = D / 32, NM = D / 16;
+  using F = Fld<BITS>;
+  const int lane = threadIdx.x & 63;
+  const int qd = lane >> 4, n = lane & 15;     // row group (tokens 4qd..4qd+3 / k-slots 8qd..8qd+7), column
+  const int H = v.cfg.n_kv_heads;
+  const BlockGeom geo = block_geom(BITS, D);
+  const bool is_lo = n >= G && n < 2 * G;
+  const float alpha = is_lo ? 1.0f : 0.0f;
+
+  // B operand of the score product for this bit width: q of column n, channels (g, 8qd+e),
+  // scaled down by the power of two its code carries
+  H8 bq[NG];
+  float qsum[NG];
+  {
+    const int head = n < G ? n : n - G;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      qsum[g] = n < 2 * G ? s_qsum[head * NG + g] : 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int f = 4 * g + (e >> 1);
+        float x = n < 2 * G ? (float)s_q[head * D + 32 * g + 8 * qd + e] : 0.f;
+        x *= 1.0f / (float)(1 << F::rel_of(f));
+        bq[g].h[e] = (_Float16)x;   // exact: power-of-two scaling of a binary16 value
+      }
+    }
+  }
+
+  const int n_pairs_total = (p1 - p0 + 1) >> 1;
+  for (int pr = wave; pr < n_pairs_total; pr += 4) {
+    const int ia = p0 + 2 * pr, ib = ia + 1;
+    const bool has_b = ib < p1;
+    const int pid_a = tab[ia], pid_b = has_b ? tab[ib] : pid_a;
+    uint32_t live_a = v.page_mask[cls][pid_a] & 0xFFFFu;
+    uint32_t live_b = has_b ? (v.page_mask[cls][pid_b] & 0xFFFFu) : 0u;
+    if (a.window > 0) {
+      // lane (qd, n) looks at slot n of page a (rows 0,1) / page b (rows 2,3)
+      const int pid = qd < 2 ? pid_a : pid_b;
+      const int d = qpos - v.slot_pos[cls][(int64_t)pid * kPage + n];
+      const uint64_t vis = __ballot(d >= 0 && d < a.window);
+      live_a &= (uint32_t)(vis & 0xFFFFull);
+      live_b &= (uint32_t)((vis >> 32) & 0xFFFFull);
+    }
+    if ((live_a | live_b) == 0) continue;
+    const uint8_t* blk_a = v.arena[cls] + ((int64_t)pid_a * H + hkv) * geo.block_bytes;
+    const uint8_t* blk_b = v.arena[cls] + ((int64_t)pid_b * H + hkv) * geo.block_bytes;
+    PageRegs<D, BITS> ra, rb;
+    if constexpr (D == 128) {
+      load_page<D, BITS>(ra, blk_a, lane, lane);
+      load_page<D, BITS>(rb, blk_b, lane, lane);
+    } else {
+      // 32 meta dwords per page: lanes x<8 of every row take page a, x>=8 page b
+      const int mi = 8 * qd + (n & 7);
+      load_page<D, BITS>(ra, blk_a, lane, mi);
+      load_page<D, BITS>(rb, blk_b, lane, mi);
+      if (n >= 8) { ra.kmeta = rb.kmeta; ra.vmeta = rb.vmeta; }
+    }
+    // per-lane converted meta: scale * 2^24 and zero-point, K and V
+    constexpr float KS = (float)(1 << (24 - F::OMIN));   // codes enter the MFMA as c * 2^(OMIN - 24)
+    const float ks_a = half_lo(ra.kmeta) * KS, kz_a = half_hi(ra.kmeta);
+    const float vs_a = half_lo(ra.vmeta), vz_a = half_hi(ra.vmeta);
+    float ks_b = ks_a, kz_b = kz_a, vs_b = vs_a, vz_b = vz_a;
+    if constexpr (D == 128) {
+      ks_b = half_lo(rb.kmeta) * KS; kz_b = half_hi(rb.kmeta);
+      vs_b = half_lo(rb.vmeta); vz_b = half_hi(rb.vmeta);
+    }
+
+    // ---------------- scores: S^T[token][column] per page
+    float sa[4], sb[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) sa[r] = sb[r] = 0.f;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      H8 ka, kb;
+#pragma unroll
+      for (int vv = 0; vv < 4; ++vv) {
+        ka.u[vv] = F::get(ra.kw, 4 * g + vv);
+        kb.u[vv] = F::get(rb.kw, 4 * g + vv);
+      }
+      const float4v z = {0.f, 0.f, 0.f, 0.f};
+      const float4v ya = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka.h, bq[g].h, z, 0, 0, 0);
+      const float4v yb = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb.h, bq[g].h, z, 0, 0, 0);
+      // scale/zero-point of (token 4qd+r, group g) sit in lane 4r+g of this row (D=128),
+      // or lane 8p+2r+g (D=64, p = page)
+#define TKV_SCORE_STEP(R)                                                                              \
+  {                                                                                                    \
+    constexpr int IA = (D == 128) ? (4 * R + GI) : (2 * R + GI);                                        \
+    constexpr int IB = (D == 128) ? (4 * R + GI) : (8 + 2 * R + GI);                                    \
+    sa[R] = fmaf(bcast_row<IA>(ks_a), ya[R], sa[R]);                                                   \
+    sa[R] = fmaf(bcast_row<IA>(kz_a), qsum[g], sa[R]);                                                 \
+    sb[R] = fmaf(bcast_row<IB>(D == 128 ? ks_b : ks_a), yb[R], sb[R]);                                 \
+    sb[R] = fmaf(bcast_row<IB>(D == 128 ? kz_b : kz_a), qsum[g], sb[R]);                               \
+  }
+#define TKV_SCORE_GROUP(GI_)            \
+  if (g == GI_) {                       \
+    constexpr int GI = GI_;             \
+    TKV_SCORE_STEP(0) TKV_SCORE_STEP(1) TKV_SCORE_STEP(2) TKV_SCORE_STEP(3) \
+  }
+      TKV_SCORE_GROUP(0)
+      TKV_SCORE_GROUP(1)
+      if constexpr (NG > 2) {
+        TKV_SCORE_GROUP(2)
+        TKV_SCORE_GROUP(3)
+      }
+    }
+    // ---------------- mask, online softmax over the 8 scores of this lane
+    float mx = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      sa[r] = ((live_a >> (4 * qd + r)) & 1u) ? sa[r] * a.scale_log2e : -INFINITY;
+      sb[r] = ((live_b >> (4 * qd + r)) & 1u) ? sb[r] * a.scale_log2e : -INFINITY;
+      mx = fmaxf(mx, fmaxf(sa[r], sb[r]));
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(st.m, mx);
+    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+    if (__any(m_new != st.m)) {
+      const float corr = exp2f(st.m - m_safe);
+#pragma unroll
+      for (int mb = 0; mb < NM; ++mb) st.o[mb] *= corr;
+#pragma unroll
+      for (int g = 0; g < NG; ++g) st.ozp[g] *= corr;
+      st.l *= corr;
+      st.m = m_new;
+    }
+    float pa[4], pb[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      pa[r] = exp2f(sa[r] - m_safe);
+      pb[r] = exp2f(sb[r] - m_safe);
+      st.l += pa[r] + pb[r];
+    }
+    // ---------------- values: per group, B = split(p * s_V), A = V codes; zero-point part on the VALU
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      H8 pg;
+#define TKV_P_STEP(R)                                                                                  \
+  {                                                                                                    \
+    constexpr int IA = (D == 128) ? (4 * R + GI) : (2 * R + GI);                                        \
+    constexpr int IB = (D == 128) ? (4 * R + GI) : (8 + 2 * R + GI);                                    \
+    xa[R] = pa[R] * bcast_row<IA>(vs_a);                                                               \
+    xb[R] = pb[R] * bcast_row<IB>(D == 128 ? vs_b : vs_a);                                             \
+    st.ozp[g] = fmaf(pa[R], bcast_row<IA>(vz_a), st.ozp[g]);                                           \
+    st.ozp[g] = fmaf(pb[R], bcast_row<IB>(D == 128 ? vz_b : vz_a), st.ozp[g]);                         \
+  }
+#define TKV_P_GROUP(GI_)                \
+  if (g == GI_) {                       \
+    constexpr int GI = GI_;             \
+    TKV_P_STEP(0) TKV_P_STEP(1) TKV_P_STEP(2) TKV_P_STEP(3) \
+  }
+      float xa[4], xb[4];
+      TKV_P_GROUP(0)
+      TKV_P_GROUP(1)
+      if constexpr (NG > 2) {
+        TKV_P_GROUP(2)
+        TKV_P_GROUP(3)
+      }
+      // two-term split: high columns carry rne16(x), low columns rne16(x - rne16(x))
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const uint32_t ha = pack_rne(xa[2 * i], xa[2 * i + 1]);
+        const uint32_t hb = pack_rne(xb[2 * i], xb[2 * i + 1]);
+        pg.u[i] = pack_rne(fmaf(-alpha, half_lo(ha), xa[2 * i]), fmaf(-alpha, half_hi(ha), xa[2 * i + 1]));
+        pg.u[2 + i] = pack_rne(fmaf(-alpha, half_lo(hb), xb[2 * i]), fmaf(-alpha, half_hi(hb), xb[2 * i + 1]));
+      }
+#pragma unroll
+      for (int mm = 0; mm < 2; ++mm) {
+        const int mb = 2 * g + mm;
+        H8 va;
+        // k-slots 8qd+e: e<4 page a slots 4qd+e, e>=4 page b; field f = u*NM + mb holds slots (2u, 2u+1)
+        va.u[0] = F::get(ra.vw, 0 * NM + mb);
+        va.u[1] = F::get(ra.vw, 1 * NM + mb);
+        va.u[2] = F::get(rb.vw, 0 * NM + mb);
+        va.u[3] = F::get(rb.vw, 1 * NM + mb);
+        st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, pg.h, st.o[mb], 0, 0, 0);
+      }
+    }
+  }
+#undef TKV_SCORE_STEP
+#undef TKV_SCORE_GROUP
+#undef TKV_P_STEP
+#undef TKV_P_GROUP
+}
+
+template <int D, int G>
+__global__ __launch_bounds__(256) void decode_mfma_kernel(thinkv_view v, DecodeArgs a) {
+  constexpr int NG = D / 32, NM = D / 16;
+  const thinkv_config& c = v.cfg;
+  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int Hq = c.n_q_heads;
+  const int seq = a.seq_ids[b];
+  __shared__ _Float16 s_q[G * D];
+  __shared__ float s_qsum[G * NG];
+  __shared__ float s_m[4][G], s_l[4][G];
+  __shared__ float s_acc[4][G][D];
+
+  int np[3], np_total = 0;
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    np[k] = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
+    np_total += np[k];
+  }
+  const int ns = n_split_of(np_total, a.pages_per_item, a.max_split);
+  if (split >= ns) return;
+  for (int i = tid; i < G * D; i += 256)
+    s_q[i] = (_Float16)load_as_f32(a.q, ((int64_t)b * Hq + hkv * G) * D + i, a.q_dtype);
+  __syncthreads();
+  if (tid < G * NG) {
+    float s = 0.f;
+    for (int i = 0; i < 32; ++i) s += (float)s_q[(tid / NG) * D + 32 * (tid % NG) + i];
+    s_qsum[tid] = s;
+  }
+  __syncthreads();
+
+  WaveState<D> st;
+#pragma unroll
+  for (int mb = 0; mb < NM; ++mb) st.o[mb] = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int g = 0; g < NG; ++g) st.ozp[g] = 0.f;
+  st.m = -INFINITY;
+  st.l = 0.f;
+  const int qpos = a.window > 0 ? a.q_pos[b] : 0;
+  const int qd = lane >> 4, n = lane & 15;
+
+  // The V codes of a class carry a power of two that depends on the bit width; the running
+  // output is kept in units of the current class and re-based at class boundaries.
+  for (int k = 0; k < 3; ++k) {
+    const int bits = c.bits_of_class[k];
+    const int p0 = (int)((int64_t)split * np[k] / ns), p1 = (int)((int64_t)(split + 1) * np[k] / ns);
+    if (p1 <= p0) continue;
+    const int32_t* tab = v.block_table + table_base(c, seq, a.layer, k);
+    // bring o[mb] into this class's units: V codes enter the MFMA as c * 2^(shift(mb) - 24)
+    float pre[NM];
+#pragma unroll
+    for (int mb = 0; mb < NM; ++mb) {
+      const int sh = bits == 2 ? Fld<2>::OMIN + Fld<2>::rel_of(mb) : (bits == 4 ? Fld<4>::OMIN + Fld<4>::rel_of(mb) : 0);
+      pre[mb] = (float)(1 << sh);
+    }
+#pragma unroll
+    for (int mb = 0; mb < NM; ++mb) st.o[mb] *= pre[mb];
+    if (bits == 2)
+      run_class<D, 2, G>(st, v, a, k, tab, p0, p1, wave, hkv, s_q, s_qsum, qpos);
+    else if (bits == 4)
+      run_class<D, 4, G>(st, v, a, k, tab, p0, p1, wave, hkv, s_q, s_qsum, qpos);
+    else
+      run_class<D, 8, G>(st, v, a, k, tab, p0, p1, wave, hkv, s_q, s_qsum, qpos);
+#pragma unroll
+    for (int mb = 0; mb < NM; ++mb) st.o[mb] *= 1.0f / pre[mb];
+  }
+
+  // ---- fold: low-half columns into their heads, row groups for l and ozp, then the four waves
+  float l = st.l;
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+  float ozp[NG];
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    float z = st.ozp[g];
+    z += __shfl_xor(z, 16, 64);
+    z += __shfl_xor(z, 32, 64);
+    ozp[g] = z;
+  }
+#pragma unroll
+  for (int mb = 0; mb < NM; ++mb) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float x = st.o[mb][r];
+      const float lo = __shfl(x, (lane & 48) | ((n + G) & 15), 64);
+      x = (x + lo) * 16777216.f + ozp[mb >> 1];
+      if (n < G) s_acc[wave][n][16 * mb + 4 * qd + r] = x;
+    }
+  }
+  if (qd == 0 && n < G) {
+    s_m[wave][n] = st.m;
+    s_l[wave][n] = l;
+  }
+  __syncthreads();
+  for (int i = tid; i < G * D; i += 256) {
+    const int g = i / D, ch = i % D;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, s_m[w][g]);
+    float L = 0.f, A = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float f = (s_m[w][g] == -INFINITY) ? 0.f : exp2f(s_m[w][g] - M);
+      L += s_l[w][g] * f;
+      A += s_acc[w][g][ch] * f;
+    }
+    float* dst = a.partial + partial_index(a, Hq, D, b, hkv * G + g, split);
+    dst[2 + ch] = A;
+    if (ch == 0) {
+      dst[0] = M;
+      dst[1] = L;
+    }
+  }
+}
+
+int decode_mfma_supported(const thinkv_config& c) {
+  const int G = c.n_q_heads / c.n_kv_heads;
+  return (c.head_dim == 64 || c.head_dim == 128) && G >= 1 && G <= 8;
+}
+
+template <int D>
+static int launch_d(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {
+  const int G = v.cfg.n_q_heads / v.cfg.n_kv_heads;
+  dim3 grid(a.max_split, v.cfg.n_kv_heads, a.B), blk(256);
+  switch (G) {
+    case 1: hipLaunchKernelGGL((decode_mfma_kernel<D, 1>), grid, blk, 0, st, v, a); break;
+    case 2: hipLaunchKernelGGL((decode_mfma_kernel<D, 2>), grid, blk, 0, st, v, a); break;
+    case 3: hipLaunchKernelGGL((decode_mfma_kernel<D, 3>), grid, blk, 0, st, v, a); break;
+    case 4: hipLaunchKernelGGL((decode_mfma_kernel<D, 4>), grid, blk, 0, st, v, a); break;
+    case 5: hipLaunchKernelGGL((decode_mfma_kernel<D, 5>), grid, blk, 0, st, v, a); break;
+    case 6: hipLaunchKernelGGL((decode_mfma_kernel<D, 6>), grid, blk, 0, st, v, a); break;
+    case 7: hipLaunchKernelGGL((decode_mfma_kernel<D, 7>), grid, blk, 0, st, v, a); break;
+    case 8: hipLaunchKernelGGL((decode_mfma_kernel<D, 8>), grid, blk, 0, st, v, a); break;
+    default: return THINKV_E_SHAPE;
+  }
+  return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
+}
+
+int launch_decode_mfma(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {
+  return v.cfg.head_dim == 128 ? launch_d<128>(v, a, st) : launch_d<64>(v, a, st);
+}
+
 }  // namespace thinkv
