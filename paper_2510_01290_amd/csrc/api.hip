@@ -15,7 +15,7 @@ int launch_decode_merge(const thinkv_view& v, const DecodeArgs& a, hipStream_t s
 int decode_mfma_supported(const thinkv_config& c);
 
 constexpr int kPagesPerItemSimple = 64;
-constexpr int kPagesPerItemMfma = 32;
+constexpr int kPagesPerItemMfma = 128;
 
 static int check_config(const thinkv_config* c) {
   if (!c) return THINKV_E_INVALID_ARG;

@@ -117,24 +117,53 @@ struct WaveState {
   float m, l;      // running maximum (log2 domain) of column n; partial sum of p over own tokens
 };
 
-// One class (bit width) of one wave's share: pages tab[p0 + 2*wave_stride ...).
-template <int D, int BITS, int G>
-__device__ __forceinline__ void run_class(WaveState<D>& st, const thinkv_view& v, const DecodeArgs& a, int cls, const int32_t* tab,
-                                          int p0, int p1, int wave, int hkv, const _Float16* s_q, const float* s_qsum, int qpos) {
-  constexpr int NG = D / 32, NM = D / 16;
-  using F = Fld<BITS>;
-  const int lane = threadIdx.x & 63;
-  const int qd = lane >> 4, n = lane & 15;     // row group (tokens 4qd..4qd+3 / k-slots 8qd..8qd+7), column
-  const int H = v.cfg.n_kv_heads;
-  const BlockGeom geo = block_geom(BITS, D);
-  const bool is_lo = n >= G && n < 2 * G;
-  const float alpha = is_lo ? 1.0f : 0.0f;
+// maximum over the four lanes that share a column (lane ^ 16, lane ^ 32), on the VALU
+__device__ __forceinline__ float col_max(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  auto r16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);   // rows (0,1) and (2,3) exchanged
+  x = fmaxf(__builtin_bit_cast(float, (uint32_t)r16[0]), __builtin_bit_cast(float, (uint32_t)r16[1]));
+  const uint32_t w = __builtin_bit_cast(uint32_t, x);
+  auto r32 = __builtin_amdgcn_permlane32_swap(w, w, false, false);   // halves exchanged
+  return fmaxf(__builtin_bit_cast(float, (uint32_t)r32[0]), __builtin_bit_cast(float, (uint32_t)r32[1]));
+}
 
-  // B operand of the score product for this bit width: q of column n, channels (g, 8qd+e),
-  // scaled down by the power of two its code carries
+struct PairIds {
+  int pid_a, pid_b;
+  uint32_t live_a, live_b;
+};
+
+template <int D, int BITS>
+struct PairRegs {
+  PageRegs<D, BITS> a, b;
+};
+
+// One class (bit width) of one wave's share of the item: page pairs wave, wave+4, ... of
+// tab[p0..p1).  Page ids and live masks are fetched two pairs ahead (scalar loads), packed
+// pages one pair ahead (vector loads into the buffer that is not being consumed).
+template <int D, int BITS, int G>
+struct ClassRunner {
+  static constexpr int NG = D / 32, NM = D / 16;
+  using F = Fld<BITS>;
+  WaveState<D>& st;
+  const thinkv_view& v;
+  const DecodeArgs& a;
+  const int cls, hkv, qpos;
+  const int32_t* tab;
+  const int p0, p1, wave;
+  int lane, qd, n;
+  float alpha;
   H8 bq[NG];
   float qsum[NG];
-  {
+
+  __device__ __forceinline__ ClassRunner(WaveState<D>& st_, const thinkv_view& v_, const DecodeArgs& a_, int cls_, const int32_t* tab_,
+                                         int p0_, int p1_, int wave_, int hkv_, const _Float16* s_q, const float* s_qsum, int qpos_)
+      : st(st_), v(v_), a(a_), cls(cls_), hkv(hkv_), qpos(qpos_), tab(tab_), p0(p0_), p1(p1_), wave(wave_) {
+    lane = threadIdx.x & 63;
+    qd = lane >> 4;
+    n = lane & 15;
+    alpha = (n >= G && n < 2 * G) ? 1.0f : 0.0f;
+    // B operand of the score product for this bit width: q of column n, channels (g, 8qd+e),
+    // scaled down by the residual power of two its code carries
     const int head = n < G ? n : n - G;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
@@ -149,39 +178,55 @@ __device__ __forceinline__ void run_class(WaveState<D>& st, const thinkv_view& v
     }
   }
 
-  const int n_pairs_total = (p1 - p0 + 1) >> 1;
-  for (int pr = wave; pr < n_pairs_total; pr += 4) {
-    const int ia = p0 + 2 * pr, ib = ia + 1;
+  __device__ __forceinline__ PairIds fetch_ids(int j) const {   // j-th pair of this wave
+    const int ia = p0 + 2 * (wave + 4 * j), ib = ia + 1;
     const bool has_b = ib < p1;
-    const int pid_a = tab[ia], pid_b = has_b ? tab[ib] : pid_a;
-    uint32_t live_a = v.page_mask[cls][pid_a] & 0xFFFFu;
-    uint32_t live_b = has_b ? (v.page_mask[cls][pid_b] & 0xFFFFu) : 0u;
+    PairIds id;
+    id.pid_a = tab[ia];
+    id.pid_b = has_b ? tab[ib] : id.pid_a;
+    id.live_a = v.page_mask[cls][id.pid_a] & 0xFFFFu;
+    id.live_b = has_b ? (v.page_mask[cls][id.pid_b] & 0xFFFFu) : 0u;
     if (a.window > 0) {
       // lane (qd, n) looks at slot n of page a (rows 0,1) / page b (rows 2,3)
-      const int pid = qd < 2 ? pid_a : pid_b;
+      const int pid = qd < 2 ? id.pid_a : id.pid_b;
       const int d = qpos - v.slot_pos[cls][(int64_t)pid * kPage + n];
       const uint64_t vis = __ballot(d >= 0 && d < a.window);
-      live_a &= (uint32_t)(vis & 0xFFFFull);
-      live_b &= (uint32_t)((vis >> 32) & 0xFFFFull);
+      id.live_a &= (uint32_t)(vis & 0xFFFFull);
+      id.live_b &= (uint32_t)((vis >> 32) & 0xFFFFull);
     }
-    if ((live_a | live_b) == 0) continue;
-    const uint8_t* blk_a = v.arena[cls] + ((int64_t)pid_a * H + hkv) * geo.block_bytes;
-    const uint8_t* blk_b = v.arena[cls] + ((int64_t)pid_b * H + hkv) * geo.block_bytes;
-    PageRegs<D, BITS> ra, rb;
+    return id;
+  }
+
+  __device__ __forceinline__ void issue_loads(PairRegs<D, BITS>& r, const PairIds& id) const {
+    if ((id.live_a | id.live_b) == 0) return;
+    const int H = v.cfg.n_kv_heads;
+    const BlockGeom geo = block_geom(BITS, D);
+    const uint8_t* blk_a = v.arena[cls] + ((int64_t)id.pid_a * H + hkv) * geo.block_bytes;
+    const uint8_t* blk_b = v.arena[cls] + ((int64_t)id.pid_b * H + hkv) * geo.block_bytes;
     if constexpr (D == 128) {
-      load_page<D, BITS>(ra, blk_a, lane, lane);
-      load_page<D, BITS>(rb, blk_b, lane, lane);
+      load_page<D, BITS>(r.a, blk_a, lane, lane);
+      load_page<D, BITS>(r.b, blk_b, lane, lane);
     } else {
       // 32 meta dwords per page: lanes x<8 of every row take page a, x>=8 page b
       const int mi = 8 * qd + (n & 7);
-      load_page<D, BITS>(ra, blk_a, lane, mi);
-      load_page<D, BITS>(rb, blk_b, lane, mi);
-      if (n >= 8) { ra.kmeta = rb.kmeta; ra.vmeta = rb.vmeta; }
+      load_page<D, BITS>(r.a, blk_a, lane, mi);
+      load_page<D, BITS>(r.b, blk_b, lane, mi);
     }
-    // per-lane converted meta: scale * 2^24 and zero-point, K and V
+  }
+
+  __device__ __forceinline__ void compute(const PairRegs<D, BITS>& r, const PairIds& id) {
+    const uint32_t live_a = id.live_a, live_b = id.live_b;
+    if ((live_a | live_b) == 0) return;
+    const PageRegs<D, BITS>& ra = r.a;
+    const PageRegs<D, BITS>& rb = r.b;
+    uint32_t kma = ra.kmeta, vma = ra.vmeta;
+    if constexpr (D == 64) {
+      if (n >= 8) { kma = rb.kmeta; vma = rb.vmeta; }
+    }
+    // per-lane converted meta: scale (times the power of two the codes lack) and zero-point
     constexpr float KS = (float)(1 << (24 - F::OMIN));   // codes enter the MFMA as c * 2^(OMIN - 24)
-    const float ks_a = half_lo(ra.kmeta) * KS, kz_a = half_hi(ra.kmeta);
-    const float vs_a = half_lo(ra.vmeta), vz_a = half_hi(ra.vmeta);
+    const float ks_a = half_lo(kma) * KS, kz_a = half_hi(kma);
+    const float vs_a = half_lo(vma), vz_a = half_hi(vma);
     float ks_b = ks_a, kz_b = kz_a, vs_b = vs_a, vz_b = vz_a;
     if constexpr (D == 128) {
       ks_b = half_lo(rb.kmeta) * KS; kz_b = half_hi(rb.kmeta);
@@ -191,7 +236,7 @@ __device__ __forceinline__ void run_class(WaveState<D>& st, const thinkv_view& v
     // ---------------- scores: S^T[token][column] per page
     float sa[4], sb[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) sa[r] = sb[r] = 0.f;
+    for (int r4 = 0; r4 < 4; ++r4) sa[r4] = sb[r4] = 0.f;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
       H8 ka, kb;
@@ -228,18 +273,26 @@ __device__ __forceinline__ void run_class(WaveState<D>& st, const thinkv_view& v
     }
     // ---------------- mask, online softmax over the 8 scores of this lane
     float mx = -INFINITY;
+    if ((live_a & live_b) == 0xFFFFu) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      sa[r] = ((live_a >> (4 * qd + r)) & 1u) ? sa[r] * a.scale_log2e : -INFINITY;
-      sb[r] = ((live_b >> (4 * qd + r)) & 1u) ? sb[r] * a.scale_log2e : -INFINITY;
-      mx = fmaxf(mx, fmaxf(sa[r], sb[r]));
+      for (int r4 = 0; r4 < 4; ++r4) {
+        sa[r4] *= a.scale_log2e;
+        sb[r4] *= a.scale_log2e;
+        mx = fmaxf(mx, fmaxf(sa[r4], sb[r4]));
+      }
+    } else {
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        sa[r4] = ((live_a >> (4 * qd + r4)) & 1u) ? sa[r4] * a.scale_log2e : -INFINITY;
+        sb[r4] = ((live_b >> (4 * qd + r4)) & 1u) ? sb[r4] * a.scale_log2e : -INFINITY;
+        mx = fmaxf(mx, fmaxf(sa[r4], sb[r4]));
+      }
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx = col_max(mx);
     const float m_new = fmaxf(st.m, mx);
     const float m_safe = m_new == -INFINITY ? 0.f : m_new;
     if (__any(m_new != st.m)) {
-      const float corr = exp2f(st.m - m_safe);
+      const float corr = __builtin_amdgcn_exp2f(st.m - m_safe);
 #pragma unroll
       for (int mb = 0; mb < NM; ++mb) st.o[mb] *= corr;
 #pragma unroll
@@ -249,10 +302,10 @@ __device__ __forceinline__ void run_class(WaveState<D>& st, const thinkv_view& v
     }
     float pa[4], pb[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      pa[r] = exp2f(sa[r] - m_safe);
-      pb[r] = exp2f(sb[r] - m_safe);
-      st.l += pa[r] + pb[r];
+    for (int r4 = 0; r4 < 4; ++r4) {
+      pa[r4] = __builtin_amdgcn_exp2f(sa[r4] - m_safe);
+      pb[r4] = __builtin_amdgcn_exp2f(sb[r4] - m_safe);
+      st.l += pa[r4] + pb[r4];
     }
     // ---------------- values: per group, B = split(p * s_V), A = V codes; zero-point part on the VALU
 #pragma unroll
@@ -299,11 +352,41 @@ __device__ __forceinline__ void run_class(WaveState<D>& st, const thinkv_view& v
         st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, pg.h, st.o[mb], 0, 0, 0);
       }
     }
-  }
 #undef TKV_SCORE_STEP
 #undef TKV_SCORE_GROUP
 #undef TKV_P_STEP
 #undef TKV_P_GROUP
+  }
+
+  __device__ __forceinline__ void run() {
+    const int n_pairs_total = (p1 - p0 + 1) >> 1;
+    const int n_my = n_pairs_total > wave ? (n_pairs_total - wave + 3) >> 2 : 0;
+    if (n_my == 0) return;
+    PairRegs<D, BITS> r0, r1;
+    PairIds id0 = fetch_ids(0);
+    PairIds id1 = n_my > 1 ? fetch_ids(1) : id0;
+    issue_loads(r0, id0);
+    for (int j = 0; j < n_my; j += 2) {
+      const bool more1 = j + 1 < n_my, more2 = j + 2 < n_my;
+      PairIds id2 = more2 ? fetch_ids(j + 2) : id0;
+      if (more1) issue_loads(r1, id1);
+      compute(r0, id0);
+      PairIds id3 = j + 3 < n_my ? fetch_ids(j + 3) : id0;
+      if (more1) {
+        if (more2) issue_loads(r0, id2);
+        compute(r1, id1);
+      }
+      id0 = id2;
+      id1 = id3;
+    }
+  }
+};
+
+template <int D, int BITS, int G>
+__device__ __forceinline__ void run_class(WaveState<D>& st, const thinkv_view& v, const DecodeArgs& a, int cls, const int32_t* tab,
+                                          int p0, int p1, int wave, int hkv, const _Float16* s_q, const float* s_qsum, int qpos) {
+  ClassRunner<D, BITS, G> cr(st, v, a, cls, tab, p0, p1, wave, hkv, s_q, s_qsum, qpos);
+  cr.run();
 }
 
 template <int D, int G>
@@ -311,7 +394,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(thinkv_view v, DecodeA
   constexpr int NG = D / 32, NM = D / 16;
   const thinkv_config& c = v.cfg;
   const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int Hq = c.n_q_heads;
   const int seq = a.seq_ids[b];
   __shared__ _Float16 s_q[G * D];
