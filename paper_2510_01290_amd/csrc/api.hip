@@ -1,5 +1,6 @@
 // C ABI entry points: argument checks and kernel dispatch.  No allocation, no global state,
 // no synchronisation.
+#include <cstdlib>
 #include "decode_common.h"
 
 namespace thinkv {
@@ -14,8 +15,6 @@ int launch_decode_mfma(const thinkv_view& v, const DecodeArgs& a, hipStream_t st
 int launch_decode_merge(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
 int decode_mfma_supported(const thinkv_config& c);
 
-constexpr int kPagesPerItemSimple = 64;
-constexpr int kPagesPerItemMfma = 128;
 
 static int check_config(const thinkv_config* c) {
   if (!c) return THINKV_E_INVALID_ARG;
@@ -43,9 +42,17 @@ static int check_view(const thinkv_view* v) {
   return THINKV_OK;
 }
 
-static int max_split_for(int max_ctx_pages, int pages_per_item) {
-  int s = (max_ctx_pages + pages_per_item - 1) / pages_per_item;
-  return s < 1 ? 1 : s;
+// pages per item of each class, and an upper bound on the items of a sequence that holds at
+// most max_ctx_pages pages (all in the class with the smallest items, plus one ragged item
+// per class)
+static int split_bound(const thinkv_config& c, int max_ctx_pages, int ppi[3]) {
+  int mn = 1 << 30;
+  for (int k = 0; k < 3; ++k) {
+    ppi[k] = pages_per_item_for_bits(c.bits_of_class[k]);
+    if (const char* e = getenv("THINKV_PPI_MUL4")) ppi[k] = ppi[k] * atoi(e) / 4;  // dev knob
+    mn = ppi[k] < mn ? ppi[k] : mn;
+  }
+  return max_ctx_pages / mn + 3;
 }
 
 static int decode_common(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
@@ -73,8 +80,7 @@ static int decode_common(const thinkv_view* view, int32_t layer, const void* q, 
   a.window = window;
   a.q_dtype = q_dtype;
   a.out_dtype = out_dtype;
-  a.pages_per_item = fast ? kPagesPerItemMfma : kPagesPerItemSimple;
-  a.max_split = max_split_for(max_ctx_pages, a.pages_per_item);
+  a.max_split = split_bound(view->cfg, max_ctx_pages, a.ppi);
   a.scale_log2e = softmax_scale * 1.4426950408889634f;
   hipStream_t st = (hipStream_t)stream;
   rc = fast ? launch_decode_mfma(*view, a, st) : launch_decode_simple(*view, a, st);
@@ -104,8 +110,8 @@ size_t thinkv_append_workspace_bytes(const thinkv_config* cfg, int32_t n_tok) {
 
 size_t thinkv_decode_workspace_bytes(const thinkv_config* cfg, int32_t B, int32_t max_ctx_pages) {
   if (check_config(cfg) || B < 0 || max_ctx_pages < 0) return 0;
-  // sized for the finer of the two split granularities
-  const int ms = max_split_for(max_ctx_pages, kPagesPerItemMfma < kPagesPerItemSimple ? kPagesPerItemMfma : kPagesPerItemSimple);
+  int ppi[3];
+  const int ms = split_bound(*cfg, max_ctx_pages, ppi);
   return (size_t)(B > 0 ? B : 1) * cfg->n_q_heads * ms * (cfg->head_dim + 2) * sizeof(float);
 }
 

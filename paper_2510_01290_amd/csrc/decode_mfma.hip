@@ -7,7 +7,7 @@
 //   values   o_c    = sum_t [ (p_t s_V(t,g(c))) * c_V(t,c) ]  +  sum_t p_t zp_V(t,g(c))
 //
 // The integer codes c are fed to v_mfma_f32_16x16x32_f16 as binary16 numbers without any
-// conversion: a b-bit field masked in place inside a 16-bit half IS the binary16 (sub)normal
+// conversion: a b-bit field masked inside a 16-bit half IS the binary16 (sub)normal
 // c * 2^(position-24); the power of two is folded into the query (for K) or into the output
 // scale (for V).  A quantisation group is 32 channels = the K extent of one MFMA, so group
 // scales multiply whole MFMA results in binary32.  Scores are computed transposed
@@ -16,9 +16,10 @@
 // that takes the low half of a two-term binary16 split of p*s_V (22 significant bits), and
 // padding.  Per-token scales reach the lanes that need them through DPP row broadcasts.
 //
-// One workgroup of four waves per (query, kv-head, split); a wave walks page pairs of its
-// share, class by class (so the bit width is a compile-time constant of the inner loop);
-// the four waves are merged through LDS into one partial (m, l, acc) per query head.
+// One workgroup of four waves per (query, kv-head, item); an item holds pages of one thought
+// type, so the bit width is a compile-time constant of the inner loop; a wave walks every
+// fourth page pair of the item; the four waves are merged through LDS into one partial
+// (m, l, acc) per query head.
 #include "decode_common.h"
 
 namespace thinkv {
@@ -37,7 +38,7 @@ union H8 {
 template <int N>
 __device__ __forceinline__ float bcast_row(float v) {
   // value of lane N of this lane's row of 16
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x150 + N, 0xf, 0xf, false));
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x150 + N, 0xf, 0xf, true));
 }
 
 __device__ __forceinline__ uint32_t pack_rne(float a, float b) {
@@ -138,8 +139,7 @@ struct PairRegs {
 };
 
 // One class (bit width) of one wave's share of the item: page pairs wave, wave+4, ... of
-// tab[p0..p1).  Page ids and live masks are fetched two pairs ahead (scalar loads), packed
-// pages one pair ahead (vector loads into the buffer that is not being consumed).
+// tab[p0..p1).
 template <int D, int BITS, int G>
 struct ClassRunner {
   static constexpr int NG = D / 32, NM = D / 16;
@@ -176,25 +176,6 @@ struct ClassRunner {
         bq[g].h[e] = (_Float16)x;   // exact: power-of-two scaling of a binary16 value
       }
     }
-  }
-
-  __device__ __forceinline__ PairIds fetch_ids(int j) const {   // j-th pair of this wave
-    const int ia = p0 + 2 * (wave + 4 * j), ib = ia + 1;
-    const bool has_b = ib < p1;
-    PairIds id;
-    id.pid_a = tab[ia];
-    id.pid_b = has_b ? tab[ib] : id.pid_a;
-    id.live_a = v.page_mask[cls][id.pid_a] & 0xFFFFu;
-    id.live_b = has_b ? (v.page_mask[cls][id.pid_b] & 0xFFFFu) : 0u;
-    if (a.window > 0) {
-      // lane (qd, n) looks at slot n of page a (rows 0,1) / page b (rows 2,3)
-      const int pid = qd < 2 ? id.pid_a : id.pid_b;
-      const int d = qpos - v.slot_pos[cls][(int64_t)pid * kPage + n];
-      const uint64_t vis = __ballot(d >= 0 && d < a.window);
-      id.live_a &= (uint32_t)(vis & 0xFFFFull);
-      id.live_b &= (uint32_t)((vis >> 32) & 0xFFFFull);
-    }
-    return id;
   }
 
   __device__ __forceinline__ void issue_loads(PairRegs<D, BITS>& r, const PairIds& id) const {
@@ -358,65 +339,73 @@ struct ClassRunner {
 #undef TKV_P_GROUP
   }
 
+  // Page ids and live masks of up to 64 pages are fetched with one vector load each (lane L
+  // holds page p0 + base + L) and handed to the pair loop through v_readlane, so the loop
+  // itself has no dependent scalar loads.  Occupancy, not software prefetch, hides the
+  // latency of the packed-page loads: each wave has one page pair in flight.
   __device__ __forceinline__ void run() {
-    const int n_pairs_total = (p1 - p0 + 1) >> 1;
-    const int n_my = n_pairs_total > wave ? (n_pairs_total - wave + 3) >> 2 : 0;
-    if (n_my == 0) return;
-    PairRegs<D, BITS> r0, r1;
-    PairIds id0 = fetch_ids(0);
-    PairIds id1 = n_my > 1 ? fetch_ids(1) : id0;
-    issue_loads(r0, id0);
-    for (int j = 0; j < n_my; j += 2) {
-      const bool more1 = j + 1 < n_my, more2 = j + 2 < n_my;
-      PairIds id2 = more2 ? fetch_ids(j + 2) : id0;
-      if (more1) issue_loads(r1, id1);
-      compute(r0, id0);
-      PairIds id3 = j + 3 < n_my ? fetch_ids(j + 3) : id0;
-      if (more1) {
-        if (more2) issue_loads(r0, id2);
-        compute(r1, id1);
+    const int n_pages = p1 - p0;
+    for (int base = 0; base < n_pages; base += 64) {
+      const int cnt = n_pages - base < 64 ? n_pages - base : 64;
+      int vpid = 0;
+      uint32_t vmask = 0;
+      if (lane < cnt) {
+        vpid = tab[p0 + base + lane];
+        vmask = v.page_mask[cls][vpid] & 0xFFFFu;
       }
-      id0 = id2;
-      id1 = id3;
+      if (a.window > 0) {
+        // visibility of the 16 slots of each page: lane L walks the slots of its own page
+        uint32_t vis = 0;
+        if (lane < cnt) {
+          const int32_t* sp = v.slot_pos[cls] + (int64_t)vpid * kPage;
+#pragma unroll
+          for (int t = 0; t < kPage; ++t) {
+            const int d = qpos - sp[t];
+            vis |= (d >= 0 && d < a.window) ? (1u << t) : 0u;
+          }
+        }
+        vmask &= vis;
+      }
+      const int n_pairs = (cnt + 1) >> 1;
+      for (int pr = wave; pr < n_pairs; pr += 4) {
+        PairIds id;
+        id.pid_a = __builtin_amdgcn_readlane(vpid, 2 * pr);
+        id.live_a = __builtin_amdgcn_readlane(vmask, 2 * pr);
+        const int ib = 2 * pr + 1 < cnt ? 2 * pr + 1 : 2 * pr;
+        id.pid_b = __builtin_amdgcn_readlane(vpid, ib);
+        id.live_b = 2 * pr + 1 < cnt ? __builtin_amdgcn_readlane(vmask, ib) : 0u;
+        PairRegs<D, BITS> r;
+        issue_loads(r, id);
+        compute(r, id);
+      }
     }
   }
 };
 
-template <int D, int BITS, int G>
-__device__ __forceinline__ void run_class(WaveState<D>& st, const thinkv_view& v, const DecodeArgs& a, int cls, const int32_t* tab,
-                                          int p0, int p1, int wave, int hkv, const _Float16* s_q, const float* s_qsum, int qpos) {
-  ClassRunner<D, BITS, G> cr(st, v, a, cls, tab, p0, p1, wave, hkv, s_q, s_qsum, qpos);
-  cr.run();
-}
-
 template <int D, int G>
-__global__ __launch_bounds__(256) void decode_mfma_kernel(thinkv_view v, DecodeArgs a) {
+struct ItemLds {
+  _Float16 q[G * D];
+  float qsum[G * (D / 32)];
+  float m[4][G], l[4][G];
+  float acc[4][G][D];
+};
+
+// Everything one workgroup does for one item whose pages hold BITS-bit codes.
+template <int D, int G, int BITS>
+__device__ __forceinline__ void run_item(const thinkv_view& v, const DecodeArgs& a, ItemLds<D, G>& lds, int cls, int item, int ns,
+                                         int np, int split, int hkv, int b, int seq) {
   constexpr int NG = D / 32, NM = D / 16;
+  using F = Fld<BITS>;
   const thinkv_config& c = v.cfg;
-  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int Hq = c.n_q_heads;
-  const int seq = a.seq_ids[b];
-  __shared__ _Float16 s_q[G * D];
-  __shared__ float s_qsum[G * NG];
-  __shared__ float s_m[4][G], s_l[4][G];
-  __shared__ float s_acc[4][G][D];
-
-  int np[3], np_total = 0;
-#pragma unroll
-  for (int k = 0; k < 3; ++k) {
-    np[k] = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
-    np_total += np[k];
-  }
-  const int ns = n_split_of(np_total, a.pages_per_item, a.max_split);
-  if (split >= ns) return;
   for (int i = tid; i < G * D; i += 256)
-    s_q[i] = (_Float16)load_as_f32(a.q, ((int64_t)b * Hq + hkv * G) * D + i, a.q_dtype);
+    lds.q[i] = (_Float16)load_as_f32(a.q, ((int64_t)b * Hq + hkv * G) * D + i, a.q_dtype);
   __syncthreads();
   if (tid < G * NG) {
     float s = 0.f;
-    for (int i = 0; i < 32; ++i) s += (float)s_q[(tid / NG) * D + 32 * (tid % NG) + i];
-    s_qsum[tid] = s;
+    for (int i = 0; i < 32; ++i) s += (float)lds.q[(tid / NG) * D + 32 * (tid % NG) + i];
+    lds.qsum[tid] = s;
   }
   __syncthreads();
 
@@ -429,31 +418,11 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(thinkv_view v, DecodeA
   st.l = 0.f;
   const int qpos = a.window > 0 ? a.q_pos[b] : 0;
   const int qd = lane >> 4, n = lane & 15;
-
-  // The V codes of a class carry a power of two that depends on the bit width; the running
-  // output is kept in units of the current class and re-based at class boundaries.
-  for (int k = 0; k < 3; ++k) {
-    const int bits = c.bits_of_class[k];
-    const int p0 = (int)((int64_t)split * np[k] / ns), p1 = (int)((int64_t)(split + 1) * np[k] / ns);
-    if (p1 <= p0) continue;
-    const int32_t* tab = v.block_table + table_base(c, seq, a.layer, k);
-    // bring o[mb] into this class's units: V codes enter the MFMA as c * 2^(shift(mb) - 24)
-    float pre[NM];
-#pragma unroll
-    for (int mb = 0; mb < NM; ++mb) {
-      const int sh = bits == 2 ? Fld<2>::OMIN + Fld<2>::rel_of(mb) : (bits == 4 ? Fld<4>::OMIN + Fld<4>::rel_of(mb) : 0);
-      pre[mb] = (float)(1 << sh);
-    }
-#pragma unroll
-    for (int mb = 0; mb < NM; ++mb) st.o[mb] *= pre[mb];
-    if (bits == 2)
-      run_class<D, 2, G>(st, v, a, k, tab, p0, p1, wave, hkv, s_q, s_qsum, qpos);
-    else if (bits == 4)
-      run_class<D, 4, G>(st, v, a, k, tab, p0, p1, wave, hkv, s_q, s_qsum, qpos);
-    else
-      run_class<D, 8, G>(st, v, a, k, tab, p0, p1, wave, hkv, s_q, s_qsum, qpos);
-#pragma unroll
-    for (int mb = 0; mb < NM; ++mb) st.o[mb] *= 1.0f / pre[mb];
+  const int p0 = (int)((int64_t)item * np / ns), p1 = (int)((int64_t)(item + 1) * np / ns);
+  const int32_t* tab = v.block_table + table_base(c, seq, a.layer, cls);
+  {
+    ClassRunner<D, BITS, G> cr(st, v, a, cls, tab, p0, p1, wave, hkv, lds.q, lds.qsum, qpos);
+    cr.run();
   }
 
   // ---- fold: low-half columns into their heads, row groups for l and ozp, then the four waves
@@ -470,30 +439,32 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(thinkv_view v, DecodeA
   }
 #pragma unroll
   for (int mb = 0; mb < NM; ++mb) {
+    // V codes entered the MFMA as c * 2^(OMIN + rel(mb) - 24)
+    const float unit = (float)(1 << (24 - F::OMIN - F::rel_of(mb)));
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       float x = st.o[mb][r];
       const float lo = __shfl(x, (lane & 48) | ((n + G) & 15), 64);
-      x = (x + lo) * 16777216.f + ozp[mb >> 1];
-      if (n < G) s_acc[wave][n][16 * mb + 4 * qd + r] = x;
+      x = (x + lo) * unit + ozp[mb >> 1];
+      if (n < G) lds.acc[wave][n][16 * mb + 4 * qd + r] = x;
     }
   }
   if (qd == 0 && n < G) {
-    s_m[wave][n] = st.m;
-    s_l[wave][n] = l;
+    lds.m[wave][n] = st.m;
+    lds.l[wave][n] = l;
   }
   __syncthreads();
   for (int i = tid; i < G * D; i += 256) {
     const int g = i / D, ch = i % D;
     float M = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) M = fmaxf(M, s_m[w][g]);
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, lds.m[w][g]);
     float L = 0.f, A = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float f = (s_m[w][g] == -INFINITY) ? 0.f : exp2f(s_m[w][g] - M);
-      L += s_l[w][g] * f;
-      A += s_acc[w][g][ch] * f;
+      const float f = (lds.m[w][g] == -INFINITY) ? 0.f : exp2f(lds.m[w][g] - M);
+      L += lds.l[w][g] * f;
+      A += lds.acc[w][g][ch] * f;
     }
     float* dst = a.partial + partial_index(a, Hq, D, b, hkv * G + g, split);
     dst[2 + ch] = A;
@@ -502,6 +473,26 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(thinkv_view v, DecodeA
       dst[1] = L;
     }
   }
+}
+
+template <int D, int G>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void decode_mfma_kernel(thinkv_view v, DecodeArgs a) {
+  const thinkv_config& c = v.cfg;
+  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+  const int seq = a.seq_ids[b];
+  __shared__ ItemLds<D, G> lds;
+  int np[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) np[k] = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
+  int cls, item, ns;
+  if (!locate_item(a, np, split, &cls, &item, &ns)) return;
+  const int bits = c.bits_of_class[cls];
+  if (bits == 2)
+    run_item<D, G, 2>(v, a, lds, cls, item, ns, np[cls], split, hkv, b, seq);
+  else if (bits == 4)
+    run_item<D, G, 4>(v, a, lds, cls, item, ns, np[cls], split, hkv, b, seq);
+  else
+    run_item<D, G, 8>(v, a, lds, cls, item, ns, np[cls], split, hkv, b, seq);
 }
 
 int decode_mfma_supported(const thinkv_config& c) {
