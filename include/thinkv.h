@@ -80,9 +80,10 @@ typedef struct {
  *   dev_status      [max_seqs * n_layers + 1] THINKV_ST_* flags
  *
  * Byte layout of one page: n_kv_heads blocks of thinkv_block_bytes(); a block is
- * [K codes: 64 chunks of CB = (head_dim/32)*b bytes][K meta: 16*(head_dim/32) dwords]
- * [V codes: 64 chunks][V meta].  A meta dword (slot*NG + group) holds the binary16 scale in
- * bits 0..15 and the binary16 zero-point in bits 16..31.  Inside a chunk a b-bit code sits at
+ * [K codes: 64 chunks of CB = (head_dim/32)*b bytes][K scale][K zero-point][V codes: 64 chunks]
+ * [V scale][V zero-point]; each scale / zero-point array is 16*NG binary16 (NG = head_dim/32)
+ * indexed slot*NG + group, except the V zero-points, indexed group*16 + slot.
+ * Inside a chunk a b-bit code sits at
  * bit 32*(f / FPH) + 16*h + b*(f % FPH), FPH = 16/b, with
  *   K, slot t, channel c: chunk 16*((c%32)/8) + t, f = 4*(c/32) + (c%8)/2, h = c%2
  *   V, slot t, channel c: chunk 16*(t/4) + c%16,   f = ((t%4)/2)*(head_dim/16) + c/16, h = t%2

@@ -11,11 +11,12 @@ A page holds P = 16 slots; head_dim D in {64,128}; NG = D/32 groups; b in {2,4,8
 Per (page, kv-head) there is one block of four regions, in this order:
 
     K codes : 64 chunks of CB = NG*b bytes          (chunk index L_K)
-    K meta  : 16*NG little-endian dwords             (dword index slot*NG + group)
+    K scale : 16*NG binary16, index slot*NG + group
+    K zp    : 16*NG binary16, index slot*NG + group
     V codes : 64 chunks of CB bytes                  (chunk index L_V)
-    V meta  : 16*NG dwords
-
-A meta dword holds the binary16 scale in bits 0..15 and the binary16 zero-point in 16..31.
+    V scale : 16*NG binary16, index slot*NG + group
+    V zp    : 16*NG binary16, index group*16 + slot  (group-major: the attention kernel reads
+                                                      a run of slots of one group)
 
 Inside a chunk a code occupies b bits at bit offset  32*(f // FPH) + 16*h + b*(f % FPH),
 FPH = 16/b, where (chunk, f, h) are
@@ -46,10 +47,10 @@ def page_bytes(bits, D, n_kv_heads):
 
 
 def region_offsets(bits, D):
-    """byte offsets of (K codes, K meta, V codes, V meta) inside a block"""
+    """byte offsets of (K codes, K scale, K zp, V codes, V scale, V zp) inside a block"""
     cb = 64 * chunk_bytes(bits, D)
-    mb = PAGE * (D // 32) * 4
-    return 0, cb, cb + mb, 2 * cb + mb
+    hb = PAGE * (D // 32) * 2
+    return 0, cb, cb + hb, cb + 2 * hb, 2 * cb + 2 * hb, 2 * cb + 3 * hb
 
 
 def k_code_bit(t, c, bits, D):
@@ -84,13 +85,13 @@ def _pack_codes(codes, bits, D, bitfn):
     return np.ascontiguousarray(dwords).view(np.uint8)          # host is little-endian
 
 
-def _pack_meta(scale, zp):
-    """scale, zp: float16 [..., 16, NG] -> uint8 [..., 16*NG*4]"""
-    s = np.ascontiguousarray(scale, dtype=np.float16).view(np.uint16).astype(np.uint32)
-    z = np.ascontiguousarray(zp, dtype=np.float16).view(np.uint16).astype(np.uint32)
-    d = (s | (z << 16)).astype(np.uint32)
-    d = np.ascontiguousarray(d.reshape(d.shape[:-2] + (d.shape[-2] * d.shape[-1],)))
-    return d.view(np.uint8)
+def _pack_halves(x, group_major=False):
+    """x: float16 [..., 16, NG] -> uint8 [..., 16*NG*2], slot-major or group-major"""
+    x = np.asarray(x, dtype=np.float16)
+    if group_major:
+        x = np.swapaxes(x, -1, -2)
+    x = np.ascontiguousarray(x)
+    return x.reshape(x.shape[:-2] + (x.shape[-2] * x.shape[-1],)).view(np.uint8)
 
 
 def pack_page_head(k_codes, k_scale, k_zp, v_codes, v_scale, v_zp, bits):
@@ -98,5 +99,5 @@ def pack_page_head(k_codes, k_scale, k_zp, v_codes, v_scale, v_zp, bits):
     Returns the uint8 [..., block_bytes] image of each (page, kv-head)."""
     D = k_codes.shape[-1]
     return np.concatenate([
-        _pack_codes(k_codes, bits, D, k_code_bit), _pack_meta(k_scale, k_zp),
-        _pack_codes(v_codes, bits, D, v_code_bit), _pack_meta(v_scale, v_zp)], axis=-1)
+        _pack_codes(k_codes, bits, D, k_code_bit), _pack_halves(k_scale), _pack_halves(k_zp),
+        _pack_codes(v_codes, bits, D, v_code_bit), _pack_halves(v_scale), _pack_halves(v_zp, group_major=True)], axis=-1)

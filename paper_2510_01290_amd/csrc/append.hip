@@ -317,7 +317,11 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
       const int mh = tid / (2 * NG), mr = tid % (2 * NG), mk = mr / NG, mg = mr % NG;
       if (h0 + mh < H) {
         uint8_t* blk = page + (int64_t)(h0 + mh) * g.block_bytes;
-        ((uint32_t*)(blk + (mk ? g.v_meta : g.k_meta)))[t * NG + mg] = s_meta[mh][mk][mg];
+        const uint32_t md = s_meta[mh][mk][mg];
+        uint16_t* sc = (uint16_t*)(blk + (mk ? g.v_scale : g.k_scale));
+        uint16_t* zp = (uint16_t*)(blk + (mk ? g.v_zp : g.k_zp));
+        sc[t * NG + mg] = (uint16_t)(md & 0xFFFFu);
+        zp[mk ? (mg * kPage + t) : (t * NG + mg)] = (uint16_t)(md >> 16);   // V zero-points are group-major
       }
     }
     __syncthreads();

@@ -15,8 +15,8 @@ constexpr int kWave = 64;
 struct BlockGeom {
   int chunk_bytes;  // CB = (D/32)*b
   int codes_bytes;  // 64*CB
-  int meta_bytes;   // 16*(D/32)*4
-  int k_codes, k_meta, v_codes, v_meta;  // region offsets
+  int half_bytes;   // 16*(D/32)*2: one array of binary16 scales or zero-points
+  int k_codes, k_scale, k_zp, v_codes, v_scale, v_zp;  // region offsets
   int block_bytes;
 };
 
@@ -24,12 +24,14 @@ __host__ __device__ inline BlockGeom block_geom(int bits, int D) {
   BlockGeom g;
   g.chunk_bytes = (D / kGroup) * bits;
   g.codes_bytes = 64 * g.chunk_bytes;
-  g.meta_bytes = kPage * (D / kGroup) * 4;
+  g.half_bytes = kPage * (D / kGroup) * 2;
   g.k_codes = 0;
-  g.k_meta = g.codes_bytes;
-  g.v_codes = g.codes_bytes + g.meta_bytes;
-  g.v_meta = 2 * g.codes_bytes + g.meta_bytes;
-  g.block_bytes = 2 * (g.codes_bytes + g.meta_bytes);
+  g.k_scale = g.codes_bytes;
+  g.k_zp = g.k_scale + g.half_bytes;
+  g.v_codes = g.k_zp + g.half_bytes;
+  g.v_scale = g.v_codes + g.codes_bytes;
+  g.v_zp = g.v_scale + g.half_bytes;
+  g.block_bytes = 2 * (g.codes_bytes + 2 * g.half_bytes);
   return g;
 }
 

@@ -28,7 +28,7 @@ struct DecodeArgs {
   float scale_log2e;    // softmax_scale * log2(e)
 };
 
-__host__ __device__ inline int pages_per_item_for_bits(int bits) { return bits == 8 ? 32 : (bits == 4 ? 64 : 96); }
+__host__ __device__ inline int pages_per_item_for_bits(int bits) { return bits == 8 ? 64 : (bits == 4 ? 128 : 192); }
 
 __device__ inline int n_items_of(int np, int ppi) { return (np + ppi - 1) / ppi; }
 

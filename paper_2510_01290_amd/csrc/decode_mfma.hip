@@ -10,11 +10,14 @@
 // conversion: a b-bit field masked inside a 16-bit half IS the binary16 (sub)normal
 // c * 2^(position-24); the power of two is folded into the query (for K) or into the output
 // scale (for V).  A quantisation group is 32 channels = the K extent of one MFMA, so group
-// scales multiply whole MFMA results in binary32.  Scores are computed transposed
-// (tokens x heads) so that their register layout is already the B-operand layout of the PV
-// product; the 16 MFMA columns carry the G query heads of the group, a duplicate of them
-// that takes the low half of a two-term binary16 split of p*s_V (22 significant bits), and
-// padding.  Per-token scales reach the lanes that need them through DPP row broadcasts.
+// scales multiply whole MFMA results in binary32; the zero-point terms are two small MFMAs of
+// their own (stored binary16 zero-points against a two-term split of the group sums of q, and
+// against a two-term split of p, which also yields the softmax denominator from a row of ones).
+// Scores are computed transposed (tokens x heads) so that their register layout is already
+// the B-operand layout of the PV product; the 16 MFMA columns carry the G query heads of the
+// group, a duplicate of them that takes the low half of the two-term binary16 splits
+// (22 significant bits), and padding.  Per-token scales reach the lanes that need them
+// through DPP row broadcasts.
 //
 // One workgroup of four waves per (query, kv-head, item); an item holds pages of one thought
 // type, so the bit width is a compile-time constant of the inner loop; a wave walks every
@@ -25,14 +28,18 @@
 namespace thinkv {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef float float2v __attribute__((ext_vector_type(2)));
-typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
 union H8 {
   half8 h;
   uint32_t u[4];
+};
+union H4 {
+  half4 h;
+  uint32_t u[2];
 };
 
 template <int N>
@@ -49,6 +56,13 @@ __device__ __forceinline__ uint32_t pack_rne(float a, float b) {
 
 __device__ __forceinline__ float half_lo(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u & 0xFFFFu)); }
 __device__ __forceinline__ float half_hi(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u >> 16)); }
+
+// two-term binary16 split of (x0, x1): returns rne16(x) in "high" lanes (alpha = 0) and
+// rne16(x - rne16(x)) in "low" lanes (alpha = 1); high + low carries 22 significant bits.
+__device__ __forceinline__ uint32_t split2(float x0, float x1, float alpha) {
+  const uint32_t h = pack_rne(x0, x1);
+  return pack_rne(fmaf(-alpha, half_lo(h), x0), fmaf(-alpha, half_hi(h), x1));
+}
 
 // Field geometry of a b-bit layout: FPH fields per 16-bit half-word.  The matrix core adds the
 // products of one instruction in a fixed-width window below the largest *nominal* product
@@ -78,16 +92,22 @@ struct Fld {
   }
 };
 
+// What one lane holds of one page: its K and V chunks, one K scale and one V scale (to be
+// broadcast along its row of 16 lanes), the K zero-points of its slot (A operand of the
+// score zero-point MFMA) and the V zero-points of four slots of its group (A operand of the
+// output zero-point MFMA).
 template <int D, int BITS>
 struct PageRegs {
   static constexpr int CW = (D / 32) * BITS / 4;  // chunk dwords
+  static constexpr int ZW = D / 64;               // dwords of K zero-points per slot
   uint32_t kw[CW], vw[CW];
-  uint32_t kmeta, vmeta;
+  uint32_t kzp[ZW], vzp[2];
+  uint16_t ks, vs;
 };
 
 template <int D, int BITS>
-__device__ __forceinline__ void load_page(PageRegs<D, BITS>& r, const uint8_t* blk, int lane, int meta_idx) {
-  constexpr int CW = PageRegs<D, BITS>::CW;
+__device__ __forceinline__ void load_page(PageRegs<D, BITS>& r, const uint8_t* blk, int lane, int scale_idx) {
+  constexpr int CW = PageRegs<D, BITS>::CW, NG = D / 32;
   const BlockGeom g = block_geom(BITS, D);
   const uint32_t* kc = (const uint32_t*)(blk + g.k_codes) + lane * CW;
   const uint32_t* vc = (const uint32_t*)(blk + g.v_codes) + lane * CW;
@@ -106,16 +126,25 @@ __device__ __forceinline__ void load_page(PageRegs<D, BITS>& r, const uint8_t* b
       r.vw[i] = b.x; r.vw[i + 1] = b.y; r.vw[i + 2] = b.z; r.vw[i + 3] = b.w;
     }
   }
-  r.kmeta = ((const uint32_t*)(blk + g.k_meta))[meta_idx];
-  r.vmeta = ((const uint32_t*)(blk + g.v_meta))[meta_idx];
+  r.ks = ((const uint16_t*)(blk + g.k_scale))[scale_idx];
+  r.vs = ((const uint16_t*)(blk + g.v_scale))[scale_idx];
+  const int t = lane & 15, qd = lane >> 4;
+  if constexpr (D == 128) {
+    const uint2 z = ((const uint2*)(blk + g.k_zp))[t];        // slot t, groups 0..3
+    r.kzp[0] = z.x; r.kzp[1] = z.y;
+  } else {
+    r.kzp[0] = ((const uint32_t*)(blk + g.k_zp))[t];          // slot t, groups 0..1
+  }
+  const uint2 z = *(const uint2*)(blk + g.v_zp + ((t & (NG - 1)) * kPage + 4 * qd) * 2);   // group t%NG, slots 4qd..4qd+3
+  r.vzp[0] = z.x; r.vzp[1] = z.y;
 }
 
 template <int D>
 struct WaveState {
   static constexpr int NG = D / 32, NM = D / 16;
-  float4v o[NM];   // o[mb][r]: channel 16*mb + 4*q + r, column n
-  float ozp[NG];   // zero-point part of the output, this lane's own tokens only
-  float m, l;      // running maximum (log2 domain) of column n; partial sum of p over own tokens
+  float4v o[NM];   // o[mb][r]: channel 16*mb + 4*qd + r of column n, in units of the class
+  float4v oz;      // rows 0..NG-1: zero-point part of the output per group; row NG: sum of p
+  float m;         // running maximum (log2 domain) of column n
 };
 
 // maximum over the four lanes that share a column (lane ^ 16, lane ^ 32), on the VALU
@@ -138,8 +167,7 @@ struct PairRegs {
   PageRegs<D, BITS> a, b;
 };
 
-// One class (bit width) of one wave's share of the item: page pairs wave, wave+4, ... of
-// tab[p0..p1).
+// One wave's share of an item: page pairs wave, wave+4, ... of tab[p0..p1).
 template <int D, int BITS, int G>
 struct ClassRunner {
   static constexpr int NG = D / 32, NM = D / 16;
@@ -152,8 +180,10 @@ struct ClassRunner {
   const int p0, p1, wave;
   int lane, qd, n;
   float alpha;
-  H8 bq[NG];
-  float qsum[NG];
+  H8 bq[NG];          // B operand of the score MFMAs
+  H4 bqs;             // B operand of the score zero-point MFMA: split of scale * sum_{i in g} q_i
+  uint32_t zmask, zones;  // A-operand row selection of the output zero-point MFMA
+  float kscale;       // 2^(24 - OMIN) * softmax_scale * log2(e)
 
   __device__ __forceinline__ ClassRunner(WaveState<D>& st_, const thinkv_view& v_, const DecodeArgs& a_, int cls_, const int32_t* tab_,
                                          int p0_, int p1_, int wave_, int hkv_, const _Float16* s_q, const float* s_qsum, int qpos_)
@@ -162,62 +192,85 @@ struct ClassRunner {
     qd = lane >> 4;
     n = lane & 15;
     alpha = (n >= G && n < 2 * G) ? 1.0f : 0.0f;
-    // B operand of the score product for this bit width: q of column n, channels (g, 8qd+e),
-    // scaled down by the residual power of two its code carries
+    kscale = (float)(1 << (24 - F::OMIN)) * a.scale_log2e;
+    const bool used = n < 2 * G;
     const int head = n < G ? n : n - G;
+    // q of column n, channels (g, 8qd+e), scaled down by the residual power of two its code carries
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      qsum[g] = n < 2 * G ? s_qsum[head * NG + g] : 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int f = 4 * g + (e >> 1);
-        float x = n < 2 * G ? (float)s_q[head * D + 32 * g + 8 * qd + e] : 0.f;
+        float x = used ? (float)s_q[head * D + 32 * g + 8 * qd + e] : 0.f;
         x *= 1.0f / (float)(1 << F::rel_of(f));
         bq[g].h[e] = (_Float16)x;   // exact: power-of-two scaling of a binary16 value
       }
     }
+    // k-slots of the 16x16x16 zero-point MFMA: D=128: (g0..g3) high terms in k 0..3 (row
+    // group 0), low terms in k 4..7 (row group 1); D=64: (g0, g1, g0, g1) = high, high, low, low
+    float qs[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int g = i % NG;
+      const float x = used ? s_qsum[head * NG + g] * a.scale_log2e : 0.f;
+      const float hi = (float)(_Float16)x;
+      const bool low_term = NG == 4 ? (qd == 1) : (i >= 2);
+      const bool live = NG == 4 ? (qd < 2) : (qd == 0);
+      qs[i] = live ? (low_term ? x - hi : hi) : 0.f;
+    }
+    bqs.u[0] = pack_rne(qs[0], qs[1]);
+    bqs.u[1] = pack_rne(qs[2], qs[3]);
+    // rows of the output zero-point MFMA: m < NG -> zero-points of group m, m == NG -> ones
+    zmask = n < NG ? 0xFFFFFFFFu : 0u;
+    zones = n == NG ? 0x3C003C00u : 0u;
   }
 
   __device__ __forceinline__ void issue_loads(PairRegs<D, BITS>& r, const PairIds& id) const {
-    if ((id.live_a | id.live_b) == 0) return;
     const int H = v.cfg.n_kv_heads;
     const BlockGeom geo = block_geom(BITS, D);
     const uint8_t* blk_a = v.arena[cls] + ((int64_t)id.pid_a * H + hkv) * geo.block_bytes;
     const uint8_t* blk_b = v.arena[cls] + ((int64_t)id.pid_b * H + hkv) * geo.block_bytes;
     if constexpr (D == 128) {
-      load_page<D, BITS>(r.a, blk_a, lane, lane);
+      load_page<D, BITS>(r.a, blk_a, lane, lane);            // scale of (slot lane/4, group lane%4)
       load_page<D, BITS>(r.b, blk_b, lane, lane);
     } else {
-      // 32 meta dwords per page: lanes x<8 of every row take page a, x>=8 page b
-      const int mi = 8 * qd + (n & 7);
-      load_page<D, BITS>(r.a, blk_a, lane, mi);
-      load_page<D, BITS>(r.b, blk_b, lane, mi);
+      // 32 scales per page: lanes x<8 of every row take page a, x>=8 page b
+      const int si = 8 * qd + (n & 7);
+      load_page<D, BITS>(r.a, blk_a, lane, si);
+      load_page<D, BITS>(r.b, blk_b, lane, si);
     }
   }
 
   __device__ __forceinline__ void compute(const PairRegs<D, BITS>& r, const PairIds& id) {
     const uint32_t live_a = id.live_a, live_b = id.live_b;
-    if ((live_a | live_b) == 0) return;
     const PageRegs<D, BITS>& ra = r.a;
     const PageRegs<D, BITS>& rb = r.b;
-    uint32_t kma = ra.kmeta, vma = ra.vmeta;
+    // scales to broadcast: D=128 one register per page; D=64 both pages share a register
+    uint16_t ksa = ra.ks, vsa = ra.vs;
     if constexpr (D == 64) {
-      if (n >= 8) { kma = rb.kmeta; vma = rb.vmeta; }
+      if (n >= 8) { ksa = rb.ks; vsa = rb.vs; }
     }
-    // per-lane converted meta: scale (times the power of two the codes lack) and zero-point
-    constexpr float KS = (float)(1 << (24 - F::OMIN));   // codes enter the MFMA as c * 2^(OMIN - 24)
-    const float ks_a = half_lo(kma) * KS, kz_a = half_hi(kma);
-    const float vs_a = half_lo(vma), vz_a = half_hi(vma);
-    float ks_b = ks_a, kz_b = kz_a, vs_b = vs_a, vz_b = vz_a;
+    const float ks_a = (float)__builtin_bit_cast(_Float16, ksa) * kscale;
+    const float vs_a = (float)__builtin_bit_cast(_Float16, vsa);
+    float ks_b = ks_a, vs_b = vs_a;
     if constexpr (D == 128) {
-      ks_b = half_lo(rb.kmeta) * KS; kz_b = half_hi(rb.kmeta);
-      vs_b = half_lo(rb.vmeta); vz_b = half_hi(rb.vmeta);
+      ks_b = (float)__builtin_bit_cast(_Float16, rb.ks) * kscale;
+      vs_b = (float)__builtin_bit_cast(_Float16, rb.vs);
     }
 
-    // ---------------- scores: S^T[token][column] per page
-    float sa[4], sb[4];
-#pragma unroll
-    for (int r4 = 0; r4 < 4; ++r4) sa[r4] = sb[r4] = 0.f;
+    // ---------------- scores: S^T[token][column] per page, log2 domain
+    // zero-point term first: zp_K[token][g] x split(scale * qsum[g][column])
+    H4 za, zb;
+    if constexpr (D == 128) {
+      za.u[0] = ra.kzp[0]; za.u[1] = ra.kzp[1];
+      zb.u[0] = rb.kzp[0]; zb.u[1] = rb.kzp[1];
+    } else {
+      za.u[0] = za.u[1] = ra.kzp[0];
+      zb.u[0] = zb.u[1] = rb.kzp[0];
+    }
+    const float4v zero = {0.f, 0.f, 0.f, 0.f};
+    float4v sa = __builtin_amdgcn_mfma_f32_16x16x16f16(za.h, bqs.h, zero, 0, 0, 0);
+    float4v sb = __builtin_amdgcn_mfma_f32_16x16x16f16(zb.h, bqs.h, zero, 0, 0, 0);
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
       H8 ka, kb;
@@ -226,19 +279,16 @@ struct ClassRunner {
         ka.u[vv] = F::get(ra.kw, 4 * g + vv);
         kb.u[vv] = F::get(rb.kw, 4 * g + vv);
       }
-      const float4v z = {0.f, 0.f, 0.f, 0.f};
-      const float4v ya = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka.h, bq[g].h, z, 0, 0, 0);
-      const float4v yb = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb.h, bq[g].h, z, 0, 0, 0);
-      // scale/zero-point of (token 4qd+r, group g) sit in lane 4r+g of this row (D=128),
+      const float4v ya = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka.h, bq[g].h, zero, 0, 0, 0);
+      const float4v yb = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb.h, bq[g].h, zero, 0, 0, 0);
+      // the scale of (token 4qd+r, group g) sits in lane 4r+g of this row (D=128),
       // or lane 8p+2r+g (D=64, p = page)
 #define TKV_SCORE_STEP(R)                                                                              \
   {                                                                                                    \
     constexpr int IA = (D == 128) ? (4 * R + GI) : (2 * R + GI);                                        \
     constexpr int IB = (D == 128) ? (4 * R + GI) : (8 + 2 * R + GI);                                    \
     sa[R] = fmaf(bcast_row<IA>(ks_a), ya[R], sa[R]);                                                   \
-    sa[R] = fmaf(bcast_row<IA>(kz_a), qsum[g], sa[R]);                                                 \
     sb[R] = fmaf(bcast_row<IB>(D == 128 ? ks_b : ks_a), yb[R], sb[R]);                                 \
-    sb[R] = fmaf(bcast_row<IB>(D == 128 ? kz_b : kz_a), qsum[g], sb[R]);                               \
   }
 #define TKV_SCORE_GROUP(GI_)            \
   if (g == GI_) {                       \
@@ -253,22 +303,14 @@ struct ClassRunner {
       }
     }
     // ---------------- mask, online softmax over the 8 scores of this lane
-    float mx = -INFINITY;
-    if ((live_a & live_b) == 0xFFFFu) {
+    if ((live_a & live_b) != 0xFFFFu) {
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        sa[r4] *= a.scale_log2e;
-        sb[r4] *= a.scale_log2e;
-        mx = fmaxf(mx, fmaxf(sa[r4], sb[r4]));
-      }
-    } else {
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        sa[r4] = ((live_a >> (4 * qd + r4)) & 1u) ? sa[r4] * a.scale_log2e : -INFINITY;
-        sb[r4] = ((live_b >> (4 * qd + r4)) & 1u) ? sb[r4] * a.scale_log2e : -INFINITY;
-        mx = fmaxf(mx, fmaxf(sa[r4], sb[r4]));
+        sa[r4] = ((live_a >> (4 * qd + r4)) & 1u) ? sa[r4] : -INFINITY;
+        sb[r4] = ((live_b >> (4 * qd + r4)) & 1u) ? sb[r4] : -INFINITY;
       }
     }
+    float mx = fmaxf(fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3])), fmaxf(fmaxf(sb[0], sb[1]), fmaxf(sb[2], sb[3])));
     mx = col_max(mx);
     const float m_new = fmaxf(st.m, mx);
     const float m_safe = m_new == -INFINITY ? 0.f : m_new;
@@ -276,9 +318,7 @@ struct ClassRunner {
       const float corr = __builtin_amdgcn_exp2f(st.m - m_safe);
 #pragma unroll
       for (int mb = 0; mb < NM; ++mb) st.o[mb] *= corr;
-#pragma unroll
-      for (int g = 0; g < NG; ++g) st.ozp[g] *= corr;
-      st.l *= corr;
+      st.oz *= corr;
       st.m = m_new;
     }
     float pa[4], pb[4];
@@ -286,41 +326,48 @@ struct ClassRunner {
     for (int r4 = 0; r4 < 4; ++r4) {
       pa[r4] = __builtin_amdgcn_exp2f(sa[r4] - m_safe);
       pb[r4] = __builtin_amdgcn_exp2f(sb[r4] - m_safe);
-      st.l += pa[r4] + pb[r4];
     }
-    // ---------------- values: per group, B = split(p * s_V), A = V codes; zero-point part on the VALU
+    // ---------------- zero-point part of the output and the softmax denominator:
+    // rows = (zp_V of group 0..NG-1, ones) x split(p)
+    {
+      H8 zp, pz;
+      zp.u[0] = (ra.vzp[0] & zmask) | zones;
+      zp.u[1] = (ra.vzp[1] & zmask) | zones;
+      zp.u[2] = (rb.vzp[0] & zmask) | zones;
+      zp.u[3] = (rb.vzp[1] & zmask) | zones;
+      pz.u[0] = split2(pa[0], pa[1], alpha);
+      pz.u[1] = split2(pa[2], pa[3], alpha);
+      pz.u[2] = split2(pb[0], pb[1], alpha);
+      pz.u[3] = split2(pb[2], pb[3], alpha);
+      st.oz = __builtin_amdgcn_mfma_f32_16x16x32_f16(zp.h, pz.h, st.oz, 0, 0, 0);
+    }
+    // ---------------- values: per group, B = split(p * s_V), A = V codes
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
       H8 pg;
+      float xa[4], xb[4];
 #define TKV_P_STEP(R)                                                                                  \
   {                                                                                                    \
     constexpr int IA = (D == 128) ? (4 * R + GI) : (2 * R + GI);                                        \
     constexpr int IB = (D == 128) ? (4 * R + GI) : (8 + 2 * R + GI);                                    \
     xa[R] = pa[R] * bcast_row<IA>(vs_a);                                                               \
     xb[R] = pb[R] * bcast_row<IB>(D == 128 ? vs_b : vs_a);                                             \
-    st.ozp[g] = fmaf(pa[R], bcast_row<IA>(vz_a), st.ozp[g]);                                           \
-    st.ozp[g] = fmaf(pb[R], bcast_row<IB>(D == 128 ? vz_b : vz_a), st.ozp[g]);                         \
   }
 #define TKV_P_GROUP(GI_)                \
   if (g == GI_) {                       \
     constexpr int GI = GI_;             \
     TKV_P_STEP(0) TKV_P_STEP(1) TKV_P_STEP(2) TKV_P_STEP(3) \
   }
-      float xa[4], xb[4];
       TKV_P_GROUP(0)
       TKV_P_GROUP(1)
       if constexpr (NG > 2) {
         TKV_P_GROUP(2)
         TKV_P_GROUP(3)
       }
-      // two-term split: high columns carry rne16(x), low columns rne16(x - rne16(x))
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const uint32_t ha = pack_rne(xa[2 * i], xa[2 * i + 1]);
-        const uint32_t hb = pack_rne(xb[2 * i], xb[2 * i + 1]);
-        pg.u[i] = pack_rne(fmaf(-alpha, half_lo(ha), xa[2 * i]), fmaf(-alpha, half_hi(ha), xa[2 * i + 1]));
-        pg.u[2 + i] = pack_rne(fmaf(-alpha, half_lo(hb), xb[2 * i]), fmaf(-alpha, half_hi(hb), xb[2 * i + 1]));
-      }
+      pg.u[0] = split2(xa[0], xa[1], alpha);
+      pg.u[1] = split2(xa[2], xa[3], alpha);
+      pg.u[2] = split2(xb[0], xb[1], alpha);
+      pg.u[3] = split2(xb[2], xb[3], alpha);
 #pragma unroll
       for (int mm = 0; mm < 2; ++mm) {
         const int mb = 2 * g + mm;
@@ -374,6 +421,7 @@ struct ClassRunner {
         const int ib = 2 * pr + 1 < cnt ? 2 * pr + 1 : 2 * pr;
         id.pid_b = __builtin_amdgcn_readlane(vpid, ib);
         id.live_b = 2 * pr + 1 < cnt ? __builtin_amdgcn_readlane(vmask, ib) : 0u;
+        if ((id.live_a | id.live_b) == 0) continue;
         PairRegs<D, BITS> r;
         issue_loads(r, id);
         compute(r, id);
@@ -402,20 +450,23 @@ __device__ __forceinline__ void run_item(const thinkv_view& v, const DecodeArgs&
   for (int i = tid; i < G * D; i += 256)
     lds.q[i] = (_Float16)load_as_f32(a.q, ((int64_t)b * Hq + hkv * G) * D + i, a.q_dtype);
   __syncthreads();
-  if (tid < G * NG) {
+  if (tid < G * NG * 4) {
+    // four threads per (head, group) sum eight channels each
+    const int hg = tid >> 2, part = tid & 3;
     float s = 0.f;
-    for (int i = 0; i < 32; ++i) s += (float)lds.q[(tid / NG) * D + 32 * (tid % NG) + i];
-    lds.qsum[tid] = s;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += (float)lds.q[(hg / NG) * D + 32 * (hg % NG) + 8 * part + i];
+    s += __shfl_xor(s, 1, 64);
+    s += __shfl_xor(s, 2, 64);
+    if (part == 0) lds.qsum[hg] = s;
   }
   __syncthreads();
 
   WaveState<D> st;
 #pragma unroll
   for (int mb = 0; mb < NM; ++mb) st.o[mb] = float4v{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int g = 0; g < NG; ++g) st.ozp[g] = 0.f;
+  st.oz = float4v{0.f, 0.f, 0.f, 0.f};
   st.m = -INFINITY;
-  st.l = 0.f;
   const int qpos = a.window > 0 ? a.q_pos[b] : 0;
   const int qd = lane >> 4, n = lane & 15;
   const int p0 = (int)((int64_t)item * np / ns), p1 = (int)((int64_t)(item + 1) * np / ns);
@@ -425,17 +476,17 @@ __device__ __forceinline__ void run_item(const thinkv_view& v, const DecodeArgs&
     cr.run();
   }
 
-  // ---- fold: low-half columns into their heads, row groups for l and ozp, then the four waves
-  float l = st.l;
-  l += __shfl_xor(l, 16, 64);
-  l += __shfl_xor(l, 32, 64);
-  float ozp[NG];
+  // ---- fold.  The zero-point MFMA left rows 0..NG-1 = zero-point part of the output per
+  // group and row NG = sum of p (rows 0..3 live in row group 0, row 4 in row group 1);
+  // high and low columns are added, then every lane of the column fetches what it needs.
+  float zsum[NG], l;
+  {
+    float t[4];
 #pragma unroll
-  for (int g = 0; g < NG; ++g) {
-    float z = st.ozp[g];
-    z += __shfl_xor(z, 16, 64);
-    z += __shfl_xor(z, 32, 64);
-    ozp[g] = z;
+    for (int r = 0; r < 4; ++r) t[r] = st.oz[r] + __shfl(st.oz[r], (lane & 48) | ((n + G) & 15), 64);
+#pragma unroll
+    for (int g = 0; g < NG; ++g) zsum[g] = __shfl(t[g], n, 64);
+    l = NG == 4 ? __shfl(t[0], 16 + n, 64) : __shfl(t[2], n, 64);
   }
 #pragma unroll
   for (int mb = 0; mb < NM; ++mb) {
@@ -445,7 +496,7 @@ __device__ __forceinline__ void run_item(const thinkv_view& v, const DecodeArgs&
     for (int r = 0; r < 4; ++r) {
       float x = st.o[mb][r];
       const float lo = __shfl(x, (lane & 48) | ((n + G) & 15), 64);
-      x = (x + lo) * unit + ozp[mb >> 1];
+      x = (x + lo) * unit + zsum[mb >> 1];
       if (n < G) lds.acc[wave][n][16 * mb + 4 * qd + r] = x;
     }
   }

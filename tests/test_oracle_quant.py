@@ -95,7 +95,7 @@ def test_binary32_input_below_zero_point_clamps():
 def _unpack_bit_by_bit(img, bits, D):
     """independent reader: walks the byte image as one big little-endian integer per chunk"""
     cb = layout.chunk_bytes(bits, D)
-    ok, km, vo, vm = layout.region_offsets(bits, D)
+    ok, ks_, kz_, vo, vs_, vz_ = layout.region_offsets(bits, D)
     kc = np.zeros((16, D), dtype=np.uint8)
     vc = np.zeros((16, D), dtype=np.uint8)
     fph = 16 // bits
@@ -114,9 +114,12 @@ def _unpack_bit_by_bit(img, bits, D):
                 q, m = lane // 16, lane % 16
                 u, mb = f // (D // 16), f % (D // 16)
                 vc[4 * q + 2 * u + h, 16 * mb + m] = vcode
-    meta = lambda o: img[o:o + 16 * (D // 32) * 4].view(np.uint32).reshape(16, D // 32)
-    half = lambda w: w.astype(np.uint16).view(np.float16)
-    return kc, half(meta(km) & 0xFFFF), half(meta(km) >> 16), vc, half(meta(vm) & 0xFFFF), half(meta(vm) >> 16)
+    ng = D // 32
+    halves = lambda o: np.array([int.from_bytes(img[o + 2 * i:o + 2 * i + 2].tobytes(), "little") for i in range(16 * ng)],
+                                dtype=np.uint16).view(np.float16)
+    slot_major = lambda o: halves(o).reshape(16, ng)
+    group_major = lambda o: np.ascontiguousarray(halves(o).reshape(ng, 16).T)
+    return kc, slot_major(ks_), slot_major(kz_), vc, slot_major(vs_), group_major(vz_)
 
 
 @pytest.mark.parametrize("D", [64, 128])
