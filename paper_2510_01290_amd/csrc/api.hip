@@ -81,6 +81,7 @@ static int decode_common(const thinkv_view* view, int32_t layer, const void* q, 
   a.q_dtype = q_dtype;
   a.out_dtype = out_dtype;
   a.max_split = split_bound(view->cfg, max_ctx_pages, a.ppi);
+  if (a.max_split > 1024) return THINKV_E_SHAPE;   // merge kernel keeps one weight per item in LDS
   a.scale_log2e = softmax_scale * 1.4426950408889634f;
   hipStream_t st = (hipStream_t)stream;
   rc = fast ? launch_decode_mfma(*view, a, st) : launch_decode_simple(*view, a, st);

@@ -154,12 +154,18 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
 }
 
 // One workgroup of D threads per (query, query head): log-sum-exp merge of the partials.
+// Maxima and weights are found with one split per thread; the weighted sum over splits is
+// unrolled so that several partial rows are in flight per thread.
+constexpr int kMaxSplit = 1024;
+
 template <int D>
 __global__ __launch_bounds__(D) void decode_merge_kernel(thinkv_view v, DecodeArgs a) {
   const thinkv_config& c = v.cfg;
   const int hq = blockIdx.x, b = blockIdx.y, ch = threadIdx.x;
   const int Hq = c.n_q_heads;
   const int seq = a.seq_ids[b];
+  __shared__ float s_w[kMaxSplit];
+  __shared__ float s_red[D / 64];
   int ns = 0;
   for (int k = 0; k < 3; ++k) {
     const int np = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
@@ -167,15 +173,45 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(thinkv_view v, DecodeAr
   }
   ns = ns < a.max_split ? ns : a.max_split;
   const float* src = a.partial + partial_index(a, Hq, D, b, hq, 0);
-  float M = -INFINITY;
-  for (int s = 0; s < ns; ++s) M = fmaxf(M, src[(int64_t)s * (D + 2)]);
-  float L = 0.f, A = 0.f;
-  for (int s = 0; s < ns; ++s) {
-    const float* p = src + (int64_t)s * (D + 2);
-    const float f = (p[0] == -INFINITY) ? 0.f : exp2f(p[0] - M);
-    L = fmaf(p[1], f, L);
-    A = fmaf(p[2 + ch], f, A);
+  // maximum over splits
+  float m_loc = -INFINITY;
+  for (int s = ch; s < ns; s += D) {
+    const float m = src[(int64_t)s * (D + 2)];
+    s_w[s] = m;
+    m_loc = fmaxf(m_loc, m);
   }
+  for (int d = 32; d >= 1; d >>= 1) m_loc = fmaxf(m_loc, __shfl_xor(m_loc, d, 64));
+  if ((ch & 63) == 0) s_red[ch >> 6] = m_loc;
+  __syncthreads();
+  float M = s_red[0];
+  for (int w = 1; w < D / 64; ++w) M = fmaxf(M, s_red[w]);
+  __syncthreads();
+  // weights and denominator
+  float l_loc = 0.f;
+  for (int s = ch; s < ns; s += D) {
+    const float m = s_w[s];
+    const float f = (m == -INFINITY) ? 0.f : exp2f(m - M);
+    s_w[s] = f;
+    l_loc = fmaf(src[(int64_t)s * (D + 2) + 1], f, l_loc);
+  }
+  for (int d = 32; d >= 1; d >>= 1) l_loc += __shfl_xor(l_loc, d, 64);
+  if ((ch & 63) == 0) s_red[ch >> 6] = l_loc;
+  __syncthreads();
+  float L = s_red[0];
+  for (int w = 1; w < D / 64; ++w) L += s_red[w];
+  // weighted sum of the partial rows
+  float A = 0.f;
+  const float* col = src + 2 + ch;
+  int s = 0;
+  for (; s + 4 <= ns; s += 4) {
+    const float x0 = col[(int64_t)(s + 0) * (D + 2)], x1 = col[(int64_t)(s + 1) * (D + 2)];
+    const float x2 = col[(int64_t)(s + 2) * (D + 2)], x3 = col[(int64_t)(s + 3) * (D + 2)];
+    A = fmaf(x0, s_w[s], A);
+    A = fmaf(x1, s_w[s + 1], A);
+    A = fmaf(x2, s_w[s + 2], A);
+    A = fmaf(x3, s_w[s + 3], A);
+  }
+  for (; s < ns; ++s) A = fmaf(col[(int64_t)s * (D + 2)], s_w[s], A);
   const float o = L > 0.f ? A / L : 0.f;
   store_from_f32(a.out, ((int64_t)b * Hq + hq) * D + ch, a.out_dtype, o);
   if (a.lse && ch == 0) a.lse[(int64_t)b * Hq + hq] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
