@@ -42,18 +42,17 @@ static int check_view(const thinkv_view* v) {
   return THINKV_OK;
 }
 
-// pages per item of each class, and an upper bound on the items of a sequence that holds at
-// most max_ctx_pages pages (all in the class with the smallest items, plus one ragged item
-// per class)
-static int split_bound(const thinkv_config& c, int max_ctx_pages, int ppi[3]) {
-  int mn = 1 << 30;
-  for (int k = 0; k < 3; ++k) {
-    ppi[k] = pages_per_item_for_bits(c.bits_of_class[k]);
-    if (const char* e = getenv("THINKV_PPI_MUL4")) ppi[k] = ppi[k] * atoi(e) / 4;  // dev knob
-    mn = ppi[k] < mn ? ppi[k] : mn;
-  }
-  return max_ctx_pages / mn + 3;
+// Pages per work item: sized so that B * Hkv * ceil(max_ctx_pages / ppi) workgroups fill the
+// 256 compute units (four workgroups each) about twice, with a floor that keeps the
+// per-item set-up small against the item.
+static int pages_per_item(const thinkv_config& c, int B, int max_ctx_pages) {
+  const int64_t total = (int64_t)max_ctx_pages * B * c.n_kv_heads;
+  int ppi = (int)((total + 2047) / 2048);
+  if (const char* e = getenv("THINKV_PPI")) ppi = atoi(e);  // dev knob
+  return ppi < 32 ? 32 : ppi;
 }
+
+static int split_bound(int max_ctx_pages, int ppi) { return (max_ctx_pages + ppi - 1) / ppi + 1; }
 
 static int decode_common(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
                          const int32_t* seq_ids, const int32_t* q_pos, int32_t B, int32_t window, float softmax_scale,
@@ -80,7 +79,8 @@ static int decode_common(const thinkv_view* view, int32_t layer, const void* q, 
   a.window = window;
   a.q_dtype = q_dtype;
   a.out_dtype = out_dtype;
-  a.max_split = split_bound(view->cfg, max_ctx_pages, a.ppi);
+  a.ppi = pages_per_item(view->cfg, B, max_ctx_pages);
+  a.max_split = split_bound(max_ctx_pages, a.ppi);
   if (a.max_split > 1024) return THINKV_E_SHAPE;   // merge kernel keeps one weight per item in LDS
   a.scale_log2e = softmax_scale * 1.4426950408889634f;
   hipStream_t st = (hipStream_t)stream;
@@ -111,8 +111,8 @@ size_t thinkv_append_workspace_bytes(const thinkv_config* cfg, int32_t n_tok) {
 
 size_t thinkv_decode_workspace_bytes(const thinkv_config* cfg, int32_t B, int32_t max_ctx_pages) {
   if (check_config(cfg) || B < 0 || max_ctx_pages < 0) return 0;
-  int ppi[3];
-  const int ms = split_bound(*cfg, max_ctx_pages, ppi);
+  // the item size never drops below 32 pages, whatever the batch
+  const int ms = split_bound(max_ctx_pages, 32);
   return (size_t)(B > 0 ? B : 1) * cfg->n_q_heads * ms * (cfg->head_dim + 2) * sizeof(float);
 }
 

@@ -19,10 +19,10 @@
 // (22 significant bits), and padding.  Per-token scales reach the lanes that need them
 // through DPP row broadcasts.
 //
-// One workgroup of four waves per (query, kv-head, item); an item holds pages of one thought
-// type, so the bit width is a compile-time constant of the inner loop; a wave walks every
-// fourth page pair of the item; the four waves are merged through LDS into one partial
-// (m, l, acc) per query head.
+// One workgroup of four waves per (query, kv-head, item); an item holds an equal share of the
+// pages of every thought type and walks them type by type, so the bit width is a
+// compile-time constant of each inner loop; a wave takes every fourth page pair; the four
+// waves are merged through LDS into one partial (m, l, acc) per query head.
 #include "decode_common.h"
 
 namespace thinkv {
@@ -438,13 +438,30 @@ struct ItemLds {
   float acc[4][G][D];
 };
 
-// Everything one workgroup does for one item whose pages hold BITS-bit codes.
-template <int D, int G, int BITS>
-__device__ __forceinline__ void run_item(const thinkv_view& v, const DecodeArgs& a, ItemLds<D, G>& lds, int cls, int item, int ns,
-                                         int np, int split, int hkv, int b, int seq) {
+template <int D>
+__device__ __forceinline__ float class_unit(int bits, int mb) {
+  // V codes of a b-bit class enter the MFMA as c * 2^(OMIN + rel(mb) - 24)
+  const int sh = bits == 2 ? Fld<2>::OMIN + Fld<2>::rel_of(mb) : (bits == 4 ? Fld<4>::OMIN + Fld<4>::rel_of(mb) : 0);
+  return (float)(1 << sh);
+}
+
+// One workgroup of four waves per (query, kv-head, item).
+template <int D, int G>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void decode_mfma_kernel(thinkv_view v, DecodeArgs a) {
   constexpr int NG = D / 32, NM = D / 16;
-  using F = Fld<BITS>;
   const thinkv_config& c = v.cfg;
+  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+  const int seq = a.seq_ids[b];
+  __shared__ ItemLds<D, G> lds;
+  int np[3], np_total = 0;
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    np[k] = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
+    np_total += np[k];
+  }
+  const int ns = n_items_of(a, np_total);
+  if (split >= ns) return;
+
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int Hq = c.n_q_heads;
   for (int i = tid; i < G * D; i += 256)
@@ -469,11 +486,28 @@ __device__ __forceinline__ void run_item(const thinkv_view& v, const DecodeArgs&
   st.m = -INFINITY;
   const int qpos = a.window > 0 ? a.q_pos[b] : 0;
   const int qd = lane >> 4, n = lane & 15;
-  const int p0 = (int)((int64_t)item * np / ns), p1 = (int)((int64_t)(item + 1) * np / ns);
-  const int32_t* tab = v.block_table + table_base(c, seq, a.layer, cls);
-  {
-    ClassRunner<D, BITS, G> cr(st, v, a, cls, tab, p0, p1, wave, hkv, lds.q, lds.qsum, qpos);
-    cr.run();
+
+  // The running output is kept in the units of the class being walked (its codes carry a
+  // power of two that depends on the bit width) and re-based at class boundaries.
+  for (int k = 0; k < 3; ++k) {
+    const int bits = c.bits_of_class[k];
+    const int p0 = (int)((int64_t)split * np[k] / ns), p1 = (int)((int64_t)(split + 1) * np[k] / ns);
+    if (p1 <= p0) continue;
+    const int32_t* tab = v.block_table + table_base(c, seq, a.layer, k);
+#pragma unroll
+    for (int mb = 0; mb < NM; ++mb) st.o[mb] *= class_unit<D>(bits, mb);
+    if (bits == 2) {
+      ClassRunner<D, 2, G> cr(st, v, a, k, tab, p0, p1, wave, hkv, lds.q, lds.qsum, qpos);
+      cr.run();
+    } else if (bits == 4) {
+      ClassRunner<D, 4, G> cr(st, v, a, k, tab, p0, p1, wave, hkv, lds.q, lds.qsum, qpos);
+      cr.run();
+    } else {
+      ClassRunner<D, 8, G> cr(st, v, a, k, tab, p0, p1, wave, hkv, lds.q, lds.qsum, qpos);
+      cr.run();
+    }
+#pragma unroll
+    for (int mb = 0; mb < NM; ++mb) st.o[mb] *= 1.0f / class_unit<D>(bits, mb);
   }
 
   // ---- fold.  The zero-point MFMA left rows 0..NG-1 = zero-point part of the output per
@@ -490,13 +524,11 @@ __device__ __forceinline__ void run_item(const thinkv_view& v, const DecodeArgs&
   }
 #pragma unroll
   for (int mb = 0; mb < NM; ++mb) {
-    // V codes entered the MFMA as c * 2^(OMIN + rel(mb) - 24)
-    const float unit = (float)(1 << (24 - F::OMIN - F::rel_of(mb)));
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       float x = st.o[mb][r];
       const float lo = __shfl(x, (lane & 48) | ((n + G) & 15), 64);
-      x = (x + lo) * unit + zsum[mb >> 1];
+      x = (x + lo) * 16777216.f + zsum[mb >> 1];
       if (n < G) lds.acc[wave][n][16 * mb + 4 * qd + r] = x;
     }
   }
@@ -524,26 +556,6 @@ __device__ __forceinline__ void run_item(const thinkv_view& v, const DecodeArgs&
       dst[1] = L;
     }
   }
-}
-
-template <int D, int G>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void decode_mfma_kernel(thinkv_view v, DecodeArgs a) {
-  const thinkv_config& c = v.cfg;
-  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
-  const int seq = a.seq_ids[b];
-  __shared__ ItemLds<D, G> lds;
-  int np[3];
-#pragma unroll
-  for (int k = 0; k < 3; ++k) np[k] = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
-  int cls, item, ns;
-  if (!locate_item(a, np, split, &cls, &item, &ns)) return;
-  const int bits = c.bits_of_class[cls];
-  if (bits == 2)
-    run_item<D, G, 2>(v, a, lds, cls, item, ns, np[cls], split, hkv, b, seq);
-  else if (bits == 4)
-    run_item<D, G, 4>(v, a, lds, cls, item, ns, np[cls], split, hkv, b, seq);
-  else
-    run_item<D, G, 8>(v, a, lds, cls, item, ns, np[cls], split, hkv, b, seq);
 }
 
 int decode_mfma_supported(const thinkv_config& c) {

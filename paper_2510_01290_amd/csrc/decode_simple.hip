@@ -27,11 +27,13 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
   __shared__ float s_m[4][GMAX], s_l[4][GMAX];
   __shared__ float s_acc[4][GMAX][D];
 
-  int np[3];
-  for (int k = 0; k < 3; ++k)
+  int np[3], np_total = 0;
+  for (int k = 0; k < 3; ++k) {
     np[k] = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
-  int k, item, ns;
-  if (!locate_item(a, np, split, &k, &item, &ns)) return;
+    np_total += np[k];
+  }
+  const int ns = n_items_of(a, np_total);
+  if (split >= ns) return;
   for (int i = tid; i < G * D; i += 256)
     s_q[i / D][i % D] = load_as_f32(a.q, ((int64_t)b * Hq + hkv * G) * D + i, a.q_dtype) * a.scale_log2e;
   __syncthreads();
@@ -46,10 +48,10 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
   }
   const int qpos = a.window > 0 ? a.q_pos[b] : 0;
 
-  {
+  for (int k = 0; k < 3; ++k) {
     const int bits = c.bits_of_class[k];
     const BlockGeom geo = block_geom(bits, D);
-    const int p0 = (int)((int64_t)item * np[k] / ns), p1 = (int)((int64_t)(item + 1) * np[k] / ns);
+    const int p0 = (int)((int64_t)split * np[k] / ns), p1 = (int)((int64_t)(split + 1) * np[k] / ns);
     const int32_t* tab = v.block_table + table_base(c, seq, a.layer, k);
     for (int pi = p0 + wave; pi < p1; pi += 4) {
       const int pid = tab[pi];
@@ -166,12 +168,10 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(thinkv_view v, DecodeAr
   const int seq = a.seq_ids[b];
   __shared__ float s_w[kMaxSplit];
   __shared__ float s_red[D / 64];
-  int ns = 0;
-  for (int k = 0; k < 3; ++k) {
-    const int np = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
-    ns += n_items_of(np, a.ppi[k]);
-  }
-  ns = ns < a.max_split ? ns : a.max_split;
+  int np_total = 0;
+  for (int k = 0; k < 3; ++k)
+    np_total += (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
+  const int ns = n_items_of(a, np_total);
   const float* src = a.partial + partial_index(a, Hq, D, b, hq, 0);
   // maximum over splits
   float m_loc = -INFINITY;
