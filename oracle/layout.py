@@ -11,12 +11,10 @@ A page holds P = 16 slots; head_dim D in {64,128}; NG = D/32 groups; b in {2,4,8
 Per (page, kv-head) there is one block of four regions, in this order:
 
     K codes : 64 chunks of CB = NG*b bytes          (chunk index L_K)
-    K scale : 16*NG binary16, index slot*NG + group
-    K zp    : 16*NG binary16, index slot*NG + group
+    K meta  : NG*4 units of eight binary16; unit group*4 + slot//4 holds the scales of its
+              four slots (slot%4 = 0..3), then their four zero-points
     V codes : 64 chunks of CB bytes                  (chunk index L_V)
-    V scale : 16*NG binary16, index slot*NG + group
-    V zp    : 16*NG binary16, index group*16 + slot  (group-major: the attention kernel reads
-                                                      a run of slots of one group)
+    V meta  : as K meta
 
 Inside a chunk a code occupies b bits at bit offset  32*(f // FPH) + 16*h + b*(f % FPH),
 FPH = 16/b, where (chunk, f, h) are
@@ -47,10 +45,10 @@ def page_bytes(bits, D, n_kv_heads):
 
 
 def region_offsets(bits, D):
-    """byte offsets of (K codes, K scale, K zp, V codes, V scale, V zp) inside a block"""
+    """byte offsets of (K codes, K meta, V codes, V meta) inside a block"""
     cb = 64 * chunk_bytes(bits, D)
-    hb = PAGE * (D // 32) * 2
-    return 0, cb, cb + hb, cb + 2 * hb, 2 * cb + 2 * hb, 2 * cb + 3 * hb
+    mb = PAGE * (D // 32) * 4
+    return 0, cb, cb + mb, 2 * cb + mb
 
 
 def k_code_bit(t, c, bits, D):
@@ -85,13 +83,18 @@ def _pack_codes(codes, bits, D, bitfn):
     return np.ascontiguousarray(dwords).view(np.uint8)          # host is little-endian
 
 
-def _pack_halves(x, group_major=False):
-    """x: float16 [..., 16, NG] -> uint8 [..., 16*NG*2], slot-major or group-major"""
-    x = np.asarray(x, dtype=np.float16)
-    if group_major:
-        x = np.swapaxes(x, -1, -2)
-    x = np.ascontiguousarray(x)
-    return x.reshape(x.shape[:-2] + (x.shape[-2] * x.shape[-1],)).view(np.uint8)
+def _pack_meta(scale, zp):
+    """scale, zp: float16 [..., 16, NG] -> uint8 [..., 16*NG*4]: for every group, for every
+    quad of slots, the four scales then the four zero-points"""
+    scale = np.asarray(scale, dtype=np.float16)
+    zp = np.asarray(zp, dtype=np.float16)
+    lead, ng = scale.shape[:-2], scale.shape[-1]
+    units = np.empty(lead + (ng, 4, 2, 4), dtype=np.float16)
+    for g in range(ng):
+        for q in range(4):
+            units[..., g, q, 0, :] = scale[..., 4 * q:4 * q + 4, g]
+            units[..., g, q, 1, :] = zp[..., 4 * q:4 * q + 4, g]
+    return np.ascontiguousarray(units).reshape(lead + (ng * 32,)).view(np.uint8)
 
 
 def pack_page_head(k_codes, k_scale, k_zp, v_codes, v_scale, v_zp, bits):
@@ -99,5 +102,5 @@ def pack_page_head(k_codes, k_scale, k_zp, v_codes, v_scale, v_zp, bits):
     Returns the uint8 [..., block_bytes] image of each (page, kv-head)."""
     D = k_codes.shape[-1]
     return np.concatenate([
-        _pack_codes(k_codes, bits, D, k_code_bit), _pack_halves(k_scale), _pack_halves(k_zp),
-        _pack_codes(v_codes, bits, D, v_code_bit), _pack_halves(v_scale), _pack_halves(v_zp, group_major=True)], axis=-1)
+        _pack_codes(k_codes, bits, D, k_code_bit), _pack_meta(k_scale, k_zp),
+        _pack_codes(v_codes, bits, D, v_code_bit), _pack_meta(v_scale, v_zp)], axis=-1)

@@ -318,10 +318,9 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
       if (h0 + mh < H) {
         uint8_t* blk = page + (int64_t)(h0 + mh) * g.block_bytes;
         const uint32_t md = s_meta[mh][mk][mg];
-        uint16_t* sc = (uint16_t*)(blk + (mk ? g.v_scale : g.k_scale));
-        uint16_t* zp = (uint16_t*)(blk + (mk ? g.v_zp : g.k_zp));
-        sc[t * NG + mg] = (uint16_t)(md & 0xFFFFu);
-        zp[mk ? (mg * kPage + t) : (t * NG + mg)] = (uint16_t)(md >> 16);   // V zero-points are group-major
+        uint16_t* meta = (uint16_t*)(blk + (mk ? g.v_meta : g.k_meta));
+        meta[meta_index(t, mg)] = (uint16_t)(md & 0xFFFFu);
+        meta[meta_index(t, mg) + 4] = (uint16_t)(md >> 16);
       }
     }
     __syncthreads();

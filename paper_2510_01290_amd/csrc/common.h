@@ -12,11 +12,14 @@ constexpr int kGroup = THINKV_GROUP_SIZE; // channels per quantisation group
 constexpr int kWave = 64;
 
 // Geometry of one (page, kv-head) block for b-bit codes and head_dim D.
+// [K codes][K meta][V codes][V meta]; a meta region is NG*4 units of 16 bytes, unit
+// (group g, slot quad qd) = g*4 + qd holding eight binary16: the scales of slots
+// 4qd..4qd+3 of group g, then their zero-points.
 struct BlockGeom {
   int chunk_bytes;  // CB = (D/32)*b
   int codes_bytes;  // 64*CB
-  int half_bytes;   // 16*(D/32)*2: one array of binary16 scales or zero-points
-  int k_codes, k_scale, k_zp, v_codes, v_scale, v_zp;  // region offsets
+  int meta_bytes;   // 16*(D/32)*4: scales and zero-points of one of K / V
+  int k_codes, k_meta, v_codes, v_meta;  // region offsets
   int block_bytes;
 };
 
@@ -24,16 +27,18 @@ __host__ __device__ inline BlockGeom block_geom(int bits, int D) {
   BlockGeom g;
   g.chunk_bytes = (D / kGroup) * bits;
   g.codes_bytes = 64 * g.chunk_bytes;
-  g.half_bytes = kPage * (D / kGroup) * 2;
+  g.meta_bytes = kPage * (D / kGroup) * 4;
   g.k_codes = 0;
-  g.k_scale = g.codes_bytes;
-  g.k_zp = g.k_scale + g.half_bytes;
-  g.v_codes = g.k_zp + g.half_bytes;
-  g.v_scale = g.v_codes + g.codes_bytes;
-  g.v_zp = g.v_scale + g.half_bytes;
-  g.block_bytes = 2 * (g.codes_bytes + 2 * g.half_bytes);
+  g.k_meta = g.codes_bytes;
+  g.v_codes = g.k_meta + g.meta_bytes;
+  g.v_meta = g.v_codes + g.codes_bytes;
+  g.block_bytes = 2 * (g.codes_bytes + g.meta_bytes);
   return g;
 }
+
+// index (in binary16 units) of the scale of (slot t, group g) inside a meta region; its
+// zero-point sits four places further
+__host__ __device__ inline int meta_index(int t, int g) { return (g * 4 + (t >> 2)) * 8 + (t & 3); }
 
 __host__ __device__ inline bool bits_ok(int b) { return b == 2 || b == 4 || b == 8; }
 

@@ -9,15 +9,22 @@
 // The integer codes c are fed to v_mfma_f32_16x16x32_f16 as binary16 numbers without any
 // conversion: a b-bit field masked inside a 16-bit half IS the binary16 (sub)normal
 // c * 2^(position-24); the power of two is folded into the query (for K) or into the output
-// scale (for V).  A quantisation group is 32 channels = the K extent of one MFMA, so group
-// scales multiply whole MFMA results in binary32; the zero-point terms are two small MFMAs of
-// their own (stored binary16 zero-points against a two-term split of the group sums of q, and
-// against a two-term split of p, which also yields the softmax denominator from a row of ones).
-// Scores are computed transposed (tokens x heads) so that their register layout is already
-// the B-operand layout of the PV product; the 16 MFMA columns carry the G query heads of the
-// group, a duplicate of them that takes the low half of the two-term binary16 splits
-// (22 significant bits), and padding.  Per-token scales reach the lanes that need them
-// through DPP row broadcasts.
+// scale (for V).  A quantisation group is 32 channels = the K extent of one MFMA.
+//
+// Column plan.  The 16 MFMA columns are cut into CS slices of GP columns (GP = 4 or 8 >= the
+// number G of query heads that share the kv-head); slice gl carries the G heads *for
+// quantisation group gl* (of the column set being worked on: D/32 groups = NSET sets of CS).
+// Scores: the query of group g is placed in slice g's columns only (zeros elsewhere) and the
+// MFMAs of the CS groups of a set accumulate into ONE 16x16 tile, tokens x (group, head).
+// Lane (column n, row quad qd) then applies, to its four tokens, the scale and zero-point of
+// ITS group -- lane-local binary32 arithmetic on values the lane loaded itself, no broadcast
+// -- and two DPP row rotations add the slices, leaving the complete score of head n % GP in
+// every slice.  That register layout is already the B-operand layout of the PV product.
+// Values: p * s_V(t, g) is likewise lane-local (each slice multiplies by its own group's
+// scale), is split once into two binary16 terms (22 significant bits), and the same B operand
+// pair serves the PV MFMAs of every group of the set: the tile of a 16-channel block is only
+// read back in the slice of its group.  The zero-point part of the output and the softmax
+// denominator are lane-local binary32 sums.
 //
 // One workgroup of four waves per (query, kv-head, item); an item holds an equal share of the
 // pages of every thought type and walks them type by type, so the bit width is a
@@ -28,8 +35,8 @@
 namespace thinkv {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef uint16_t ushort2v __attribute__((ext_vector_type(2)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef float float2v __attribute__((ext_vector_type(2)));
 
@@ -37,15 +44,12 @@ union H8 {
   half8 h;
   uint32_t u[4];
 };
-union H4 {
-  half4 h;
-  uint32_t u[2];
-};
 
-template <int N>
-__device__ __forceinline__ float bcast_row(float v) {
-  // value of lane N of this lane's row of 16
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x150 + N, 0xf, 0xf, true));
+// x + (x of the lane DIST places further round this lane's row of 16)
+template <int DIST>
+__device__ __forceinline__ float add_row_ror(float x) {
+  const int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x120 + DIST, 0xf, 0xf, true);
+  return x + __builtin_bit_cast(float, y);
 }
 
 __device__ __forceinline__ uint32_t pack_rne(float a, float b) {
@@ -56,12 +60,10 @@ __device__ __forceinline__ uint32_t pack_rne(float a, float b) {
 
 __device__ __forceinline__ float half_lo(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u & 0xFFFFu)); }
 __device__ __forceinline__ float half_hi(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u >> 16)); }
-
-// two-term binary16 split of (x0, x1): returns rne16(x) in "high" lanes (alpha = 0) and
-// rne16(x - rne16(x)) in "low" lanes (alpha = 1); high + low carries 22 significant bits.
-__device__ __forceinline__ uint32_t split2(float x0, float x1, float alpha) {
-  const uint32_t h = pack_rne(x0, x1);
-  return pack_rne(fmaf(-alpha, half_lo(h), x0), fmaf(-alpha, half_hi(h), x1));
+// binary16 number r (0..3) of the dword pair (a, b)
+template <int R>
+__device__ __forceinline__ float half_of(uint32_t a, uint32_t b) {
+  return R == 0 ? half_lo(a) : (R == 1 ? half_hi(a) : (R == 2 ? half_lo(b) : half_hi(b)));
 }
 
 // Field geometry of a b-bit layout: FPH fields per 16-bit half-word.  The matrix core adds the
@@ -82,7 +84,9 @@ struct Fld {
     const int word = f / FPH, pos = f % FPH;
     const uint32_t x = w[word];
     if constexpr (BITS == 8) {
-      return (pos == 0 ? x : (x >> 8)) & MASK;
+      if (pos == 0) return x & MASK;
+      const ushort2v y = __builtin_bit_cast(ushort2v, x) >> (uint16_t)8;   // both halves at once
+      return __builtin_bit_cast(uint32_t, y);
     } else {
       // field pair (pos & ~1, pos | 1) starts at bit BITS*(pos & ~1); bring it to bit OMIN
       const int from = BITS * (pos & ~1);
@@ -92,22 +96,26 @@ struct Fld {
   }
 };
 
-// What one lane holds of one page: its K and V chunks, one K scale and one V scale (to be
-// broadcast along its row of 16 lanes), the K zero-points of its slot (A operand of the
-// score zero-point MFMA) and the V zero-points of four slots of its group (A operand of the
-// output zero-point MFMA).
-template <int D, int BITS>
-struct PageRegs {
-  static constexpr int CW = (D / 32) * BITS / 4;  // chunk dwords
-  static constexpr int ZW = D / 64;               // dwords of K zero-points per slot
-  uint32_t kw[CW], vw[CW];
-  uint32_t kzp[ZW], vzp[2];
-  uint16_t ks, vs;
+// How the 16 columns are shared between query heads and quantisation groups.
+template <int D, int GP>
+struct Cols {
+  static constexpr int NG = D / 32;
+  static constexpr int CS = (16 / GP) < NG ? (16 / GP) : NG;   // groups (slices) per column set
+  static constexpr int NSET = NG / CS;
 };
 
-template <int D, int BITS>
-__device__ __forceinline__ void load_page(PageRegs<D, BITS>& r, const uint8_t* blk, int lane, int scale_idx) {
-  constexpr int CW = PageRegs<D, BITS>::CW, NG = D / 32;
+// What one lane holds of one page: its K and V chunks and, per column set, the scales and
+// zero-points of (its slice's group, its four slots) for K and for V.
+template <int D, int BITS, int NSET>
+struct PageRegs {
+  static constexpr int CW = (D / 32) * BITS / 4;  // chunk dwords
+  uint32_t kw[CW], vw[CW];
+  uint4 km[NSET], vm[NSET];   // (scale 0|1, scale 2|3, zero-point 0|1, zero-point 2|3)
+};
+
+template <int D, int BITS, int NSET>
+__device__ __forceinline__ void load_page(PageRegs<D, BITS, NSET>& r, const uint8_t* blk, int lane, const int* meta_off) {
+  constexpr int CW = PageRegs<D, BITS, NSET>::CW;
   const BlockGeom g = block_geom(BITS, D);
   const uint32_t* kc = (const uint32_t*)(blk + g.k_codes) + lane * CW;
   const uint32_t* vc = (const uint32_t*)(blk + g.v_codes) + lane * CW;
@@ -126,25 +134,21 @@ __device__ __forceinline__ void load_page(PageRegs<D, BITS>& r, const uint8_t* b
       r.vw[i] = b.x; r.vw[i + 1] = b.y; r.vw[i + 2] = b.z; r.vw[i + 3] = b.w;
     }
   }
-  r.ks = ((const uint16_t*)(blk + g.k_scale))[scale_idx];
-  r.vs = ((const uint16_t*)(blk + g.v_scale))[scale_idx];
-  const int t = lane & 15, qd = lane >> 4;
-  if constexpr (D == 128) {
-    const uint2 z = ((const uint2*)(blk + g.k_zp))[t];        // slot t, groups 0..3
-    r.kzp[0] = z.x; r.kzp[1] = z.y;
-  } else {
-    r.kzp[0] = ((const uint32_t*)(blk + g.k_zp))[t];          // slot t, groups 0..1
+#pragma unroll
+  for (int s = 0; s < NSET; ++s) {
+    r.km[s] = *(const uint4*)(blk + g.k_meta + meta_off[s]);
+    r.vm[s] = *(const uint4*)(blk + g.v_meta + meta_off[s]);
   }
-  const uint2 z = *(const uint2*)(blk + g.v_zp + ((t & (NG - 1)) * kPage + 4 * qd) * 2);   // group t%NG, slots 4qd..4qd+3
-  r.vzp[0] = z.x; r.vzp[1] = z.y;
 }
 
-template <int D>
+template <int D, int NSET>
 struct WaveState {
-  static constexpr int NG = D / 32, NM = D / 16;
-  float4v o[NM];   // o[mb][r]: channel 16*mb + 4*qd + r of column n, in units of the class
-  float4v oz;      // rows 0..NG-1: zero-point part of the output per group; row NG: sum of p
-  float m;         // running maximum (log2 domain) of column n
+  static constexpr int NM = D / 16;
+  float4v o[NM];    // o[mb][r]: channel 16*mb + 4*qd + r of column n, in units of the class
+  float oz[NSET];   // this lane's share of sum_t p_t zp_V(t, group of the lane's slice)
+  float l;          // this lane's share of sum_t p_t
+  float m;          // running maximum (log2 domain) of column n; -inf before the first live token
+  float m_sub;      // what the exponent subtracts: m, or 0 while m is -inf
 };
 
 // maximum over the four lanes that share a column (lane ^ 16, lane ^ 32), on the VALU
@@ -162,228 +166,192 @@ struct PairIds {
   uint32_t live_a, live_b;
 };
 
-template <int D, int BITS>
+template <int D, int BITS, int NSET>
 struct PairRegs {
-  PageRegs<D, BITS> a, b;
+  PageRegs<D, BITS, NSET> a, b;
 };
 
+// 0xFFFF in each half of the result whose slot (bit 2j, bit 2j+1 of m4) is live
+__device__ __forceinline__ uint32_t half_mask(uint32_t m4, int j) {
+  return ((m4 >> (2 * j)) & 1u ? 0x0000FFFFu : 0u) | ((m4 >> (2 * j + 1)) & 1u ? 0xFFFF0000u : 0u);
+}
+
 // One wave's share of an item: page pairs wave, wave+4, ... of tab[p0..p1).
-template <int D, int BITS, int G>
+template <int D, int BITS, int GP>
 struct ClassRunner {
-  static constexpr int NG = D / 32, NM = D / 16;
+  using CL = Cols<D, GP>;
+  static constexpr int NG = D / 32, NM = D / 16, CS = CL::CS, NSET = CL::NSET;
   using F = Fld<BITS>;
-  WaveState<D>& st;
+  using Pair = PairRegs<D, BITS, NSET>;
+  WaveState<D, NSET>& st;
   const thinkv_view& v;
   const DecodeArgs& a;
   const int cls, hkv, qpos;
   const int32_t* tab;
   const int p0, p1, wave;
   int lane, qd, n;
-  float alpha;
-  H8 bq[NG];          // B operand of the score MFMAs
-  H4 bqs;             // B operand of the score zero-point MFMA: split of scale * sum_{i in g} q_i
-  uint32_t zmask, zones;  // A-operand row selection of the output zero-point MFMA
-  float kscale;       // 2^(24 - OMIN) * softmax_scale * log2(e)
+  int meta_off[NSET];  // byte offset, inside a meta region, of this lane's unit per column set
+  H8 bq[NG];           // B operands of the score MFMAs: q of group g in slice g % CS, zeros elsewhere
+  float qs[NSET];      // 2^(OMIN-24) * sum_{i in group} q_i of this lane's (slice group, head)
+  float kappa;         // 2^(24-OMIN) * softmax_scale * log2(e): MFMA score units -> log2 domain
 
-  __device__ __forceinline__ ClassRunner(WaveState<D>& st_, const thinkv_view& v_, const DecodeArgs& a_, int cls_, const int32_t* tab_,
-                                         int p0_, int p1_, int wave_, int hkv_, const _Float16* s_q, const float* s_qsum, int qpos_)
+  __device__ __forceinline__ ClassRunner(WaveState<D, NSET>& st_, const thinkv_view& v_, const DecodeArgs& a_, int cls_,
+                                         const int32_t* tab_, int p0_, int p1_, int wave_, int hkv_, int G, const _Float16* s_q,
+                                         const float* s_qsum, int qpos_)
       : st(st_), v(v_), a(a_), cls(cls_), hkv(hkv_), qpos(qpos_), tab(tab_), p0(p0_), p1(p1_), wave(wave_) {
     lane = threadIdx.x & 63;
     qd = lane >> 4;
     n = lane & 15;
-    alpha = (n >= G && n < 2 * G) ? 1.0f : 0.0f;
-    kscale = (float)(1 << (24 - F::OMIN)) * a.scale_log2e;
-    const bool used = n < 2 * G;
-    const int head = n < G ? n : n - G;
-    // q of column n, channels (g, 8qd+e), scaled down by the residual power of two its code carries
+    const int gl = n / GP, head = n % GP;
+    const bool used = gl < CS && head < G;
+    const int glc = gl < CS ? gl : CS - 1;   // unused slices read slice CS-1's unit (finite, multiplied by zeros)
+    kappa = (float)(1 << (24 - F::OMIN)) * a.scale_log2e;
+#pragma unroll
+    for (int s = 0; s < NSET; ++s) {
+      const int g = s * CS + glc;
+      meta_off[s] = (g * 4 + qd) * 16;
+      qs[s] = used ? s_qsum[head * NG + g] * (1.0f / (float)(1 << (24 - F::OMIN))) : 0.f;
+    }
+    // q of this lane's head, channels 32g + 8qd + e, scaled down by the residual power of two its code carries
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
+      const bool mine = used && (g % CS) == gl;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int f = 4 * g + (e >> 1);
-        float x = used ? (float)s_q[head * D + 32 * g + 8 * qd + e] : 0.f;
+        float x = mine ? (float)s_q[head * D + 32 * g + 8 * qd + e] : 0.f;
         x *= 1.0f / (float)(1 << F::rel_of(f));
         bq[g].h[e] = (_Float16)x;   // exact: power-of-two scaling of a binary16 value
       }
     }
-    // k-slots of the 16x16x16 zero-point MFMA: D=128: (g0..g3) high terms in k 0..3 (row
-    // group 0), low terms in k 4..7 (row group 1); D=64: (g0, g1, g0, g1) = high, high, low, low
-    float qs[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int g = i % NG;
-      const float x = used ? s_qsum[head * NG + g] * a.scale_log2e : 0.f;
-      const float hi = (float)(_Float16)x;
-      const bool low_term = NG == 4 ? (qd == 1) : (i >= 2);
-      const bool live = NG == 4 ? (qd < 2) : (qd == 0);
-      qs[i] = live ? (low_term ? x - hi : hi) : 0.f;
-    }
-    bqs.u[0] = pack_rne(qs[0], qs[1]);
-    bqs.u[1] = pack_rne(qs[2], qs[3]);
-    // rows of the output zero-point MFMA: m < NG -> zero-points of group m, m == NG -> ones
-    zmask = n < NG ? 0xFFFFFFFFu : 0u;
-    zones = n == NG ? 0x3C003C00u : 0u;
   }
 
-  __device__ __forceinline__ void issue_loads(PairRegs<D, BITS>& r, const PairIds& id) const {
+  __device__ __forceinline__ void issue_loads(Pair& r, const PairIds& id) const {
     const int H = v.cfg.n_kv_heads;
     const BlockGeom geo = block_geom(BITS, D);
     const uint8_t* blk_a = v.arena[cls] + ((int64_t)id.pid_a * H + hkv) * geo.block_bytes;
     const uint8_t* blk_b = v.arena[cls] + ((int64_t)id.pid_b * H + hkv) * geo.block_bytes;
-    if constexpr (D == 128) {
-      load_page<D, BITS>(r.a, blk_a, lane, lane);            // scale of (slot lane/4, group lane%4)
-      load_page<D, BITS>(r.b, blk_b, lane, lane);
-    } else {
-      // 32 scales per page: lanes x<8 of every row take page a, x>=8 page b
-      const int si = 8 * qd + (n & 7);
-      load_page<D, BITS>(r.a, blk_a, lane, si);
-      load_page<D, BITS>(r.b, blk_b, lane, si);
-    }
+    load_page<D, BITS, NSET>(r.a, blk_a, lane, meta_off);
+    load_page<D, BITS, NSET>(r.b, blk_b, lane, meta_off);
   }
 
-  __device__ __forceinline__ void compute(const PairRegs<D, BITS>& r, const PairIds& id) {
-    const uint32_t live_a = id.live_a, live_b = id.live_b;
-    const PageRegs<D, BITS>& ra = r.a;
-    const PageRegs<D, BITS>& rb = r.b;
-    // scales to broadcast: D=128 one register per page; D=64 both pages share a register
-    uint16_t ksa = ra.ks, vsa = ra.vs;
-    if constexpr (D == 64) {
-      if (n >= 8) { ksa = rb.ks; vsa = rb.vs; }
-    }
-    const float ks_a = (float)__builtin_bit_cast(_Float16, ksa) * kscale;
-    const float vs_a = (float)__builtin_bit_cast(_Float16, vsa);
-    float ks_b = ks_a, vs_b = vs_a;
-    if constexpr (D == 128) {
-      ks_b = (float)__builtin_bit_cast(_Float16, rb.ks) * kscale;
-      vs_b = (float)__builtin_bit_cast(_Float16, rb.vs);
-    }
-
-    // ---------------- scores: S^T[token][column] per page, log2 domain
-    // zero-point term first: zp_K[token][g] x split(scale * qsum[g][column])
-    H4 za, zb;
-    if constexpr (D == 128) {
-      za.u[0] = ra.kzp[0]; za.u[1] = ra.kzp[1];
-      zb.u[0] = rb.kzp[0]; zb.u[1] = rb.kzp[1];
-    } else {
-      za.u[0] = za.u[1] = ra.kzp[0];
-      zb.u[0] = zb.u[1] = rb.kzp[0];
-    }
+  // scores of one page for this lane's four tokens, in MFMA units (times kappa = log2 domain)
+  __device__ __forceinline__ void page_scores(const PageRegs<D, BITS, NSET>& r, float* s) const {
     const float4v zero = {0.f, 0.f, 0.f, 0.f};
-    float4v sa = __builtin_amdgcn_mfma_f32_16x16x16f16(za.h, bqs.h, zero, 0, 0, 0);
-    float4v sb = __builtin_amdgcn_mfma_f32_16x16x16f16(zb.h, bqs.h, zero, 0, 0, 0);
+    float4v c[NSET];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      H8 ka, kb;
+    for (int set = 0; set < NSET; ++set) {
 #pragma unroll
-      for (int vv = 0; vv < 4; ++vv) {
-        ka.u[vv] = F::get(ra.kw, 4 * g + vv);
-        kb.u[vv] = F::get(rb.kw, 4 * g + vv);
-      }
-      const float4v ya = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka.h, bq[g].h, zero, 0, 0, 0);
-      const float4v yb = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb.h, bq[g].h, zero, 0, 0, 0);
-      // the scale of (token 4qd+r, group g) sits in lane 4r+g of this row (D=128),
-      // or lane 8p+2r+g (D=64, p = page)
-#define TKV_SCORE_STEP(R)                                                                              \
-  {                                                                                                    \
-    constexpr int IA = (D == 128) ? (4 * R + GI) : (2 * R + GI);                                        \
-    constexpr int IB = (D == 128) ? (4 * R + GI) : (8 + 2 * R + GI);                                    \
-    sa[R] = fmaf(bcast_row<IA>(ks_a), ya[R], sa[R]);                                                   \
-    sb[R] = fmaf(bcast_row<IB>(D == 128 ? ks_b : ks_a), yb[R], sb[R]);                                 \
-  }
-#define TKV_SCORE_GROUP(GI_)            \
-  if (g == GI_) {                       \
-    constexpr int GI = GI_;             \
-    TKV_SCORE_STEP(0) TKV_SCORE_STEP(1) TKV_SCORE_STEP(2) TKV_SCORE_STEP(3) \
-  }
-      TKV_SCORE_GROUP(0)
-      TKV_SCORE_GROUP(1)
-      if constexpr (NG > 2) {
-        TKV_SCORE_GROUP(2)
-        TKV_SCORE_GROUP(3)
+      for (int gl = 0; gl < CS; ++gl) {
+        const int g = set * CS + gl;
+        H8 ka;
+#pragma unroll
+        for (int vv = 0; vv < 4; ++vv) ka.u[vv] = F::get(r.kw, 4 * g + vv);
+        c[set] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka.h, bq[g].h, gl == 0 ? zero : c[set], 0, 0, 0);
       }
     }
-    // ---------------- mask, online softmax over the 8 scores of this lane
+#define TKV_SCORE(R)                                                                             \
+  {                                                                                              \
+    float acc = 0.f;                                                                             \
+    _Pragma("unroll") for (int set = 0; set < NSET; ++set) {                                     \
+      const float z = half_of<R>(r.km[set].z, r.km[set].w) * qs[set];                            \
+      const float t = fmaf(half_of<R>(r.km[set].x, r.km[set].y), c[set][R], z);                  \
+      acc = set == 0 ? t : acc + t;                                                              \
+    }                                                                                            \
+    acc = add_row_ror<8>(acc);                                                                   \
+    if constexpr (GP == 4) acc = add_row_ror<4>(acc);                                            \
+    s[R] = acc;                                                                                  \
+  }
+    TKV_SCORE(0) TKV_SCORE(1) TKV_SCORE(2) TKV_SCORE(3)
+#undef TKV_SCORE
+  }
+
+  __device__ __forceinline__ void compute(const Pair& r, const PairIds& id) {
+    const uint32_t live_a = id.live_a, live_b = id.live_b;
+    float sa[4], sb[4];
+    page_scores(r.a, sa);
+    page_scores(r.b, sb);
+    uint4 vma[NSET], vmb[NSET];
+#pragma unroll
+    for (int set = 0; set < NSET; ++set) {
+      vma[set] = r.a.vm[set];
+      vmb[set] = r.b.vm[set];
+    }
+    // ---------------- dead slots: score -inf, and V scale / zero-point 0 so that whatever bytes the
+    // slot holds never meet the arithmetic
     if ((live_a & live_b) != 0xFFFFu) {
+      const uint32_t la = (live_a >> (4 * qd)) & 0xFu, lb = (live_b >> (4 * qd)) & 0xFu;
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        sa[r4] = ((live_a >> (4 * qd + r4)) & 1u) ? sa[r4] : -INFINITY;
-        sb[r4] = ((live_b >> (4 * qd + r4)) & 1u) ? sb[r4] : -INFINITY;
+        sa[r4] = ((la >> r4) & 1u) ? sa[r4] : -INFINITY;
+        sb[r4] = ((lb >> r4) & 1u) ? sb[r4] : -INFINITY;
+      }
+      const uint32_t a01 = half_mask(la, 0), a23 = half_mask(la, 1), b01 = half_mask(lb, 0), b23 = half_mask(lb, 1);
+#pragma unroll
+      for (int set = 0; set < NSET; ++set) {
+        vma[set].x &= a01; vma[set].y &= a23; vma[set].z &= a01; vma[set].w &= a23;
+        vmb[set].x &= b01; vmb[set].y &= b23; vmb[set].z &= b01; vmb[set].w &= b23;
       }
     }
-    float mx = fmaxf(fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3])), fmaxf(fmaxf(sb[0], sb[1]), fmaxf(sb[2], sb[3])));
-    mx = col_max(mx);
-    const float m_new = fmaxf(st.m, mx);
-    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-    if (__any(m_new != st.m)) {
-      const float corr = __builtin_amdgcn_exp2f(st.m - m_safe);
+    // ---------------- online softmax over the 8 scores of this lane; the running maximum only
+    // moves when some lane of the wave sees a score above it
+    const float mx = fmaxf(fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3])), fmaxf(fmaxf(sb[0], sb[1]), fmaxf(sb[2], sb[3]))) * kappa;
+    if (__any(mx > st.m)) {
+      const float m_new = fmaxf(st.m, col_max(mx));
+      const float m_sub = m_new == -INFINITY ? 0.f : m_new;
+      const float corr = __builtin_amdgcn_exp2f(st.m - m_sub);
 #pragma unroll
       for (int mb = 0; mb < NM; ++mb) st.o[mb] *= corr;
-      st.oz *= corr;
+#pragma unroll
+      for (int set = 0; set < NSET; ++set) st.oz[set] *= corr;
+      st.l *= corr;
       st.m = m_new;
+      st.m_sub = m_sub;
     }
     float pa[4], pb[4];
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
-      pa[r4] = __builtin_amdgcn_exp2f(sa[r4] - m_safe);
-      pb[r4] = __builtin_amdgcn_exp2f(sb[r4] - m_safe);
+      pa[r4] = __builtin_amdgcn_exp2f(fmaf(sa[r4], kappa, -st.m_sub));
+      pb[r4] = __builtin_amdgcn_exp2f(fmaf(sb[r4], kappa, -st.m_sub));
     }
-    // ---------------- zero-point part of the output and the softmax denominator:
-    // rows = (zp_V of group 0..NG-1, ones) x split(p)
-    {
-      H8 zp, pz;
-      zp.u[0] = (ra.vzp[0] & zmask) | zones;
-      zp.u[1] = (ra.vzp[1] & zmask) | zones;
-      zp.u[2] = (rb.vzp[0] & zmask) | zones;
-      zp.u[3] = (rb.vzp[1] & zmask) | zones;
-      pz.u[0] = split2(pa[0], pa[1], alpha);
-      pz.u[1] = split2(pa[2], pa[3], alpha);
-      pz.u[2] = split2(pb[0], pb[1], alpha);
-      pz.u[3] = split2(pb[2], pb[3], alpha);
-      st.oz = __builtin_amdgcn_mfma_f32_16x16x32_f16(zp.h, pz.h, st.oz, 0, 0, 0);
-    }
-    // ---------------- values: per group, B = split(p * s_V), A = V codes
+    st.l += ((pa[0] + pa[1]) + (pa[2] + pa[3])) + ((pb[0] + pb[1]) + (pb[2] + pb[3]));
+    // ---------------- values, per column set: B = two-term split of p * s_V, A = V codes
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      H8 pg;
-      float xa[4], xb[4];
-#define TKV_P_STEP(R)                                                                                  \
-  {                                                                                                    \
-    constexpr int IA = (D == 128) ? (4 * R + GI) : (2 * R + GI);                                        \
-    constexpr int IB = (D == 128) ? (4 * R + GI) : (8 + 2 * R + GI);                                    \
-    xa[R] = pa[R] * bcast_row<IA>(vs_a);                                                               \
-    xb[R] = pb[R] * bcast_row<IB>(D == 128 ? vs_b : vs_a);                                             \
+    for (int set = 0; set < NSET; ++set) {
+      float xa[4], xb[4], z = st.oz[set];
+#define TKV_PV(R)                                                     \
+  {                                                                   \
+    z = fmaf(half_of<R>(vma[set].z, vma[set].w), pa[R], z);           \
+    z = fmaf(half_of<R>(vmb[set].z, vmb[set].w), pb[R], z);           \
+    xa[R] = half_of<R>(vma[set].x, vma[set].y) * pa[R];               \
+    xb[R] = half_of<R>(vmb[set].x, vmb[set].y) * pb[R];               \
   }
-#define TKV_P_GROUP(GI_)                \
-  if (g == GI_) {                       \
-    constexpr int GI = GI_;             \
-    TKV_P_STEP(0) TKV_P_STEP(1) TKV_P_STEP(2) TKV_P_STEP(3) \
-  }
-      TKV_P_GROUP(0)
-      TKV_P_GROUP(1)
-      if constexpr (NG > 2) {
-        TKV_P_GROUP(2)
-        TKV_P_GROUP(3)
-      }
-      pg.u[0] = split2(xa[0], xa[1], alpha);
-      pg.u[1] = split2(xa[2], xa[3], alpha);
-      pg.u[2] = split2(xb[0], xb[1], alpha);
-      pg.u[3] = split2(xb[2], xb[3], alpha);
+      TKV_PV(0) TKV_PV(1) TKV_PV(2) TKV_PV(3)
+#undef TKV_PV
+      st.oz[set] = z;
+      // k-slots 8qd+e: e<4 page a slots 4qd+e, e>=4 page b
+      H8 hi, lo;
+      hi.u[0] = pack_rne(xa[0], xa[1]);
+      hi.u[1] = pack_rne(xa[2], xa[3]);
+      hi.u[2] = pack_rne(xb[0], xb[1]);
+      hi.u[3] = pack_rne(xb[2], xb[3]);
+      lo.u[0] = pack_rne(fmaf(-1.0f, half_lo(hi.u[0]), xa[0]), fmaf(-1.0f, half_hi(hi.u[0]), xa[1]));
+      lo.u[1] = pack_rne(fmaf(-1.0f, half_lo(hi.u[1]), xa[2]), fmaf(-1.0f, half_hi(hi.u[1]), xa[3]));
+      lo.u[2] = pack_rne(fmaf(-1.0f, half_lo(hi.u[2]), xb[0]), fmaf(-1.0f, half_hi(hi.u[2]), xb[1]));
+      lo.u[3] = pack_rne(fmaf(-1.0f, half_lo(hi.u[3]), xb[2]), fmaf(-1.0f, half_hi(hi.u[3]), xb[3]));
 #pragma unroll
-      for (int mm = 0; mm < 2; ++mm) {
-        const int mb = 2 * g + mm;
+      for (int mm = 0; mm < 2 * CS; ++mm) {
+        const int mb = 2 * CS * set + mm;
         H8 va;
-        // k-slots 8qd+e: e<4 page a slots 4qd+e, e>=4 page b; field f = u*NM + mb holds slots (2u, 2u+1)
-        va.u[0] = F::get(ra.vw, 0 * NM + mb);
-        va.u[1] = F::get(ra.vw, 1 * NM + mb);
-        va.u[2] = F::get(rb.vw, 0 * NM + mb);
-        va.u[3] = F::get(rb.vw, 1 * NM + mb);
-        st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, pg.h, st.o[mb], 0, 0, 0);
+        // field f = u*NM + mb holds slots (2u, 2u+1) of the lane's slot quad
+        va.u[0] = F::get(r.a.vw, 0 * NM + mb);
+        va.u[1] = F::get(r.a.vw, 1 * NM + mb);
+        va.u[2] = F::get(r.b.vw, 0 * NM + mb);
+        va.u[3] = F::get(r.b.vw, 1 * NM + mb);
+        st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, hi.h, st.o[mb], 0, 0, 0);
+        st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, lo.h, st.o[mb], 0, 0, 0);
       }
     }
-#undef TKV_SCORE_STEP
-#undef TKV_SCORE_GROUP
-#undef TKV_P_STEP
-#undef TKV_P_GROUP
   }
 
   // Page ids and live masks of up to 64 pages are fetched with one vector load each (lane L
@@ -422,7 +390,7 @@ struct ClassRunner {
         id.pid_b = __builtin_amdgcn_readlane(vpid, ib);
         id.live_b = 2 * pr + 1 < cnt ? __builtin_amdgcn_readlane(vmask, ib) : 0u;
         if ((id.live_a | id.live_b) == 0) continue;
-        PairRegs<D, BITS> r;
+        Pair r;
         issue_loads(r, id);
         compute(r, id);
       }
@@ -430,12 +398,12 @@ struct ClassRunner {
   }
 };
 
-template <int D, int G>
+template <int D, int GP>
 struct ItemLds {
-  _Float16 q[G * D];
-  float qsum[G * (D / 32)];
-  float m[4][G], l[4][G];
-  float acc[4][G][D];
+  _Float16 q[GP * D];
+  float qsum[GP * (D / 32)];
+  float m[4][GP], l[4][GP];
+  float acc[4][GP][D];
 };
 
 template <int D>
@@ -446,13 +414,14 @@ __device__ __forceinline__ float class_unit(int bits, int mb) {
 }
 
 // One workgroup of four waves per (query, kv-head, item).
-template <int D, int G>
+template <int D, int GP>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void decode_mfma_kernel(thinkv_view v, DecodeArgs a) {
-  constexpr int NG = D / 32, NM = D / 16;
+  using CL = Cols<D, GP>;
+  constexpr int NG = D / 32, NM = D / 16, CS = CL::CS, NSET = CL::NSET;
   const thinkv_config& c = v.cfg;
   const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
   const int seq = a.seq_ids[b];
-  __shared__ ItemLds<D, G> lds;
+  __shared__ ItemLds<D, GP> lds;
   int np[3], np_total = 0;
 #pragma unroll
   for (int k = 0; k < 3; ++k) {
@@ -463,7 +432,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   if (split >= ns) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int Hq = c.n_q_heads;
+  const int Hq = c.n_q_heads, G = Hq / c.n_kv_heads;
   for (int i = tid; i < G * D; i += 256)
     lds.q[i] = (_Float16)load_as_f32(a.q, ((int64_t)b * Hq + hkv * G) * D + i, a.q_dtype);
   __syncthreads();
@@ -479,11 +448,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   }
   __syncthreads();
 
-  WaveState<D> st;
+  WaveState<D, NSET> st;
 #pragma unroll
   for (int mb = 0; mb < NM; ++mb) st.o[mb] = float4v{0.f, 0.f, 0.f, 0.f};
-  st.oz = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int set = 0; set < NSET; ++set) st.oz[set] = 0.f;
+  st.l = 0.f;
   st.m = -INFINITY;
+  st.m_sub = 0.f;
   const int qpos = a.window > 0 ? a.q_pos[b] : 0;
   const int qd = lane >> 4, n = lane & 15;
 
@@ -497,44 +469,44 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
 #pragma unroll
     for (int mb = 0; mb < NM; ++mb) st.o[mb] *= class_unit<D>(bits, mb);
     if (bits == 2) {
-      ClassRunner<D, 2, G> cr(st, v, a, k, tab, p0, p1, wave, hkv, lds.q, lds.qsum, qpos);
+      ClassRunner<D, 2, GP> cr(st, v, a, k, tab, p0, p1, wave, hkv, G, lds.q, lds.qsum, qpos);
       cr.run();
     } else if (bits == 4) {
-      ClassRunner<D, 4, G> cr(st, v, a, k, tab, p0, p1, wave, hkv, lds.q, lds.qsum, qpos);
+      ClassRunner<D, 4, GP> cr(st, v, a, k, tab, p0, p1, wave, hkv, G, lds.q, lds.qsum, qpos);
       cr.run();
     } else {
-      ClassRunner<D, 8, G> cr(st, v, a, k, tab, p0, p1, wave, hkv, lds.q, lds.qsum, qpos);
+      ClassRunner<D, 8, GP> cr(st, v, a, k, tab, p0, p1, wave, hkv, G, lds.q, lds.qsum, qpos);
       cr.run();
     }
 #pragma unroll
     for (int mb = 0; mb < NM; ++mb) st.o[mb] *= 1.0f / class_unit<D>(bits, mb);
   }
 
-  // ---- fold.  The zero-point MFMA left rows 0..NG-1 = zero-point part of the output per
-  // group and row NG = sum of p (rows 0..3 live in row group 0, row 4 in row group 1);
-  // high and low columns are added, then every lane of the column fetches what it needs.
-  float zsum[NG], l;
-  {
-    float t[4];
+  // ---- fold.  The four lanes of a column (row quads) each hold a share of the denominator
+  // and of the zero-point sums; the tile of channel block mb is valid in the slice of its group.
+  const int gl = n / GP, head = n % GP;
+  float l = st.l;
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+  float zsum[NSET];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) t[r] = st.oz[r] + __shfl(st.oz[r], (lane & 48) | ((n + G) & 15), 64);
-#pragma unroll
-    for (int g = 0; g < NG; ++g) zsum[g] = __shfl(t[g], n, 64);
-    l = NG == 4 ? __shfl(t[0], 16 + n, 64) : __shfl(t[2], n, 64);
+  for (int set = 0; set < NSET; ++set) {
+    float z = st.oz[set];
+    z += __shfl_xor(z, 16, 64);
+    z += __shfl_xor(z, 32, 64);
+    zsum[set] = z;
   }
 #pragma unroll
   for (int mb = 0; mb < NM; ++mb) {
+    const int g = mb >> 1, set = g / CS;
+    if (gl == g % CS && head < G) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      float x = st.o[mb][r];
-      const float lo = __shfl(x, (lane & 48) | ((n + G) & 15), 64);
-      x = (x + lo) * 16777216.f + zsum[mb >> 1];
-      if (n < G) lds.acc[wave][n][16 * mb + 4 * qd + r] = x;
+      for (int r = 0; r < 4; ++r) lds.acc[wave][head][16 * mb + 4 * qd + r] = st.o[mb][r] * 16777216.f + zsum[set];
     }
   }
-  if (qd == 0 && n < G) {
-    lds.m[wave][n] = st.m;
-    lds.l[wave][n] = l;
+  if (qd == 0 && gl == 0 && head < G) {
+    lds.m[wave][head] = st.m;
+    lds.l[wave][head] = l;
   }
   __syncthreads();
   for (int i = tid; i < G * D; i += 256) {
@@ -567,17 +539,12 @@ template <int D>
 static int launch_d(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {
   const int G = v.cfg.n_q_heads / v.cfg.n_kv_heads;
   dim3 grid(a.max_split, v.cfg.n_kv_heads, a.B), blk(256);
-  switch (G) {
-    case 1: hipLaunchKernelGGL((decode_mfma_kernel<D, 1>), grid, blk, 0, st, v, a); break;
-    case 2: hipLaunchKernelGGL((decode_mfma_kernel<D, 2>), grid, blk, 0, st, v, a); break;
-    case 3: hipLaunchKernelGGL((decode_mfma_kernel<D, 3>), grid, blk, 0, st, v, a); break;
-    case 4: hipLaunchKernelGGL((decode_mfma_kernel<D, 4>), grid, blk, 0, st, v, a); break;
-    case 5: hipLaunchKernelGGL((decode_mfma_kernel<D, 5>), grid, blk, 0, st, v, a); break;
-    case 6: hipLaunchKernelGGL((decode_mfma_kernel<D, 6>), grid, blk, 0, st, v, a); break;
-    case 7: hipLaunchKernelGGL((decode_mfma_kernel<D, 7>), grid, blk, 0, st, v, a); break;
-    case 8: hipLaunchKernelGGL((decode_mfma_kernel<D, 8>), grid, blk, 0, st, v, a); break;
-    default: return THINKV_E_SHAPE;
-  }
+  if (G <= 4)
+    hipLaunchKernelGGL((decode_mfma_kernel<D, 4>), grid, blk, 0, st, v, a);
+  else if (G <= 8)
+    hipLaunchKernelGGL((decode_mfma_kernel<D, 8>), grid, blk, 0, st, v, a);
+  else
+    return THINKV_E_SHAPE;
   return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
 }
 

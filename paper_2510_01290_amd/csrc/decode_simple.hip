@@ -68,13 +68,12 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
       uint32_t kw[8];
       const uint32_t* kc = (const uint32_t*)(blk + geo.k_codes + lane * geo.chunk_bytes);
       for (int w = 0; w < geo.chunk_bytes / 4; ++w) kw[w] = kc[w];
-      const _Float16* ksc = (const _Float16*)(blk + geo.k_scale);
-      const _Float16* kzp = (const _Float16*)(blk + geo.k_zp);
+      const _Float16* kmeta = (const _Float16*)(blk + geo.k_meta);
       float part[GMAX];
       for (int g = 0; g < GMAX; ++g) part[g] = 0.f;
       for (int grp = 0; grp < NG; ++grp) {
-        const float sc = (float)ksc[t * NG + grp];
-        const float zp = (float)kzp[t * NG + grp];
+        const float sc = (float)kmeta[meta_index(t, grp)];
+        const float zp = (float)kmeta[meta_index(t, grp) + 4];
         for (int e = 0; e < 8; ++e) {
           const float kh = fmaf((float)field(kw, 4 * grp + (e >> 1), e & 1, bits), sc, zp);
           const int ch = 32 * grp + 8 * j + e;
@@ -105,15 +104,14 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
       uint32_t vw[8];
       const uint32_t* vc = (const uint32_t*)(blk + geo.v_codes + lane * geo.chunk_bytes);
       for (int w = 0; w < geo.chunk_bytes / 4; ++w) vw[w] = vc[w];
-      const _Float16* vsc = (const _Float16*)(blk + geo.v_scale);
-      const _Float16* vzp = (const _Float16*)(blk + geo.v_zp);
+      const _Float16* vmeta = (const _Float16*)(blk + geo.v_meta);
       for (int r = 0; r < 4; ++r) {
         const int tok = 4 * vq + r;
         float pr[GMAX];
         for (int g = 0; g < GMAX; ++g) pr[g] = (g < G) ? __shfl(p[g], tok, 64) : 0.f;
         for (int mb = 0; mb < NM; ++mb) {
-          const float sc = (float)vsc[tok * NG + (mb >> 1)];
-          const float zp = (float)vzp[(mb >> 1) * kPage + tok];
+          const float sc = (float)vmeta[meta_index(tok, mb >> 1)];
+          const float zp = (float)vmeta[meta_index(tok, mb >> 1) + 4];
           const float vh = fmaf((float)field(vw, (r >> 1) * NM + mb, r & 1, bits), sc, zp);
           for (int g = 0; g < GMAX; ++g)
             if (g < G) acc[g][mb] = fmaf(pr[g], vh, acc[g][mb]);

@@ -95,7 +95,7 @@ def test_binary32_input_below_zero_point_clamps():
 def _unpack_bit_by_bit(img, bits, D):
     """independent reader: walks the byte image as one big little-endian integer per chunk"""
     cb = layout.chunk_bytes(bits, D)
-    ok, ks_, kz_, vo, vs_, vz_ = layout.region_offsets(bits, D)
+    ok, km_, vo, vm_ = layout.region_offsets(bits, D)
     kc = np.zeros((16, D), dtype=np.uint8)
     vc = np.zeros((16, D), dtype=np.uint8)
     fph = 16 // bits
@@ -115,11 +115,19 @@ def _unpack_bit_by_bit(img, bits, D):
                 u, mb = f // (D // 16), f % (D // 16)
                 vc[4 * q + 2 * u + h, 16 * mb + m] = vcode
     ng = D // 32
-    halves = lambda o: np.array([int.from_bytes(img[o + 2 * i:o + 2 * i + 2].tobytes(), "little") for i in range(16 * ng)],
-                                dtype=np.uint16).view(np.float16)
-    slot_major = lambda o: halves(o).reshape(16, ng)
-    group_major = lambda o: np.ascontiguousarray(halves(o).reshape(ng, 16).T)
-    return kc, slot_major(ks_), slot_major(kz_), vc, slot_major(vs_), group_major(vz_)
+    def meta(o):
+        """binary16 number i of a meta region: unit i//8 = group*4 + slot quad; i%8 < 4 scale, else zero-point"""
+        sc = np.zeros((16, ng), dtype=np.float16)
+        zp = np.zeros((16, ng), dtype=np.float16)
+        for i in range(16 * ng * 2):
+            val = np.array([int.from_bytes(img[o + 2 * i:o + 2 * i + 2].tobytes(), "little")], dtype=np.uint16).view(np.float16)[0]
+            unit, e = divmod(i, 8)
+            grp, quad = divmod(unit, 4)
+            (sc if e < 4 else zp)[4 * quad + e % 4, grp] = val
+        return sc, zp
+    ks, kz = meta(km_)
+    vs, vz = meta(vm_)
+    return kc, ks, kz, vc, vs, vz
 
 
 @pytest.mark.parametrize("D", [64, 128])
