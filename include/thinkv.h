@@ -80,9 +80,9 @@ typedef struct {
  *   dev_status      [max_seqs * n_layers + 1] THINKV_ST_* flags
  *
  * Byte layout of one page: n_kv_heads blocks of thinkv_block_bytes(); a block is
- * [K codes: 64 chunks of CB = (head_dim/32)*b bytes][K scale][K zero-point][V codes: 64 chunks]
- * [V scale][V zero-point]; each scale / zero-point array is 16*NG binary16 (NG = head_dim/32)
- * indexed slot*NG + group, except the V zero-points, indexed group*16 + slot.
+ * [K codes: 64 chunks of CB = (head_dim/32)*b bytes][K meta][V codes: 64 chunks][V meta];
+ * a meta region is NG*4 units (NG = head_dim/32) of eight binary16: unit group*4 + slot/4 holds
+ * the scales of its four slots (slot%4 = 0..3), then their four zero-points.
  * Inside a chunk a b-bit code sits at
  * bit 32*(f / FPH) + 16*h + b*(f % FPH), FPH = 16/b, with
  *   K, slot t, channel c: chunk 16*((c%32)/8) + t, f = 4*(c/32) + (c%8)/2, h = c%2
@@ -118,7 +118,9 @@ size_t thinkv_append_workspace_bytes(const thinkv_config* cfg, int32_t n_tok);
 size_t thinkv_decode_workspace_bytes(const thinkv_config* cfg, int32_t B, int32_t max_ctx_pages);
 
 /* Puts a view into the empty state: free stacks filled so that pages come out 0,1,2,...,
- * tables -1, counters and flags 0, slot_pos -1.  Arena bytes are not touched. */
+ * tables -1, counters and flags 0, slot_pos -1, arenas zero-filled (attention reads the
+ * never-written slots of a partly filled page and discards them by their live bit, so their
+ * scales and zero-points have to be finite numbers).  arena[c] must be 16-byte aligned. */
 int thinkv_init_view(const thinkv_view* view, void* stream /* hipStream_t */);
 
 /*

@@ -101,18 +101,17 @@ class Cache:
     """Device buffers of one cache (torch tensors) and the thinkv_view that points at them."""
 
     def __init__(self, n_layers, n_q_heads, n_kv_heads, head_dim, bits_of_class, max_seqs, max_pages,
-                 arena_pages, device="cuda:0", zero_arena=True):
+                 arena_pages, device="cuda:0"):
         load()
         self.device = torch.device(device)
         self.cfg = make_config(n_layers, n_q_heads, n_kv_heads, head_dim, bits_of_class, max_seqs, max_pages)
         self.bits_of_class = tuple(bits_of_class)
         self.arena_pages = tuple(int(x) for x in arena_pages)
         d = self.device
-        mk = torch.zeros if zero_arena else torch.empty
         self.page_bytes = [thinkv_page_bytes(self.cfg, b) for b in bits_of_class]
         if 0 in self.page_bytes:
             raise RuntimeError("unsupported geometry")
-        self.arena = [mk(max(1, n) * pb, dtype=torch.uint8, device=d) for n, pb in zip(self.arena_pages, self.page_bytes)]
+        self.arena = [torch.empty(max(1, n) * pb, dtype=torch.uint8, device=d) for n, pb in zip(self.arena_pages, self.page_bytes)]
         self.free_stack = [torch.empty(max(1, n), dtype=torch.int32, device=d) for n in self.arena_pages]
         self.free_top = torch.empty(3, dtype=torch.int32, device=d)
         self.block_table = torch.empty((max_seqs, n_layers, 3, max_pages), dtype=torch.int32, device=d)

@@ -42,12 +42,15 @@ static int check_view(const thinkv_view* v) {
   return THINKV_OK;
 }
 
-// Pages per work item: sized so that B * Hkv * ceil(max_ctx_pages / ppi) workgroups fill the
-// 256 compute units (four workgroups each) about twice, with a floor that keeps the
-// per-item set-up small against the item.
+// Pages per work item.  A compute unit holds three workgroups of the decode kernel, so the chip
+// holds 768; a launch whose B * Hkv * ceil(max_ctx_pages / ppi) workgroups fill it a whole
+// number of times (twice, where the context allows) leaves no ragged last round.  The floor
+// keeps the per-item set-up small against the item.
 static int pages_per_item(const thinkv_config& c, int B, int max_ctx_pages) {
-  const int64_t total = (int64_t)max_ctx_pages * B * c.n_kv_heads;
-  int ppi = (int)((total + 2047) / 2048);
+  const int64_t heads = (int64_t)B * c.n_kv_heads;
+  int64_t n_items = (1536 + heads / 2) / heads;   // items per (query, kv-head)
+  if (n_items < 1) n_items = 1;
+  int ppi = (int)((max_ctx_pages + n_items - 1) / n_items);
   if (const char* e = getenv("THINKV_PPI")) ppi = atoi(e);  // dev knob
   return ppi < 32 ? 32 : ppi;
 }

@@ -171,11 +171,6 @@ struct PairRegs {
   PageRegs<D, BITS, NSET> a, b;
 };
 
-// 0xFFFF in each half of the result whose slot (bit 2j, bit 2j+1 of m4) is live
-__device__ __forceinline__ uint32_t half_mask(uint32_t m4, int j) {
-  return ((m4 >> (2 * j)) & 1u ? 0x0000FFFFu : 0u) | ((m4 >> (2 * j + 1)) & 1u ? 0xFFFF0000u : 0u);
-}
-
 // One wave's share of an item: page pairs wave, wave+4, ... of tab[p0..p1).
 template <int D, int BITS, int GP>
 struct ClassRunner {
@@ -194,6 +189,7 @@ struct ClassRunner {
   H8 bq[NG];           // B operands of the score MFMAs: q of group g in slice g % CS, zeros elsewhere
   float qs[NSET];      // 2^(OMIN-24) * sum_{i in group} q_i of this lane's (slice group, head)
   float kappa;         // 2^(24-OMIN) * softmax_scale * log2(e): MFMA score units -> log2 domain
+  float neg1;          // -1, kept opaque so that x - (float)h stays one fused mixed-precision instruction
 
   __device__ __forceinline__ ClassRunner(WaveState<D, NSET>& st_, const thinkv_view& v_, const DecodeArgs& a_, int cls_,
                                          const int32_t* tab_, int p0_, int p1_, int wave_, int hkv_, int G, const _Float16* s_q,
@@ -206,6 +202,8 @@ struct ClassRunner {
     const bool used = gl < CS && head < G;
     const int glc = gl < CS ? gl : CS - 1;   // unused slices read slice CS-1's unit (finite, multiplied by zeros)
     kappa = (float)(1 << (24 - F::OMIN)) * a.scale_log2e;
+    neg1 = -1.0f;
+    asm volatile("" : "+v"(neg1));
 #pragma unroll
     for (int s = 0; s < NSET; ++s) {
       const int g = s * CS + glc;
@@ -254,7 +252,7 @@ struct ClassRunner {
   {                                                                                              \
     float acc = 0.f;                                                                             \
     _Pragma("unroll") for (int set = 0; set < NSET; ++set) {                                     \
-      const float z = half_of<R>(r.km[set].z, r.km[set].w) * qs[set];                            \
+      const float z = fmaf(half_of<R>(r.km[set].z, r.km[set].w), qs[set], 0.0f);                 \
       const float t = fmaf(half_of<R>(r.km[set].x, r.km[set].y), c[set][R], z);                  \
       acc = set == 0 ? t : acc + t;                                                              \
     }                                                                                            \
@@ -271,26 +269,14 @@ struct ClassRunner {
     float sa[4], sb[4];
     page_scores(r.a, sa);
     page_scores(r.b, sb);
-    uint4 vma[NSET], vmb[NSET];
-#pragma unroll
-    for (int set = 0; set < NSET; ++set) {
-      vma[set] = r.a.vm[set];
-      vmb[set] = r.b.vm[set];
-    }
-    // ---------------- dead slots: score -inf, and V scale / zero-point 0 so that whatever bytes the
-    // slot holds never meet the arithmetic
+    // ---------------- dead slots: score -inf, hence p = 0.  Their scales and zero-points are finite
+    // (stale, or zero in a slot never written: arenas start zero-filled), so they drop out of every sum.
     if ((live_a & live_b) != 0xFFFFu) {
       const uint32_t la = (live_a >> (4 * qd)) & 0xFu, lb = (live_b >> (4 * qd)) & 0xFu;
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         sa[r4] = ((la >> r4) & 1u) ? sa[r4] : -INFINITY;
         sb[r4] = ((lb >> r4) & 1u) ? sb[r4] : -INFINITY;
-      }
-      const uint32_t a01 = half_mask(la, 0), a23 = half_mask(la, 1), b01 = half_mask(lb, 0), b23 = half_mask(lb, 1);
-#pragma unroll
-      for (int set = 0; set < NSET; ++set) {
-        vma[set].x &= a01; vma[set].y &= a23; vma[set].z &= a01; vma[set].w &= a23;
-        vmb[set].x &= b01; vmb[set].y &= b23; vmb[set].z &= b01; vmb[set].w &= b23;
       }
     }
     // ---------------- online softmax over the 8 scores of this lane; the running maximum only
@@ -321,10 +307,10 @@ struct ClassRunner {
       float xa[4], xb[4], z = st.oz[set];
 #define TKV_PV(R)                                                     \
   {                                                                   \
-    z = fmaf(half_of<R>(vma[set].z, vma[set].w), pa[R], z);           \
-    z = fmaf(half_of<R>(vmb[set].z, vmb[set].w), pb[R], z);           \
-    xa[R] = half_of<R>(vma[set].x, vma[set].y) * pa[R];               \
-    xb[R] = half_of<R>(vmb[set].x, vmb[set].y) * pb[R];               \
+    z = fmaf(half_of<R>(r.a.vm[set].z, r.a.vm[set].w), pa[R], z);           \
+    z = fmaf(half_of<R>(r.b.vm[set].z, r.b.vm[set].w), pb[R], z);           \
+    xa[R] = fmaf(half_of<R>(r.a.vm[set].x, r.a.vm[set].y), pa[R], 0.0f);    \
+    xb[R] = fmaf(half_of<R>(r.b.vm[set].x, r.b.vm[set].y), pb[R], 0.0f);    \
   }
       TKV_PV(0) TKV_PV(1) TKV_PV(2) TKV_PV(3)
 #undef TKV_PV
@@ -335,10 +321,10 @@ struct ClassRunner {
       hi.u[1] = pack_rne(xa[2], xa[3]);
       hi.u[2] = pack_rne(xb[0], xb[1]);
       hi.u[3] = pack_rne(xb[2], xb[3]);
-      lo.u[0] = pack_rne(fmaf(-1.0f, half_lo(hi.u[0]), xa[0]), fmaf(-1.0f, half_hi(hi.u[0]), xa[1]));
-      lo.u[1] = pack_rne(fmaf(-1.0f, half_lo(hi.u[1]), xa[2]), fmaf(-1.0f, half_hi(hi.u[1]), xa[3]));
-      lo.u[2] = pack_rne(fmaf(-1.0f, half_lo(hi.u[2]), xb[0]), fmaf(-1.0f, half_hi(hi.u[2]), xb[1]));
-      lo.u[3] = pack_rne(fmaf(-1.0f, half_lo(hi.u[3]), xb[2]), fmaf(-1.0f, half_hi(hi.u[3]), xb[3]));
+      lo.u[0] = pack_rne(fmaf(neg1, half_lo(hi.u[0]), xa[0]), fmaf(neg1, half_hi(hi.u[0]), xa[1]));
+      lo.u[1] = pack_rne(fmaf(neg1, half_lo(hi.u[1]), xa[2]), fmaf(neg1, half_hi(hi.u[1]), xa[3]));
+      lo.u[2] = pack_rne(fmaf(neg1, half_lo(hi.u[2]), xb[0]), fmaf(neg1, half_hi(hi.u[2]), xb[1]));
+      lo.u[3] = pack_rne(fmaf(neg1, half_lo(hi.u[3]), xb[2]), fmaf(neg1, half_hi(hi.u[3]), xb[3]));
 #pragma unroll
       for (int mm = 0; mm < 2 * CS; ++mm) {
         const int mb = 2 * CS * set + mm;

@@ -62,8 +62,20 @@ int launch_evict(const thinkv_view& v, int layer, const int32_t* ev_seq, const i
   return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
 }
 
+// Zero-fill of an arena in 16-byte stores (page sizes are multiples of 16 bytes).  A page can
+// hold slots that were never written; attention reads them and discards them by their live
+// bit, which is only safe if their scales and zero-points are finite numbers.
+__global__ __launch_bounds__(256) void arena_clear_kernel(uint4* p, int64_t n16) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) p[i] = uint4{0u, 0u, 0u, 0u};
+}
+
 int launch_init(const thinkv_view& v, hipStream_t st) {
   hipLaunchKernelGGL(init_kernel, dim3(1024), dim3(256), 0, st, v);
+  for (int k = 0; k < 3; ++k) {
+    const int64_t n16 = v.arena_pages[k] * (int64_t)v.cfg.n_kv_heads * block_geom(v.cfg.bits_of_class[k], v.cfg.head_dim).block_bytes / 16;
+    if (n16 > 0) hipLaunchKernelGGL(arena_clear_kernel, dim3(2048), dim3(256), 0, st, (uint4*)v.arena[k], n16);
+  }
   return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
 }
 
