@@ -19,6 +19,10 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK = 8.0e12
+# HBM bytes of one decode-attention launch (split-K kernel + merge) on the default workload, from
+# rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a copy of known size
+# (profiles/decode_attention_cfg2_32k_hbm_traffic.txt); other workloads report null
+TRAFFIC_DEFAULT_BYTES = 746.5e6
 
 
 def main():
@@ -31,6 +35,8 @@ def main():
     ap.add_argument("--variant", default="fast", choices=["fast", "valu"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (gives FETCH_SIZE / WRITE_SIZE a known size to be scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (one MI355X per box); --gpus must be 1")
@@ -128,21 +134,30 @@ def main():
     attn_s = float(attn_ms.mean()) * 1e-3
     achieved = attn_bytes / attn_s / 1e9
     line = {
-        "metric": "hybrid-quant paged decode attention, algorithmic HBM GB/s of one decode step at 32k ctx",
+        "metric": "hybrid-quant paged decode attn: \u00b5s/step + HBM GB/s (% of peak) at 32k ctx",
         "value": step_bytes / (ms_step * 1e-3) / 1e9,
         "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "us_per_step": ms_step * 1e3, "attn_us_mean": float(attn_ms.mean() * 1e3), "attn_us_min": float(attn_ms.min() * 1e3),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 codes x f16 q on MFMA, f32 accumulate" if args.variant == "fast" else "f32",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16" if args.variant == "fast" else "f32",
         "data": "synthetic",
         "config": {"workload": wl.name + " (R1-Llama-8B layer: 32 q / 8 kv heads, head_dim 128, bf16; T8/R4/E2, 30% E + 10% R evicted and refilled)",
                    "batch": args.batch, "live_tokens_per_seq": int(sum(live_by_class) / args.batch), "page_size": 16,
                    "live_by_class_TER": live_by_class, "kernel": args.variant, "build_seconds": round(build_s, 1),
                    "step": "evict 1 + append 1 + decode attention, per sequence"},
         "roofline": {"bound": "hbm", "kernel": "decode attention (split-K kernel + merge)", "achieved": achieved, "peak": HBM_PEAK / 1e9,
-                     "unit": "GB/s", "frac": achieved * 1e9 / HBM_PEAK, "traffic": None, "algorithmic_bytes_per_launch": attn_bytes},
+                     "unit": "GB/s", "frac": achieved * 1e9 / HBM_PEAK,
+                     "traffic": TRAFFIC_DEFAULT_BYTES if (args.ctx == 32768 and args.batch == 16 and args.variant == "fast") else None, "algorithmic_bytes_per_launch": attn_bytes},
         "host_wall_ms_per_step": wall / args.steps * 1e3,
     }
+    if args.copy_calibration:
+        # 2^28 int16 elements: reads 512 MiB, writes 512 MiB per call, in an elementwise kernel
+        # whose name (a unary functor on short) no other kernel of this run shares
+        src = torch.ones(1 << 28, dtype=torch.int16, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, args, nsteps, ev_handles, new_cls, np, torch, synth, parity)
     print(json.dumps(line))
