@@ -122,9 +122,10 @@ def main():
 
     # ---- algorithmic bytes of one step (from the tables as they stand after the run)
     live_by_class = []
+    sm = (gc.slot_mask[:, 0] & 0xFFFF).cpu().numpy().astype(np.uint16)        # [seq][type][list position]
+    npg = gc.n_pages[:, 0].cpu().numpy()
     for c in range(3):
-        m = (gc.page_mask[c][:gc.arena_pages[c]] & 0xFFFF).cpu().numpy().astype(np.uint16)
-        live_by_class.append(int(np.unpackbits(m.view(np.uint8)).sum()))
+        live_by_class.append(int(sum(np.unpackbits(sm[s, c, :npg[s, c]].view(np.uint8)).sum() for s in range(args.batch))))
     pages_visited = int(gc.n_pages[:, 0].sum().item())
     H, D, Hq = g.n_kv_heads, g.head_dim, g.n_q_heads
     kv_bytes = sum(n * H * 2 * (D * b // 8 + D // 32 * 4) for n, b in zip(live_by_class, g.bits_of_class))

@@ -73,8 +73,10 @@ typedef struct {
  *   block_table     [max_seqs][n_layers][3][max_pages] physical page numbers, -1 = unused
  *   n_pages         [max_seqs][n_layers][3]
  *   page_filled[c]  [arena_pages[c]] slots ever written, 0..16 (the paper's "# Filled")
- *   page_mask[c]    [arena_pages[c]] bits 0..15: slot holds a live token;
- *                                    bits 16..31: slot soft-evicted and reclaimable
+ *   slot_mask       [max_seqs][n_layers][3][max_pages], parallel to block_table (the table's
+ *                   "eviction mask" column): bits 0..15: slot holds a live token; bits 16..31:
+ *                   slot soft-evicted and reclaimable.  Kept in list order so that attention and
+ *                   append read the masks of a page list as one contiguous run.
  *   slot_pos[c]     [arena_pages[c]][16] logical position of the token in the slot, -1 = none
  *   n_live          [max_seqs][n_layers] live tokens
  *   dev_status      [max_seqs * n_layers + 1] THINKV_ST_* flags
@@ -97,7 +99,7 @@ typedef struct {
   int32_t* block_table;     /* DEVICE */
   int32_t* n_pages;         /* DEVICE */
   uint8_t* page_filled[3];  /* DEVICE */
-  uint32_t* page_mask[3];   /* DEVICE */
+  uint32_t* slot_mask;      /* DEVICE */
   int32_t* slot_pos[3];     /* DEVICE */
   int32_t* n_live;          /* DEVICE */
   uint32_t* dev_status;     /* DEVICE */

@@ -27,7 +27,7 @@ class Config(C.Structure):
 class View(C.Structure):
     _fields_ = [("cfg", Config), ("arena", C.c_void_p * 3), ("arena_pages", C.c_int64 * 3),
                 ("free_stack", C.c_void_p * 3), ("free_top", C.c_void_p), ("block_table", C.c_void_p),
-                ("n_pages", C.c_void_p), ("page_filled", C.c_void_p * 3), ("page_mask", C.c_void_p * 3),
+                ("n_pages", C.c_void_p), ("page_filled", C.c_void_p * 3), ("slot_mask", C.c_void_p),
                 ("slot_pos", C.c_void_p * 3), ("n_live", C.c_void_p), ("dev_status", C.c_void_p)]
 
 
@@ -117,7 +117,7 @@ class Cache:
         self.block_table = torch.empty((max_seqs, n_layers, 3, max_pages), dtype=torch.int32, device=d)
         self.n_pages = torch.empty((max_seqs, n_layers, 3), dtype=torch.int32, device=d)
         self.page_filled = [torch.empty(max(1, n), dtype=torch.uint8, device=d) for n in self.arena_pages]
-        self.page_mask = [torch.empty(max(1, n), dtype=torch.int32, device=d) for n in self.arena_pages]
+        self.slot_mask = torch.empty((max_seqs, n_layers, 3, max_pages), dtype=torch.int32, device=d)
         self.slot_pos = [torch.empty((max(1, n), 16), dtype=torch.int32, device=d) for n in self.arena_pages]
         self.n_live = torch.empty((max_seqs, n_layers), dtype=torch.int32, device=d)
         self.dev_status = torch.empty(max_seqs * n_layers + 1, dtype=torch.int32, device=d)
@@ -128,10 +128,10 @@ class Cache:
             v.arena_pages[k] = self.arena_pages[k]
             v.free_stack[k] = self.free_stack[k].data_ptr()
             v.page_filled[k] = self.page_filled[k].data_ptr()
-            v.page_mask[k] = self.page_mask[k].data_ptr()
             v.slot_pos[k] = self.slot_pos[k].data_ptr()
         v.free_top = self.free_top.data_ptr()
         v.block_table = self.block_table.data_ptr()
+        v.slot_mask = self.slot_mask.data_ptr()
         v.n_pages = self.n_pages.data_ptr()
         v.n_live = self.n_live.data_ptr()
         v.dev_status = self.dev_status.data_ptr()

@@ -35,10 +35,10 @@ static int check_view(const thinkv_view* v) {
   if (rc) return rc;
   for (int k = 0; k < 3; ++k) {
     if (v->arena_pages[k] < 0 || v->arena_pages[k] > 0x7fffffff) return THINKV_E_INVALID_ARG;
-    if (v->arena_pages[k] > 0 && (!v->arena[k] || !v->free_stack[k] || !v->page_filled[k] || !v->page_mask[k] || !v->slot_pos[k]))
+    if (v->arena_pages[k] > 0 && (!v->arena[k] || !v->free_stack[k] || !v->page_filled[k] || !v->slot_pos[k]))
       return THINKV_E_INVALID_ARG;
   }
-  if (!v->free_top || !v->block_table || !v->n_pages || !v->n_live || !v->dev_status) return THINKV_E_INVALID_ARG;
+  if (!v->free_top || !v->block_table || !v->slot_mask || !v->n_pages || !v->n_live || !v->dev_status) return THINKV_E_INVALID_ARG;
   return THINKV_OK;
 }
 

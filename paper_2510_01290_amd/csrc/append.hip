@@ -125,12 +125,13 @@ __global__ __launch_bounds__(256) void append_plan_kernel(thinkv_view v, int lay
       }
       const int np = v.n_pages[npages_index(c, s, layer, k)];
       const int32_t* tab = v.block_table + table_base(c, s, layer, k);
+      const uint32_t* msk = v.slot_mask + table_base(c, s, layer, k);
       int* pre = ws.pre + ((int64_t)s * 3 + k) * c.max_pages;
       int runR = 0;
       for (int b0 = 0; b0 < np; b0 += 256) {
         int pi = b0 + tid;
         int cnt = 0;
-        if (pi < np) cnt = __popc(v.page_mask[k][tab[pi]] >> 16);
+        if (pi < np) cnt = __popc(msk[pi] >> 16);
         int ex;
         int tot = block_excl_scan(cnt, &ex, s_scan);
         if (pi < np) pre[pi] = runR + ex;
@@ -218,7 +219,7 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
           }
           pi = lo;
           pid = tab[pi];
-          uint32_t e = v.page_mask[cls][pid] >> 16;
+          uint32_t e = v.slot_mask[table_base(c, s, layer, cls) + pi] >> 16;
           for (int j = k - pre[pi]; j > 0; --j) e &= e - 1;
           slot = __ffs(e) - 1;
           ok = 1;
@@ -337,10 +338,10 @@ __global__ __launch_bounds__(256) void append_commit_kernel(thinkv_view v, int l
     const int n = pl.n[k], R = pl.R[k], tail = pl.tail[k], np = pl.np_old[k], grant = pl.grant[k];
     if (n == 0) continue;
     int32_t* tab = v.block_table + table_base(c, s, layer, k);
+    uint32_t* msk = v.slot_mask + table_base(c, s, layer, k);
     const int* pre = ws.pre + ((int64_t)s * 3 + k) * c.max_pages;
     for (int pi = tid; pi < np; pi += 256) {
-      const int pid = tab[pi];
-      uint32_t m = v.page_mask[k][pid];
+      uint32_t m = msk[pi];
       uint32_t e = m >> 16;
       int take = n - pre[pi];
       const int have = __popc(e);
@@ -354,11 +355,12 @@ __global__ __launch_bounds__(256) void append_commit_kernel(thinkv_view v, int l
       m = (m | bits) & ~(bits << 16);
       if (pi == np - 1 && tail > 0 && n > R) {
         const int add = (n - R) < tail ? (n - R) : tail;
+        const int pid = tab[pi];
         const int f = v.page_filled[k][pid];
         m |= ((1u << add) - 1u) << f;
         v.page_filled[k][pid] = (uint8_t)(f + add);
       }
-      v.page_mask[k][pid] = m;
+      msk[pi] = m;
     }
     for (int i = tid; i < grant; i += 256) {
       const int pid = v.free_stack[k][ws.avail_old[k] - 1 - (pl.base[k] + i)];
@@ -366,7 +368,7 @@ __global__ __launch_bounds__(256) void append_commit_kernel(thinkv_view v, int l
       cnt = cnt > kPage ? kPage : cnt;
       tab[np + i] = pid;
       v.page_filled[k][pid] = (uint8_t)cnt;
-      v.page_mask[k][pid] = (1u << cnt) - 1u;
+      msk[np + i] = (1u << cnt) - 1u;
       for (int sl = cnt; sl < kPage; ++sl) v.slot_pos[k][(int64_t)pid * kPage + sl] = -1;
     }
     const int cap = R + tail + kPage * grant;

@@ -352,7 +352,7 @@ struct ClassRunner {
       uint32_t vmask = 0;
       if (lane < cnt) {
         vpid = tab[p0 + base + lane];
-        vmask = v.page_mask[cls][vpid] & 0xFFFFu;
+        vmask = v.slot_mask[(tab - v.block_table) + p0 + base + lane] & 0xFFFFu;
       }
       if (a.window > 0) {
         // visibility of the 16 slots of each page: lane L walks the slots of its own page

@@ -53,9 +53,10 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
     const BlockGeom geo = block_geom(bits, D);
     const int p0 = (int)((int64_t)split * np[k] / ns), p1 = (int)((int64_t)(split + 1) * np[k] / ns);
     const int32_t* tab = v.block_table + table_base(c, seq, a.layer, k);
+    const uint32_t* msk = v.slot_mask + table_base(c, seq, a.layer, k);
     for (int pi = p0 + wave; pi < p1; pi += 4) {
       const int pid = tab[pi];
-      uint32_t live = v.page_mask[k][pid] & 0xFFFFu;
+      uint32_t live = msk[pi] & 0xFFFFu;
       if (a.window > 0) {
         const int sp = v.slot_pos[k][(int64_t)pid * kPage + t];
         const int d = qpos - sp;

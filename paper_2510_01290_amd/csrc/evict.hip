@@ -23,11 +23,11 @@ __global__ __launch_bounds__(256) void evict_kernel(thinkv_view v, int layer, co
     atomicOr(status, THINKV_ST_BAD_SLOT);
     return;
   }
-  const int pid = v.block_table[table_base(c, s, layer, cls) + pi];
+  uint32_t* mask = &v.slot_mask[table_base(c, s, layer, cls) + pi];
   const uint32_t bit = 1u << slot;
-  const uint32_t old = atomicAnd(&v.page_mask[cls][pid], ~bit);
+  const uint32_t old = atomicAnd(mask, ~bit);
   if (old & bit) {
-    atomicOr(&v.page_mask[cls][pid], bit << 16);
+    atomicOr(mask, bit << 16);
     atomicSub(&v.n_live[sl_index(c, s, layer)], 1);
   } else {
     atomicOr(status, THINKV_ST_EVICT_DEAD);
@@ -43,13 +43,15 @@ __global__ __launch_bounds__(256) void init_kernel(thinkv_view v) {
     for (int64_t i = tid; i < n; i += stride) {
       v.free_stack[k][i] = (int32_t)(n - 1 - i);
       v.page_filled[k][i] = 0;
-      v.page_mask[k][i] = 0;
     }
     for (int64_t i = tid; i < n * kPage; i += stride) v.slot_pos[k][i] = -1;
     if (tid == 0) v.free_top[k] = (int32_t)n;
   }
   const int64_t nt = (int64_t)c.max_seqs * c.n_layers * 3 * c.max_pages;
-  for (int64_t i = tid; i < nt; i += stride) v.block_table[i] = -1;
+  for (int64_t i = tid; i < nt; i += stride) {
+    v.block_table[i] = -1;
+    v.slot_mask[i] = 0;
+  }
   const int64_t nsl = (int64_t)c.max_seqs * c.n_layers;
   for (int64_t i = tid; i < nsl * 3; i += stride) v.n_pages[i] = 0;
   for (int64_t i = tid; i < nsl; i += stride) v.n_live[i] = 0;

@@ -58,7 +58,7 @@ def gpu_tables(gc):
     t = dict(table=gc.block_table.cpu().numpy(), n_pages=gc.n_pages.cpu().numpy(), n_live=gc.n_live.cpu().numpy(),
              status=gc.dev_status.cpu().numpy().view(np.uint32), free_top=gc.free_top.cpu().numpy())
     t["filled"] = [x.cpu().numpy() for x in gc.page_filled]
-    t["mask"] = [x.cpu().numpy().view(np.uint32) for x in gc.page_mask]
+    t["mask"] = gc.slot_mask.cpu().numpy().view(np.uint32)      # [seq][layer][type][list position]
     t["slot_pos"] = [x.cpu().numpy() for x in gc.slot_pos]
     t["free_stack"] = [x.cpu().numpy() for x in gc.free_stack]
     return t
@@ -77,14 +77,15 @@ def compare_bookkeeping_full(oc, gc):
             for c in range(3):
                 n = int(oc.n_pages[s, l, c])
                 assert np.array_equal(t["table"][s, l, c, :n], oc.table[s, l, c, :n]), ("block_table", s, l, c)
+                pages = oc.table[s, l, c, :n]
+                assert np.array_equal(t["mask"][s, l, c, :n] & 0xFFFF, oc.valid[c][pages]), ("live bits", s, l, c)
+                assert np.array_equal(t["mask"][s, l, c, :n] >> 16, oc.evict[c][pages]), ("evict bits", s, l, c)
     for c in range(3):
         n = int(oc.cfg.arena_pages[c])
         top = int(oc.free_top[c])
         assert np.array_equal(t["free_stack"][c][:top], oc.free_stack[c][:top]), "free_stack"
         used = np.setdiff1d(np.arange(n), oc.free_stack[c][:top])
         assert np.array_equal(t["filled"][c][used], oc.filled[c][used]), "filled"
-        assert np.array_equal(t["mask"][c][used] & 0xFFFF, oc.valid[c][used]), "live bits"
-        assert np.array_equal(t["mask"][c][used] >> 16, oc.evict[c][used]), "evict bits"
         assert np.array_equal(t["slot_pos"][c][used], oc.slot_pos[c][used]), "slot_pos"
 
 
@@ -100,8 +101,8 @@ def compare_sequences(oc, gc, pairs, check_bytes=True):
             po = oc.table[so, l, c, :n]
             pg = t["table"][sg, l, c, :n]
             assert np.array_equal(t["filled"][c][pg], oc.filled[c][po]), ("filled", sg, l, c)
-            assert np.array_equal(t["mask"][c][pg] & 0xFFFF, oc.valid[c][po]), ("live bits", sg, l, c)
-            assert np.array_equal(t["mask"][c][pg] >> 16, oc.evict[c][po]), ("evict bits", sg, l, c)
+            assert np.array_equal(t["mask"][sg, l, c, :n] & 0xFFFF, oc.valid[c][po]), ("live bits", sg, l, c)
+            assert np.array_equal(t["mask"][sg, l, c, :n] >> 16, oc.evict[c][po]), ("evict bits", sg, l, c)
             assert np.array_equal(t["slot_pos"][c][pg], oc.slot_pos[c][po]), ("slot_pos", sg, l, c)
             if check_bytes and n:
                 pb = gc.page_bytes[c]
