@@ -356,3 +356,46 @@ def config_gptoss(seed=3, n_seqs=128, n_layers=24, ctx_lo=4096, ctx_hi=32768, re
 def stress_contexts(seed=4, n_seqs=256, lo=1024, hi=65536):
     rng = np.random.default_rng(seed + 2000)
     return np.exp(rng.uniform(np.log(lo), np.log(hi), size=n_seqs)).astype(np.int64)
+
+
+def stress_decode(name, geom, seed, ctx_tokens, n_steps, evict_every=16, evict_frac=0.05, lowest=E):
+    """Config 5: bulk-build ragged contexts, then n_steps decode steps; a step appends one token
+    per sequence, and every `evict_every`-th step ends with an eviction pass that removes
+    `evict_frac` of the live tokens of the lowest-importance class (seeded uniform choice, drawn
+    per layer).  The decode query of the last step is the one the attention check uses."""
+    rng = np.random.default_rng(seed)
+    ctx = np.asarray(ctx_tokens, dtype=np.int64)
+    n_seqs, L = len(ctx), geom.n_layers
+    classes = []
+    for s in range(n_seqs):
+        c, _ = thought_classes(rng, int(ctx[s]) + n_steps)
+        classes.append(c[:int(ctx[s]) + n_steps])
+    ops = []
+    seqs = np.arange(n_seqs, dtype=np.int32)
+    ones = np.ones(n_seqs, dtype=np.int64)
+    for l in range(L):
+        ops.append(Append(l, seqs, np.zeros(n_seqs, np.int64), ctx.copy()))
+        live_low = [np.flatnonzero(classes[s][:ctx[s]] == lowest) for s in range(n_seqs)]
+        for st in range(n_steps):
+            ops.append(Append(l, seqs, ctx + st, ones))
+            for s in range(n_seqs):
+                if classes[s][ctx[s] + st] == lowest:
+                    live_low[s] = np.append(live_low[s], ctx[s] + st)
+            if (st + 1) % evict_every == 0:
+                es, ep = [], []
+                for s in range(n_seqs):
+                    n = int(round(evict_frac * len(live_low[s])))
+                    if n == 0:
+                        continue
+                    drop = rng.choice(live_low[s], size=n, replace=False)
+                    live_low[s] = np.setdiff1d(live_low[s], drop)
+                    es.append(np.full(n, s, dtype=np.int32))
+                    ep.append(np.sort(drop))
+                if es:
+                    ops.append(Evict(l, np.concatenate(es), np.concatenate(ep)))
+    return Workload(name, geom, seed, n_seqs, classes, ops, tuple([0] * L), (ctx + n_steps - 1).astype(np.int32))
+
+
+def config_stress(seed=4, n_seqs=256, n_layers=32, n_steps=64):
+    g = Geometry(n_layers, 32, 8, 128, "bf16")
+    return stress_decode("cfg5-stress-8b", g, seed, stress_contexts(seed, n_seqs), n_steps)

@@ -34,6 +34,11 @@ def arena_need(wl, slack=1.25):
     return tuple(int(x) for x in tot)
 
 
+def arena_need_one(wl, s):
+    """per-class page counts that hold ONE sequence in ONE layer (for an oracle that replays a sample)"""
+    return tuple(int((wl.classes[s] == c).sum() + 15) // 16 + 4 for c in range(3))
+
+
 def max_pages_need(wl):
     m = 1
     for s in range(wl.n_seqs):

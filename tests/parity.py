@@ -149,48 +149,70 @@ class Case:
     wl: object
     sample: list = None          # (seq, layer) pairs the oracle replays; None = everything
     variants: tuple = ("fast", "valu")
+    cross_check_all: bool = False   # sampled cases: also compare the two device kernels on every sequence
 
 
 def case_tiny(seed=0, bits=(8, 2, 4)):
     return Case(synth.config_tiny(seed, bits))
 
 
+def _check_rows(worst, got, lse, ref, ref_lse, dt, variant, where):
+    err = np.abs(got - ref)
+    allow = TOL + (half_ulp(ref, dt) if dt != torch.float32 else 0.0)
+    key = f"attn_max_abs_err_{'f32' if dt == torch.float32 else str(dt).split('.')[-1]}" + ("" if variant == "fast" else "_valu")
+    worst[key] = max(worst.get(key, 0.0), float(err.max()))
+    assert np.all(err <= allow), (key, where, float(err.max()))
+    fin = np.isfinite(ref_lse)
+    assert np.array_equal(np.isfinite(lse), fin), ("lse finiteness", where)
+    assert np.all(np.abs(lse[fin] - ref_lse[fin]) <= 1e-3), ("lse", where, float(np.abs(lse[fin] - ref_lse[fin]).max()))
+
+
 def run_case(case, check_bytes=True, out_dtypes=(torch.float32,)):
+    """Replays the workload on the device; replays all of it (or the sampled (sequence, layer)
+    pairs) on the oracle; compares handles, bookkeeping, page bytes and attention.  Attention is
+    always launched for the whole batch, as the benchmark launches it; in sampled cases the rows
+    of the sampled sequences are the ones compared with the oracle."""
     wl = case.wl
     gc = make_gpu_cache(wl)
     gr = synth.ScriptRunner(wl, GpuBackend(gc)).run()
     torch.cuda.synchronize()
+    assert int(gc.dev_status.abs().sum().item()) == 0, "device flags set while replaying the workload"
     res = {"workload": wl.name}
+    all_seqs = list(range(wl.n_seqs))
+    per_layer = {}          # layer -> list of (workload seq, oracle seq, oracle cache)
     if case.sample is None:
         ob = make_oracle(wl)
         orr = synth.ScriptRunner(wl, ob).run()
         for key in gr.handle:
             assert np.array_equal(gr.handle[key], orr.handle[key]), ("handles", key)
         compare_bookkeeping_full(ob.cache, gc)
-        pairs = [(s, s, l) for s in range(wl.n_seqs) for l in range(wl.geom.n_layers)]
+        pairs = [(s, s, l) for s in all_seqs for l in range(wl.geom.n_layers)]
         compare_sequences(ob.cache, gc, pairs, check_bytes)
-        att = [(l, list(range(wl.n_seqs)), list(range(wl.n_seqs)), ob.cache) for l in range(wl.geom.n_layers)]
+        for l in range(wl.geom.n_layers):
+            per_layer[l] = [(s, s, ob.cache) for s in all_seqs]
     else:
-        att = []
         for s, l in case.sample:
-            ob = make_oracle(wl)
+            ob = make_oracle(wl, max_seqs=wl.n_seqs, arena_pages=backends.arena_need_one(wl, s))
             orr = synth.ScriptRunner(wl, ob, layers=[l], seqs=[s]).run()
             assert np.array_equal(gr.handle[(l, s)], orr.handle[(l, s)]), ("handles", s, l)
             compare_sequences(ob.cache, gc, [(s, s, l)], check_bytes)
-            att.append((l, [s], [s], ob.cache))
+            per_layer.setdefault(l, []).append((s, s, ob.cache))
     worst = {}
-    for l, so, sw, oc in att:
-        ref, ref_lse = oracle_attention(oc, wl, l, so, sw)
+    for l, rows in per_layer.items():
+        refs = {}
+        for sw, so, oc in rows:
+            r, rl = oracle_attention(oc, wl, l, [so], [sw])
+            refs[sw] = (r[0], rl[0])
+        outs = {}
         for variant in case.variants:
             for dt in out_dtypes:
-                got, lse = gpu_attention(gc, wl, gr, l, dt, variant, seqs=sw)
-                err = np.abs(got - ref)
-                allow = TOL + (half_ulp(ref, dt) if dt != torch.float32 else 0.0)
-                key = f"attn_max_abs_err_{'f32' if dt == torch.float32 else str(dt).split('.')[-1]}" + ("" if variant == "fast" else "_valu")
-                worst[key] = max(worst.get(key, 0.0), float(err.max()))
-                assert np.all(err <= allow), (key, l, float(err.max()))
-                fin = np.isfinite(ref_lse)
-                assert np.array_equal(np.isfinite(lse), fin)
-                assert np.all(np.abs(lse[fin] - ref_lse[fin]) <= 1e-3), ("lse", float(np.abs(lse[fin] - ref_lse[fin]).max()))
+                got, lse = gpu_attention(gc, wl, gr, l, dt, variant, seqs=all_seqs)
+                outs[(variant, dt)] = got
+                for sw in refs:
+                    _check_rows(worst, got[sw], lse[sw], refs[sw][0], refs[sw][1], dt, variant, (l, sw))
+        if case.cross_check_all and ("fast", torch.float32) in outs and ("valu", torch.float32) in outs:
+            d = float(np.abs(outs[("fast", torch.float32)] - outs[("valu", torch.float32)]).max())
+            worst["fast_vs_valu_all_rows"] = max(worst.get("fast_vs_valu_all_rows", 0.0), d)
+            assert d <= TOL, ("fast vs valu kernel", l, d)
     res.update(worst)
     return res
