@@ -88,7 +88,17 @@ __global__ __launch_bounds__(256) void append_plan_kernel(thinkv_view v, int lay
   __shared__ int s_scan[5];
   const thinkv_config& c = v.cfg;
   const int s = blockIdx.x, tid = threadIdx.x;
-  if (tid == 0) {
+  if (n_tok <= 4096) {
+    // small call (decode-style): every thread looks at a few tokens and the two that see the
+    // sequence's first and last token publish the range
+    if (tid == 0) s_rng[0] = s_rng[1] = 0;
+    __syncthreads();
+    for (int i = tid; i < n_tok; i += 256) {
+      if (tok_seq[i] != s) continue;
+      if (i == 0 || tok_seq[i - 1] != s) s_rng[0] = i;
+      if (i == n_tok - 1 || tok_seq[i + 1] != s) s_rng[1] = i + 1;
+    }
+  } else if (tid == 0) {
     int lo = 0, hi = n_tok;  // lower_bound(s)
     while (lo < hi) {
       int mid = (lo + hi) >> 1;
@@ -103,6 +113,15 @@ __global__ __launch_bounds__(256) void append_plan_kernel(thinkv_view v, int lay
     s_rng[1] = lo2;
   }
   __syncthreads();
+  // page counts and never-used slots in the last page of every type: three lanes walk the three
+  // dependent load chains (page count -> last page id -> fill count) side by side
+  __shared__ int s_np[3], s_tail[3];
+  if (tid < 3) {
+    const int npk = v.n_pages[npages_index(c, s, layer, tid)];
+    s_np[tid] = npk;
+    s_tail[tid] = npk > 0 ? kPage - (int)v.page_filled[tid][v.block_table[table_base(c, s, layer, tid) + npk - 1]] : 0;
+  }
+  __syncthreads();
   const int lo = s_rng[0], hi = s_rng[1];
   SeqPlan pl;
   pl.lo = lo;
@@ -113,36 +132,46 @@ __global__ __launch_bounds__(256) void append_plan_kernel(thinkv_view v, int lay
     pl.np_old[k] = 0;
   }
   if (lo < hi) {
+    // rank of every token among the call's tokens of its type: the three types' 0/1 flags are
+    // scanned together, ten bits each (a chunk holds at most 256 tokens)
+    int running[3] = {0, 0, 0};
+    for (int b0 = lo; b0 < hi; b0 += 256) {
+      const int i = b0 + tid;
+      const int cl = i < hi ? (int)tok_class[i] : 3;
+      const int flag = cl < 3 ? 1 << (10 * cl) : 0;
+      int ex;
+      const int tot = block_excl_scan(flag, &ex, s_scan);
+      if (cl < 3) ws.tok_rank[i] = running[cl] + ((ex >> (10 * cl)) & 1023);
+      for (int k = 0; k < 3; ++k) running[k] += (tot >> (10 * k)) & 1023;
+    }
+    // exclusive prefix of the reclaimable-slot counts over each page list: every thread takes a
+    // contiguous run of pages of every type (all masks are requested before the first scan), so
+    // one block scan per type suffices
+    int mine[3], q0[3], q1[3];
     for (int k = 0; k < 3; ++k) {
-      int running = 0;
-      for (int b0 = lo; b0 < hi; b0 += 256) {
-        int i = b0 + tid;
-        int is = (i < hi && tok_class[i] == k) ? 1 : 0;
-        int ex;
-        int tot = block_excl_scan(is, &ex, s_scan);
-        if (is) ws.tok_rank[i] = running + ex;
-        running += tot;
-      }
-      const int np = v.n_pages[npages_index(c, s, layer, k)];
-      const int32_t* tab = v.block_table + table_base(c, s, layer, k);
+      const uint32_t* msk = v.slot_mask + table_base(c, s, layer, k);
+      const int np = s_np[k], per = (np + 255) / 256;
+      q0[k] = tid * per;
+      q1[k] = q0[k] + per < np ? q0[k] + per : np;
+      mine[k] = 0;
+      for (int pi = q0[k]; pi < q1[k]; ++pi) mine[k] += __popc(msk[pi] >> 16);
+    }
+    for (int k = 0; k < 3; ++k) {
       const uint32_t* msk = v.slot_mask + table_base(c, s, layer, k);
       int* pre = ws.pre + ((int64_t)s * 3 + k) * c.max_pages;
-      int runR = 0;
-      for (int b0 = 0; b0 < np; b0 += 256) {
-        int pi = b0 + tid;
-        int cnt = 0;
-        if (pi < np) cnt = __popc(msk[pi] >> 16);
-        int ex;
-        int tot = block_excl_scan(cnt, &ex, s_scan);
-        if (pi < np) pre[pi] = runR + ex;
-        runR += tot;
+      const int np = s_np[k];
+      int ex;
+      const int runR = block_excl_scan(mine[k], &ex, s_scan);
+      for (int pi = q0[k]; pi < q1[k]; ++pi) {
+        pre[pi] = ex;
+        ex += __popc(msk[pi] >> 16);
       }
-      int tail = np > 0 ? kPage - (int)v.page_filled[k][tab[np - 1]] : 0;
-      int need = running - runR - tail;
+      const int tail = s_tail[k];
+      int need = running[k] - runR - tail;
       need = need > 0 ? (need + kPage - 1) / kPage : 0;
-      int room = c.max_pages - np;
+      const int room = c.max_pages - np;
       need = need < room ? need : room;
-      pl.n[k] = running;
+      pl.n[k] = running[k];
       pl.R[k] = runR;
       pl.tail[k] = tail;
       pl.np_old[k] = np;
@@ -182,22 +211,27 @@ __global__ __launch_bounds__(256) void append_grant_kernel(thinkv_view v, Append
 }
 
 // ---------------------------------------------------------------------------------------------
-// place: one block per token.
+// place: one block per (token, share of the kv-heads); every block of a token derives the same
+// slot, block 0 records it.
 template <int D>
 __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int layer, const void* __restrict__ k_new,
                                                            const void* __restrict__ v_new, const int32_t* __restrict__ tok_seq,
                                                            const int32_t* __restrict__ tok_pos, const uint8_t* __restrict__ tok_class,
-                                                           int32_t* __restrict__ tok_handle, int n_tok, int in_dtype, AppendWs ws) {
+                                                           int32_t* __restrict__ tok_handle, int n_tok, int in_dtype, AppendWs ws,
+                                                           int heads_per_block) {
   constexpr int NG = D / kGroup;        // groups per row
   constexpr int NM = D / 16;            // 16-channel blocks per row
   constexpr int HP = 256 / (2 * D);     // heads handled per pass
-  __shared__ int s_place[4];            // type, page id, slot, ok
+  __shared__ int s_place[5];            // type, page id, slot, ok, index in the page list
   __shared__ uint8_t s_codes[HP][2][D];
   __shared__ uint32_t s_meta[HP][2][NG];
   const thinkv_config& c = v.cfg;
   const int i = blockIdx.x, tid = threadIdx.x;
+  // slot selection.  Thread 0 settles every case that is a closed form; the page of the k-th
+  // reclaimable slot (k < R) is found by all threads, each testing a stride of the page list.
+  __shared__ int s_find[4];   // 1 = search wanted, sequence, type, rank
   if (tid == 0) {
-    int ok = 0, cls = 0, pid = 0, slot = 0, pi = 0;
+    int ok = 0, cls = 0, pid = 0, slot = 0, pi = 0, find = 0, k = 0;
     const int s = tok_seq[i];
     if (s < 0 || s >= c.max_seqs) {
       atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEQ);
@@ -207,22 +241,11 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
       if (cls > 2) {
         atomicOr(&v.dev_status[sl_index(c, s, layer)], THINKV_ST_BAD_CLASS);
       } else if (i >= pl.lo && i < pl.hi) {
-        const int k = ws.tok_rank[i];
+        k = ws.tok_rank[i];
         const int32_t* tab = v.block_table + table_base(c, s, layer, cls);
         const int R = pl.R[cls], tail = pl.tail[cls], np = pl.np_old[cls];
         if (k < R) {
-          const int* pre = ws.pre + ((int64_t)s * 3 + cls) * c.max_pages;
-          int lo = 0, hi = np - 1;  // largest pi with pre[pi] <= k
-          while (lo < hi) {
-            int mid = (lo + hi + 1) >> 1;
-            if (pre[mid] <= k) lo = mid; else hi = mid - 1;
-          }
-          pi = lo;
-          pid = tab[pi];
-          uint32_t e = v.slot_mask[table_base(c, s, layer, cls) + pi] >> 16;
-          for (int j = k - pre[pi]; j > 0; --j) e &= e - 1;
-          slot = __ffs(e) - 1;
-          ok = 1;
+          find = 1;
         } else if (k < R + tail) {
           pi = np - 1;
           pid = tab[pi];
@@ -239,12 +262,32 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
         }
       }
     }
+    s_find[0] = find; s_find[1] = s; s_find[2] = cls; s_find[3] = k;
+    s_place[0] = cls; s_place[1] = pid; s_place[2] = slot; s_place[3] = ok; s_place[4] = pi;
+  }
+  __syncthreads();
+  if (s_find[0]) {
+    const int s = s_find[1], cls = s_find[2], k = s_find[3];
+    const int np = ws.plan[s].np_old[cls];
+    const int64_t tb = table_base(c, s, layer, cls);
+    const int* pre = ws.pre + ((int64_t)s * 3 + cls) * c.max_pages;
+    for (int pi = tid; pi < np; pi += 256) {
+      uint32_t e = v.slot_mask[tb + pi] >> 16;
+      const int first = pre[pi];
+      if (k >= first && k < first + __popc(e)) {   // exactly one page of the list
+        for (int j = k - first; j > 0; --j) e &= e - 1;
+        s_place[1] = v.block_table[tb + pi];
+        s_place[2] = __ffs(e) - 1;
+        s_place[3] = 1;
+        s_place[4] = pi;
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0 && blockIdx.y == 0) {
+    const int cls = s_place[0], pid = s_place[1], slot = s_place[2], ok = s_place[3], pi = s_place[4];
     if (ok) v.slot_pos[cls][(int64_t)pid * kPage + slot] = tok_pos[i];
     if (tok_handle) tok_handle[i] = ok ? THINKV_HANDLE(cls, pi, slot) : -1;
-    s_place[0] = cls;
-    s_place[1] = pid;
-    s_place[2] = slot;
-    s_place[3] = ok;
   }
   __syncthreads();
   if (!s_place[3]) return;
@@ -257,9 +300,10 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
   const int CB = g.chunk_bytes, FPH = 16 / bits, CPB = 8 / bits;  // codes per byte
 
   const int hs = tid / (2 * D), r = tid % (2 * D), kind = r / D, ch = r % D;
-  for (int h0 = 0; h0 < H; h0 += HP) {
+  const int h_end = (int)(blockIdx.y + 1) * heads_per_block < H ? (int)(blockIdx.y + 1) * heads_per_block : H;
+  for (int h0 = blockIdx.y * heads_per_block; h0 < h_end; h0 += HP) {
     const int h = h0 + hs;
-    if (h < H) {
+    if (h < h_end) {
       const void* src = kind ? v_new : k_new;
       const float x = load_as_f32(src, ((int64_t)i * H + h) * D + ch, in_dtype);
       float mn = x, mx = x;
@@ -389,12 +433,18 @@ int launch_append(const thinkv_view& v, int layer, const void* k_new, const void
   const int S = v.cfg.max_seqs;
   hipLaunchKernelGGL(append_plan_kernel, dim3(S), dim3(256), 0, st, v, layer, tok_seq, tok_class, n_tok, ws);
   hipLaunchKernelGGL(append_grant_kernel, dim3(1), dim3(256), 0, st, v, ws);
+  // A decode-style call (few tokens) spreads the kv-heads of a token over several workgroups so
+  // that their load-quantise-store chains run side by side; a bulk call keeps one workgroup per
+  // token, which repeats the slot selection once instead of once per pass.
+  const int H = v.cfg.n_kv_heads, hp = v.cfg.head_dim == 128 ? 1 : 2;
+  const int hpb = n_tok <= 4096 ? hp : ((H + hp - 1) / hp) * hp;
+  const dim3 grid(n_tok, (H + hpb - 1) / hpb);
   if (v.cfg.head_dim == 128)
-    hipLaunchKernelGGL(append_place_kernel<128>, dim3(n_tok), dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
-                       tok_class, tok_handle, n_tok, in_dtype, ws);
+    hipLaunchKernelGGL(append_place_kernel<128>, grid, dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
+                       tok_class, tok_handle, n_tok, in_dtype, ws, hpb);
   else
-    hipLaunchKernelGGL(append_place_kernel<64>, dim3(n_tok), dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
-                       tok_class, tok_handle, n_tok, in_dtype, ws);
+    hipLaunchKernelGGL(append_place_kernel<64>, grid, dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
+                       tok_class, tok_handle, n_tok, in_dtype, ws, hpb);
   hipLaunchKernelGGL(append_commit_kernel, dim3(S), dim3(256), 0, st, v, layer, ws);
   return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
 }
