@@ -210,17 +210,24 @@ struct ClassRunner {
       meta_off[s] = (g * 4 + qd) * 16;
       qs[s] = used ? s_qsum[head * NG + g] * (1.0f / (float)(1 << (24 - F::OMIN))) : 0.f;
     }
-    // q of this lane's head, channels 32g + 8qd + e, scaled down by the residual power of two its code carries
+    // q of this lane's head and slice group(s), channels 32g + 8qd + e: one 16-byte LDS read per
+    // column set, scaled down by the residual power of two the codes of those fields carry (exact:
+    // power-of-two scaling of binary16 values), then dealt to the group's operand; the operands of
+    // the other groups are zero in this lane.  Branch-free, so the reads are issued together.
+    H8 mine[NSET];
+#pragma unroll
+    for (int s = 0; s < NSET; ++s) {
+      const int g = s * CS + glc;
+      const uint4 raw = *(const uint4*)(s_q + (used ? head : 0) * D + 32 * g + 8 * qd);
+      mine[s].u[0] = raw.x; mine[s].u[1] = raw.y; mine[s].u[2] = raw.z; mine[s].u[3] = raw.w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) mine[s].h[e] *= (_Float16)(1.0f / (float)(1 << F::rel_of(e >> 1)));   // rel_of depends on the field's parity only
+    }
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      const bool mine = used && (g % CS) == gl;
+      const bool on = used && (g % CS) == gl;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int f = 4 * g + (e >> 1);
-        float x = mine ? (float)s_q[head * D + 32 * g + 8 * qd + e] : 0.f;
-        x *= 1.0f / (float)(1 << F::rel_of(f));
-        bq[g].h[e] = (_Float16)x;   // exact: power-of-two scaling of a binary16 value
-      }
+      for (int w = 0; w < 4; ++w) bq[g].u[w] = on ? mine[g / CS].u[w] : 0u;
     }
   }
 
