@@ -42,20 +42,34 @@ static int check_view(const thinkv_view* v) {
   return THINKV_OK;
 }
 
-// Pages per work item.  A compute unit holds three workgroups of the decode kernel, so the chip
-// holds 768; a launch whose B * Hkv * ceil(max_ctx_pages / ppi) workgroups fill it a whole
-// number of times (twice, where the context allows) leaves no ragged last round.  The floor
-// keeps the per-item set-up small against the item.
-static int pages_per_item(const thinkv_config& c, int B, int max_ctx_pages) {
-  const int64_t heads = (int64_t)B * c.n_kv_heads;
-  int64_t n_items = (1536 + heads / 2) / heads;   // items per (query, kv-head)
-  if (n_items < 1) n_items = 1;
-  int ppi = (int)((max_ctx_pages + n_items - 1) / n_items);
-  if (const char* e = getenv("THINKV_PPI")) ppi = atoi(e);  // dev knob
-  return ppi < 32 ? 32 : ppi;
+// Work-item sizes.  A compute unit holds three workgroups of the decode kernel, so the chip
+// holds 768, and every item pays a fixed price (query set-up, three type switches, fold) worth
+// about a fifth of a 180-page item.  Where the launch has few (query, kv-head) pairs the items
+// are therefore sized so that the workgroups of the longest sequences fill the chip exactly
+// once; where it has many, so that the launch runs about four rounds of equal items, whose
+// end is levelled well enough by their number.  The floor keeps the set-up small against the item.
+constexpr int kMinPagesPerItem = 32;
+
+static int small_items() {
+  if (const char* e = getenv("THINKV_NSMALL")) return atoi(e);  // dev knob
+  return 0;
 }
 
-static int split_bound(int max_ctx_pages, int ppi) { return (max_ctx_pages + ppi - 1) / ppi + 1; }
+static int pages_per_item(const thinkv_config& c, int B, int max_ctx_pages) {
+  const int64_t heads = (int64_t)B * c.n_kv_heads;
+  int64_t n_big = heads <= 384 ? 768 / heads : (4 * 768 + heads - 1) / heads;   // big items per (query, kv-head)
+  if (n_big < 1) n_big = 1;
+  int ppi = (int)((max_ctx_pages + n_big - 1) / n_big);
+  if (const char* e = getenv("THINKV_PPI")) ppi = atoi(e);  // dev knob
+  return ppi < kMinPagesPerItem ? kMinPagesPerItem : ppi;
+}
+
+// grid extents for sequences of at most max_ctx_pages pages
+static void split_bounds(int max_ctx_pages, int ppi, int* max_big, int* max_small) {
+  const ItemPlan p = plan_items(ppi, small_items(), 1 << 30, 1 << 30, max_ctx_pages);
+  *max_big = p.n_big > 0 ? p.n_big : 1;
+  *max_small = small_items() > 0 ? small_items() : 1;
+}
 
 static int decode_common(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
                          const int32_t* seq_ids, const int32_t* q_pos, int32_t B, int32_t window, float softmax_scale,
@@ -84,7 +98,9 @@ static int decode_common(const thinkv_view* view, int32_t layer, const void* q, 
   a.q_dtype = q_dtype;
   a.out_dtype = out_dtype;
   a.ppi = pages_per_item(view->cfg, B, max_ctx_pages);
-  a.max_split = split_bound(max_ctx_pages, a.ppi);
+  a.n_small = small_items();
+  split_bounds(max_ctx_pages, a.ppi, &a.max_big, &a.max_small);
+  a.max_split = a.max_big + a.max_small;
   if (a.max_split > 1024) return THINKV_E_SHAPE;   // merge kernel keeps one weight per item in LDS
   a.scale_log2e = softmax_scale * 1.4426950408889634f;
   hipStream_t st = (hipStream_t)stream;
@@ -115,8 +131,10 @@ size_t thinkv_append_workspace_bytes(const thinkv_config* cfg, int32_t n_tok) {
 
 size_t thinkv_decode_workspace_bytes(const thinkv_config* cfg, int32_t B, int32_t max_ctx_pages) {
   if (check_config(cfg) || B < 0 || max_ctx_pages < 0) return 0;
-  // the item size never drops below 32 pages, whatever the batch
-  const int ms = split_bound(max_ctx_pages, 32);
+  // the item size never drops below kMinPagesPerItem pages, whatever the batch
+  int mb, msm;
+  split_bounds(max_ctx_pages, kMinPagesPerItem, &mb, &msm);
+  const int ms = mb + msm;
   return (size_t)(B > 0 ? B : 1) * cfg->n_q_heads * ms * (cfg->head_dim + 2) * sizeof(float);
 }
 

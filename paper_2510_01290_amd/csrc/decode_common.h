@@ -1,13 +1,17 @@
 // Split-K bookkeeping shared by the decode-attention kernels and the merge kernel.
 //
-// The context of one (query, kv-head) is cut into n = ceil(pages / ppi) work items.  Item s
-// takes, from each of the three per-type page lists, the pages [s*np_c/n, (s+1)*np_c/n), so
-// every item gets the same share of every precision and items of one sequence cost the same.
-// ppi (pages per item) is chosen on the host so that a launch fills the machine a whole
-// number of times; n is derived on the device from the page counts, identically in the
-// attention and merge kernels.  Each item writes, per query head, a partial (m, l, acc[D]):
-// running maximum of the scaled scores in the log2 domain, sum of 2^(score - m), and the
-// unnormalised weighted value sum.
+// The context of one (query, kv-head) is cut into work items.  Item sizes are counted in
+// quarter units: the sequence's pages make U = ceil(4 * pages / ppi) units; the last n_small of
+// them (a host choice, possibly none) become SMALL items of one unit, the others are dealt to
+// BIG items of four units (about ppi pages; the last big item may be shorter).  The grid lists
+// every big item of the launch before any small one, so the small items start last and can
+// level the end of a launch that runs several rounds of workgroups.  An item takes the
+// same fraction [u0 / U, u1 / U) of each of the three per-type page lists, so items of one
+// sequence cost the same per unit whatever the precision mix.  ppi is chosen on the host so
+// that the big items fill the machine a whole number of times; item counts are derived on the
+// device from the page counts, identically in the attention and merge kernels.  Each item
+// writes, per query head, a partial (m, l, acc[D]): running maximum of the scaled scores in the
+// log2 domain, sum of 2^(score - m), and the unnormalised weighted value sum.
 #pragma once
 #include "common.h"
 
@@ -21,14 +25,57 @@ struct DecodeArgs {
   const int32_t* q_pos;
   float* partial;       // [B][Hq][max_split][D + 2]
   int layer, B, window, q_dtype, out_dtype;
-  int ppi;              // pages per item
-  int max_split;        // grid extent of the split dimension (>= items of any sequence)
+  int ppi;              // pages per big item
+  int n_small;          // small items wanted per (query, kv-head)
+  int max_big, max_small;   // grid extents (>= the counts of any sequence)
+  int max_split;        // max_big + max_small: partial rows per (query, head)
   float scale_log2e;    // softmax_scale * log2(e)
 };
 
-__device__ inline int n_items_of(const DecodeArgs& a, int np_total) {
-  const int s = (np_total + a.ppi - 1) / a.ppi;
-  return s < a.max_split ? s : a.max_split;
+struct ItemPlan {
+  int n_big, n_small, units;
+};
+
+__host__ __device__ inline ItemPlan plan_items(int ppi, int n_small_wanted, int max_big, int max_small, int np_total) {
+  ItemPlan p;
+  p.units = (int)(((int64_t)np_total * 4 + ppi - 1) / ppi);
+  p.n_small = p.units < n_small_wanted ? p.units : n_small_wanted;
+  p.n_big = (p.units - p.n_small + 3) / 4;
+  if (p.n_big > max_big) p.n_big = max_big;           // never on a launch sized by the host's bound
+  if (p.n_small > max_small) p.n_small = max_small;
+  return p;
+}
+
+// item i of the plan covers units [u0, u1) of p.units; items 0 .. n_big-1 are the big ones
+__device__ inline void item_units(const ItemPlan& p, int i, int* u0, int* u1) {
+  const int big_units = p.units - p.n_small;
+  if (i < p.n_big) {
+    *u0 = 4 * i;
+    *u1 = 4 * i + 4 < big_units ? 4 * i + 4 : big_units;
+  } else {
+    *u0 = big_units + (i - p.n_big);
+    *u1 = *u0 + 1;
+  }
+}
+
+// Which (query, kv-head, item) workgroup `id` of the 1-D grid works on: all big items of the
+// launch come first, then all small ones.  `j` is the item's index among the big (or small)
+// items of its (query, kv-head); the caller checks it against the sequence's plan.
+__device__ inline void locate_workgroup(const DecodeArgs& a, int n_kv_heads, int id, int* b, int* hkv, int* j, bool* small) {
+  const int n_big_total = a.max_big * n_kv_heads * a.B;
+  int rest;
+  if (id < n_big_total) {
+    *j = id % a.max_big;
+    rest = id / a.max_big;
+    *small = false;
+  } else {
+    id -= n_big_total;
+    *j = id % a.max_small;
+    rest = id / a.max_small;
+    *small = true;
+  }
+  *hkv = rest % n_kv_heads;
+  *b = rest / n_kv_heads;
 }
 
 __device__ inline int64_t partial_index(const DecodeArgs& a, int Hq, int D, int b, int hq, int split) {

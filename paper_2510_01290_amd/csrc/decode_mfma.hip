@@ -412,7 +412,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   using CL = Cols<D, GP>;
   constexpr int NG = D / 32, NM = D / 16, CS = CL::CS, NSET = CL::NSET;
   const thinkv_config& c = v.cfg;
-  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+  int b, hkv, item_j;
+  bool item_small;
+  locate_workgroup(a, c.n_kv_heads, blockIdx.x, &b, &hkv, &item_j, &item_small);
   const int seq = a.seq_ids[b];
   __shared__ ItemLds<D, GP> lds;
   int np[3], np_total = 0;
@@ -421,8 +423,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
     np[k] = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
     np_total += np[k];
   }
-  const int ns = n_items_of(a, np_total);
-  if (split >= ns) return;
+  const ItemPlan plan = plan_items(a.ppi, a.n_small, a.max_big, a.max_small, np_total);
+  if (item_j >= (item_small ? plan.n_small : plan.n_big)) return;
+  const int split = item_small ? plan.n_big + item_j : item_j;   // the item's row among the partials
+  int u0, u1;
+  item_units(plan, split, &u0, &u1);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int Hq = c.n_q_heads, G = Hq / c.n_kv_heads;
@@ -454,9 +459,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
 
   // The running output is kept in the units of the class being walked (its codes carry a
   // power of two that depends on the bit width) and re-based at class boundaries.
-  for (int k = 0; k < 3; ++k) {
+  // Waves and workgroups start on different types: a pair of 8-bit pages moves three times the
+  // bytes of a pair of 2-bit pages for the same arithmetic, so if every wave walked the types in
+  // the same order the whole chip would swing between bandwidth-bound and issue-bound phases.
+  const int rot = (wave + split + hkv + b) % 3;
+  for (int kk = 0; kk < 3; ++kk) {
+    const int k = kk + rot < 3 ? kk + rot : kk + rot - 3;
     const int bits = c.bits_of_class[k];
-    const int p0 = (int)((int64_t)split * np[k] / ns), p1 = (int)((int64_t)(split + 1) * np[k] / ns);
+    const int npk = k == 0 ? np[0] : (k == 1 ? np[1] : np[2]);
+    const int p0 = (int)((int64_t)u0 * npk / plan.units), p1 = (int)((int64_t)u1 * npk / plan.units);
     if (p1 <= p0) continue;
     const int32_t* tab = v.block_table + table_base(c, seq, a.layer, k);
 #pragma unroll
@@ -531,7 +542,7 @@ int decode_mfma_supported(const thinkv_config& c) {
 template <int D>
 static int launch_d(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {
   const int G = v.cfg.n_q_heads / v.cfg.n_kv_heads;
-  dim3 grid(a.max_split, v.cfg.n_kv_heads, a.B), blk(256);
+  dim3 grid(a.max_split * v.cfg.n_kv_heads * a.B), blk(256);
   if (G <= 4)
     hipLaunchKernelGGL((decode_mfma_kernel<D, 4>), grid, blk, 0, st, v, a);
   else if (G <= 8)

@@ -19,7 +19,9 @@ template <int D>
 __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, DecodeArgs a) {
   constexpr int NG = D / kGroup, NM = D / 16, GMAX = 8;
   const thinkv_config& c = v.cfg;
-  const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+  int b, hkv, item_j;
+  bool item_small;
+  locate_workgroup(a, c.n_kv_heads, blockIdx.x, &b, &hkv, &item_j, &item_small);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int Hq = c.n_q_heads, H = c.n_kv_heads, G = Hq / H;
   const int seq = a.seq_ids[b];
@@ -32,8 +34,11 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
     np[k] = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
     np_total += np[k];
   }
-  const int ns = n_items_of(a, np_total);
-  if (split >= ns) return;
+  const ItemPlan plan = plan_items(a.ppi, a.n_small, a.max_big, a.max_small, np_total);
+  if (item_j >= (item_small ? plan.n_small : plan.n_big)) return;
+  const int split = item_small ? plan.n_big + item_j : item_j;   // the item's row among the partials
+  int u0, u1;
+  item_units(plan, split, &u0, &u1);
   for (int i = tid; i < G * D; i += 256)
     s_q[i / D][i % D] = load_as_f32(a.q, ((int64_t)b * Hq + hkv * G) * D + i, a.q_dtype) * a.scale_log2e;
   __syncthreads();
@@ -51,7 +56,7 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
   for (int k = 0; k < 3; ++k) {
     const int bits = c.bits_of_class[k];
     const BlockGeom geo = block_geom(bits, D);
-    const int p0 = (int)((int64_t)split * np[k] / ns), p1 = (int)((int64_t)(split + 1) * np[k] / ns);
+    const int p0 = (int)((int64_t)u0 * np[k] / plan.units), p1 = (int)((int64_t)u1 * np[k] / plan.units);
     const int32_t* tab = v.block_table + table_base(c, seq, a.layer, k);
     const uint32_t* msk = v.slot_mask + table_base(c, seq, a.layer, k);
     for (int pi = p0 + wave; pi < p1; pi += 4) {
@@ -170,7 +175,8 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(thinkv_view v, DecodeAr
   int np_total = 0;
   for (int k = 0; k < 3; ++k)
     np_total += (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
-  const int ns = n_items_of(a, np_total);
+  const ItemPlan plan = plan_items(a.ppi, a.n_small, a.max_big, a.max_small, np_total);
+  const int ns = plan.n_big + plan.n_small;
   const float* src = a.partial + partial_index(a, Hq, D, b, hq, 0);
   // maximum over splits
   float m_loc = -INFINITY;
@@ -217,7 +223,7 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(thinkv_view v, DecodeAr
 }
 
 int launch_decode_simple(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {
-  dim3 grid(a.max_split, v.cfg.n_kv_heads, a.B);
+  dim3 grid(a.max_split * v.cfg.n_kv_heads * a.B);
   if (v.cfg.head_dim == 128)
     hipLaunchKernelGGL(decode_simple_kernel<128>, grid, dim3(256), 0, st, v, a);
   else
