@@ -79,6 +79,8 @@ typedef struct {
  *                   append read the masks of a page list as one contiguous run.
  *   slot_pos[c]     [arena_pages[c]][16] logical position of the token in the slot, -1 = none
  *   n_live          [max_seqs][n_layers] live tokens
+ *   work_counters   [n_layers][max_seqs][n_kv_heads][4] scratch of thinkv_decode_attention (shared
+ *                   work queues of the workgroups of one query and kv-head); zero between calls
  *   dev_status      [max_seqs * n_layers + 1] THINKV_ST_* flags
  *
  * Byte layout of one page: n_kv_heads blocks of thinkv_block_bytes(); a block is
@@ -102,6 +104,7 @@ typedef struct {
   uint32_t* slot_mask;      /* DEVICE */
   int32_t* slot_pos[3];     /* DEVICE */
   int32_t* n_live;          /* DEVICE */
+  uint32_t* work_counters;  /* DEVICE */
   uint32_t* dev_status;     /* DEVICE */
 } thinkv_view;
 

@@ -26,10 +26,18 @@
 // read back in the slice of its group.  The zero-point part of the output and the softmax
 // denominator are lane-local binary32 sums.
 //
-// One workgroup of four waves per (query, kv-head, item); an item holds an equal share of the
-// pages of every thought type and walks them type by type, so the bit width is a
-// compile-time constant of each inner loop; a wave takes every fourth page pair; the four
-// waves are merged through LDS into one partial (m, l, acc) per query head.
+// One workgroup of four waves per (query, kv-head, item); the pages of every thought type are
+// walked type by type, so the bit width is a compile-time constant of each inner loop; the
+// four waves are merged through LDS into one partial (m, l, acc) per query head.
+//
+// Work distribution.  On sliding-window layers an item owns a fixed share of each type's page
+// list and a wave takes every fourth page pair of it.  On full-attention layers the launch is
+// sized so that all workgroups are resident at once, and the waves of all workgroups of one
+// (query, kv-head) draw chunks of page pairs from three shared counters (one per type) until
+// the lists are empty: the kernel is bound by memory there, compute units do not all see the
+// same bandwidth, and a fixed split would leave the fast ones idle for the last fifth of the
+// launch.  Which workgroup adds a pair to its partial does not matter: the merge kernel sums
+// the partials of a head whatever they hold.
 #include "decode_common.h"
 
 namespace thinkv {
@@ -347,6 +355,48 @@ struct ClassRunner {
     }
   }
 
+  // Dynamic chunks: the type's whole page list tab[0 .. n_pages) is cut into chunks of kChunkPairs
+  // page pairs; *counter hands out chunk numbers to every wave of every workgroup of this
+  // (query, kv-head).  The next chunk number is requested before the current chunk is worked
+  // on, so the round trip of the atomic hides behind a chunk of compute.
+  static constexpr int kChunkPairs = 4;
+  __device__ __forceinline__ int take_chunk(uint32_t* counter) const {
+    int r = 0;
+    if (lane == 0) r = (int)atomicAdd(counter, 1u);
+    return r;   // valid in lane 0; read with readfirstlane when needed
+  }
+  __device__ __forceinline__ void run_dynamic(int n_pages, uint32_t* counter) {
+    const int n_pairs = (n_pages + 1) >> 1;
+    const int n_chunks = (n_pairs + kChunkPairs - 1) / kChunkPairs;
+    const uint32_t* msk = v.slot_mask + (tab - v.block_table);
+    int j = __builtin_amdgcn_readfirstlane(take_chunk(counter));
+    while (j < n_chunks) {
+      const int pg0 = 2 * kChunkPairs * j;
+      const int cnt = n_pages - pg0 < 2 * kChunkPairs ? n_pages - pg0 : 2 * kChunkPairs;
+      int vpid = 0;
+      uint32_t vmask = 0;
+      if (lane < cnt) {
+        vpid = tab[pg0 + lane];
+        vmask = msk[pg0 + lane] & 0xFFFFu;
+      }
+      const int r_next = take_chunk(counter);
+      const int np2 = (cnt + 1) >> 1;
+      for (int pr = 0; pr < np2; ++pr) {
+        PairIds id;
+        id.pid_a = __builtin_amdgcn_readlane(vpid, 2 * pr);
+        id.live_a = __builtin_amdgcn_readlane(vmask, 2 * pr);
+        const int ib = 2 * pr + 1 < cnt ? 2 * pr + 1 : 2 * pr;
+        id.pid_b = __builtin_amdgcn_readlane(vpid, ib);
+        id.live_b = 2 * pr + 1 < cnt ? __builtin_amdgcn_readlane(vmask, ib) : 0u;
+        if ((id.live_a | id.live_b) == 0) continue;
+        Pair r;
+        issue_loads(r, id);
+        compute(r, id);
+      }
+      j = __builtin_amdgcn_readfirstlane(r_next);
+    }
+  }
+
   // Page ids and live masks of up to 64 pages are fetched with one vector load each (lane L
   // holds page p0 + base + L) and handed to the pair loop through v_readlane, so the loop
   // itself has no dependent scalar loads.  Occupancy, not software prefetch, hides the
@@ -406,8 +456,8 @@ __device__ __forceinline__ float class_unit(int bits, int mb) {
   return (float)(1 << sh);
 }
 
-// One workgroup of four waves per (query, kv-head, item).
-template <int D, int GP>
+// One workgroup of four waves per (query, kv-head, item).  WIN: sliding-window layer (static shares).
+template <int D, int GP, bool WIN>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void decode_mfma_kernel(thinkv_view v, DecodeArgs a) {
   using CL = Cols<D, GP>;
   constexpr int NG = D / 32, NM = D / 16, CS = CL::CS, NSET = CL::NSET;
@@ -454,7 +504,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   st.l = 0.f;
   st.m = -INFINITY;
   st.m_sub = 0.f;
-  const int qpos = a.window > 0 ? a.q_pos[b] : 0;
+  const int qpos = WIN ? a.q_pos[b] : 0;
   const int qd = lane >> 4, n = lane & 15;
 
   // The running output is kept in the units of the class being walked (its codes carry a
@@ -467,21 +517,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
     const int k = kk + rot < 3 ? kk + rot : kk + rot - 3;
     const int bits = c.bits_of_class[k];
     const int npk = k == 0 ? np[0] : (k == 1 ? np[1] : np[2]);
-    const int p0 = (int)((int64_t)u0 * npk / plan.units), p1 = (int)((int64_t)u1 * npk / plan.units);
+    const int p0 = WIN ? (int)((int64_t)u0 * npk / plan.units) : 0, p1 = WIN ? (int)((int64_t)u1 * npk / plan.units) : npk;
     if (p1 <= p0) continue;
     const int32_t* tab = v.block_table + table_base(c, seq, a.layer, k);
+    uint32_t* counter = v.work_counters + (((int64_t)a.layer * c.max_seqs + b) * c.n_kv_heads + hkv) * 4 + k;
 #pragma unroll
     for (int mb = 0; mb < NM; ++mb) st.o[mb] *= class_unit<D>(bits, mb);
-    if (bits == 2) {
-      ClassRunner<D, 2, GP> cr(st, v, a, k, tab, p0, p1, wave, hkv, G, lds.q, lds.qsum, qpos);
-      cr.run();
-    } else if (bits == 4) {
-      ClassRunner<D, 4, GP> cr(st, v, a, k, tab, p0, p1, wave, hkv, G, lds.q, lds.qsum, qpos);
-      cr.run();
-    } else {
-      ClassRunner<D, 8, GP> cr(st, v, a, k, tab, p0, p1, wave, hkv, G, lds.q, lds.qsum, qpos);
-      cr.run();
-    }
+#define TKV_RUN(B_)                                                                                        \
+  {                                                                                                        \
+    ClassRunner<D, B_, GP> cr(st, v, a, k, tab, p0, p1, wave, hkv, G, lds.q, lds.qsum, qpos);               \
+    if constexpr (WIN) cr.run();                                                                           \
+    else cr.run_dynamic(npk, counter);                                                                     \
+  }
+    if (bits == 2) TKV_RUN(2) else if (bits == 4) TKV_RUN(4) else TKV_RUN(8)
+#undef TKV_RUN
 #pragma unroll
     for (int mb = 0; mb < NM; ++mb) st.o[mb] *= 1.0f / class_unit<D>(bits, mb);
   }
@@ -539,17 +588,23 @@ int decode_mfma_supported(const thinkv_config& c) {
   return (c.head_dim == 64 || c.head_dim == 128) && G >= 1 && G <= 8;
 }
 
-template <int D>
-static int launch_d(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {
+template <int D, bool WIN>
+static int launch_dw(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {
   const int G = v.cfg.n_q_heads / v.cfg.n_kv_heads;
   dim3 grid(a.max_split * v.cfg.n_kv_heads * a.B), blk(256);
   if (G <= 4)
-    hipLaunchKernelGGL((decode_mfma_kernel<D, 4>), grid, blk, 0, st, v, a);
+    hipLaunchKernelGGL((decode_mfma_kernel<D, 4, WIN>), grid, blk, 0, st, v, a);
   else if (G <= 8)
-    hipLaunchKernelGGL((decode_mfma_kernel<D, 8>), grid, blk, 0, st, v, a);
+    hipLaunchKernelGGL((decode_mfma_kernel<D, 8, WIN>), grid, blk, 0, st, v, a);
   else
     return THINKV_E_SHAPE;
   return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
+}
+
+// the dynamic path needs one counter row per query: B <= max_seqs, else the static shares serve
+template <int D>
+static int launch_d(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {
+  return (a.window > 0 || a.B > v.cfg.max_seqs) ? launch_dw<D, true>(v, a, st) : launch_dw<D, false>(v, a, st);
 }
 
 int launch_decode_mfma(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {

@@ -217,6 +217,9 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(thinkv_view v, DecodeAr
     A = fmaf(x3, s_w[s + 3], A);
   }
   for (; s < ns; ++s) A = fmaf(col[(int64_t)s * (D + 2)], s_w[s], A);
+  // the work queues of this (query, kv-head) are left empty for the next call
+  if (ch < 4 && hq % (Hq / c.n_kv_heads) == 0 && b < c.max_seqs)
+    v.work_counters[(((int64_t)a.layer * c.max_seqs + b) * c.n_kv_heads + hq / (Hq / c.n_kv_heads)) * 4 + ch] = 0u;
   const float o = L > 0.f ? A / L : 0.f;
   store_from_f32(a.out, ((int64_t)b * Hq + hq) * D + ch, a.out_dtype, o);
   if (a.lse && ch == 0) a.lse[(int64_t)b * Hq + hq] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
