@@ -79,8 +79,10 @@ typedef struct {
  *                   append read the masks of a page list as one contiguous run.
  *   slot_pos[c]     [arena_pages[c]][16] logical position of the token in the slot, -1 = none
  *   n_live          [max_seqs][n_layers] live tokens
- *   work_counters   [n_layers][max_seqs][n_kv_heads][4] scratch of thinkv_decode_attention (shared
- *                   work queues of the workgroups of one query and kv-head); zero between calls
+ *   work_counters   [n_layers][max_seqs][n_kv_heads][4] scratch of thinkv_decode_attention: per
+ *                   (layer, query index, kv-head) the heads of three work queues (one per type)
+ *                   and a spare word; zero between calls (init zeroes them, every call leaves
+ *                   them zero), so two decode calls on one (view, layer) must not overlap
  *   dev_status      [max_seqs * n_layers + 1] THINKV_ST_* flags
  *
  * Byte layout of one page: n_kv_heads blocks of thinkv_block_bytes(); a block is
@@ -173,7 +175,7 @@ int thinkv_evict(const thinkv_view* view, int32_t layer, const int32_t* ev_seq, 
  *   q        DEVICE [B][n_q_heads][head_dim] of q_dtype (F16 or BF16)
  *   out      DEVICE [B][n_q_heads][head_dim] of out_dtype
  *   lse      DEVICE [B][n_q_heads] float, may be NULL: log-sum-exp of the scaled scores
- *   seq_ids  DEVICE [B] which sequence each query belongs to
+ *   seq_ids  DEVICE [B] which sequence each query belongs to; B <= max_seqs
  *   q_pos    DEVICE [B] logical position of the query (used only when window > 0)
  *   max_ctx_pages  host upper bound on pages (all types) any attended sequence holds
  *

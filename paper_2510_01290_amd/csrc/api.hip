@@ -78,6 +78,7 @@ static int decode_common(const thinkv_view* view, int32_t layer, const void* q, 
   int rc = check_view(view);
   if (rc) return rc;
   if (B < 0 || layer < 0 || layer >= view->cfg.n_layers || window < 0 || max_ctx_pages < 0) return THINKV_E_INVALID_ARG;
+  if (B > view->cfg.max_seqs) return THINKV_E_INVALID_ARG;   // one row of work counters per query
   if (!(softmax_scale > 0.0f) || !(softmax_scale < 3.0e38f)) return THINKV_E_INVALID_ARG;   // also rejects NaN
   if (B == 0) return THINKV_OK;
   if (!q || !out || !seq_ids || !workspace || (window > 0 && !q_pos)) return THINKV_E_INVALID_ARG;

@@ -61,19 +61,20 @@ __device__ inline void item_units(const ItemPlan& p, int i, int* u0, int* u1) {
 // Which (query, kv-head, item) workgroup `id` of the 1-D grid works on: all big items of the
 // launch come first, then all small ones.  `j` is the item's index among the big (or small)
 // items of its (query, kv-head); the caller checks it against the sequence's plan.
+// Workgroup id -> (query, kv-head, item).  Big items come first, item-major: ids [j * heads,
+// (j + 1) * heads) are item j of every head, and head h's item j sits at offset (h + j) mod heads
+// of that run.  Two things follow.  The hardware starts workgroups in id order and a SIMD favours
+// its oldest wave, so the workgroups of the first third of a chip-filling launch run visibly faster
+// than those of the last third: item-major order gives every head workgroups of every age.  And
+// ids go round the XCDs (id mod 8), so the shift by j puts the items of a head on different XCDs.
 __device__ inline void locate_workgroup(const DecodeArgs& a, int n_kv_heads, int id, int* b, int* hkv, int* j, bool* small) {
-  const int n_big_total = a.max_big * n_kv_heads * a.B;
-  int rest;
-  if (id < n_big_total) {
-    *j = id % a.max_big;
-    rest = id / a.max_big;
-    *small = false;
-  } else {
-    id -= n_big_total;
-    *j = id % a.max_small;
-    rest = id / a.max_small;
-    *small = true;
-  }
+  const int heads = n_kv_heads * a.B;
+  const int n_big_total = a.max_big * heads;
+  *small = id >= n_big_total;
+  if (*small) id -= n_big_total;
+  *j = id / heads;
+  int rest = id % heads - *j % heads;
+  if (rest < 0) rest += heads;
   *hkv = rest % n_kv_heads;
   *b = rest / n_kv_heads;
 }

@@ -117,3 +117,9 @@ def test_flags_and_degenerate_cases():
         assert not got[2].any() and not got[3].any() and np.all(np.isneginf(lse[2:]))
         assert np.abs(got[1] - ref[1]).max() <= 1e-6               # one live token: its value row
         assert np.abs(lse[:2] - ref_lse[:2]).max() <= 1e-3
+    # more queries in one call than the view has rows of work counters for: refused, not run
+    q5 = torch.zeros((5, 8, 64), dtype=torch.float16, device=dev)
+    out5 = torch.zeros((5, 8, 64), dtype=torch.float32, device=dev)
+    seq5 = torch.zeros(5, dtype=torch.int32, device=dev)
+    with pytest.raises(RuntimeError, match="invalid argument"):
+        B.thinkv_decode_attention(gc, 0, q5, out5, None, seq5, None, 0, 0.125, 4)
