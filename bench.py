@@ -33,6 +33,9 @@ def main():
     ap.add_argument("--ctx", type=int, default=32768, help="live tokens per sequence")
     ap.add_argument("--batch", type=int, default=16)
     ap.add_argument("--variant", default="fast", choices=["fast", "valu"])
+    ap.add_argument("--workload", default="cfg2-32k", choices=["cfg2-32k", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5"],
+                    help="cfg2-32k (default): the headline step.  The others time decode attention alone on that "
+                         "configuration's cache (a step = one attention call per built layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -50,7 +53,11 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    nsteps = args.steps + args.warmup
+    if args.workload != "cfg2-32k":
+        print(json.dumps(attention_only(args, np, torch, B, synth, parity, dev)))
+        return
+    n_extra = 20   # steps after the timed region, with every call bracketed by events
+    nsteps = args.steps + args.warmup + n_extra
     wl = synth.config_llama8b_layer(seed=1, n_seqs=args.batch, ctx=args.ctx, refill_chunk=64,
                                     name=f"cfg2-shape B={args.batch} ctx={args.ctx}")
     g = wl.geom
@@ -118,6 +125,19 @@ def main():
     wall = time.perf_counter() - t0
     ms_step = e0.elapsed_time(e1) / args.steps
     attn_ms = np.array([a.elapsed_time(b) for a, b in evs])
+    # per-call times of the other two entry points, outside the timed region
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_extra)]
+    for j in range(n_extra):
+        i = args.warmup + args.steps + j
+        marks[j][0].record()
+        B.thinkv_evict(gc, 0, ev_seq, ev_h[i])
+        marks[j][1].record()
+        B.thinkv_append_quantized(gc, 0, k_new[i], v_new[i], ev_seq, t_pos[i], t_cls[i], h_out)
+        marks[j][2].record()
+        decode(gc, 0, q_all[i], out, lse, ev_seq, t_pos[i], 0, scale, max_ctx_pages)
+    torch.cuda.synchronize()
+    evict_us = float(np.median([m[0].elapsed_time(m[1]) for m in marks]) * 1e3)
+    append_us = float(np.median([m[1].elapsed_time(m[2]) for m in marks]) * 1e3)
     assert int(gc.dev_status.abs().sum().item()) == 0, "device flags set during the timed steps"
 
     # ---- algorithmic bytes of one step (from the tables as they stand after the run)
@@ -140,6 +160,7 @@ def main():
         "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "us_per_step": ms_step * 1e3, "attn_us_mean": float(attn_ms.mean() * 1e3), "attn_us_min": float(attn_ms.min() * 1e3),
+        "attn_us_median": float(np.median(attn_ms) * 1e3), "evict_us_median": evict_us, "append_us_median": append_us,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16" if args.variant == "fast" else "f32",
         "data": "synthetic",
         "config": {"workload": wl.name + " (R1-Llama-8B layer: 32 q / 8 kv heads, head_dim 128, bf16; T8/R4/E2, 30% E + 10% R evicted and refilled)",
@@ -162,6 +183,92 @@ def main():
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, args, nsteps, ev_handles, new_cls, np, torch, synth, parity)
     print(json.dumps(line))
+
+
+def attention_only(args, np, torch, B, synth, parity, dev):
+    """Decode attention alone on one of the other configurations: the cache is built by the
+    configuration's own script (bulk append, eviction, refill or budgeted decode), then a step is
+    one attention call per built layer for the whole batch."""
+    wl = {"cfg1": lambda: synth.config_tiny(),
+          "cfg2": lambda: synth.config_llama8b_layer(seed=1, n_seqs=16, ctx=8192, refill_chunk=64),
+          "cfg3": lambda: synth.config_qwen14b_budget(),
+          "cfg4": lambda: synth.config_gptoss(n_layers=4),
+          "cfg5": lambda: synth.config_stress(n_layers=2, n_steps=32)}[args.workload]()
+    g = wl.geom
+    t0 = time.time()
+    gc = parity.make_gpu_cache(wl)
+    synth.ScriptRunner(wl, parity.GpuBackend(gc)).run()
+    torch.cuda.synchronize()
+    build_s = time.time() - t0
+    assert int(gc.dev_status.abs().sum().item()) == 0, "device flags set while building the cache"
+    L, S = g.n_layers, wl.n_seqs
+    q = [torch.stack([synth.query_rows(wl.seed, l, s_, 0, g, dev) for s_ in range(S)]).contiguous() for l in range(L)]
+    out = torch.empty(q[0].shape, dtype=q[0].dtype, device=dev)
+    lse = torch.empty((S, g.n_q_heads), dtype=torch.float32, device=dev)
+    sid = torch.arange(S, dtype=torch.int32, device=dev)
+    qp = torch.from_numpy(wl.q_pos.astype(np.int32)).to(dev)
+    mcp = [int(gc.n_pages[:, l].sum(-1).max().item()) for l in range(L)]
+    scale = g.head_dim ** -0.5
+
+    def step(marks=None):
+        for l in range(L):
+            if marks is not None:
+                marks[l][0].record()
+            B.thinkv_decode_attention(gc, l, q[l], out, lse, sid, qp, wl.window_of_layer[l], scale, mcp[l])
+            if marks is not None:
+                marks[l][1].record()
+
+    for _ in range(args.warmup):
+        step()
+    marks = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)] for _ in range(args.steps)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(args.steps):
+        step(marks[i])
+    e1.record()
+    torch.cuda.synchronize()
+    ms_step = e0.elapsed_time(e1) / args.steps
+    per_layer_us = np.array([[a.elapsed_time(b) * 1e3 for a, b in m] for m in marks])     # [steps][layers]
+    # algorithmic bytes per layer: live tokens visible to the query, page ids + masks, q and out
+    H, D, Hq = g.n_kv_heads, g.head_dim, g.n_q_heads
+    npg = gc.n_pages.cpu().numpy()
+    sm = (gc.slot_mask & 0xFFFF).cpu().numpy().astype(np.uint16)
+    layer_bytes, layer_live = [], []
+    for l in range(L):
+        W = wl.window_of_layer[l]
+        tot, live_l = 0, 0
+        for c in range(3):
+            tok_b = H * 2 * (D * g.bits_of_class[c] // 8 + D // 32 * 4)
+            if W == 0:
+                n = int(sum(np.unpackbits(sm[s_, l, c, :npg[s_, l, c]].view(np.uint8)).sum() for s_ in range(S)))
+            else:
+                pos = gc.slot_pos[c].cpu().numpy()
+                n = 0
+                for s_ in range(S):
+                    ids = gc.block_table[s_, l, c, :npg[s_, l, c]].cpu().numpy()
+                    m = np.unpackbits(sm[s_, l, c, :npg[s_, l, c]].view(np.uint8).reshape(-1, 2), axis=1, bitorder="little").astype(bool)
+                    d = int(wl.q_pos[s_]) - pos[ids]
+                    n += int((m & (d >= 0) & (d < W)).sum())
+            tot += n * tok_b
+            live_l += n
+        pages = int(npg[:, l].sum())
+        tot += pages * (8 + (64 if W else 0)) + S * Hq * D * (2 + q[0].element_size())
+        layer_bytes.append(tot)
+        layer_live.append(live_l)
+    med = np.median(per_layer_us, axis=0)
+    return {
+        "metric": "hybrid-quant paged decode attn: \u00b5s/step + HBM GB/s (% of peak) at 32k ctx",
+        "value": sum(layer_bytes) / (ms_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": wl.name, "batch": S, "layers_built": L, "window_of_layer": list(wl.window_of_layer),
+                   "step": "decode attention alone, one call per built layer", "build_seconds": round(build_s, 1),
+                   "live_tokens_visible_per_layer": layer_live},
+        "per_layer": [{"layer": l, "window": int(wl.window_of_layer[l]), "attn_us_median": float(med[l]),
+                       "attn_us_min": float(per_layer_us[:, l].min()), "algorithmic_bytes": int(layer_bytes[l]),
+                       "GB/s": layer_bytes[l] / (med[l] * 1e-6) / 1e9, "frac_of_8TBps": layer_bytes[l] / (med[l] * 1e-6) / HBM_PEAK}
+                      for l in range(L)],
+    }
 
 
 def cpu_baseline(wl, args, nsteps, ev_handles, new_cls, np, torch, synth, parity):

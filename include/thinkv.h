@@ -78,6 +78,9 @@ typedef struct {
  *                   slot soft-evicted and reclaimable.  Kept in list order so that attention and
  *                   append read the masks of a page list as one contiguous run.
  *   slot_pos[c]     [arena_pages[c]][16] logical position of the token in the slot, -1 = none
+ *   page_pos_max[c] [arena_pages[c]] an upper bound of the page's slot_pos entries: the largest
+ *                   position ever written into the page (-1 = none).  Sliding-window attention
+ *                   skips pages whose bound lies before the window without reading slot_pos.
  *   n_live          [max_seqs][n_layers] live tokens
  *   work_counters   [n_layers][max_seqs][n_kv_heads][4] scratch of thinkv_decode_attention: per
  *                   (layer, query index, kv-head) the heads of three work queues (one per type)
@@ -105,6 +108,7 @@ typedef struct {
   uint8_t* page_filled[3];  /* DEVICE */
   uint32_t* slot_mask;      /* DEVICE */
   int32_t* slot_pos[3];     /* DEVICE */
+  int32_t* page_pos_max[3]; /* DEVICE */
   int32_t* n_live;          /* DEVICE */
   uint32_t* work_counters;  /* DEVICE */
   uint32_t* dev_status;     /* DEVICE */
@@ -125,7 +129,7 @@ size_t thinkv_append_workspace_bytes(const thinkv_config* cfg, int32_t n_tok);
 size_t thinkv_decode_workspace_bytes(const thinkv_config* cfg, int32_t B, int32_t max_ctx_pages);
 
 /* Puts a view into the empty state: free stacks filled so that pages come out 0,1,2,...,
- * tables -1, counters and flags 0, slot_pos -1, arenas zero-filled (attention reads the
+ * tables -1, counters and flags 0, slot_pos and page_pos_max -1, arenas zero-filled (attention reads the
  * never-written slots of a partly filled page and discards them by their live bit, so their
  * scales and zero-points have to be finite numbers).  arena[c] must be 16-byte aligned. */
 int thinkv_init_view(const thinkv_view* view, void* stream /* hipStream_t */);

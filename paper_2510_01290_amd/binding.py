@@ -28,7 +28,7 @@ class View(C.Structure):
     _fields_ = [("cfg", Config), ("arena", C.c_void_p * 3), ("arena_pages", C.c_int64 * 3),
                 ("free_stack", C.c_void_p * 3), ("free_top", C.c_void_p), ("block_table", C.c_void_p),
                 ("n_pages", C.c_void_p), ("page_filled", C.c_void_p * 3), ("slot_mask", C.c_void_p),
-                ("slot_pos", C.c_void_p * 3), ("n_live", C.c_void_p), ("work_counters", C.c_void_p), ("dev_status", C.c_void_p)]
+                ("slot_pos", C.c_void_p * 3), ("page_pos_max", C.c_void_p * 3), ("n_live", C.c_void_p), ("work_counters", C.c_void_p), ("dev_status", C.c_void_p)]
 
 
 def load():
@@ -119,6 +119,7 @@ class Cache:
         self.page_filled = [torch.empty(max(1, n), dtype=torch.uint8, device=d) for n in self.arena_pages]
         self.slot_mask = torch.empty((max_seqs, n_layers, 3, max_pages), dtype=torch.int32, device=d)
         self.slot_pos = [torch.empty((max(1, n), 16), dtype=torch.int32, device=d) for n in self.arena_pages]
+        self.page_pos_max = [torch.empty(max(1, n), dtype=torch.int32, device=d) for n in self.arena_pages]
         self.n_live = torch.empty((max_seqs, n_layers), dtype=torch.int32, device=d)
         self.work_counters = torch.empty((n_layers, max_seqs, n_kv_heads, 4), dtype=torch.int32, device=d)
         self.dev_status = torch.empty(max_seqs * n_layers + 1, dtype=torch.int32, device=d)
@@ -130,6 +131,7 @@ class Cache:
             v.free_stack[k] = self.free_stack[k].data_ptr()
             v.page_filled[k] = self.page_filled[k].data_ptr()
             v.slot_pos[k] = self.slot_pos[k].data_ptr()
+            v.page_pos_max[k] = self.page_pos_max[k].data_ptr()
         v.free_top = self.free_top.data_ptr()
         v.block_table = self.block_table.data_ptr()
         v.slot_mask = self.slot_mask.data_ptr()

@@ -35,7 +35,7 @@ static int check_view(const thinkv_view* v) {
   if (rc) return rc;
   for (int k = 0; k < 3; ++k) {
     if (v->arena_pages[k] < 0 || v->arena_pages[k] > 0x7fffffff) return THINKV_E_INVALID_ARG;
-    if (v->arena_pages[k] > 0 && (!v->arena[k] || !v->free_stack[k] || !v->page_filled[k] || !v->slot_pos[k]))
+    if (v->arena_pages[k] > 0 && (!v->arena[k] || !v->free_stack[k] || !v->page_filled[k] || !v->slot_pos[k] || !v->page_pos_max[k]))
       return THINKV_E_INVALID_ARG;
   }
   if (!v->free_top || !v->block_table || !v->slot_mask || !v->n_pages || !v->n_live || !v->work_counters || !v->dev_status) return THINKV_E_INVALID_ARG;
@@ -55,9 +55,18 @@ static int small_items() {
   return 0;
 }
 
-static int pages_per_item(const thinkv_config& c, int B, int max_ctx_pages) {
+// A sliding-window layer is another matter: only the pages that hold one of the last W positions
+// are worked on, the rest of the page list is merely scanned (a few bytes a page), so the fixed
+// price of an item dominates.  There an item scans at least 256 pages (64 per wave), and a
+// (query, kv-head) gets several items only while that still fills the chip once.
+static int pages_per_item(const thinkv_config& c, int B, int max_ctx_pages, int window) {
   const int64_t heads = (int64_t)B * c.n_kv_heads;
   int64_t n_big = heads <= 384 ? 768 / heads : (4 * 768 + heads - 1) / heads;   // big items per (query, kv-head)
+  if (window > 0) {
+    n_big = 768 / heads;
+    const int64_t most = (max_ctx_pages + 255) / 256;
+    if (n_big > most) n_big = most;
+  }
   if (n_big < 1) n_big = 1;
   int ppi = (int)((max_ctx_pages + n_big - 1) / n_big);
   if (const char* e = getenv("THINKV_PPI")) ppi = atoi(e);  // dev knob
@@ -98,7 +107,7 @@ static int decode_common(const thinkv_view* view, int32_t layer, const void* q, 
   a.window = window;
   a.q_dtype = q_dtype;
   a.out_dtype = out_dtype;
-  a.ppi = pages_per_item(view->cfg, B, max_ctx_pages);
+  a.ppi = pages_per_item(view->cfg, B, max_ctx_pages, window);
   a.n_small = small_items();
   split_bounds(max_ctx_pages, a.ppi, &a.max_big, &a.max_small);
   a.max_split = a.max_big + a.max_small;

@@ -286,7 +286,10 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
   }
   if (tid == 0 && blockIdx.y == 0) {
     const int cls = s_place[0], pid = s_place[1], slot = s_place[2], ok = s_place[3], pi = s_place[4];
-    if (ok) v.slot_pos[cls][(int64_t)pid * kPage + slot] = tok_pos[i];
+    if (ok) {
+      v.slot_pos[cls][(int64_t)pid * kPage + slot] = tok_pos[i];
+      atomicMax(&v.page_pos_max[cls][pid], tok_pos[i]);
+    }
     if (tok_handle) tok_handle[i] = ok ? THINKV_HANDLE(cls, pi, slot) : -1;
   }
   __syncthreads();

@@ -397,13 +397,16 @@ struct ClassRunner {
     }
   }
 
-  // Page ids and live masks of up to 64 pages are fetched with one vector load each (lane L
-  // holds page p0 + base + L) and handed to the pair loop through v_readlane, so the loop
-  // itself has no dependent scalar loads.  Occupancy, not software prefetch, hides the
-  // latency of the packed-page loads: each wave has one page pair in flight.
+  // Static share (sliding-window layers): page ids and live masks of up to 64 pages are fetched
+  // with one vector load each (lane L holds page p0 + base + L).  A page can hold a visible
+  // token only if the largest position ever written into it lies inside the window, so one
+  // word per page (page_pos_max) settles most pages; a lane reads the 16 positions of its page
+  // only when that test passes.  The four waves take every fourth run of 64 pages; the pages of
+  // a run that still have a visible slot are paired up, and ids and masks reach the pair code
+  // through v_readlane.
   __device__ __forceinline__ void run() {
     const int n_pages = p1 - p0;
-    for (int base = 0; base < n_pages; base += 64) {
+    for (int base = 64 * wave; base < n_pages; base += 256) {
       const int cnt = n_pages - base < 64 ? n_pages - base : 64;
       int vpid = 0;
       uint32_t vmask = 0;
@@ -412,27 +415,33 @@ struct ClassRunner {
         vmask = v.slot_mask[(tab - v.block_table) + p0 + base + lane] & 0xFFFFu;
       }
       if (a.window > 0) {
-        // visibility of the 16 slots of each page: lane L walks the slots of its own page
         uint32_t vis = 0;
-        if (lane < cnt) {
-          const int32_t* sp = v.slot_pos[cls] + (int64_t)vpid * kPage;
+        if (vmask != 0 && v.page_pos_max[cls][vpid] > qpos - a.window) {
+          const int4* sp = (const int4*)(v.slot_pos[cls] + (int64_t)vpid * kPage);
 #pragma unroll
-          for (int t = 0; t < kPage; ++t) {
-            const int d = qpos - sp[t];
-            vis |= (d >= 0 && d < a.window) ? (1u << t) : 0u;
+          for (int t4 = 0; t4 < kPage / 4; ++t4) {
+            const int4 pos = sp[t4];
+            const int d0 = qpos - pos.x, d1 = qpos - pos.y, d2 = qpos - pos.z, d3 = qpos - pos.w;
+            vis |= ((d0 >= 0 && d0 < a.window) ? 1u : 0u) << (4 * t4);
+            vis |= ((d1 >= 0 && d1 < a.window) ? 2u : 0u) << (4 * t4);
+            vis |= ((d2 >= 0 && d2 < a.window) ? 4u : 0u) << (4 * t4);
+            vis |= ((d3 >= 0 && d3 < a.window) ? 8u : 0u) << (4 * t4);
           }
         }
         vmask &= vis;
       }
-      const int n_pairs = (cnt + 1) >> 1;
-      for (int pr = wave; pr < n_pairs; pr += 4) {
+      uint64_t todo = __ballot(vmask != 0);
+      while (todo) {
+        const int ia = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        const bool two = todo != 0;
+        const int ib = two ? __builtin_ctzll(todo) : ia;
+        if (two) todo &= todo - 1;
         PairIds id;
-        id.pid_a = __builtin_amdgcn_readlane(vpid, 2 * pr);
-        id.live_a = __builtin_amdgcn_readlane(vmask, 2 * pr);
-        const int ib = 2 * pr + 1 < cnt ? 2 * pr + 1 : 2 * pr;
+        id.pid_a = __builtin_amdgcn_readlane(vpid, ia);
+        id.live_a = __builtin_amdgcn_readlane(vmask, ia);
         id.pid_b = __builtin_amdgcn_readlane(vpid, ib);
-        id.live_b = 2 * pr + 1 < cnt ? __builtin_amdgcn_readlane(vmask, ib) : 0u;
-        if ((id.live_a | id.live_b) == 0) continue;
+        id.live_b = two ? __builtin_amdgcn_readlane(vmask, ib) : 0u;
         Pair r;
         issue_loads(r, id);
         compute(r, id);

@@ -43,6 +43,7 @@ __global__ __launch_bounds__(256) void init_kernel(thinkv_view v) {
     for (int64_t i = tid; i < n; i += stride) {
       v.free_stack[k][i] = (int32_t)(n - 1 - i);
       v.page_filled[k][i] = 0;
+      v.page_pos_max[k][i] = -1;
     }
     for (int64_t i = tid; i < n * kPage; i += stride) v.slot_pos[k][i] = -1;
     if (tid == 0) v.free_top[k] = (int32_t)n;

@@ -263,10 +263,11 @@ def budgeted_decode(name, geom, seed, n_seqs, n_steps, budget, steps_per_call=16
                     retention=(64, 32, 16, 8, 4), evict_order=(E, R, T)):
     """Config 3: n_steps decode appends per sequence under a live-token budget.  Whenever a
     sequence holds more than `budget` live tokens, the oldest segment of the least important
-    class that is still above its next retention level is cut down to that level by a seeded
-    uniform choice (the paper's budget case of thought-adaptive eviction, Sec. 4.3, with the
-    K-means pick replaced by a random one).  All layers share the token classes; eviction
-    choices are drawn per layer."""
+    class that is still above the lowest retention level is cut down to the next level below
+    its current size by a seeded uniform choice (the paper's budget case of thought-adaptive
+    eviction, Sec. 4.3, with the K-means pick replaced by a random one).  The level follows from
+    the segment's size alone, so a segment that was cut while still growing can be cut again.
+    All layers share the token classes; eviction choices are drawn per layer."""
     rng = np.random.default_rng(seed)
     L = geom.n_layers
     classes, segs = [], []
@@ -277,9 +278,8 @@ def budgeted_decode(name, geom, seed, n_seqs, n_steps, budget, steps_per_call=16
     ops = []
     seqs = np.arange(n_seqs, dtype=np.int32)
     for l in range(L):
-        # per sequence: segment id -> live positions, retention level index
+        # per sequence: segment id -> live positions
         live = [dict() for _ in range(n_seqs)]
-        level = [dict() for _ in range(n_seqs)]
         n_live = np.zeros(n_seqs, dtype=np.int64)
         t = 0
         while t < n_steps:
@@ -290,7 +290,6 @@ def budgeted_decode(name, geom, seed, n_seqs, n_steps, budget, steps_per_call=16
                 sg = segs[s][t:t + n]
                 for g in np.unique(sg).tolist():
                     live[s].setdefault(g, []).extend((t + np.flatnonzero(sg == g)).tolist())
-                    level[s].setdefault(g, 0)
                 n_live[s] += n
                 while n_live[s] > budget:
                     pick = None
@@ -298,7 +297,7 @@ def budgeted_decode(name, geom, seed, n_seqs, n_steps, budget, steps_per_call=16
                         for g in sorted(live[s]):
                             if classes[s][live[s][g][0]] != c:
                                 continue
-                            lv = level[s][g]
+                            lv = 0
                             while lv < len(retention) and retention[lv] >= len(live[s][g]):
                                 lv += 1
                             if lv < len(retention):
@@ -313,7 +312,6 @@ def budgeted_decode(name, geom, seed, n_seqs, n_steps, budget, steps_per_call=16
                     cur = np.array(live[s][g])
                     drop = rng.choice(cur, size=len(cur) - keep, replace=False)
                     live[s][g] = sorted(set(cur.tolist()) - set(drop.tolist()))
-                    level[s][g] = lv + 1
                     n_live[s] -= len(drop)
                     es.append(np.full(len(drop), s, dtype=np.int32))
                     ep.append(np.sort(drop))

@@ -60,6 +60,7 @@ def gpu_tables(gc):
     t["filled"] = [x.cpu().numpy() for x in gc.page_filled]
     t["mask"] = gc.slot_mask.cpu().numpy().view(np.uint32)      # [seq][layer][type][list position]
     t["slot_pos"] = [x.cpu().numpy() for x in gc.slot_pos]
+    t["pos_max"] = [x.cpu().numpy() for x in gc.page_pos_max]
     t["free_stack"] = [x.cpu().numpy() for x in gc.free_stack]
     return t
 
@@ -87,6 +88,10 @@ def compare_bookkeeping_full(oc, gc):
         used = np.setdiff1d(np.arange(n), oc.free_stack[c][:top])
         assert np.array_equal(t["filled"][c][used], oc.filled[c][used]), "filled"
         assert np.array_equal(t["slot_pos"][c][used], oc.slot_pos[c][used]), "slot_pos"
+        # the window kernel's page filter: never below any position the page holds, -1 on untouched pages
+        assert (t["pos_max"][c][used] >= oc.slot_pos[c][used].max(axis=1)).all(), "page_pos_max below a stored position"
+        free = oc.free_stack[c][:top]
+        assert (t["pos_max"][c][free] == -1).all(), "page_pos_max set on a page never handed out"
 
 
 def compare_sequences(oc, gc, pairs, check_bytes=True):
@@ -104,6 +109,8 @@ def compare_sequences(oc, gc, pairs, check_bytes=True):
             assert np.array_equal(t["mask"][sg, l, c, :n] & 0xFFFF, oc.valid[c][po]), ("live bits", sg, l, c)
             assert np.array_equal(t["mask"][sg, l, c, :n] >> 16, oc.evict[c][po]), ("evict bits", sg, l, c)
             assert np.array_equal(t["slot_pos"][c][pg], oc.slot_pos[c][po]), ("slot_pos", sg, l, c)
+            if n:
+                assert (t["pos_max"][c][pg] >= oc.slot_pos[c][po].max(axis=1)).all(), ("page_pos_max", sg, l, c)
             if check_bytes and n:
                 pb = gc.page_bytes[c]
                 idx = torch.from_numpy(pg.astype(np.int64)).to(gc.device)
