@@ -9,12 +9,16 @@
 //     k < R + tail     slot filled + (k - R) of the last page                  (tail = 16 - filled)
 //     otherwise        slot (k-R-tail) % 16 of the (k-R-tail)/16-th new page
 // and new pages are granted to sequences in ascending sequence id, which is token order.
-// Four kernels, all on the caller's stream:
+// Three kernels, all on the caller's stream:
 //   plan   (block per sequence)  token ranks per type, prefix popcounts of the reclaimable bits,
 //                                pages needed
-//   grant  (one block)           exclusive scan of the needs over sequences against the pools
 //   place  (block per token)     slot lookup, quantisation, packing, slot_pos, handle
 //   commit (block per sequence)  masks, fill counts, page lists, counters
+// The grant of new pages (exclusive sum of the needs of the sequences before s, against what the
+// pool held when the call began) is a sum over at most max_seqs small numbers: every block that
+// wants it works it out for itself rather than waiting for a kernel of its own.  A decode step
+// appends one token per sequence, so the call is a chain of short dependent launches and one
+// launch less is a good part of its time.
 #include "common.h"
 
 namespace thinkv {
@@ -57,6 +61,16 @@ static AppendWs carve(const thinkv_config& c, int n_tok, void* ws) {
   p += align256((size_t)(n_tok > 0 ? n_tok : 1) * 4);
   w.pre = (int*)p;
   return w;
+}
+
+// Sum over a 256-thread block (every thread gets it).
+__device__ inline int block_sum(int v, int* lds /*[5]*/) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return lds[0] + lds[1] + lds[2] + lds[3];
 }
 
 // exclusive scan of one int per thread over a 256-thread block; returns the block total
@@ -179,35 +193,21 @@ __global__ __launch_bounds__(256) void append_plan_kernel(thinkv_view v, int lay
     }
   }
   if (tid == 0) ws.plan[s] = pl;
+  if (s == 0 && tid < 3) ws.avail_old[tid] = v.free_top[tid];   // the pools as the call finds them
 }
 
-__global__ __launch_bounds__(256) void append_grant_kernel(thinkv_view v, AppendWs ws) {
-  __shared__ int s_scan[5];
-  const int tid = threadIdx.x, S = v.cfg.max_seqs;
-  for (int k = 0; k < 3; ++k) {
-    const int avail = v.free_top[k];
-    int running = 0;
-    for (int b0 = 0; b0 < S; b0 += 256) {
-      int s = b0 + tid;
-      int need = s < S ? ws.plan[s].need[k] : 0;
-      int ex;
-      int tot = block_excl_scan(need, &ex, s_scan);
-      if (s < S) {
-        int base = running + ex;
-        int left = avail - base;
-        int g = left < 0 ? 0 : (left < need ? left : need);
-        ws.plan[s].base[k] = base < avail ? base : avail;
-        ws.plan[s].grant[k] = g;
-      }
-      running += tot;
-    }
-    __syncthreads();
-    if (tid == 0) {
-      ws.avail_old[k] = avail;
-      v.free_top[k] = avail - (running < avail ? running : avail);
-    }
-    __syncthreads();
-  }
+// New pages of type k granted to sequence s: base = pages wanted by the sequences before s
+// (pop order), grant = what the pool (avail pages when the call began) still covers of s's own
+// need.  Called by every thread of the block.
+__device__ inline void grant_of(const thinkv_view& v, const AppendWs& ws, int s, int k, int* base, int* grant, int* lds /*[5]*/) {
+  const int avail = ws.avail_old[k];
+  int before = 0;
+  for (int t = threadIdx.x; t < s; t += 256) before += ws.plan[t].need[k];
+  before = block_sum(before, lds);
+  const int need = ws.plan[s].need[k];
+  const int left = avail - before;
+  *base = before < avail ? before : avail;
+  *grant = left < 0 ? 0 : (left < need ? left : need);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -229,7 +229,8 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
   const int i = blockIdx.x, tid = threadIdx.x;
   // slot selection.  Thread 0 settles every case that is a closed form; the page of the k-th
   // reclaimable slot (k < R) is found by all threads, each testing a stride of the page list.
-  __shared__ int s_find[4];   // 1 = search wanted, sequence, type, rank
+  __shared__ int s_find[4];   // 1 = search wanted / 2 = grant wanted, sequence, type, rank
+  __shared__ int s_scan[5];
   if (tid == 0) {
     int ok = 0, cls = 0, pid = 0, slot = 0, pi = 0, find = 0, k = 0;
     const int s = tok_seq[i];
@@ -252,13 +253,7 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
           slot = (int)v.page_filled[cls][pid] + (k - R);
           ok = 1;
         } else {
-          const int kk = k - R - tail, npi = kk >> 4;
-          if (npi < pl.grant[cls]) {
-            pi = np + npi;
-            slot = kk & 15;
-            pid = v.free_stack[cls][ws.avail_old[cls] - 1 - (pl.base[cls] + npi)];
-            ok = 1;
-          }
+          find = 2;   // a new page: which one depends on the grant, worked out by the whole block
         }
       }
     }
@@ -266,7 +261,7 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
     s_place[0] = cls; s_place[1] = pid; s_place[2] = slot; s_place[3] = ok; s_place[4] = pi;
   }
   __syncthreads();
-  if (s_find[0]) {
+  if (s_find[0] == 1) {
     const int s = s_find[1], cls = s_find[2], k = s_find[3];
     const int np = ws.plan[s].np_old[cls];
     const int64_t tb = table_base(c, s, layer, cls);
@@ -280,6 +275,22 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
         s_place[2] = __ffs(e) - 1;
         s_place[3] = 1;
         s_place[4] = pi;
+      }
+    }
+    __syncthreads();
+  }
+  if (s_find[0] == 2) {
+    const int s = s_find[1], cls = s_find[2], k = s_find[3];
+    int base, grant;
+    grant_of(v, ws, s, cls, &base, &grant, s_scan);
+    if (tid == 0) {
+      const SeqPlan& pl = ws.plan[s];
+      const int kk = k - pl.R[cls] - pl.tail[cls], npi = kk >> 4;
+      if (npi < grant) {
+        s_place[1] = v.free_stack[cls][ws.avail_old[cls] - 1 - (base + npi)];
+        s_place[2] = kk & 15;
+        s_place[3] = 1;
+        s_place[4] = pl.np_old[cls] + npi;
       }
     }
     __syncthreads();
@@ -379,11 +390,24 @@ __global__ __launch_bounds__(256) void append_commit_kernel(thinkv_view v, int l
   const thinkv_config& c = v.cfg;
   const int s = blockIdx.x, tid = threadIdx.x;
   const SeqPlan pl = ws.plan[s];
+  __shared__ int s_scan[5];
+  if (s == 0) {
+    // the pools after the call: what all sequences together were granted is gone
+    for (int k = 0; k < 3; ++k) {
+      int want = 0;
+      for (int t = tid; t < c.max_seqs; t += 256) want += ws.plan[t].need[k];
+      want = block_sum(want, s_scan);
+      const int avail = ws.avail_old[k];
+      if (tid == 0) v.free_top[k] = avail - (want < avail ? want : avail);
+    }
+  }
   if (pl.lo >= pl.hi) return;
   int placed_all = 0, short_any = 0;
   for (int k = 0; k < 3; ++k) {
-    const int n = pl.n[k], R = pl.R[k], tail = pl.tail[k], np = pl.np_old[k], grant = pl.grant[k];
+    const int n = pl.n[k], R = pl.R[k], tail = pl.tail[k], np = pl.np_old[k];
     if (n == 0) continue;
+    int base = 0, grant = 0;
+    if (pl.need[k] > 0) grant_of(v, ws, s, k, &base, &grant, s_scan);
     int32_t* tab = v.block_table + table_base(c, s, layer, k);
     uint32_t* msk = v.slot_mask + table_base(c, s, layer, k);
     const int* pre = ws.pre + ((int64_t)s * 3 + k) * c.max_pages;
@@ -410,7 +434,7 @@ __global__ __launch_bounds__(256) void append_commit_kernel(thinkv_view v, int l
       msk[pi] = m;
     }
     for (int i = tid; i < grant; i += 256) {
-      const int pid = v.free_stack[k][ws.avail_old[k] - 1 - (pl.base[k] + i)];
+      const int pid = v.free_stack[k][ws.avail_old[k] - 1 - (base + i)];
       int cnt = n - R - tail - kPage * i;
       cnt = cnt > kPage ? kPage : cnt;
       tab[np + i] = pid;
@@ -435,7 +459,6 @@ int launch_append(const thinkv_view& v, int layer, const void* k_new, const void
   AppendWs ws = carve(v.cfg, n_tok, workspace);
   const int S = v.cfg.max_seqs;
   hipLaunchKernelGGL(append_plan_kernel, dim3(S), dim3(256), 0, st, v, layer, tok_seq, tok_class, n_tok, ws);
-  hipLaunchKernelGGL(append_grant_kernel, dim3(1), dim3(256), 0, st, v, ws);
   // A decode-style call (few tokens) spreads the kv-heads of a token over several workgroups so
   // that their load-quantise-store chains run side by side; a bulk call keeps one workgroup per
   // token, which repeats the slot selection once instead of once per pass.
