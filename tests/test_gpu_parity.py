@@ -123,3 +123,83 @@ def test_flags_and_degenerate_cases():
     seq5 = torch.zeros(5, dtype=torch.int32, device=dev)
     with pytest.raises(RuntimeError, match="invalid argument"):
         B.thinkv_decode_attention(gc, 0, q5, out5, None, seq5, None, 0, 0.125, 4)
+
+
+def test_sequences_compete_for_the_last_pages_in_one_call():
+    _say("one append call in which four sequences want more new pages than the pools hold")
+    from paper_2510_01290_amd import binding as B
+    geom = synth.Geometry(1, 8, 2, 64, "f16", (8, 2, 4))
+    wl = synth.Workload("pool", geom, 0, 4, [np.zeros(64, np.uint8)] * 4, [], (0,), np.zeros(4, np.int32))
+    # type 0: five pages for 4 x 2 wanted; type 1: three pages for 1 + 2 + 2 wanted; type 2 untouched
+    gc = parity.make_gpu_cache(wl, arena_pages=(5, 3, 2), max_pages=4)
+    ob = parity.make_oracle(wl, arena_pages=(5, 3, 2), max_pages=4)
+    gb = parity.GpuBackend(gc)
+    seqs, pos, cls = [], [], []
+    for s, (n0, n1) in enumerate([(20, 5), (30, 0), (17, 20), (32, 18)]):   # tokens of type 0 / type 1 per sequence
+        c = [0] * n0 + [1] * n1
+        rng = np.random.default_rng(100 + s)
+        rng.shuffle(c)
+        seqs += [s] * len(c)
+        pos += list(range(len(c)))
+        cls += c
+    n = len(seqs)
+    k = synth.normals((7, 1), 0, n * 2 * 64, "cpu").view(n, 2, 64).to(torch.float16)
+    v = synth.normals((7, 2), 0, n * 2 * 64, "cpu").view(n, 2, 64).to(torch.float16)
+    a = gb.append(0, k.to(gc.device), v.to(gc.device), np.array(seqs), np.array(pos), np.array(cls, dtype=np.uint8))
+    b = ob.append(0, k, v, np.array(seqs), np.array(pos), np.array(cls, dtype=np.uint8))
+    assert np.array_equal(a, b), (a, b)
+    assert (a == -1).any() and (a != -1).any()
+    parity.compare_bookkeeping_full(ob.cache, gc)
+    st = gc.dev_status.cpu().numpy()
+    # type 0: sequences 0 and 1 get two pages each, sequence 2 the last one, sequence 3 none
+    assert np.array_equal(gc.n_pages[:, 0, 0].cpu().numpy(), [2, 2, 1, 0])
+    assert np.array_equal(gc.n_pages[:, 0, 1].cpu().numpy(), [1, 0, 2, 0])
+    assert [bool(x & B.ST_NOPAGES) for x in st[:4]] == [False, False, True, True]
+    assert gc.free_top.cpu().numpy().tolist() == [0, 0, 2]
+    # a second call finds the pools empty for types 0 and 1 and still fills the tails that are left
+    seqs2, pos2, cls2 = [0] * 14, list(range(100, 114)), [0] * 14                  # sequence 0: 12 free slots in its last page
+    k2 = synth.normals((8, 1), 0, 14 * 2 * 64, "cpu").view(14, 2, 64).to(torch.float16)
+    a2 = gb.append(0, k2.to(gc.device), k2.to(gc.device), np.array(seqs2), np.array(pos2), np.array(cls2, dtype=np.uint8))
+    b2 = ob.append(0, k2, k2, np.array(seqs2), np.array(pos2), np.array(cls2, dtype=np.uint8))
+    assert np.array_equal(a2, b2) and (a2[:12] != -1).all() and (a2[12:] == -1).all()
+    parity.compare_bookkeeping_full(ob.cache, gc)
+    parity.compare_sequences(ob.cache, gc, [(s, s, 0) for s in range(4)], check_bytes=True)
+
+
+def test_window_with_positions_out_of_order():
+    _say("sliding window over pages whose positions were written out of order and reused")
+    geom = synth.Geometry(1, 8, 2, 64, "f16", (8, 2, 4))
+    n = 96
+    wl = synth.Workload("winpos", geom, 3, 1, [np.zeros(4096, np.uint8)], [], (40,), np.array([2000], np.int32))
+    gc = parity.make_gpu_cache(wl, arena_pages=(8, 8, 8), max_pages=8)
+    ob = parity.make_oracle(wl, arena_pages=(8, 8, 8), max_pages=8)
+    gb = parity.GpuBackend(gc)
+    rng = np.random.default_rng(5)
+    # 96 tokens over three types with positions in a scrambled order: recent and old positions share pages
+    pos = rng.permutation(np.arange(1900, 1900 + n)).astype(np.int64)
+    cls = rng.integers(0, 3, size=n).astype(np.uint8)
+    k = synth.normals((9, 1), 0, n * 2 * 64, "cpu").view(n, 2, 64).to(torch.float16)
+    v = synth.normals((9, 2), 0, n * 2 * 64, "cpu").view(n, 2, 64).to(torch.float16)
+    ha = gb.append(0, k.to(gc.device), v.to(gc.device), np.zeros(n, np.int64), pos, cls)
+    hb = ob.append(0, k, v, np.zeros(n, np.int64), pos, cls)
+    assert np.array_equal(ha, hb)
+    # evict the most recent third (their positions stay behind as the pages' upper bounds), refill with old positions
+    ev = ha[np.argsort(pos)[-32:]]
+    gb.evict(0, np.zeros(32, np.int64), ev)
+    ob.evict(0, np.zeros(32, np.int64), ev)
+    pos2 = np.arange(100, 116, dtype=np.int64)
+    cls2 = rng.integers(0, 3, size=16).astype(np.uint8)
+    k2 = synth.normals((9, 3), 0, 16 * 2 * 64, "cpu").view(16, 2, 64).to(torch.float16)
+    assert np.array_equal(gb.append(0, k2.to(gc.device), k2.to(gc.device), np.zeros(16, np.int64), pos2, cls2),
+                          ob.append(0, k2, k2, np.zeros(16, np.int64), pos2, cls2))
+    parity.compare_bookkeeping_full(ob.cache, gc)
+    for qp in (1995, 1940, 1966, 130, 50):
+        wl.q_pos = np.array([qp], dtype=np.int32)
+        ref, ref_lse = parity.oracle_attention(ob.cache, wl, 0, [0], [0])
+        for variant in ("fast", "valu"):
+            got, lse = parity.gpu_attention(gc, wl, None, 0, torch.float32, variant, max_ctx_pages=24)
+            assert np.abs(got - ref).max() <= parity.TOL, (qp, variant, np.abs(got - ref).max())
+            fin = np.isfinite(ref_lse)
+            assert np.array_equal(np.isfinite(lse), fin)
+            assert not fin.any() or np.abs(lse[fin] - ref_lse[fin]).max() <= 1e-3
+            assert fin.any() or not got.any()                      # nothing visible: zeros and -inf
