@@ -135,7 +135,19 @@ def main():
         B.thinkv_append_quantized(gc, 0, k_new[i], v_new[i], ev_seq, t_pos[i], t_cls[i], h_out)
         marks[j][2].record()
         decode(gc, 0, q_all[i], out, lse, ev_seq, t_pos[i], 0, scale, max_ctx_pages)
+    # decode attention with the attention-sparsity statistic riding on it (same cache state)
+    sp = torch.empty(args.batch, dtype=torch.float32, device=dev)
+    smarks = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_extra)]
+    if args.variant == "fast":
+        i = nsteps - 1
+        for j in range(n_extra + 3):
+            if j >= 3:
+                smarks[j - 3][0].record()
+            B.thinkv_decode_attention_sparsity(gc, 0, q_all[i], out, lse, sp, ev_seq, t_pos[i], 0, scale, max_ctx_pages)
+            if j >= 3:
+                smarks[j - 3][1].record()
     torch.cuda.synchronize()
+    attn_sparsity_us = float(np.median([a.elapsed_time(b) for a, b in smarks]) * 1e3) if args.variant == "fast" else None
     evict_us = float(np.median([m[0].elapsed_time(m[1]) for m in marks]) * 1e3)
     append_us = float(np.median([m[1].elapsed_time(m[2]) for m in marks]) * 1e3)
     assert int(gc.dev_status.abs().sum().item()) == 0, "device flags set during the timed steps"
@@ -161,6 +173,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "us_per_step": ms_step * 1e3, "attn_us_mean": float(attn_ms.mean() * 1e3), "attn_us_min": float(attn_ms.min() * 1e3),
         "attn_us_median": float(np.median(attn_ms) * 1e3), "evict_us_median": evict_us, "append_us_median": append_us,
+        "attn_with_sparsity_statistic_us_median": attn_sparsity_us,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16" if args.variant == "fast" else "f32",
         "data": "synthetic",
         "config": {"workload": wl.name + " (R1-Llama-8B layer: 32 q / 8 kv heads, head_dim 128, bf16; T8/R4/E2, 30% E + 10% R evicted and refilled)",

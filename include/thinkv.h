@@ -197,6 +197,35 @@ int thinkv_decode_attention_valu(const thinkv_view* view, int32_t layer, const v
                                  float softmax_scale, thinkv_dtype q_dtype, thinkv_dtype out_dtype,
                                  int32_t max_ctx_pages, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Decode attention plus the attention-sparsity statistic of the step, from which the paper reads
+ * the thought type (Sec. 4.1: the normalised attention scores of a decode step, an entry being
+ * negligible below 1 % of its row's maximum; appendix "Grouped-Query Attention": per group of
+ * query heads the scaled scores q_{h,g} . k^_j * softmax_scale are max-pooled over the G heads,
+ * the pooled row is renormalised by a softmax over the keys, and the fractions of negligible
+ * entries are averaged over the groups).  The keys are the same visible live set as for the
+ * attention output.
+ *
+ *   sparsity   DEVICE [B] float, not NULL: mean over kv-heads of
+ *              #{ j : softmax(pooled)_j < 0.01 * max_j softmax(pooled)_j } / #visible tokens,
+ *              0 where nothing is visible.  Scores are binary32; an entry within rounding of the
+ *              boundary may fall on either side.
+ *   workspace  at least thinkv_decode_sparsity_workspace_bytes(cfg, B, max_ctx_pages): the pooled
+ *              score of every slot is kept between the kernels, 64 bytes per page and kv-head.
+ *              Sequences longer than max_ctx_pages pages are counted over their first
+ *              max_ctx_pages pages only.
+ * Everything else as thinkv_decode_attention, which this call otherwise equals (same out, lse).
+ * The thresholds that turn the statistic into a thought type come from calibration and stay
+ * with the caller.  Needs head_dim 64 or 128 and at most 8 query heads per kv-head
+ * (THINKV_E_UNSUPPORTED otherwise).
+ */
+size_t thinkv_decode_sparsity_workspace_bytes(const thinkv_config* cfg, int32_t B, int32_t max_ctx_pages);
+int thinkv_decode_attention_sparsity(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
+                                     float* sparsity, const int32_t* seq_ids, const int32_t* q_pos, int32_t B,
+                                     int32_t window, float softmax_scale, thinkv_dtype q_dtype,
+                                     thinkv_dtype out_dtype, int32_t max_ctx_pages, void* workspace,
+                                     size_t workspace_bytes, void* stream);
+
 const char* thinkv_status_string(int status);
 
 #ifdef __cplusplus

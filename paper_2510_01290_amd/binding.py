@@ -15,7 +15,8 @@ _DT = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
 ST_NOPAGES, ST_BAD_CLASS, ST_BAD_SLOT, ST_EVICT_DEAD, ST_BAD_SEQ = 1, 2, 4, 8, 16
 EXPORTS = ["thinkv_block_bytes", "thinkv_page_bytes", "thinkv_append_workspace_bytes",
            "thinkv_decode_workspace_bytes", "thinkv_init_view", "thinkv_append_quantized", "thinkv_evict",
-           "thinkv_decode_attention", "thinkv_decode_attention_valu", "thinkv_status_string"]
+           "thinkv_decode_attention", "thinkv_decode_attention_valu", "thinkv_decode_sparsity_workspace_bytes",
+           "thinkv_decode_attention_sparsity", "thinkv_status_string"]
 
 
 class Config(C.Structure):
@@ -57,6 +58,11 @@ def load():
         fn = getattr(lib, name)
         fn.restype = C.c_int
         fn.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, vp, i32, i32, C.c_float, C.c_int, C.c_int, i32, vp, sz, vp]
+    lib.thinkv_decode_sparsity_workspace_bytes.restype = sz
+    lib.thinkv_decode_sparsity_workspace_bytes.argtypes = [C.POINTER(Config), i32, i32]
+    lib.thinkv_decode_attention_sparsity.restype = C.c_int
+    lib.thinkv_decode_attention_sparsity.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, vp, vp, i32, i32, C.c_float, C.c_int, C.c_int,
+                                                     i32, vp, sz, vp]
     lib.thinkv_status_string.restype = C.c_char_p
     lib.thinkv_status_string.argtypes = [C.c_int]
     _lib = lib
@@ -189,6 +195,22 @@ def _decode(fn, cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale
 def thinkv_decode_attention(cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale, max_ctx_pages, stream=None):
     _decode(load().thinkv_decode_attention, cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale,
             max_ctx_pages, stream)
+
+
+def thinkv_decode_attention_sparsity(cache, layer, q, out, lse, sparsity, seq_ids, q_pos, window, softmax_scale, max_ctx_pages,
+                                     stream=None):
+    B = int(q.shape[0])
+    assert q.is_contiguous() and out.is_contiguous() and tuple(q.shape) == tuple(out.shape)
+    assert tuple(q.shape[1:]) == (cache.cfg.n_q_heads, cache.cfg.head_dim)
+    assert seq_ids.dtype == torch.int32 and (q_pos is None or q_pos.dtype == torch.int32)
+    assert lse is None or (lse.dtype == torch.float32 and lse.numel() == B * cache.cfg.n_q_heads)
+    assert sparsity.dtype == torch.float32 and sparsity.numel() == B and sparsity.is_contiguous()
+    nb = load().thinkv_decode_sparsity_workspace_bytes(C.byref(cache.cfg), B, int(max_ctx_pages))
+    ws = cache.workspace(nb)
+    _check(load().thinkv_decode_attention_sparsity(
+        C.byref(cache.view), layer, _ptr(q), _ptr(out), _ptr(lse), _ptr(sparsity), _ptr(seq_ids), _ptr(q_pos), B, window,
+        float(softmax_scale), _DT[q.dtype], _DT[out.dtype], int(max_ctx_pages), _ptr(ws), ws.numel(), _stream(stream)),
+        "thinkv_decode_attention_sparsity")
 
 
 def thinkv_decode_attention_valu(cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale, max_ctx_pages, stream=None):

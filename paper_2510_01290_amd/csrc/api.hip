@@ -12,6 +12,9 @@ int launch_evict(const thinkv_view& v, int layer, const int32_t* ev_seq, const i
 int launch_init(const thinkv_view& v, hipStream_t st);
 int launch_decode_simple(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
 int launch_decode_mfma(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
+int launch_decode_mfma_stat(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
+int launch_stat_fill(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
+int launch_stat_count(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
 int launch_decode_merge(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
 int decode_mfma_supported(const thinkv_config& c);
 
@@ -83,7 +86,7 @@ static void split_bounds(int max_ctx_pages, int ppi, int* max_big, int* max_smal
 static int decode_common(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
                          const int32_t* seq_ids, const int32_t* q_pos, int32_t B, int32_t window, float softmax_scale,
                          int q_dtype, int out_dtype, int32_t max_ctx_pages, void* workspace, size_t workspace_bytes,
-                         void* stream, bool fast) {
+                         void* stream, bool fast, float* sparsity = nullptr) {
   int rc = check_view(view);
   if (rc) return rc;
   if (B < 0 || layer < 0 || layer >= view->cfg.n_layers || window < 0 || max_ctx_pages < 0) return THINKV_E_INVALID_ARG;
@@ -93,8 +96,10 @@ static int decode_common(const thinkv_view* view, int32_t layer, const void* q, 
   if (!q || !out || !seq_ids || !workspace || (window > 0 && !q_pos)) return THINKV_E_INVALID_ARG;
   if (q_dtype != THINKV_F16 && q_dtype != THINKV_BF16) return THINKV_E_UNSUPPORTED;
   if (out_dtype != THINKV_F16 && out_dtype != THINKV_BF16 && out_dtype != THINKV_F32) return THINKV_E_UNSUPPORTED;
-  if (workspace_bytes < thinkv_decode_workspace_bytes(&view->cfg, B, max_ctx_pages)) return THINKV_E_WORKSPACE;
+  const size_t partial_bytes = thinkv_decode_workspace_bytes(&view->cfg, B, max_ctx_pages);
+  if (workspace_bytes < (sparsity ? thinkv_decode_sparsity_workspace_bytes(&view->cfg, B, max_ctx_pages) : partial_bytes)) return THINKV_E_WORKSPACE;
   fast = fast && decode_mfma_supported(view->cfg);
+  if (sparsity && !fast) return THINKV_E_UNSUPPORTED;
   DecodeArgs a;
   a.q = q;
   a.out = out;
@@ -113,7 +118,22 @@ static int decode_common(const thinkv_view* view, int32_t layer, const void* q, 
   a.max_split = a.max_big + a.max_small;
   if (a.max_split > 1024) return THINKV_E_SHAPE;   // merge kernel keeps one weight per item in LDS
   a.scale_log2e = softmax_scale * 1.4426950408889634f;
+  a.stat = nullptr;
+  a.stat_stride = 0;
+  a.sparsity = sparsity;
   hipStream_t st = (hipStream_t)stream;
+  if (sparsity) {
+    // pooled scores behind the partials (whose size is a multiple of 16 bytes)
+    a.stat = (float*)((char*)workspace + ((partial_bytes + 255) & ~(size_t)255));
+    a.stat_stride = (int64_t)kPage * (max_ctx_pages > 0 ? max_ctx_pages : 1);
+    rc = launch_stat_fill(*view, a, st);
+    if (rc) return rc;
+    rc = launch_decode_mfma_stat(*view, a, st);
+    if (rc) return rc;
+    rc = launch_decode_merge(*view, a, st);
+    if (rc) return rc;
+    return launch_stat_count(*view, a, st);
+  }
   rc = fast ? launch_decode_mfma(*view, a, st) : launch_decode_simple(*view, a, st);
   if (rc) return rc;
   return launch_decode_merge(*view, a, st);
@@ -146,6 +166,13 @@ size_t thinkv_decode_workspace_bytes(const thinkv_config* cfg, int32_t B, int32_
   split_bounds(max_ctx_pages, kMinPagesPerItem, &mb, &msm);
   const int ms = mb + msm;
   return (size_t)(B > 0 ? B : 1) * cfg->n_q_heads * ms * (cfg->head_dim + 2) * sizeof(float);
+}
+
+size_t thinkv_decode_sparsity_workspace_bytes(const thinkv_config* cfg, int32_t B, int32_t max_ctx_pages) {
+  const size_t partial = thinkv_decode_workspace_bytes(cfg, B, max_ctx_pages);
+  if (partial == 0) return 0;
+  return ((partial + 255) & ~(size_t)255) +
+         (size_t)(B > 0 ? B : 1) * cfg->n_kv_heads * (kPage * (size_t)(max_ctx_pages > 0 ? max_ctx_pages : 1) + 1) * sizeof(float);
 }
 
 int thinkv_init_view(const thinkv_view* view, void* stream) {
@@ -193,6 +220,15 @@ int thinkv_decode_attention_valu(const thinkv_view* view, int32_t layer, const v
                                  void* workspace, size_t workspace_bytes, void* stream) {
   return decode_common(view, layer, q, out, lse, seq_ids, q_pos, B, window, softmax_scale, (int)q_dtype, (int)out_dtype,
                        max_ctx_pages, workspace, workspace_bytes, stream, false);
+}
+
+int thinkv_decode_attention_sparsity(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
+                                     float* sparsity, const int32_t* seq_ids, const int32_t* q_pos, int32_t B,
+                                     int32_t window, float softmax_scale, thinkv_dtype q_dtype, thinkv_dtype out_dtype,
+                                     int32_t max_ctx_pages, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!sparsity && B > 0) return THINKV_E_INVALID_ARG;
+  return decode_common(view, layer, q, out, lse, seq_ids, q_pos, B, window, softmax_scale, (int)q_dtype, (int)out_dtype,
+                       max_ctx_pages, workspace, workspace_bytes, stream, true, sparsity);
 }
 
 const char* thinkv_status_string(int status) {

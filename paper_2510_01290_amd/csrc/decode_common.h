@@ -30,6 +30,10 @@ struct DecodeArgs {
   int max_big, max_small;   // grid extents (>= the counts of any sequence)
   int max_split;        // max_big + max_small: partial rows per (query, head)
   float scale_log2e;    // softmax_scale * log2(e)
+  // sparsity statistic (null / 0 on plain attention calls)
+  float* stat;          // [B][n_kv_heads][stat_stride] pooled scores, 16 per page in page-list order (types 0, 1, 2)
+  int64_t stat_stride;  // floats per (query, kv-head): 16 * max_ctx_pages
+  float* sparsity;      // [B]
 };
 
 struct ItemPlan {

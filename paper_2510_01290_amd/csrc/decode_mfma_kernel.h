@@ -1,0 +1,668 @@
+// Decode attention on the matrix cores (gfx950).
+//
+// The affine dequantisation is distributed over the dot products so that the matrix cores
+// only ever see exact operands:
+//
+//   scores   q.k^_t = sum_g [ s_K(t,g) * (sum_{i in g} q_i c_K(t,i)) + zp_K(t,g) * (sum_{i in g} q_i) ]
+//   values   o_c    = sum_t [ (p_t s_V(t,g(c))) * c_V(t,c) ]  +  sum_t p_t zp_V(t,g(c))
+//
+// The integer codes c are fed to v_mfma_f32_16x16x32_f16 as binary16 numbers without any
+// conversion: a b-bit field masked inside a 16-bit half IS the binary16 (sub)normal
+// c * 2^(position-24); the power of two is folded into the query (for K) or into the output
+// scale (for V).  A quantisation group is 32 channels = the K extent of one MFMA.
+//
+// Column plan.  The 16 MFMA columns are cut into CS slices of GP columns (GP = 4 or 8 >= the
+// number G of query heads that share the kv-head); slice gl carries the G heads *for
+// quantisation group gl* (of the column set being worked on: D/32 groups = NSET sets of CS).
+// Scores: the query of group g is placed in slice g's columns only (zeros elsewhere) and the
+// MFMAs of the CS groups of a set accumulate into ONE 16x16 tile, tokens x (group, head).
+// Lane (column n, row quad qd) then applies, to its four tokens, the scale and zero-point of
+// ITS group -- lane-local binary32 arithmetic on values the lane loaded itself, no broadcast
+// -- and two DPP row rotations add the slices, leaving the complete score of head n % GP in
+// every slice.  That register layout is already the B-operand layout of the PV product.
+// Values: p * s_V(t, g) is likewise lane-local (each slice multiplies by its own group's
+// scale), is split once into two binary16 terms (22 significant bits), and the same B operand
+// pair serves the PV MFMAs of every group of the set: the tile of a 16-channel block is only
+// read back in the slice of its group.  The zero-point part of the output and the softmax
+// denominator are lane-local binary32 sums.
+//
+// One workgroup of four waves per (query, kv-head, item); the pages of every thought type are
+// walked type by type, so the bit width is a compile-time constant of each inner loop; the
+// four waves are merged through LDS into one partial (m, l, acc) per query head.
+//
+// Work distribution.  On sliding-window layers an item owns a fixed share of each type's page
+// list and a wave takes every fourth page pair of it.  On full-attention layers the launch is
+// sized so that all workgroups are resident at once, and the waves of all workgroups of one
+// (query, kv-head) draw chunks of page pairs from three shared counters (one per type) until
+// the lists are empty: the kernel is bound by memory there, compute units do not all see the
+// same bandwidth, and a fixed split would leave the fast ones idle for the last fifth of the
+// launch.  Which workgroup adds a pair to its partial does not matter: the merge kernel sums
+// the partials of a head whatever they hold.
+#pragma once
+#include "decode_common.h"
+
+namespace thinkv {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef uint16_t ushort2v __attribute__((ext_vector_type(2)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef float float2v __attribute__((ext_vector_type(2)));
+
+union H8 {
+  half8 h;
+  uint32_t u[4];
+};
+
+// x + (x of the lane DIST places further round this lane's row of 16)
+template <int DIST>
+__device__ __forceinline__ float add_row_ror(float x) {
+  const int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x120 + DIST, 0xf, 0xf, true);
+  return x + __builtin_bit_cast(float, y);
+}
+
+// max(x, x of another lane), the other lane chosen by a DPP control word: 0xB1 / 0x4E swap
+// neighbours / pairs inside a quad of lanes, 0x120 + d rotates the row of 16 by d
+template <int CTRL>
+__device__ __forceinline__ float max_dpp(float x) {
+  const int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true);
+  return fmaxf(x, __builtin_bit_cast(float, y));
+}
+
+__device__ __forceinline__ uint32_t pack_rne(float a, float b) {
+  float2v f = {a, b};
+  half2v h = __builtin_convertvector(f, half2v);
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+__device__ __forceinline__ float half_lo(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u & 0xFFFFu)); }
+__device__ __forceinline__ float half_hi(uint32_t u) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(u >> 16)); }
+// binary16 number r (0..3) of the dword pair (a, b)
+template <int R>
+__device__ __forceinline__ float half_of(uint32_t a, uint32_t b) {
+  return R == 0 ? half_lo(a) : (R == 1 ? half_hi(a) : (R == 2 ? half_lo(b) : half_hi(b)));
+}
+
+// Field geometry of a b-bit layout: FPH fields per 16-bit half-word.  The matrix core adds the
+// products of one instruction in a fixed-width window below the largest *nominal* product
+// exponent, and a subnormal operand keeps its nominal exponent (2^-14) however many leading
+// zeros it has -- so a code left at the bottom of the half-word would cost up to ten bits of the
+// sum.  Every field is therefore moved, by one shift shared with its neighbour field, to sit
+// just under bit 11 (offset OMIN or OMIN + BITS), and only the residual 2^REL is folded into
+// the other operand.  8-bit codes fill the low byte as they are.
+template <int BITS>
+struct Fld {
+  static constexpr int FPH = 16 / BITS;
+  static constexpr uint32_t MASK = ((1u << BITS) - 1u) * 0x00010001u;
+  static constexpr int OMIN = BITS == 2 ? 7 : (BITS == 4 ? 3 : 0);
+  __device__ static constexpr int rel_of(int f) { return BITS == 8 ? 0 : BITS * ((f % FPH) & 1); }
+  // operand register (two codes: low/high half) for field f of the chunk words w[]
+  __device__ static __forceinline__ uint32_t get(const uint32_t* w, int f) {
+    const int word = f / FPH, pos = f % FPH;
+    const uint32_t x = w[word];
+    if constexpr (BITS == 8) {
+      if (pos == 0) return x & MASK;
+      const ushort2v y = __builtin_bit_cast(ushort2v, x) >> (uint16_t)8;   // both halves at once
+      return __builtin_bit_cast(uint32_t, y);
+    } else {
+      // field pair (pos & ~1, pos | 1) starts at bit BITS*(pos & ~1); bring it to bit OMIN
+      const int from = BITS * (pos & ~1);
+      const uint32_t y = from <= OMIN ? (x << (OMIN - from)) : (x >> (from - OMIN));
+      return y & (MASK << (OMIN + BITS * (pos & 1)));
+    }
+  }
+};
+
+// How the 16 columns are shared between query heads and quantisation groups.
+template <int D, int GP>
+struct Cols {
+  static constexpr int NG = D / 32;
+  static constexpr int CS = (16 / GP) < NG ? (16 / GP) : NG;   // groups (slices) per column set
+  static constexpr int NSET = NG / CS;
+};
+
+// What one lane holds of one page: its K and V chunks and, per column set, the scales and
+// zero-points of (its slice's group, its four slots) for K and for V.
+template <int D, int BITS, int NSET>
+struct PageRegs {
+  static constexpr int CW = (D / 32) * BITS / 4;  // chunk dwords
+  uint32_t kw[CW], vw[CW];
+  uint4 km[NSET], vm[NSET];   // (scale 0|1, scale 2|3, zero-point 0|1, zero-point 2|3)
+};
+
+template <int D, int BITS, int NSET>
+__device__ __forceinline__ void load_page(PageRegs<D, BITS, NSET>& r, const uint8_t* blk, int lane, const int* meta_off) {
+  constexpr int CW = PageRegs<D, BITS, NSET>::CW;
+  const BlockGeom g = block_geom(BITS, D);
+  const uint32_t* kc = (const uint32_t*)(blk + g.k_codes) + lane * CW;
+  const uint32_t* vc = (const uint32_t*)(blk + g.v_codes) + lane * CW;
+  if constexpr (CW == 1) {
+    r.kw[0] = kc[0];
+    r.vw[0] = vc[0];
+  } else if constexpr (CW == 2) {
+    const uint2 a = *(const uint2*)kc, b = *(const uint2*)vc;
+    r.kw[0] = a.x; r.kw[1] = a.y;
+    r.vw[0] = b.x; r.vw[1] = b.y;
+  } else {
+#pragma unroll
+    for (int i = 0; i < CW; i += 4) {
+      const uint4 a = *(const uint4*)(kc + i), b = *(const uint4*)(vc + i);
+      r.kw[i] = a.x; r.kw[i + 1] = a.y; r.kw[i + 2] = a.z; r.kw[i + 3] = a.w;
+      r.vw[i] = b.x; r.vw[i + 1] = b.y; r.vw[i + 2] = b.z; r.vw[i + 3] = b.w;
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < NSET; ++s) {
+    r.km[s] = *(const uint4*)(blk + g.k_meta + meta_off[s]);
+    r.vm[s] = *(const uint4*)(blk + g.v_meta + meta_off[s]);
+  }
+}
+
+template <int D, int NSET>
+struct WaveState {
+  static constexpr int NM = D / 16;
+  float4v o[NM];    // o[mb][r]: channel 16*mb + 4*qd + r of column n, in units of the class
+  float oz[NSET];   // this lane's share of sum_t p_t zp_V(t, group of the lane's slice)
+  float l;          // this lane's share of sum_t p_t
+  float m;          // running maximum (log2 domain) of column n; -inf before the first live token
+  float m_sub;      // what the exponent subtracts: m, or 0 while m is -inf
+};
+
+// maximum over the four lanes that share a column (lane ^ 16, lane ^ 32), on the VALU
+__device__ __forceinline__ float col_max(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  auto r16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);   // rows (0,1) and (2,3) exchanged
+  x = fmaxf(__builtin_bit_cast(float, (uint32_t)r16[0]), __builtin_bit_cast(float, (uint32_t)r16[1]));
+  const uint32_t w = __builtin_bit_cast(uint32_t, x);
+  auto r32 = __builtin_amdgcn_permlane32_swap(w, w, false, false);   // halves exchanged
+  return fmaxf(__builtin_bit_cast(float, (uint32_t)r32[0]), __builtin_bit_cast(float, (uint32_t)r32[1]));
+}
+
+struct PairIds {
+  int pid_a, pid_b;
+  uint32_t live_a, live_b;
+  int idx_a, idx_b;   // positions in the type's page list (idx_b = -1: no second page); used by STAT only
+};
+
+template <int D, int BITS, int NSET>
+struct PairRegs {
+  PageRegs<D, BITS, NSET> a, b;
+};
+
+// One wave's share of an item: page pairs wave, wave+4, ... of tab[p0..p1).
+// STAT: besides attending, leave the group-pooled score of every visited slot (the maximum over
+// the query heads of the group of the scaled score, log2 domain; -inf for a dead or invisible
+// slot) in a[.].stat, for the attention-sparsity statistic.
+template <int D, int BITS, int GP, bool STAT>
+struct ClassRunner {
+  using CL = Cols<D, GP>;
+  static constexpr int NG = D / 32, NM = D / 16, CS = CL::CS, NSET = CL::NSET;
+  using F = Fld<BITS>;
+  using Pair = PairRegs<D, BITS, NSET>;
+  WaveState<D, NSET>& st;
+  const thinkv_view& v;
+  const DecodeArgs& a;
+  const int cls, hkv, qpos;
+  const int32_t* tab;
+  const int p0, p1, wave;
+  int lane, qd, n;
+  int meta_off[NSET];  // byte offset, inside a meta region, of this lane's unit per column set
+  H8 bq[NG];           // B operands of the score MFMAs: q of group g in slice g % CS, zeros elsewhere
+  float qs[NSET];      // 2^(OMIN-24) * sum_{i in group} q_i of this lane's (slice group, head)
+  float kappa;         // 2^(24-OMIN) * softmax_scale * log2(e): MFMA score units -> log2 domain
+  float neg1;          // -1, kept opaque so that x - (float)h stays one fused mixed-precision instruction
+  float* stat;         // STAT: pooled scores of this type's page list, 16 per page
+  int stat_room;       // STAT: pages of this list the buffer has room for (the host's bound on the context)
+  bool head_ok;        // this lane's column belongs to a query head of the group
+
+  __device__ __forceinline__ ClassRunner(WaveState<D, NSET>& st_, const thinkv_view& v_, const DecodeArgs& a_, int cls_,
+                                         const int32_t* tab_, int p0_, int p1_, int wave_, int hkv_, int G, const _Float16* s_q,
+                                         const float* s_qsum, int qpos_, float* stat_, int stat_room_)
+      : st(st_), v(v_), a(a_), cls(cls_), hkv(hkv_), qpos(qpos_), tab(tab_), p0(p0_), p1(p1_), wave(wave_), stat(stat_), stat_room(stat_room_) {
+    lane = threadIdx.x & 63;
+    qd = lane >> 4;
+    n = lane & 15;
+    const int gl = n / GP, head = n % GP;
+    const bool used = gl < CS && head < G;
+    head_ok = head < G;
+    const int glc = gl < CS ? gl : CS - 1;   // unused slices read slice CS-1's unit (finite, multiplied by zeros)
+    kappa = (float)(1 << (24 - F::OMIN)) * a.scale_log2e;
+    neg1 = -1.0f;
+    asm volatile("" : "+v"(neg1));
+#pragma unroll
+    for (int s = 0; s < NSET; ++s) {
+      const int g = s * CS + glc;
+      meta_off[s] = (g * 4 + qd) * 16;
+      qs[s] = used ? s_qsum[head * NG + g] * (1.0f / (float)(1 << (24 - F::OMIN))) : 0.f;
+    }
+    // q of this lane's head and slice group(s), channels 32g + 8qd + e: one 16-byte LDS read per
+    // column set, scaled down by the residual power of two the codes of those fields carry (exact:
+    // power-of-two scaling of binary16 values), then dealt to the group's operand; the operands of
+    // the other groups are zero in this lane.  Branch-free, so the reads are issued together.
+    H8 mine[NSET];
+#pragma unroll
+    for (int s = 0; s < NSET; ++s) {
+      const int g = s * CS + glc;
+      const uint4 raw = *(const uint4*)(s_q + (used ? head : 0) * D + 32 * g + 8 * qd);
+      mine[s].u[0] = raw.x; mine[s].u[1] = raw.y; mine[s].u[2] = raw.z; mine[s].u[3] = raw.w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) mine[s].h[e] *= (_Float16)(1.0f / (float)(1 << F::rel_of(e >> 1)));   // rel_of depends on the field's parity only
+    }
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const bool on = used && (g % CS) == gl;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) bq[g].u[w] = on ? mine[g / CS].u[w] : 0u;
+    }
+  }
+
+  __device__ __forceinline__ void issue_loads(Pair& r, const PairIds& id) const {
+    const int H = v.cfg.n_kv_heads;
+    const BlockGeom geo = block_geom(BITS, D);
+    const uint8_t* blk_a = v.arena[cls] + ((int64_t)id.pid_a * H + hkv) * geo.block_bytes;
+    const uint8_t* blk_b = v.arena[cls] + ((int64_t)id.pid_b * H + hkv) * geo.block_bytes;
+    load_page<D, BITS, NSET>(r.a, blk_a, lane, meta_off);
+    load_page<D, BITS, NSET>(r.b, blk_b, lane, meta_off);
+  }
+
+  // scores of one page for this lane's four tokens, in MFMA units (times kappa = log2 domain)
+  __device__ __forceinline__ void page_scores(const PageRegs<D, BITS, NSET>& r, float* s) const {
+    const float4v zero = {0.f, 0.f, 0.f, 0.f};
+    float4v c[NSET];
+#pragma unroll
+    for (int set = 0; set < NSET; ++set) {
+#pragma unroll
+      for (int gl = 0; gl < CS; ++gl) {
+        const int g = set * CS + gl;
+        H8 ka;
+#pragma unroll
+        for (int vv = 0; vv < 4; ++vv) ka.u[vv] = F::get(r.kw, 4 * g + vv);
+        c[set] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka.h, bq[g].h, gl == 0 ? zero : c[set], 0, 0, 0);
+      }
+    }
+#define TKV_SCORE(R)                                                                             \
+  {                                                                                              \
+    float acc = 0.f;                                                                             \
+    _Pragma("unroll") for (int set = 0; set < NSET; ++set) {                                     \
+      const float z = fmaf(half_of<R>(r.km[set].z, r.km[set].w), qs[set], 0.0f);                 \
+      const float t = fmaf(half_of<R>(r.km[set].x, r.km[set].y), c[set][R], z);                  \
+      acc = set == 0 ? t : acc + t;                                                              \
+    }                                                                                            \
+    acc = add_row_ror<8>(acc);                                                                   \
+    if constexpr (GP == 4) acc = add_row_ror<4>(acc);                                            \
+    s[R] = acc;                                                                                  \
+  }
+    TKV_SCORE(0) TKV_SCORE(1) TKV_SCORE(2) TKV_SCORE(3)
+#undef TKV_SCORE
+  }
+
+  __device__ __forceinline__ void compute(const Pair& r, const PairIds& id) {
+    const uint32_t live_a = id.live_a, live_b = id.live_b;
+    float sa[4], sb[4];
+    page_scores(r.a, sa);
+    page_scores(r.b, sb);
+    // ---------------- dead slots: score -inf, hence p = 0.  Their scales and zero-points are finite
+    // (stale, or zero in a slot never written: arenas start zero-filled), so they drop out of every sum.
+    if ((live_a & live_b) != 0xFFFFu) {
+      const uint32_t la = (live_a >> (4 * qd)) & 0xFu, lb = (live_b >> (4 * qd)) & 0xFu;
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        sa[r4] = ((la >> r4) & 1u) ? sa[r4] : -INFINITY;
+        sb[r4] = ((lb >> r4) & 1u) ? sb[r4] : -INFINITY;
+      }
+    }
+    if constexpr (STAT) {
+      // pooled scores: maximum over the heads of the group, i.e. over the GP lanes of a slice (all
+      // slices hold the same totals); the lanes of column 0 store their four slots of each page
+      float ua[4], ub[4];
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        ua[r4] = head_ok ? sa[r4] * kappa : -INFINITY;
+        ub[r4] = head_ok ? sb[r4] * kappa : -INFINITY;
+        // a quad of lanes, then (eight heads) the quad four lanes on: the row of 16 holds CS
+        // identical slices, so rotating the row by four reaches the other half of the slice
+        ua[r4] = max_dpp<0x4E>(max_dpp<0xB1>(ua[r4]));
+        ub[r4] = max_dpp<0x4E>(max_dpp<0xB1>(ub[r4]));
+        if constexpr (GP == 8) {
+          ua[r4] = max_dpp<0x124>(ua[r4]);
+          ub[r4] = max_dpp<0x124>(ub[r4]);
+        }
+      }
+      if (n == 0) {
+        if (id.idx_a < stat_room) *(float4*)(stat + (int64_t)id.idx_a * kPage + 4 * qd) = make_float4(ua[0], ua[1], ua[2], ua[3]);
+        if (id.idx_b >= 0 && id.idx_b < stat_room)
+          *(float4*)(stat + (int64_t)id.idx_b * kPage + 4 * qd) = make_float4(ub[0], ub[1], ub[2], ub[3]);
+      }
+    }
+    // ---------------- online softmax over the 8 scores of this lane; the running maximum only
+    // moves when some lane of the wave sees a score above it
+    const float mx = fmaxf(fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3])), fmaxf(fmaxf(sb[0], sb[1]), fmaxf(sb[2], sb[3]))) * kappa;
+    if (__any(mx > st.m)) {
+      const float m_new = fmaxf(st.m, col_max(mx));
+      const float m_sub = m_new == -INFINITY ? 0.f : m_new;
+      const float corr = __builtin_amdgcn_exp2f(st.m - m_sub);
+#pragma unroll
+      for (int mb = 0; mb < NM; ++mb) st.o[mb] *= corr;
+#pragma unroll
+      for (int set = 0; set < NSET; ++set) st.oz[set] *= corr;
+      st.l *= corr;
+      st.m = m_new;
+      st.m_sub = m_sub;
+    }
+    float pa[4], pb[4];
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      pa[r4] = __builtin_amdgcn_exp2f(fmaf(sa[r4], kappa, -st.m_sub));
+      pb[r4] = __builtin_amdgcn_exp2f(fmaf(sb[r4], kappa, -st.m_sub));
+    }
+    st.l += ((pa[0] + pa[1]) + (pa[2] + pa[3])) + ((pb[0] + pb[1]) + (pb[2] + pb[3]));
+    // ---------------- values, per column set: B = two-term split of p * s_V, A = V codes
+#pragma unroll
+    for (int set = 0; set < NSET; ++set) {
+      float xa[4], xb[4], z = st.oz[set];
+#define TKV_PV(R)                                                     \
+  {                                                                   \
+    z = fmaf(half_of<R>(r.a.vm[set].z, r.a.vm[set].w), pa[R], z);           \
+    z = fmaf(half_of<R>(r.b.vm[set].z, r.b.vm[set].w), pb[R], z);           \
+    xa[R] = fmaf(half_of<R>(r.a.vm[set].x, r.a.vm[set].y), pa[R], 0.0f);    \
+    xb[R] = fmaf(half_of<R>(r.b.vm[set].x, r.b.vm[set].y), pb[R], 0.0f);    \
+  }
+      TKV_PV(0) TKV_PV(1) TKV_PV(2) TKV_PV(3)
+#undef TKV_PV
+      st.oz[set] = z;
+      // k-slots 8qd+e: e<4 page a slots 4qd+e, e>=4 page b
+      H8 hi, lo;
+      hi.u[0] = pack_rne(xa[0], xa[1]);
+      hi.u[1] = pack_rne(xa[2], xa[3]);
+      hi.u[2] = pack_rne(xb[0], xb[1]);
+      hi.u[3] = pack_rne(xb[2], xb[3]);
+      lo.u[0] = pack_rne(fmaf(neg1, half_lo(hi.u[0]), xa[0]), fmaf(neg1, half_hi(hi.u[0]), xa[1]));
+      lo.u[1] = pack_rne(fmaf(neg1, half_lo(hi.u[1]), xa[2]), fmaf(neg1, half_hi(hi.u[1]), xa[3]));
+      lo.u[2] = pack_rne(fmaf(neg1, half_lo(hi.u[2]), xb[0]), fmaf(neg1, half_hi(hi.u[2]), xb[1]));
+      lo.u[3] = pack_rne(fmaf(neg1, half_lo(hi.u[3]), xb[2]), fmaf(neg1, half_hi(hi.u[3]), xb[3]));
+#pragma unroll
+      for (int mm = 0; mm < 2 * CS; ++mm) {
+        const int mb = 2 * CS * set + mm;
+        H8 va;
+        // field f = u*NM + mb holds slots (2u, 2u+1) of the lane's slot quad
+        va.u[0] = F::get(r.a.vw, 0 * NM + mb);
+        va.u[1] = F::get(r.a.vw, 1 * NM + mb);
+        va.u[2] = F::get(r.b.vw, 0 * NM + mb);
+        va.u[3] = F::get(r.b.vw, 1 * NM + mb);
+        st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, hi.h, st.o[mb], 0, 0, 0);
+        st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, lo.h, st.o[mb], 0, 0, 0);
+      }
+    }
+  }
+
+  // Dynamic chunks: the type's whole page list tab[0 .. n_pages) is cut into chunks of kChunkPairs
+  // page pairs; *counter hands out chunk numbers to every wave of every workgroup of this
+  // (query, kv-head).  The next chunk number is requested before the current chunk is worked
+  // on, so the round trip of the atomic hides behind a chunk of compute.
+  static constexpr int kChunkPairs = 4;
+  __device__ __forceinline__ int take_chunk(uint32_t* counter) const {
+    int r = 0;
+    if (lane == 0) r = (int)atomicAdd(counter, 1u);
+    return r;   // valid in lane 0; read with readfirstlane when needed
+  }
+  __device__ __forceinline__ void run_dynamic(int n_pages, uint32_t* counter) {
+    const int n_pairs = (n_pages + 1) >> 1;
+    const int n_chunks = (n_pairs + kChunkPairs - 1) / kChunkPairs;
+    const uint32_t* msk = v.slot_mask + (tab - v.block_table);
+    int j = __builtin_amdgcn_readfirstlane(take_chunk(counter));
+    while (j < n_chunks) {
+      const int pg0 = 2 * kChunkPairs * j;
+      const int cnt = n_pages - pg0 < 2 * kChunkPairs ? n_pages - pg0 : 2 * kChunkPairs;
+      int vpid = 0;
+      uint32_t vmask = 0;
+      if (lane < cnt) {
+        vpid = tab[pg0 + lane];
+        vmask = msk[pg0 + lane] & 0xFFFFu;
+      }
+      const int r_next = take_chunk(counter);
+      const int np2 = (cnt + 1) >> 1;
+      for (int pr = 0; pr < np2; ++pr) {
+        PairIds id;
+        id.pid_a = __builtin_amdgcn_readlane(vpid, 2 * pr);
+        id.live_a = __builtin_amdgcn_readlane(vmask, 2 * pr);
+        const int ib = 2 * pr + 1 < cnt ? 2 * pr + 1 : 2 * pr;
+        id.pid_b = __builtin_amdgcn_readlane(vpid, ib);
+        id.live_b = 2 * pr + 1 < cnt ? __builtin_amdgcn_readlane(vmask, ib) : 0u;
+        id.idx_a = pg0 + 2 * pr;
+        id.idx_b = 2 * pr + 1 < cnt ? pg0 + 2 * pr + 1 : -1;
+        if ((id.live_a | id.live_b) == 0) continue;
+        Pair r;
+        issue_loads(r, id);
+        compute(r, id);
+      }
+      j = __builtin_amdgcn_readfirstlane(r_next);
+    }
+  }
+
+  // Static share (sliding-window layers): page ids and live masks of up to 64 pages are fetched
+  // with one vector load each (lane L holds page p0 + base + L).  A page can hold a visible
+  // token only if the largest position ever written into it lies inside the window, so one
+  // word per page (page_pos_max) settles most pages; a lane reads the 16 positions of its page
+  // only when that test passes.  The four waves take every fourth run of 64 pages; the pages of
+  // a run that still have a visible slot are paired up, and ids and masks reach the pair code
+  // through v_readlane.
+  __device__ __forceinline__ void run() {
+    const int n_pages = p1 - p0;
+    for (int base = 64 * wave; base < n_pages; base += 256) {
+      const int cnt = n_pages - base < 64 ? n_pages - base : 64;
+      int vpid = 0;
+      uint32_t vmask = 0;
+      if (lane < cnt) {
+        vpid = tab[p0 + base + lane];
+        vmask = v.slot_mask[(tab - v.block_table) + p0 + base + lane] & 0xFFFFu;
+      }
+      if (a.window > 0) {
+        uint32_t vis = 0;
+        if (vmask != 0 && v.page_pos_max[cls][vpid] > qpos - a.window) {
+          const int4* sp = (const int4*)(v.slot_pos[cls] + (int64_t)vpid * kPage);
+#pragma unroll
+          for (int t4 = 0; t4 < kPage / 4; ++t4) {
+            const int4 pos = sp[t4];
+            const int d0 = qpos - pos.x, d1 = qpos - pos.y, d2 = qpos - pos.z, d3 = qpos - pos.w;
+            vis |= ((d0 >= 0 && d0 < a.window) ? 1u : 0u) << (4 * t4);
+            vis |= ((d1 >= 0 && d1 < a.window) ? 2u : 0u) << (4 * t4);
+            vis |= ((d2 >= 0 && d2 < a.window) ? 4u : 0u) << (4 * t4);
+            vis |= ((d3 >= 0 && d3 < a.window) ? 8u : 0u) << (4 * t4);
+          }
+        }
+        vmask &= vis;
+      }
+      uint64_t todo = __ballot(vmask != 0);
+      while (todo) {
+        const int ia = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        const bool two = todo != 0;
+        const int ib = two ? __builtin_ctzll(todo) : ia;
+        if (two) todo &= todo - 1;
+        PairIds id;
+        id.pid_a = __builtin_amdgcn_readlane(vpid, ia);
+        id.live_a = __builtin_amdgcn_readlane(vmask, ia);
+        id.pid_b = __builtin_amdgcn_readlane(vpid, ib);
+        id.live_b = two ? __builtin_amdgcn_readlane(vmask, ib) : 0u;
+        id.idx_a = p0 + base + ia;
+        id.idx_b = two ? p0 + base + ib : -1;
+        Pair r;
+        issue_loads(r, id);
+        compute(r, id);
+      }
+    }
+  }
+};
+
+template <int D, int GP>
+struct ItemLds {
+  _Float16 q[GP * D];
+  float qsum[GP * (D / 32)];
+  float m[4][GP], l[4][GP];
+  float acc[4][GP][D];
+};
+
+template <int D>
+__device__ __forceinline__ float class_unit(int bits, int mb) {
+  // V codes of a b-bit class enter the MFMA as c * 2^(OMIN + rel(mb) - 24)
+  const int sh = bits == 2 ? Fld<2>::OMIN + Fld<2>::rel_of(mb) : (bits == 4 ? Fld<4>::OMIN + Fld<4>::rel_of(mb) : 0);
+  return (float)(1 << sh);
+}
+
+// One workgroup of four waves per (query, kv-head, item).  WIN: sliding-window layer (static shares).
+template <int D, int GP, bool WIN, bool STAT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void decode_mfma_kernel(thinkv_view v, DecodeArgs a) {
+  using CL = Cols<D, GP>;
+  constexpr int NG = D / 32, NM = D / 16, CS = CL::CS, NSET = CL::NSET;
+  const thinkv_config& c = v.cfg;
+  int b, hkv, item_j;
+  bool item_small;
+  locate_workgroup(a, c.n_kv_heads, blockIdx.x, &b, &hkv, &item_j, &item_small);
+  const int seq = a.seq_ids[b];
+  __shared__ ItemLds<D, GP> lds;
+  int np[3], np_total = 0;
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    np[k] = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
+    np_total += np[k];
+  }
+  const ItemPlan plan = plan_items(a.ppi, a.n_small, a.max_big, a.max_small, np_total);
+  if (item_j >= (item_small ? plan.n_small : plan.n_big)) return;
+  const int split = item_small ? plan.n_big + item_j : item_j;   // the item's row among the partials
+  int u0, u1;
+  item_units(plan, split, &u0, &u1);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int Hq = c.n_q_heads, G = Hq / c.n_kv_heads;
+  for (int i = tid; i < G * D; i += 256)
+    lds.q[i] = (_Float16)load_as_f32(a.q, ((int64_t)b * Hq + hkv * G) * D + i, a.q_dtype);
+  __syncthreads();
+  if (tid < G * NG * 4) {
+    // four threads per (head, group) sum eight channels each
+    const int hg = tid >> 2, part = tid & 3;
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += (float)lds.q[(hg / NG) * D + 32 * (hg % NG) + 8 * part + i];
+    s += __shfl_xor(s, 1, 64);
+    s += __shfl_xor(s, 2, 64);
+    if (part == 0) lds.qsum[hg] = s;
+  }
+  __syncthreads();
+
+  WaveState<D, NSET> st;
+#pragma unroll
+  for (int mb = 0; mb < NM; ++mb) st.o[mb] = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int set = 0; set < NSET; ++set) st.oz[set] = 0.f;
+  st.l = 0.f;
+  st.m = -INFINITY;
+  st.m_sub = 0.f;
+  const int qpos = WIN ? a.q_pos[b] : 0;
+  const int qd = lane >> 4, n = lane & 15;
+
+  // The running output is kept in the units of the class being walked (its codes carry a
+  // power of two that depends on the bit width) and re-based at class boundaries.
+  // Waves and workgroups start on different types: a pair of 8-bit pages moves three times the
+  // bytes of a pair of 2-bit pages for the same arithmetic, so if every wave walked the types in
+  // the same order the whole chip would swing between bandwidth-bound and issue-bound phases.
+  const int rot = (wave + split + hkv + b) % 3;
+  for (int kk = 0; kk < 3; ++kk) {
+    const int k = kk + rot < 3 ? kk + rot : kk + rot - 3;
+    const int bits = c.bits_of_class[k];
+    const int npk = k == 0 ? np[0] : (k == 1 ? np[1] : np[2]);
+    const int p0 = WIN ? (int)((int64_t)u0 * npk / plan.units) : 0, p1 = WIN ? (int)((int64_t)u1 * npk / plan.units) : npk;
+    if (p1 <= p0) continue;
+    const int32_t* tab = v.block_table + table_base(c, seq, a.layer, k);
+    uint32_t* counter = v.work_counters + (((int64_t)a.layer * c.max_seqs + b) * c.n_kv_heads + hkv) * 4 + k;
+    // STAT: the pooled scores of a (query, kv-head) lie in the order of the three page lists
+    float* stat = nullptr;
+    int stat_room = 0;
+    if constexpr (STAT) {
+      const int before = k == 0 ? 0 : (k == 1 ? np[0] : np[0] + np[1]);
+      stat = a.stat + ((int64_t)b * c.n_kv_heads + hkv) * a.stat_stride + (int64_t)before * kPage;
+      stat_room = (int)(a.stat_stride / kPage) - before;
+    }
+#pragma unroll
+    for (int mb = 0; mb < NM; ++mb) st.o[mb] *= class_unit<D>(bits, mb);
+#define TKV_RUN(B_)                                                                                        \
+  {                                                                                                        \
+    ClassRunner<D, B_, GP, STAT> cr(st, v, a, k, tab, p0, p1, wave, hkv, G, lds.q, lds.qsum, qpos, stat, stat_room); \
+    if constexpr (WIN) cr.run();                                                                           \
+    else cr.run_dynamic(npk, counter);                                                                     \
+  }
+    if (bits == 2) TKV_RUN(2) else if (bits == 4) TKV_RUN(4) else TKV_RUN(8)
+#undef TKV_RUN
+#pragma unroll
+    for (int mb = 0; mb < NM; ++mb) st.o[mb] *= 1.0f / class_unit<D>(bits, mb);
+  }
+
+  // ---- fold.  The four lanes of a column (row quads) each hold a share of the denominator
+  // and of the zero-point sums; the tile of channel block mb is valid in the slice of its group.
+  const int gl = n / GP, head = n % GP;
+  float l = st.l;
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+  float zsum[NSET];
+#pragma unroll
+  for (int set = 0; set < NSET; ++set) {
+    float z = st.oz[set];
+    z += __shfl_xor(z, 16, 64);
+    z += __shfl_xor(z, 32, 64);
+    zsum[set] = z;
+  }
+#pragma unroll
+  for (int mb = 0; mb < NM; ++mb) {
+    const int g = mb >> 1, set = g / CS;
+    if (gl == g % CS && head < G) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) lds.acc[wave][head][16 * mb + 4 * qd + r] = st.o[mb][r] * 16777216.f + zsum[set];
+    }
+  }
+  if (qd == 0 && gl == 0 && head < G) {
+    lds.m[wave][head] = st.m;
+    lds.l[wave][head] = l;
+  }
+  __syncthreads();
+  for (int i = tid; i < G * D; i += 256) {
+    const int g = i / D, ch = i % D;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, lds.m[w][g]);
+    float L = 0.f, A = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float f = (lds.m[w][g] == -INFINITY) ? 0.f : exp2f(lds.m[w][g] - M);
+      L += lds.l[w][g] * f;
+      A += lds.acc[w][g][ch] * f;
+    }
+    float* dst = a.partial + partial_index(a, Hq, D, b, hkv * G + g, split);
+    dst[2 + ch] = A;
+    if (ch == 0) {
+      dst[0] = M;
+      dst[1] = L;
+    }
+  }
+}
+
+template <int D, bool WIN, bool STAT>
+static int launch_dw(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {
+  const int G = v.cfg.n_q_heads / v.cfg.n_kv_heads;
+  dim3 grid((a.max_big + a.max_small) * v.cfg.n_kv_heads * a.B), blk(256);
+  if (G <= 4)
+    hipLaunchKernelGGL((decode_mfma_kernel<D, 4, WIN, STAT>), grid, blk, 0, st, v, a);
+  else if (G <= 8)
+    hipLaunchKernelGGL((decode_mfma_kernel<D, 8, WIN, STAT>), grid, blk, 0, st, v, a);
+  else
+    return THINKV_E_SHAPE;
+  return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
+}
+
+// sliding-window layers take static shares, full-attention layers the shared work queues
+template <bool STAT>
+static int launch_decode_mfma_t(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {
+  if (v.cfg.head_dim == 128)
+    return a.window > 0 ? launch_dw<128, true, STAT>(v, a, st) : launch_dw<128, false, STAT>(v, a, st);
+  return a.window > 0 ? launch_dw<64, true, STAT>(v, a, st) : launch_dw<64, false, STAT>(v, a, st);
+}
+
+}  // namespace thinkv
