@@ -1,0 +1,165 @@
+"""Thought-adaptive eviction over the oracle cache: which tokens of a thought segment survive
+(test infrastructure; see oracle/__init__.py).
+
+Sec. 4.3 of the paper ("Think Before you Evict"): a segment of a thought type that is selected
+for eviction the n-th time is cut down to R_n tokens, R = {64, 32, 16, 8, 4}; the survivors are
+chosen by K-means over the segment's post-RoPE keys with K = min(|segment|, R_n): "the cluster
+centroids correspond to keys that are retained, and the corresponding value tokens are
+preserved" (appendix "TBE Eviction Policy": one representative key-value pair per cluster).
+Case 1 anneals every preceding segment when a transition segment ends; Case 2, when the cache
+is over its budget, anneals the oldest segment of the least important type until it fits.
+
+The paper fixes neither the K-means variant, its initialisation, its stopping rule nor any
+tie-break.  This reading (the kernels implement the same one):
+
+  points      x_i = the token's stored keys, dequantised (zp + code * scale), all kv-heads
+              concatenated: eviction is per token, so one clustering serves all heads; tokens
+              in ascending position
+  K >= N      everything survives
+  init        centroid j = point floor(j * N / K)  (evenly spaced over the segment)
+  Lloyd       assign every point to its nearest centroid (squared Euclidean distance; ties ->
+              lowest cluster); stop when no assignment changed or after max_iters assignments;
+              otherwise move every centroid to the mean of its points (a cluster that lost all
+              its points keeps its centroid) and repeat
+  survivors   of every non-empty cluster the point nearest its centroid (ties -> lowest index; a
+              cluster of two points, both equally near their mean whatever the rounding says,
+              keeps the earlier one); so at most K tokens survive, exactly K when no cluster is
+              empty
+
+Everything in binary64.  The decisions are comparisons of floating-point numbers; `margin`
+reports how close the closest one was, so that a test can tell a genuine disagreement with a
+binary32 implementation from a coin toss.
+"""
+import numpy as np
+
+from . import quant
+from .cache import split_handle
+
+RETENTION = (64, 32, 16, 8, 4)
+IMPORTANCE = (0, 1, 2)      # least important first: transition, execution, reasoning (Sec. 4.1 / 4.2 ordering)
+
+
+def _sqdist(x, c):
+    """[N, K] squared distances, written out (no expansion into norms and dot products)"""
+    d = x[:, None, :] - c[None, :, :]
+    return np.einsum("nkd,nkd->nk", d, d)
+
+
+def kmeans_select(x, keep, max_iters=8):
+    """x [N, dim] binary64, points in segment order.  Returns (survivors: sorted indices,
+    margin: smallest gap between the best and the second-best candidate over all decisions,
+    relative to the mean squared norm of the points, objective after every assignment)."""
+    x = np.asarray(x, dtype=np.float64)
+    n = x.shape[0]
+    k = min(n, int(keep))
+    if k >= n:
+        return np.arange(n), np.inf, []
+    cent = x[(np.arange(k) * n) // k].copy()
+    scale = max(float(np.mean(np.einsum("nd,nd->n", x, x))), 1e-300)
+    margin = np.inf
+    prev = None
+    objective = []
+    for _ in range(max_iters):
+        d = _sqdist(x, cent)
+        assign = np.argmin(d, axis=1)                      # first minimum: ties -> lowest cluster
+        if k > 1:
+            two = np.partition(d, 1, axis=1)[:, :2]
+            margin = min(margin, float((two[:, 1] - two[:, 0]).min()) / scale)
+        objective.append(float(d[np.arange(n), assign].sum()))
+        if prev is not None and np.array_equal(assign, prev):
+            break
+        for j in range(k):
+            members = np.flatnonzero(assign == j)
+            if members.size:
+                cent[j] = x[members].mean(axis=0)
+        prev = assign
+    d = _sqdist(x, cent)
+    survivors = []
+    for j in range(k):
+        members = np.flatnonzero(prev == j)
+        if members.size == 0:
+            continue
+        if members.size <= 2:
+            survivors.append(int(members[0]))              # two points are equally near their mean: the earlier one
+            continue
+        dj = d[members, j]
+        survivors.append(int(members[np.argmin(dj)]))      # first minimum: ties -> lowest index
+        two = np.partition(dj, 1)[:2]
+        margin = min(margin, float(two[1] - two[0]) / scale)
+    return np.array(sorted(survivors), dtype=np.int64), margin, objective
+
+
+def segment_keys(cache, layer, seq, handles):
+    """dequantised keys [N, Hkv * D] (binary64) of the listed slots of one sequence"""
+    H, D = cache.cfg.n_kv_heads, cache.cfg.head_dim
+    out = np.zeros((len(handles), H * D))
+    for i, h in enumerate(handles):
+        c, pi, slot = split_handle(h)
+        pid = int(cache.table[seq, layer, c, pi])
+        out[i] = quant.dequantize(cache.k_codes[c][pid, :, slot, :], cache.k_scale[c][pid, :, slot, :],
+                                  cache.k_zp[c][pid, :, slot, :]).reshape(-1)
+    return out
+
+
+def select_evictions(cache, layer, tok_seq, tok_handle, seg_offset, seg_keep, max_iters=8):
+    """The call the kernels implement: segments given as runs [seg_offset[s], seg_offset[s+1]) of
+    (sequence, handle) lists, tokens of a segment in ascending position.  Returns (ev_handle
+    [n_tok]: the handle of every token to evict, -1 for a survivor; smallest margin)."""
+    tok_handle = np.asarray(tok_handle, dtype=np.int64)
+    ev = tok_handle.copy()
+    margin = np.inf
+    for s in range(len(seg_keep)):
+        lo, hi = int(seg_offset[s]), int(seg_offset[s + 1])
+        if hi <= lo:
+            continue
+        x = segment_keys(cache, layer, int(tok_seq[lo]), tok_handle[lo:hi])
+        keep, m, _ = kmeans_select(x, int(seg_keep[s]), max_iters)
+        ev[lo + keep] = -1
+        margin = min(margin, m)
+    return ev.astype(np.int32), margin
+
+
+def anneal_plan(seg_type, seg_live, transition_ended, n_live, budget, retention=RETENTION, importance=IMPORTANCE):
+    """Which segments of one (sequence, layer) are cut, and to how many tokens (Sec. 4.3).
+
+    seg_type[i], seg_live[i]: thought type and live tokens of segment i, oldest first; the last
+    segment is the one being generated and is never touched.  The level of a segment follows
+    from its size: it is cut to the largest retention value below its size.
+    Case 1 (transition_ended): every preceding segment above the lowest retention value goes
+    down one level.  Case 2: while more than `budget` tokens are live, the oldest segment of the
+    least important type that can still shrink goes down one level.
+    Returns [(segment, keep)] in the order the cuts are made; a segment may appear twice."""
+    live = [int(v) for v in seg_live]
+    total = int(n_live)
+    cuts = []
+
+    def next_level(size):
+        for r in retention:
+            if r < size:
+                return r
+        return None
+
+    last = len(live) - 1
+    if transition_ended:
+        for i in range(last):
+            r = next_level(live[i])
+            if r is not None:
+                cuts.append((i, r))
+                total -= live[i] - r
+                live[i] = r
+    while total > budget:
+        pick = None
+        for t in importance:
+            for i in range(last):
+                if seg_type[i] == t and next_level(live[i]) is not None:
+                    pick = i
+                    break
+            if pick is not None:
+                break
+        if pick is None:
+            break
+        r = next_level(live[pick])
+        cuts.append((pick, r))
+        total -= live[pick] - r
+        live[pick] = r
+    return cuts
