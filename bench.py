@@ -146,6 +146,37 @@ def main():
             B.thinkv_decode_attention_sparsity(gc, 0, q_all[i], out, lse, sp, ev_seq, t_pos[i], 0, scale, max_ctx_pages)
             if j >= 3:
                 smarks[j - 3][1].record()
+    # survivor choice of thought-adaptive eviction: 8 segments of 128 consecutive live tokens per sequence, cut to 64
+    tbe = None
+    if args.variant == "fast":
+        t_seq, t_h, off = [], [], [0]
+        for s in range(args.batch):
+            hs = gr.handle[(0, s)]
+            alive = np.flatnonzero(hs[:4096] != -1)
+            dead = np.zeros(len(hs), dtype=bool)
+            for op in wl.ops:
+                if isinstance(op, synth.Evict):
+                    dead[op.pos[op.seqs == s]] = True
+            alive = alive[~dead[alive]][:1024]
+            for a0 in range(0, len(alive) - 127, 128):
+                t_seq += [s] * 128
+                t_h += [int(x) for x in hs[alive[a0:a0 + 128]]]
+                off.append(len(t_h))
+        d_seq = torch.tensor(t_seq, dtype=torch.int32, device=dev)
+        d_h = torch.tensor(t_h, dtype=torch.int32, device=dev)
+        d_off = torch.tensor(off, dtype=torch.int32, device=dev)
+        d_keep = torch.full((len(off) - 1,), 64, dtype=torch.int32, device=dev)
+        d_ev = torch.empty_like(d_h)
+        tm = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+        B.thinkv_tbe_select(gc, 0, d_seq, d_h, d_off, d_keep, d_ev)
+        for a_, b_ in tm:
+            a_.record()
+            B.thinkv_tbe_select(gc, 0, d_seq, d_h, d_off, d_keep, d_ev)
+            b_.record()
+        torch.cuda.synchronize()
+        tbe = {"segments": len(off) - 1, "tokens_per_segment": 128, "keep": 64, "max_iters": 8,
+               "us_median": float(np.median([a_.elapsed_time(b_) for a_, b_ in tm]) * 1e3),
+               "survivors": int((d_ev == -1).sum().item())}
     torch.cuda.synchronize()
     attn_sparsity_us = float(np.median([a.elapsed_time(b) for a, b in smarks]) * 1e3) if args.variant == "fast" else None
     evict_us = float(np.median([m[0].elapsed_time(m[1]) for m in marks]) * 1e3)
@@ -173,7 +204,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "us_per_step": ms_step * 1e3, "attn_us_mean": float(attn_ms.mean() * 1e3), "attn_us_min": float(attn_ms.min() * 1e3),
         "attn_us_median": float(np.median(attn_ms) * 1e3), "evict_us_median": evict_us, "append_us_median": append_us,
-        "attn_with_sparsity_statistic_us_median": attn_sparsity_us,
+        "attn_with_sparsity_statistic_us_median": attn_sparsity_us, "tbe_select": tbe,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16" if args.variant == "fast" else "f32",
         "data": "synthetic",
         "config": {"workload": wl.name + " (R1-Llama-8B layer: 32 q / 8 kv heads, head_dim 128, bf16; T8/R4/E2, 30% E + 10% R evicted and refilled)",

@@ -48,8 +48,12 @@ typedef enum {
 #define THINKV_ST_BAD_SLOT 4u   /* evict handle names no page of that sequence               */
 #define THINKV_ST_EVICT_DEAD 8u /* evict of a slot that holds no live token (ignored)        */
 #define THINKV_ST_BAD_SEQ 16u   /* sequence id outside [0, max_seqs)                         */
+#define THINKV_ST_BAD_SEGMENT 32u /* thinkv_tbe_select: segment larger than THINKV_TBE_MAX_SEGMENT or
+                                    keep outside 1..THINKV_TBE_MAX_KEEP; nothing of it is evicted */
 
 #define THINKV_PAGE_SIZE 16
+#define THINKV_TBE_MAX_SEGMENT 256 /* live tokens of one segment handed to thinkv_tbe_select */
+#define THINKV_TBE_MAX_KEEP 64     /* largest retention level (the paper's schedule starts at 64) */
 #define THINKV_GROUP_SIZE 32
 
 /* Static geometry; host memory, passed by value inside thinkv_view. */
@@ -165,6 +169,8 @@ int thinkv_append_quantized(const thinkv_view* view, int32_t layer, const void* 
  *   ev_seq, ev_handle  DEVICE [n_ev]
  * Sets the slot's reclaimable bit, clears its live bit, decrements n_live.  A handle whose slot
  * holds no live token is ignored (THINKV_ST_EVICT_DEAD); duplicates in one call count once.
+ * A handle of -1 (what append reports for a token it could not place, and what
+ * thinkv_tbe_select writes for a survivor) is skipped without a flag.
  */
 int thinkv_evict(const thinkv_view* view, int32_t layer, const int32_t* ev_seq, const int32_t* ev_handle,
                  int32_t n_ev, void* stream);
@@ -196,6 +202,40 @@ int thinkv_decode_attention_valu(const thinkv_view* view, int32_t layer, const v
                                  const int32_t* seq_ids, const int32_t* q_pos, int32_t B, int32_t window,
                                  float softmax_scale, thinkv_dtype q_dtype, thinkv_dtype out_dtype,
                                  int32_t max_ctx_pages, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Thought-adaptive eviction, the choice of survivors (Sec. 4.3 "Think Before you Evict" and
+ * appendix "TBE Eviction Policy"): a thought segment picked for eviction is cut down to
+ * K = min(|segment|, keep) tokens by K-means over its keys; of every cluster the member nearest
+ * the centroid survives, with its value.  The paper fixes no K-means variant; this one is
+ * Lloyd's algorithm on the stored keys, dequantised, all kv-heads of a token concatenated, tokens
+ * in the order listed: initial centroid j = point floor(j*N/K); assign to the nearest centroid
+ * (squared distance, ties to the lowest cluster); stop when no assignment changed or after
+ * max_iters assignments, else move the centroids to the means of their points (an emptied
+ * cluster keeps its centroid); survivors = per non-empty cluster the nearest member (ties to the
+ * lowest index; of two members the earlier one).  At most K tokens of a segment survive.
+ * Which segments are cut, and to what size (the paper's Case 1 / Case 2 and retention schedule
+ * {64,32,16,8,4}), is the caller's decision and arrives as seg_keep.
+ *
+ *   tok_seq, tok_handle  DEVICE [n_tok] the live tokens of the segments, segment after segment,
+ *                        inside a segment in ascending position; all tokens of a segment belong
+ *                        to one sequence
+ *   seg_offset           DEVICE [n_seg + 1] segment s owns tokens [seg_offset[s], seg_offset[s+1]),
+ *                        at most THINKV_TBE_MAX_SEGMENT of them
+ *   seg_keep             DEVICE [n_seg] tokens to retain, 1..THINKV_TBE_MAX_KEEP
+ *   ev_handle            DEVICE [n_tok] out: the token's handle if it is to be evicted, -1 if it
+ *                        survives -- ready for thinkv_evict(view, layer, tok_seq, ev_handle, n_tok),
+ *                        which skips entries of -1
+ *   workspace            at least thinkv_tbe_workspace_bytes(cfg, n_tok, n_seg)
+ * Arithmetic is binary32; a decision between two candidates closer than rounding may differ
+ * from a binary64 evaluation.  Device-side errors: THINKV_ST_BAD_SLOT / BAD_SEQ for a token that
+ * does not exist (it clusters as the origin and is never evicted), THINKV_ST_BAD_SEGMENT (in the
+ * last word of dev_status) for a segment outside the limits (nothing of it is evicted).
+ */
+size_t thinkv_tbe_workspace_bytes(const thinkv_config* cfg, int32_t n_tok, int32_t n_seg);
+int thinkv_tbe_select(const thinkv_view* view, int32_t layer, const int32_t* tok_seq, const int32_t* tok_handle,
+                      const int32_t* seg_offset, const int32_t* seg_keep, int32_t n_seg, int32_t n_tok,
+                      int32_t max_iters, int32_t* ev_handle, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Decode attention plus the attention-sparsity statistic of the step, from which the paper reads

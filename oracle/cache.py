@@ -168,6 +168,8 @@ class OracleCache:
                 self.status[-1] |= ST_BAD_SEQ
                 continue
             sl = s * cfg.n_layers + layer
+            if int(h) == -1:
+                continue                           # placeholder: no token
             c, pi, slot = split_handle(h)
             if int(h) < 0 or c > 2 or pi >= self.n_pages[s, layer, c]:
                 self.status[sl] |= ST_BAD_SLOT

@@ -104,19 +104,19 @@ def segment_keys(cache, layer, seq, handles):
 def select_evictions(cache, layer, tok_seq, tok_handle, seg_offset, seg_keep, max_iters=8):
     """The call the kernels implement: segments given as runs [seg_offset[s], seg_offset[s+1]) of
     (sequence, handle) lists, tokens of a segment in ascending position.  Returns (ev_handle
-    [n_tok]: the handle of every token to evict, -1 for a survivor; smallest margin)."""
+    [n_tok]: the handle of every token to evict, -1 for a survivor; margins [n_seg]: the
+    smallest margin met inside each segment)."""
     tok_handle = np.asarray(tok_handle, dtype=np.int64)
     ev = tok_handle.copy()
-    margin = np.inf
+    margins = np.full(len(seg_keep), np.inf)
     for s in range(len(seg_keep)):
         lo, hi = int(seg_offset[s]), int(seg_offset[s + 1])
         if hi <= lo:
             continue
         x = segment_keys(cache, layer, int(tok_seq[lo]), tok_handle[lo:hi])
-        keep, m, _ = kmeans_select(x, int(seg_keep[s]), max_iters)
+        keep, margins[s], _ = kmeans_select(x, int(seg_keep[s]), max_iters)
         ev[lo + keep] = -1
-        margin = min(margin, m)
-    return ev.astype(np.int32), margin
+    return ev.astype(np.int32), margins
 
 
 def anneal_plan(seg_type, seg_live, transition_ended, n_live, budget, retention=RETENTION, importance=IMPORTANCE):

@@ -12,11 +12,11 @@ _lib = None
 
 F16, BF16, F32 = 0, 1, 2
 _DT = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
-ST_NOPAGES, ST_BAD_CLASS, ST_BAD_SLOT, ST_EVICT_DEAD, ST_BAD_SEQ = 1, 2, 4, 8, 16
+ST_NOPAGES, ST_BAD_CLASS, ST_BAD_SLOT, ST_EVICT_DEAD, ST_BAD_SEQ, ST_BAD_SEGMENT = 1, 2, 4, 8, 16, 32
 EXPORTS = ["thinkv_block_bytes", "thinkv_page_bytes", "thinkv_append_workspace_bytes",
            "thinkv_decode_workspace_bytes", "thinkv_init_view", "thinkv_append_quantized", "thinkv_evict",
            "thinkv_decode_attention", "thinkv_decode_attention_valu", "thinkv_decode_sparsity_workspace_bytes",
-           "thinkv_decode_attention_sparsity", "thinkv_status_string"]
+           "thinkv_decode_attention_sparsity", "thinkv_tbe_workspace_bytes", "thinkv_tbe_select", "thinkv_status_string"]
 
 
 class Config(C.Structure):
@@ -63,6 +63,10 @@ def load():
     lib.thinkv_decode_attention_sparsity.restype = C.c_int
     lib.thinkv_decode_attention_sparsity.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, vp, vp, i32, i32, C.c_float, C.c_int, C.c_int,
                                                      i32, vp, sz, vp]
+    lib.thinkv_tbe_workspace_bytes.restype = sz
+    lib.thinkv_tbe_workspace_bytes.argtypes = [C.POINTER(Config), i32, i32]
+    lib.thinkv_tbe_select.restype = C.c_int
+    lib.thinkv_tbe_select.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp]
     lib.thinkv_status_string.restype = C.c_char_p
     lib.thinkv_status_string.argtypes = [C.c_int]
     _lib = lib
@@ -195,6 +199,18 @@ def _decode(fn, cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale
 def thinkv_decode_attention(cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale, max_ctx_pages, stream=None):
     _decode(load().thinkv_decode_attention, cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale,
             max_ctx_pages, stream)
+
+
+def thinkv_tbe_select(cache, layer, tok_seq, tok_handle, seg_offset, seg_keep, ev_handle, max_iters=8, stream=None):
+    n_tok, n_seg = int(tok_handle.numel()), int(seg_keep.numel())
+    for t in (tok_seq, tok_handle, seg_offset, seg_keep, ev_handle):
+        assert t.dtype == torch.int32 and t.is_contiguous()
+    assert tok_seq.numel() == n_tok and ev_handle.numel() == n_tok and seg_offset.numel() == n_seg + 1
+    nb = load().thinkv_tbe_workspace_bytes(C.byref(cache.cfg), n_tok, n_seg)
+    ws = cache.workspace(nb)
+    _check(load().thinkv_tbe_select(C.byref(cache.view), layer, _ptr(tok_seq), _ptr(tok_handle), _ptr(seg_offset), _ptr(seg_keep),
+                                    n_seg, n_tok, int(max_iters), _ptr(ev_handle), _ptr(ws), ws.numel(), _stream(stream)),
+           "thinkv_tbe_select")
 
 
 def thinkv_decode_attention_sparsity(cache, layer, q, out, lse, sparsity, seq_ids, q_pos, window, softmax_scale, max_ctx_pages,

@@ -12,6 +12,10 @@ int launch_evict(const thinkv_view& v, int layer, const int32_t* ev_seq, const i
 int launch_init(const thinkv_view& v, hipStream_t st);
 int launch_decode_simple(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
 int launch_decode_mfma(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
+size_t tbe_ws_bytes(const thinkv_config& c, int n_tok, int n_seg);
+int launch_tbe_select(const thinkv_view& v, int layer, const int32_t* tok_seq, const int32_t* tok_handle, const int32_t* seg_offset,
+                      const int32_t* seg_keep, int n_seg, int n_tok, int max_iters, int32_t* ev_handle, void* workspace,
+                      hipStream_t st);
 int launch_decode_mfma_stat(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
 int launch_stat_fill(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
 int launch_stat_count(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
@@ -229,6 +233,24 @@ int thinkv_decode_attention_sparsity(const thinkv_view* view, int32_t layer, con
   if (!sparsity && B > 0) return THINKV_E_INVALID_ARG;
   return decode_common(view, layer, q, out, lse, seq_ids, q_pos, B, window, softmax_scale, (int)q_dtype, (int)out_dtype,
                        max_ctx_pages, workspace, workspace_bytes, stream, true, sparsity);
+}
+
+size_t thinkv_tbe_workspace_bytes(const thinkv_config* cfg, int32_t n_tok, int32_t n_seg) {
+  if (check_config(cfg) || n_tok < 0 || n_seg < 0) return 0;
+  return tbe_ws_bytes(*cfg, n_tok, n_seg);
+}
+
+int thinkv_tbe_select(const thinkv_view* view, int32_t layer, const int32_t* tok_seq, const int32_t* tok_handle,
+                      const int32_t* seg_offset, const int32_t* seg_keep, int32_t n_seg, int32_t n_tok,
+                      int32_t max_iters, int32_t* ev_handle, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_view(view);
+  if (rc) return rc;
+  if (n_seg < 0 || n_tok < 0 || max_iters < 1 || layer < 0 || layer >= view->cfg.n_layers) return THINKV_E_INVALID_ARG;
+  if (n_seg == 0 || n_tok == 0) return THINKV_OK;
+  if (!tok_seq || !tok_handle || !seg_offset || !seg_keep || !ev_handle || !workspace) return THINKV_E_INVALID_ARG;
+  if (workspace_bytes < tbe_ws_bytes(view->cfg, n_tok, n_seg)) return THINKV_E_WORKSPACE;
+  return launch_tbe_select(*view, layer, tok_seq, tok_handle, seg_offset, seg_keep, n_seg, n_tok, max_iters, ev_handle,
+                           workspace, (hipStream_t)stream);
 }
 
 const char* thinkv_status_string(int status) {

@@ -16,6 +16,7 @@ __global__ __launch_bounds__(256) void evict_kernel(thinkv_view v, int layer, co
     return;
   }
   const int32_t h = ev_handle[i];
+  if (h == -1) return;   // placeholder: no token
   const uint32_t uh = (uint32_t)h;
   const int cls = uh >> 28, pi = (uh >> 4) & 0xFFFFFF, slot = uh & 15;
   uint32_t* status = &v.dev_status[sl_index(c, s, layer)];

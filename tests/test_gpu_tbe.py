@@ -1,0 +1,152 @@
+"""Thought-adaptive eviction, choice of survivors: HIP path against the oracle (needs an MI355X).
+
+Every decision of the K-means (nearest centroid, nearest member) compares two floating-point
+numbers, in binary32 on the device and binary64 in the oracle.  The oracle reports, per segment,
+the smallest gap it met between a winner and its runner-up (relative to the mean squared norm
+of the points).  A segment whose gap is far above binary32 rounding must come out token for
+token as in the oracle; a segment with a closer call may legitimately differ and is checked
+for validity only (one survivor per cluster at most, survivors are tokens of the segment);
+the cases are checked to consist almost entirely of the first kind."""
+import numpy as np
+import pytest
+import torch
+
+import parity
+from oracle import tbe as otbe
+from paper_2510_01290_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+MIN_MARGIN = 3e-5     # binary32 distances over 128..1,024 channels carry a relative error of about 1e-6
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _segments(wl, gr, layer, seqs, dead):
+    """runs of equal thought type of each sequence -> (tok_seq, tok_handle, seg_offset) over their live tokens"""
+    tok_seq, tok_handle, off = [], [], [0]
+    for s in seqs:
+        cls = wl.classes[s][:int(wl.q_pos[s]) + 1]
+        hs = gr.handle[(layer, s)]
+        cut = np.flatnonzero(np.diff(cls)) + 1
+        runs = []
+        for lo, hi in zip(np.r_[0, cut], np.r_[cut, len(cls)]):
+            # neighbouring segments of one type show up as one long run: cut it at the generator's longest segment
+            runs += [(a, min(a + 192, hi)) for a in range(lo, hi, 192)]
+        for lo, hi in runs:
+            pos = [p for p in range(lo, hi) if hs[p] != -1 and not dead[s][p]]
+            if not pos:
+                continue
+            tok_seq += [s] * len(pos)
+            tok_handle += [int(hs[p]) for p in pos]
+            off.append(len(tok_handle))
+    return np.array(tok_seq, np.int32), np.array(tok_handle, np.int32), np.array(off, np.int32)
+
+
+def _dead(wl):
+    dead = [np.zeros(len(c), bool) for c in wl.classes]
+    for op in wl.ops:
+        if isinstance(op, synth.Evict):
+            for s, p in zip(op.seqs, op.pos):
+                dead[int(s)][int(p)] = True
+    return dead
+
+
+def _gpu_select(gc, layer, tok_seq, tok_handle, off, keep, max_iters=8):
+    from paper_2510_01290_amd import binding as B
+    d = gc.device
+    ev = torch.full((len(tok_handle),), 12345, dtype=torch.int32, device=d)
+    B.thinkv_tbe_select(gc, layer, torch.from_numpy(tok_seq).to(d), torch.from_numpy(tok_handle).to(d), torch.from_numpy(off).to(d),
+                        torch.from_numpy(keep).to(d), ev, max_iters=max_iters)
+    torch.cuda.synchronize()
+    return ev.cpu().numpy()
+
+
+def _case(wl, keep_of, max_iters=8, layer=0):
+    gc = parity.make_gpu_cache(wl)
+    gr = synth.ScriptRunner(wl, parity.GpuBackend(gc)).run()
+    ob = parity.make_oracle(wl)
+    synth.ScriptRunner(wl, ob).run()
+    torch.cuda.synchronize()
+    tok_seq, tok_handle, off = _segments(wl, gr, layer, range(wl.n_seqs), _dead(wl))
+    sizes = np.diff(off)
+    keep = np.array([keep_of(int(n)) for n in sizes], np.int32)
+    want, margins = otbe.select_evictions(ob.cache, layer, tok_seq, tok_handle, off, keep, max_iters)
+    got = _gpu_select(gc, layer, tok_seq, tok_handle, off, keep, max_iters)
+    clear = margins > MIN_MARGIN
+    assert clear.mean() >= 0.6, f"too many near-ties for a meaningful comparison ({clear.mean():.2f} clear)"
+    same = 0
+    for sg, (a, b) in enumerate(zip(off[:-1], off[1:])):
+        eq = np.array_equal(got[a:b], want[a:b])
+        same += int(eq)
+        assert eq or not clear[sg], ("segment", sg, "margin", margins[sg], np.flatnonzero(got[a:b] != want[a:b])[:8])
+        kept = got[a:b] == -1
+        assert 1 <= kept.sum() <= min(b - a, keep[sg]) and np.array_equal(got[a:b][~kept], tok_handle[a:b][~kept])
+    want = got          # from here on both sides evict what the device chose
+    margin = margins.min()
+    # the list goes straight into the evict call; tables and attention afterwards agree with the oracle
+    from paper_2510_01290_amd import binding as B
+    B.thinkv_evict(gc, layer, torch.from_numpy(tok_seq).to(gc.device), torch.from_numpy(got).to(gc.device))
+    ob.cache.evict_slots(layer, tok_seq, want)
+    parity.compare_bookkeeping_full(ob.cache, gc)
+    assert int(gc.dev_status.abs().sum().item()) == 0
+    ref, ref_lse = parity.oracle_attention(ob.cache, wl, layer, list(range(wl.n_seqs)), list(range(wl.n_seqs)))
+    out, lse = parity.gpu_attention(gc, wl, None, layer)
+    assert np.abs(out - ref).max() <= parity.TOL
+    return {"workload": wl.name, "segments": len(keep), "tokens": len(tok_handle), "evicted": int((got != -1).sum()),
+            "segments_equal_to_oracle": same, "segments_with_a_clear_margin": int(clear.sum()), "smallest_margin": float(margin)}
+
+
+def test_tbe_first_anneal_of_every_segment():
+    _say("K-means survivors: every segment of three sequences cut to the first retention level (scaled down: 16)")
+    geom = synth.Geometry(1, 8, 2, 64, "f16", (8, 2, 4))
+    wl = synth.bulk_evict_refill("tbe-a", geom, 21, 3, np.array([700, 260, 1500]), {}, refill_chunk=1)
+    _say(_case(wl, lambda n: 16))
+
+
+def test_tbe_schedule_levels_llama_shape():
+    _say("K-means survivors on the 8B shape (8 kv-heads x 128): segments of 64..192 tokens cut to 64, short ones to 32 / 16 / 8 / 4")
+    geom = synth.Geometry(1, 32, 8, 128, "bf16", (8, 2, 4))
+    wl = synth.bulk_evict_refill("tbe-b", geom, 22, 2, np.array([1200, 900]), {synth.E: 0.2}, refill_chunk=4)
+    level = lambda n: next((r for r in otbe.RETENTION if r < n), 4)
+    _say(_case(wl, level))
+
+
+def test_tbe_single_assignment_pass_and_paper_precision_map():
+    _say("K-means survivors with max_iters = 1 under the paper's R8/E4/T2 map")
+    geom = synth.Geometry(1, 10, 2, 128, "bf16", (2, 4, 8))
+    wl = synth.bulk_evict_refill("tbe-c", geom, 23, 2, np.array([500, 333]), {synth.R: 0.1}, refill_chunk=2)
+    _say(_case(wl, lambda n: 8, max_iters=1))
+
+
+def test_tbe_limits_and_degenerate_segments():
+    _say("segments outside the limits, keep >= size, single-token segments, bad tokens")
+    from paper_2510_01290_amd import binding as B
+    geom = synth.Geometry(1, 8, 2, 64, "f16", (8, 2, 4))
+    wl = synth.bulk_evict_refill("tbe-d", geom, 24, 1, np.array([600]), {}, refill_chunk=1)
+    gc = parity.make_gpu_cache(wl)
+    gr = synth.ScriptRunner(wl, parity.GpuBackend(gc)).run()
+    hs = gr.handle[(0, 0)]
+    live = [int(h) for h in hs[:600] if h != -1]
+    # segment 0: 300 tokens (over the limit); 1: keep 0; 2: keep 65; 3: keep >= size; 4: one token; 5: empty; 6: regular
+    off = np.array([0, 300, 310, 320, 330, 331, 331, 371], np.int32)
+    keep = np.array([64, 0, 65, 10, 4, 4, 8], np.int32)
+    th = np.array(live[:371], np.int32)
+    ts = np.zeros(371, np.int32)
+    got = _gpu_select(gc, 0, ts, th, off, keep)
+    assert (got[:331] == -1).all()                                 # nothing evicted from segments 0..4
+    assert (got[331:] != 12345).all() and np.count_nonzero(got[331:] == -1) <= 8 and np.count_nonzero(got[331:] == -1) >= 1
+    ev = got[331:] != -1
+    assert np.array_equal(got[331:][ev], th[331:][ev])
+    st = gc.dev_status.cpu().numpy()
+    assert st[-1] & B.ST_BAD_SEGMENT and not st[0]
+    # a handle that names no page and a sequence that does not exist: flagged, never evicted
+    gc.dev_status.zero_()
+    th2 = th[331:371].copy()
+    th2[3] = (1 << 28) | (4000 << 4)
+    ts2 = np.zeros(40, np.int32)
+    got2 = _gpu_select(gc, 0, ts2, th2, np.array([0, 40], np.int32), np.array([8], np.int32))
+    assert gc.dev_status.cpu().numpy()[0] & B.ST_BAD_SLOT
+    assert np.count_nonzero(got2 == -1) <= 8

@@ -83,7 +83,8 @@ def test_select_evictions_reads_the_stored_keys():
     cls = np.repeat(np.array([2, 1, 0], np.uint8), 16)
     h = c.append(0, k, k, np.ones(n, np.int64), np.arange(n), cls)
     off = [0, 16, 32, 48]
-    ev, margin = tbe.select_evictions(c, 0, np.ones(n, np.int64), h, off, [4, 8, 16])
+    ev, margins = tbe.select_evictions(c, 0, np.ones(n, np.int64), h, off, [4, 8, 16])
+    assert margins.shape == (3,) and margins[2] == np.inf          # keep >= size: no decision was taken
     for s, keep in enumerate([4, 8, 16]):
         seg = ev[off[s]:off[s + 1]]
         assert (seg == -1).sum() == min(keep, 16)
