@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--workload", default="cfg2-32k", choices=["cfg2-32k", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5"],
                     help="cfg2-32k (default): the headline step.  The others time decode attention alone on that "
                          "configuration's cache (a step = one attention call per built layer)")
+    ap.add_argument("--replicas", type=int, default=3,
+                    help="identical copies of the cache the steps rotate over, so that the data of a step was last touched "
+                         "replicas steps ago (3 x 0.75 GB is far beyond the 256 MB memory-side cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -65,11 +68,16 @@ def main():
     arena = tuple(int(x + args.batch * (nsteps // 16 + 2)) for x in backends.arena_need(wl))
     maxp = backends.max_pages_need(wl) + nsteps // 16 + 2
     t0 = time.time()
-    gc = parity.make_gpu_cache(wl, arena_pages=arena, max_pages=maxp)
-    gr = synth.ScriptRunner(wl, parity.GpuBackend(gc)).run()
+    gcs = []
+    for _ in range(max(1, args.replicas)):
+        gc_r = parity.make_gpu_cache(wl, arena_pages=arena, max_pages=maxp)
+        gr = synth.ScriptRunner(wl, parity.GpuBackend(gc_r)).run()       # the same script: same handles in every copy
+        gcs.append(gc_r)
+    gc = gcs[0]
     torch.cuda.synchronize()
     build_s = time.time() - t0
-    assert int(gc.dev_status.abs().sum().item()) == 0, "device flags set while building the cache"
+    for gc_r in gcs:
+        assert int(gc_r.dev_status.abs().sum().item()) == 0, "device flags set while building the cache"
 
     # ---- per-step inputs, resident on the device before timing starts
     rng = np.random.default_rng(1234)
@@ -102,6 +110,7 @@ def main():
     decode = B.thinkv_decode_attention if args.variant == "fast" else B.thinkv_decode_attention_valu
 
     def step(i, ev=None):
+        gc = gcs[i % len(gcs)]
         B.thinkv_evict(gc, 0, ev_seq, ev_h[i])
         B.thinkv_append_quantized(gc, 0, k_new[i], v_new[i], ev_seq, t_pos[i], t_cls[i], h_out)
         if ev is not None:
@@ -129,23 +138,27 @@ def main():
     marks = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_extra)]
     for j in range(n_extra):
         i = args.warmup + args.steps + j
+        gc = gcs[i % len(gcs)]
         marks[j][0].record()
         B.thinkv_evict(gc, 0, ev_seq, ev_h[i])
         marks[j][1].record()
         B.thinkv_append_quantized(gc, 0, k_new[i], v_new[i], ev_seq, t_pos[i], t_cls[i], h_out)
         marks[j][2].record()
         decode(gc, 0, q_all[i], out, lse, ev_seq, t_pos[i], 0, scale, max_ctx_pages)
-    # decode attention with the attention-sparsity statistic riding on it (same cache state)
+    gc = gcs[0]
+    # decode attention with the attention-sparsity statistic riding on it
     sp = torch.empty(args.batch, dtype=torch.float32, device=dev)
     smarks = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_extra)]
     if args.variant == "fast":
         i = nsteps - 1
         for j in range(n_extra + 3):
+            gc = gcs[j % len(gcs)]
             if j >= 3:
                 smarks[j - 3][0].record()
             B.thinkv_decode_attention_sparsity(gc, 0, q_all[i], out, lse, sp, ev_seq, t_pos[i], 0, scale, max_ctx_pages)
             if j >= 3:
                 smarks[j - 3][1].record()
+    gc = gcs[0]
     # survivor choice of thought-adaptive eviction: 8 segments of 128 consecutive live tokens per sequence, cut to 64
     tbe = None
     if args.variant == "fast":
@@ -181,7 +194,8 @@ def main():
     attn_sparsity_us = float(np.median([a.elapsed_time(b) for a, b in smarks]) * 1e3) if args.variant == "fast" else None
     evict_us = float(np.median([m[0].elapsed_time(m[1]) for m in marks]) * 1e3)
     append_us = float(np.median([m[1].elapsed_time(m[2]) for m in marks]) * 1e3)
-    assert int(gc.dev_status.abs().sum().item()) == 0, "device flags set during the timed steps"
+    for gc_r in gcs:
+        assert int(gc_r.dev_status.abs().sum().item()) == 0, "device flags set during the timed steps"
 
     # ---- algorithmic bytes of one step (from the tables as they stand after the run)
     live_by_class = []
@@ -209,7 +223,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name + " (R1-Llama-8B layer: 32 q / 8 kv heads, head_dim 128, bf16; T8/R4/E2, 30% E + 10% R evicted and refilled)",
                    "batch": args.batch, "live_tokens_per_seq": int(sum(live_by_class) / args.batch), "page_size": 16,
-                   "live_by_class_TER": live_by_class, "kernel": args.variant, "build_seconds": round(build_s, 1),
+                   "live_by_class_TER": live_by_class, "kernel": args.variant, "build_seconds": round(build_s, 1), "cache_replicas": len(gcs),
                    "step": "evict 1 + append 1 + decode attention, per sequence"},
         "roofline": {"bound": "hbm", "kernel": "decode attention (split-K kernel + merge)", "achieved": achieved, "peak": HBM_PEAK / 1e9,
                      "unit": "GB/s", "frac": achieved * 1e9 / HBM_PEAK,
@@ -243,8 +257,17 @@ def attention_only(args, np, torch, B, synth, parity, dev):
     gc = parity.make_gpu_cache(wl)
     synth.ScriptRunner(wl, parity.GpuBackend(gc)).run()
     torch.cuda.synchronize()
-    build_s = time.time() - t0
     assert int(gc.dev_status.abs().sum().item()) == 0, "device flags set while building the cache"
+    # Copies of the cache to rotate over, so that a call does not find its pages in the 256 MB
+    # memory-side cache from the call before: enough for 1 GB in all, at most four.
+    stored = sum(int(gc.n_pages[:, :, c].sum().item()) * gc.page_bytes[c] for c in range(3))
+    n_rep = int(min(4, max(1, -(-(1 << 30) // max(stored, 1)))))
+    gcs = [gc]
+    for _ in range(n_rep - 1):
+        gcs.append(parity.make_gpu_cache(wl))
+        synth.ScriptRunner(wl, parity.GpuBackend(gcs[-1])).run()
+    torch.cuda.synchronize()
+    build_s = time.time() - t0
     L, S = g.n_layers, wl.n_seqs
     q = [torch.stack([synth.query_rows(wl.seed, l, s_, 0, g, dev) for s_ in range(S)]).contiguous() for l in range(L)]
     out = torch.empty(q[0].shape, dtype=q[0].dtype, device=dev)
@@ -254,26 +277,36 @@ def attention_only(args, np, torch, B, synth, parity, dev):
     mcp = [int(gc.n_pages[:, l].sum(-1).max().item()) for l in range(L)]
     scale = g.head_dim ** -0.5
 
-    def step(marks=None):
+    def step(i, marks=None, rotate=True):
+        c_ = gcs[i % len(gcs)] if rotate else gcs[0]
         for l in range(L):
             if marks is not None:
                 marks[l][0].record()
-            B.thinkv_decode_attention(gc, l, q[l], out, lse, sid, qp, wl.window_of_layer[l], scale, mcp[l])
+            B.thinkv_decode_attention(c_, l, q[l], out, lse, sid, qp, wl.window_of_layer[l], scale, mcp[l])
             if marks is not None:
                 marks[l][1].record()
 
-    for _ in range(args.warmup):
-        step()
-    marks = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)] for _ in range(args.steps)]
+    def new_marks():
+        return [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)] for _ in range(args.steps)]
+
+    for i in range(args.warmup):
+        step(i)
+    marks = new_marks()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e0.record()
     for i in range(args.steps):
-        step(marks[i])
+        step(i, marks[i])
     e1.record()
     torch.cuda.synchronize()
     ms_step = e0.elapsed_time(e1) / args.steps
     per_layer_us = np.array([[a.elapsed_time(b) * 1e3 for a, b in m] for m in marks])     # [steps][layers]
+    # the same on one copy only ("hot": what fits stays in the memory-side cache between calls)
+    hot = new_marks()
+    for i in range(args.steps):
+        step(i, hot[i], rotate=False)
+    torch.cuda.synchronize()
+    hot_us = np.median(np.array([[a.elapsed_time(b) * 1e3 for a, b in m] for m in hot]), axis=0)
     # algorithmic bytes per layer: live tokens visible to the query, page ids + masks, q and out
     H, D, Hq = g.n_kv_heads, g.head_dim, g.n_q_heads
     npg = gc.n_pages.cpu().numpy()
@@ -307,9 +340,11 @@ def attention_only(args, np, torch, B, synth, parity, dev):
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": wl.name, "batch": S, "layers_built": L, "window_of_layer": list(wl.window_of_layer),
                    "step": "decode attention alone, one call per built layer", "build_seconds": round(build_s, 1),
+                   "cache_replicas": len(gcs), "stored_bytes_per_replica": int(stored),
                    "live_tokens_visible_per_layer": layer_live},
         "per_layer": [{"layer": l, "window": int(wl.window_of_layer[l]), "attn_us_median": float(med[l]),
-                       "attn_us_min": float(per_layer_us[:, l].min()), "algorithmic_bytes": int(layer_bytes[l]),
+                       "attn_us_min": float(per_layer_us[:, l].min()), "attn_us_median_one_copy_hot": float(hot_us[l]),
+                       "algorithmic_bytes": int(layer_bytes[l]),
                        "GB/s": layer_bytes[l] / (med[l] * 1e-6) / 1e9, "frac_of_8TBps": layer_bytes[l] / (med[l] * 1e-6) / HBM_PEAK}
                       for l in range(L)],
     }
