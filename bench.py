@@ -158,6 +158,27 @@ def main():
             B.thinkv_decode_attention_sparsity(gc, 0, q_all[i], out, lse, sp, ev_seq, t_pos[i], 0, scale, max_ctx_pages)
             if j >= 3:
                 smarks[j - 3][1].record()
+    # bulk (prefill-style) append: 2,048 tokens for each of 16 sequences in one call, type R, into an empty cache
+    S_b, n_b = 16, 2048
+    bc = B.Cache(1, g.n_q_heads, g.n_kv_heads, g.head_dim, g.bits_of_class, S_b, n_b // 16 + 2, (1, 1, S_b * (n_b // 16) + 8), device=dev)
+    kb = torch.randn((S_b * n_b, g.n_kv_heads, g.head_dim), device=dev, dtype=torch.float32).to(k_new.dtype)
+    sb = torch.arange(S_b, dtype=torch.int32, device=dev).repeat_interleave(n_b)
+    pb = torch.arange(n_b, dtype=torch.int32, device=dev).repeat(S_b)
+    cb = torch.full((S_b * n_b,), synth.R, dtype=torch.uint8, device=dev)
+    bulk_us = []
+    for j in range(4):
+        B.thinkv_init_view(bc)
+        a_, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a_.record()
+        B.thinkv_append_quantized(bc, 0, kb, kb, sb, pb, cb)
+        b_.record()
+        torch.cuda.synchronize()
+        if j:
+            bulk_us.append(a_.elapsed_time(b_) * 1e3)
+    assert int(bc.dev_status.abs().sum().item()) == 0 and int(bc.n_live.sum().item()) == S_b * n_b
+    bulk = {"tokens": S_b * n_b, "us_median": float(np.median(bulk_us)), "tokens_per_s": S_b * n_b / (float(np.median(bulk_us)) * 1e-6),
+            "input_GB_per_s": 2 * kb.numel() * kb.element_size() / (float(np.median(bulk_us)) * 1e-6) / 1e9}
+    del bc, kb
     gc = gcs[0]
     # survivor choice of thought-adaptive eviction: 8 segments of 128 consecutive live tokens per sequence, cut to 64
     tbe = None
@@ -218,7 +239,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "us_per_step": ms_step * 1e3, "attn_us_mean": float(attn_ms.mean() * 1e3), "attn_us_min": float(attn_ms.min() * 1e3),
         "attn_us_median": float(np.median(attn_ms) * 1e3), "evict_us_median": evict_us, "append_us_median": append_us,
-        "attn_with_sparsity_statistic_us_median": attn_sparsity_us, "tbe_select": tbe,
+        "attn_with_sparsity_statistic_us_median": attn_sparsity_us, "tbe_select": tbe, "bulk_append": bulk,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16" if args.variant == "fast" else "f32",
         "data": "synthetic",
         "config": {"workload": wl.name + " (R1-Llama-8B layer: 32 q / 8 kv heads, head_dim 128, bf16; T8/R4/E2, 30% E + 10% R evicted and refilled)",

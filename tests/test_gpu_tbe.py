@@ -150,3 +150,89 @@ def test_tbe_limits_and_degenerate_segments():
     got2 = _gpu_select(gc, 0, ts2, th2, np.array([0, 40], np.int32), np.array([8], np.int32))
     assert gc.dev_status.cpu().numpy()[0] & B.ST_BAD_SLOT
     assert np.count_nonzero(got2 == -1) <= 8
+
+
+def test_tbe_driven_budgeted_decode():
+    """decode under a token budget with the evictions chosen the paper's way: the annealing plan
+    (Case 1 when a transition segment ends, Case 2 while over budget) names segments and sizes,
+    the device picks the survivors by K-means, the list goes to thinkv_evict; the oracle follows
+    step by step"""
+    _say("budgeted decode driven by the annealing plan and K-means survivors")
+    from paper_2510_01290_amd import binding as B
+    geom = synth.Geometry(1, 8, 2, 64, "bf16", (8, 2, 4))
+    S, steps, per_call, budget = 2, 1536, 8, 400
+    rng = np.random.default_rng(31)
+    classes = [synth.thought_classes(rng, steps)[0] for _ in range(S)]
+    wl = synth.Workload("tbe-decode", geom, 31, S, classes, [], (0,), np.full(S, steps - 1, np.int32))
+    pages = steps // 16 + 8
+    gc = parity.make_gpu_cache(wl, arena_pages=(S * pages, S * pages, S * pages), max_pages=pages)
+    ob = parity.make_oracle(wl, arena_pages=(S * pages, S * pages, S * pages), max_pages=pages)
+    gb = parity.GpuBackend(gc)
+    dev = gc.device
+    handle = [np.full(steps, -1, np.int64) for _ in range(S)]
+    alive = [np.zeros(steps, bool) for _ in range(S)]
+    n_cuts = n_clear = n_same = 0
+    for t0 in range(0, steps, per_call):
+        n = min(per_call, steps - t0)
+        seqs = np.repeat(np.arange(S), n)
+        pos = np.tile(np.arange(t0, t0 + n), S)
+        cls = np.concatenate([classes[s][t0:t0 + n] for s in range(S)]).astype(np.uint8)
+        k = torch.cat([synth.kv_rows(wl.seed, 0, s, 0, t0, t0 + n, geom, torch.device("cpu")) for s in range(S)])
+        v = torch.cat([synth.kv_rows(wl.seed, 0, s, 1, t0, t0 + n, geom, torch.device("cpu")) for s in range(S)])
+        ha = gb.append(0, k.to(dev), v.to(dev), seqs, pos, cls)
+        hb = ob.append(0, k, v, seqs, pos, cls)
+        assert np.array_equal(ha, hb)
+        for s in range(S):
+            handle[s][t0:t0 + n] = ha[s * n:(s + 1) * n]
+            alive[s][t0:t0 + n] = True
+        # segments so far: runs of one type, cut at 192 tokens
+        t_seq, t_h, off, keep = [], [], [0], []
+        cut_pos = []
+        for s in range(S):
+            c = classes[s][:t0 + n]
+            edges = np.flatnonzero(np.diff(c)) + 1
+            runs = []
+            for lo, hi in zip(np.r_[0, edges], np.r_[edges, len(c)]):
+                runs += [(a, min(a + 192, hi)) for a in range(lo, hi, 192)]
+            live = [int(alive[s][a:b].sum()) for a, b in runs]
+            types = [int(c[a]) for a, _ in runs]
+            ended = len(runs) >= 2 and types[-2] == synth.T and runs[-1][0] >= t0      # a transition segment ended in this call
+            plan = otbe.anneal_plan(types, live, ended, int(alive[s].sum()), budget)
+            seen = set()
+            for i, r in plan:
+                if i in seen:
+                    continue                      # one cut per segment and call; the rest follows on the next call
+                seen.add(i)
+                a, b = runs[i]
+                p = a + np.flatnonzero(alive[s][a:b])
+                t_seq += [s] * len(p)
+                t_h += handle[s][p].tolist()
+                off.append(len(t_h))
+                keep.append(r)
+                cut_pos.append((s, p))
+        if not keep:
+            continue
+        t_seq, t_h, off, keep = (np.array(x, np.int32) for x in (t_seq, t_h, off, keep))
+        got = _gpu_select(gc, 0, t_seq, t_h, off, keep)
+        want, margins = otbe.select_evictions(ob.cache, 0, t_seq, t_h, off, keep)
+        for sg, (a, b) in enumerate(zip(off[:-1], off[1:])):
+            eq = np.array_equal(got[a:b], want[a:b])
+            n_cuts += 1
+            n_clear += int(margins[sg] > MIN_MARGIN)
+            n_same += int(eq)
+            assert eq or margins[sg] <= MIN_MARGIN, (t0, sg, margins[sg])
+            kept = got[a:b] == -1
+            assert 1 <= kept.sum() <= keep[sg]
+            s, p = cut_pos[sg]
+            alive[s][p[~kept]] = False
+        B.thinkv_evict(gc, 0, torch.from_numpy(t_seq).to(dev), torch.from_numpy(got).to(dev))
+        ob.cache.evict_slots(0, t_seq, got)
+    assert n_cuts > 20 and n_clear >= 0.6 * n_cuts
+    parity.compare_bookkeeping_full(ob.cache, gc)
+    assert int(gc.dev_status.abs().sum().item()) == 0
+    live_now = gc.n_live[:, 0].cpu().numpy()
+    assert np.all(live_now <= budget + per_call), live_now          # the plan keeps the cache at its budget
+    ref, ref_lse = parity.oracle_attention(ob.cache, wl, 0, list(range(S)), list(range(S)))
+    out, lse = parity.gpu_attention(gc, wl, None, 0)
+    assert np.abs(out - ref).max() <= parity.TOL
+    _say({"cuts": n_cuts, "clear": n_clear, "equal_to_oracle": n_same, "live": live_now.tolist()})
