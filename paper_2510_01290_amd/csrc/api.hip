@@ -57,34 +57,27 @@ static int check_view(const thinkv_view* v) {
 // end is levelled well enough by their number.  The floor keeps the set-up small against the item.
 constexpr int kMinPagesPerItem = 32;
 
-static int small_items() {
-  if (const char* e = getenv("THINKV_NSMALL")) return atoi(e);  // dev knob
-  return 0;
-}
-
 // A sliding-window layer is another matter: only the pages that hold one of the last W positions
 // are worked on, the rest of the page list is merely scanned (a few bytes a page), so the fixed
 // price of an item dominates.  There an item scans at least 256 pages (64 per wave), and a
 // (query, kv-head) gets several items only while that still fills the chip once.
 static int pages_per_item(const thinkv_config& c, int B, int max_ctx_pages, int window) {
   const int64_t heads = (int64_t)B * c.n_kv_heads;
-  int64_t n_big = heads <= 384 ? 768 / heads : (4 * 768 + heads - 1) / heads;   // big items per (query, kv-head)
+  int64_t n_items = heads <= 384 ? 768 / heads : (4 * 768 + heads - 1) / heads;   // items per (query, kv-head)
   if (window > 0) {
-    n_big = 768 / heads;
+    n_items = 768 / heads;
     const int64_t most = (max_ctx_pages + 255) / 256;
-    if (n_big > most) n_big = most;
+    if (n_items > most) n_items = most;
   }
-  if (n_big < 1) n_big = 1;
-  int ppi = (int)((max_ctx_pages + n_big - 1) / n_big);
-  if (const char* e = getenv("THINKV_PPI")) ppi = atoi(e);  // dev knob
+  if (n_items < 1) n_items = 1;
+  int ppi = (int)((max_ctx_pages + n_items - 1) / n_items);
   return ppi < kMinPagesPerItem ? kMinPagesPerItem : ppi;
 }
 
 // grid extents for sequences of at most max_ctx_pages pages
-static void split_bounds(int max_ctx_pages, int ppi, int* max_big, int* max_small) {
-  const ItemPlan p = plan_items(ppi, small_items(), 1 << 30, 1 << 30, max_ctx_pages);
-  *max_big = p.n_big > 0 ? p.n_big : 1;
-  *max_small = small_items() > 0 ? small_items() : 1;
+static int split_bound(int max_ctx_pages, int ppi) {
+  const ItemPlan p = plan_items(ppi, 1 << 30, max_ctx_pages);
+  return p.n_items > 0 ? p.n_items : 1;
 }
 
 static int decode_common(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
@@ -117,9 +110,7 @@ static int decode_common(const thinkv_view* view, int32_t layer, const void* q, 
   a.q_dtype = q_dtype;
   a.out_dtype = out_dtype;
   a.ppi = pages_per_item(view->cfg, B, max_ctx_pages, window);
-  a.n_small = small_items();
-  split_bounds(max_ctx_pages, a.ppi, &a.max_big, &a.max_small);
-  a.max_split = a.max_big + a.max_small;
+  a.max_split = split_bound(max_ctx_pages, a.ppi);
   if (a.max_split > 1024) return THINKV_E_SHAPE;   // merge kernel keeps one weight per item in LDS
   a.scale_log2e = softmax_scale * 1.4426950408889634f;
   a.stat = nullptr;
@@ -166,9 +157,7 @@ size_t thinkv_append_workspace_bytes(const thinkv_config* cfg, int32_t n_tok) {
 size_t thinkv_decode_workspace_bytes(const thinkv_config* cfg, int32_t B, int32_t max_ctx_pages) {
   if (check_config(cfg) || B < 0 || max_ctx_pages < 0) return 0;
   // the item size never drops below kMinPagesPerItem pages, whatever the batch
-  int mb, msm;
-  split_bounds(max_ctx_pages, kMinPagesPerItem, &mb, &msm);
-  const int ms = mb + msm;
+  const int ms = split_bound(max_ctx_pages, kMinPagesPerItem);
   return (size_t)(B > 0 ? B : 1) * cfg->n_q_heads * ms * (cfg->head_dim + 2) * sizeof(float);
 }
 

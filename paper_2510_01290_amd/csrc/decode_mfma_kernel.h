@@ -516,8 +516,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   constexpr int NG = D / 32, NM = D / 16, CS = CL::CS, NSET = CL::NSET;
   const thinkv_config& c = v.cfg;
   int b, hkv, item_j;
-  bool item_small;
-  locate_workgroup(a, c.n_kv_heads, blockIdx.x, &b, &hkv, &item_j, &item_small);
+  locate_workgroup(a, c.n_kv_heads, blockIdx.x, &b, &hkv, &item_j);
   const int seq = a.seq_ids[b];
   __shared__ ItemLds<D, GP> lds;
   int np[3], np_total = 0;
@@ -526,9 +525,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
     np[k] = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
     np_total += np[k];
   }
-  const ItemPlan plan = plan_items(a.ppi, a.n_small, a.max_big, a.max_small, np_total);
-  if (item_j >= (item_small ? plan.n_small : plan.n_big)) return;
-  const int split = item_small ? plan.n_big + item_j : item_j;   // the item's row among the partials
+  const ItemPlan plan = plan_items(a.ppi, a.max_split, np_total);
+  if (item_j >= plan.n_items) return;
+  const int split = item_j;   // the item's row among the partials
   int u0, u1;
   item_units(plan, split, &u0, &u1);
 
@@ -647,7 +646,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
 template <int D, bool WIN, bool STAT>
 static int launch_dw(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {
   const int G = v.cfg.n_q_heads / v.cfg.n_kv_heads;
-  dim3 grid((a.max_big + a.max_small) * v.cfg.n_kv_heads * a.B), blk(256);
+  dim3 grid(a.max_split * v.cfg.n_kv_heads * a.B), blk(256);
   if (G <= 4)
     hipLaunchKernelGGL((decode_mfma_kernel<D, 4, WIN, STAT>), grid, blk, 0, st, v, a);
   else if (G <= 8)

@@ -20,8 +20,7 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
   constexpr int NG = D / kGroup, NM = D / 16, GMAX = 8;
   const thinkv_config& c = v.cfg;
   int b, hkv, item_j;
-  bool item_small;
-  locate_workgroup(a, c.n_kv_heads, blockIdx.x, &b, &hkv, &item_j, &item_small);
+  locate_workgroup(a, c.n_kv_heads, blockIdx.x, &b, &hkv, &item_j);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int Hq = c.n_q_heads, H = c.n_kv_heads, G = Hq / H;
   const int seq = a.seq_ids[b];
@@ -34,9 +33,9 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
     np[k] = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
     np_total += np[k];
   }
-  const ItemPlan plan = plan_items(a.ppi, a.n_small, a.max_big, a.max_small, np_total);
-  if (item_j >= (item_small ? plan.n_small : plan.n_big)) return;
-  const int split = item_small ? plan.n_big + item_j : item_j;   // the item's row among the partials
+  const ItemPlan plan = plan_items(a.ppi, a.max_split, np_total);
+  if (item_j >= plan.n_items) return;
+  const int split = item_j;   // the item's row among the partials
   int u0, u1;
   item_units(plan, split, &u0, &u1);
   for (int i = tid; i < G * D; i += 256)
@@ -175,8 +174,7 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(thinkv_view v, DecodeAr
   int np_total = 0;
   for (int k = 0; k < 3; ++k)
     np_total += (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
-  const ItemPlan plan = plan_items(a.ppi, a.n_small, a.max_big, a.max_small, np_total);
-  const int ns = plan.n_big + plan.n_small;
+  const int ns = plan_items(a.ppi, a.max_split, np_total).n_items;
   const float* src = a.partial + partial_index(a, Hq, D, b, hq, 0);
   // maximum over splits
   float m_loc = -INFINITY;
