@@ -90,6 +90,8 @@ typedef struct {
  *                   (layer, query index, kv-head) the heads of three work queues (one per type)
  *                   and a spare word; zero between calls (init zeroes them, every call leaves
  *                   them zero), so two decode calls on one (view, layer) must not overlap
+ *   append_counters [max_seqs] scratch of thinkv_append_quantized (arrival counts of the
+ *                   workgroups of a sequence); zero between calls
  *   dev_status      [max_seqs * n_layers + 1] THINKV_ST_* flags
  *
  * Byte layout of one page: n_kv_heads blocks of thinkv_block_bytes(); a block is
@@ -115,6 +117,7 @@ typedef struct {
   int32_t* page_pos_max[3]; /* DEVICE */
   int32_t* n_live;          /* DEVICE */
   uint32_t* work_counters;  /* DEVICE */
+  uint32_t* append_counters;/* DEVICE */
   uint32_t* dev_status;     /* DEVICE */
 } thinkv_view;
 

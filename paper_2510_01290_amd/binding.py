@@ -29,7 +29,8 @@ class View(C.Structure):
     _fields_ = [("cfg", Config), ("arena", C.c_void_p * 3), ("arena_pages", C.c_int64 * 3),
                 ("free_stack", C.c_void_p * 3), ("free_top", C.c_void_p), ("block_table", C.c_void_p),
                 ("n_pages", C.c_void_p), ("page_filled", C.c_void_p * 3), ("slot_mask", C.c_void_p),
-                ("slot_pos", C.c_void_p * 3), ("page_pos_max", C.c_void_p * 3), ("n_live", C.c_void_p), ("work_counters", C.c_void_p), ("dev_status", C.c_void_p)]
+                ("slot_pos", C.c_void_p * 3), ("page_pos_max", C.c_void_p * 3), ("n_live", C.c_void_p), ("work_counters", C.c_void_p), ("append_counters", C.c_void_p),
+                ("dev_status", C.c_void_p)]
 
 
 def load():
@@ -132,6 +133,7 @@ class Cache:
         self.page_pos_max = [torch.empty(max(1, n), dtype=torch.int32, device=d) for n in self.arena_pages]
         self.n_live = torch.empty((max_seqs, n_layers), dtype=torch.int32, device=d)
         self.work_counters = torch.empty((n_layers, max_seqs, n_kv_heads, 4), dtype=torch.int32, device=d)
+        self.append_counters = torch.empty(max_seqs, dtype=torch.int32, device=d)
         self.dev_status = torch.empty(max_seqs * n_layers + 1, dtype=torch.int32, device=d)
         v = View()
         v.cfg = self.cfg
@@ -148,6 +150,7 @@ class Cache:
         v.n_pages = self.n_pages.data_ptr()
         v.n_live = self.n_live.data_ptr()
         v.work_counters = self.work_counters.data_ptr()
+        v.append_counters = self.append_counters.data_ptr()
         v.dev_status = self.dev_status.data_ptr()
         self.view = v
         self._ws = None

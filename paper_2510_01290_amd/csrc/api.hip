@@ -45,7 +45,7 @@ static int check_view(const thinkv_view* v) {
     if (v->arena_pages[k] > 0 && (!v->arena[k] || !v->free_stack[k] || !v->page_filled[k] || !v->slot_pos[k] || !v->page_pos_max[k]))
       return THINKV_E_INVALID_ARG;
   }
-  if (!v->free_top || !v->block_table || !v->slot_mask || !v->n_pages || !v->n_live || !v->work_counters || !v->dev_status) return THINKV_E_INVALID_ARG;
+  if (!v->free_top || !v->block_table || !v->slot_mask || !v->n_pages || !v->n_live || !v->work_counters || !v->append_counters || !v->dev_status) return THINKV_E_INVALID_ARG;
   return THINKV_OK;
 }
 

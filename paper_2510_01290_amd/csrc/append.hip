@@ -9,11 +9,19 @@
 //     k < R + tail     slot filled + (k - R) of the last page                  (tail = 16 - filled)
 //     otherwise        slot (k-R-tail) % 16 of the (k-R-tail)/16-th new page
 // and new pages are granted to sequences in ascending sequence id, which is token order.
-// Three kernels, all on the caller's stream:
+// Three steps in two kernels, both on the caller's stream:
 //   plan   (block per sequence)  token ranks per type, prefix popcounts of the reclaimable bits,
 //                                pages needed
 //   place  (block per token)     slot lookup, quantisation, packing, slot_pos, handle
 //   commit (block per sequence)  masks, fill counts, page lists, counters
+// The commit of a sequence changes tables that the place blocks of the sequence's tokens read
+// (masks, fill counts, page list), and reads nothing that they write.  So it needs no kernel of
+// its own, only to come after those reads: every place block, once its slot is settled, bumps
+// an arrival counter of its sequence (view->append_counters), and the block that completes the
+// count commits the sequence before it goes on to quantise its own token.  Reads-before-writes
+// is all that has to hold, so no fence is involved (a release fence costs an L2 write-back here).
+// A bulk call (more than 4,096 tokens: thousands of blocks would bump one sequence's counter) keeps
+// a commit kernel of its own.
 // The grant of new pages (exclusive sum of the needs of the sequences before s, against what the
 // pool held when the call began) is a sum over at most max_seqs small numbers: every block that
 // wants it works it out for itself rather than waiting for a kernel of its own.  A decode step
@@ -210,6 +218,9 @@ __device__ inline void grant_of(const thinkv_view& v, const AppendWs& ws, int s,
   *grant = left < 0 ? 0 : (left < need ? left : need);
 }
 
+__device__ void update_pools(const thinkv_view& v, const AppendWs& ws, int* s_scan);
+__device__ void commit_sequence(const thinkv_view& v, int layer, const AppendWs& ws, int s, int* s_scan);
+
 // ---------------------------------------------------------------------------------------------
 // place: one block per (token, share of the kv-heads); every block of a token derives the same
 // slot, block 0 records it.
@@ -218,11 +229,11 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
                                                            const void* __restrict__ v_new, const int32_t* __restrict__ tok_seq,
                                                            const int32_t* __restrict__ tok_pos, const uint8_t* __restrict__ tok_class,
                                                            int32_t* __restrict__ tok_handle, int n_tok, int in_dtype, AppendWs ws,
-                                                           int heads_per_block) {
+                                                           int heads_per_block, int commit_here) {
   constexpr int NG = D / kGroup;        // groups per row
   constexpr int NM = D / 16;            // 16-channel blocks per row
   constexpr int HP = 256 / (2 * D);     // heads handled per pass
-  __shared__ int s_place[5];            // type, page id, slot, ok, index in the page list
+  __shared__ int s_place[7];            // type, page id, slot, ok, index in the page list, arrivals wanted, last to arrive
   __shared__ uint8_t s_codes[HP][2][D];
   __shared__ uint32_t s_meta[HP][2][NG];
   const thinkv_config& c = v.cfg;
@@ -232,13 +243,15 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
   __shared__ int s_find[4];   // 1 = search wanted / 2 = grant wanted, sequence, type, rank
   __shared__ int s_scan[5];
   if (tid == 0) {
-    int ok = 0, cls = 0, pid = 0, slot = 0, pi = 0, find = 0, k = 0;
+    int ok = 0, cls = 0, pid = 0, slot = 0, pi = 0, find = 0, k = 0, target = 0;
     const int s = tok_seq[i];
     if (s < 0 || s >= c.max_seqs) {
       atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEQ);
     } else {
       cls = tok_class[i];
       const SeqPlan& pl = ws.plan[s];
+      // every block of every token inside the sequence's range reports to the sequence
+      if (i >= pl.lo && i < pl.hi) target = (pl.hi - pl.lo) * (int)gridDim.y;
       if (cls > 2) {
         atomicOr(&v.dev_status[sl_index(c, s, layer)], THINKV_ST_BAD_CLASS);
       } else if (i >= pl.lo && i < pl.hi) {
@@ -258,7 +271,7 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
       }
     }
     s_find[0] = find; s_find[1] = s; s_find[2] = cls; s_find[3] = k;
-    s_place[0] = cls; s_place[1] = pid; s_place[2] = slot; s_place[3] = ok; s_place[4] = pi;
+    s_place[0] = cls; s_place[1] = pid; s_place[2] = slot; s_place[3] = ok; s_place[4] = pi; s_place[5] = target;
   }
   __syncthreads();
   if (s_find[0] == 1) {
@@ -303,6 +316,21 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
     }
     if (tok_handle) tok_handle[i] = ok ? THINKV_HANDLE(cls, pi, slot) : -1;
   }
+  __syncthreads();
+  // Everything this block reads of the sequence's tables has been read.  Report; the block that
+  // completes the sequence's count commits it (and puts the counter back to zero).
+  if (tid == 0) {
+    const int target = s_place[5], s = s_find[1];
+    int last = 0;
+    if (target > 0 && commit_here) {
+      last = atomicAdd(&v.append_counters[s], 1u) == (uint32_t)target - 1u;
+      if (last) v.append_counters[s] = 0u;
+    }
+    s_place[6] = last;
+  }
+  __syncthreads();
+  if (s_place[6]) commit_sequence(v, layer, ws, s_find[1], s_scan);
+  if (commit_here && blockIdx.x == 0 && blockIdx.y == 0) update_pools(v, ws, s_scan);
   __syncthreads();
   if (!s_place[3]) return;
   const int cls = s_place[0], pid = s_place[1], t = s_place[2];
@@ -386,21 +414,25 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
   }
 }
 
-__global__ __launch_bounds__(256) void append_commit_kernel(thinkv_view v, int layer, AppendWs ws) {
-  const thinkv_config& c = v.cfg;
-  const int s = blockIdx.x, tid = threadIdx.x;
-  const SeqPlan pl = ws.plan[s];
-  __shared__ int s_scan[5];
-  if (s == 0) {
-    // the pools after the call: what all sequences together were granted is gone
-    for (int k = 0; k < 3; ++k) {
-      int want = 0;
-      for (int t = tid; t < c.max_seqs; t += 256) want += ws.plan[t].need[k];
-      want = block_sum(want, s_scan);
-      const int avail = ws.avail_old[k];
-      if (tid == 0) v.free_top[k] = avail - (want < avail ? want : avail);
-    }
+// The pools after the call: what all sequences together were granted is gone.  (One block;
+// nothing in the call reads free_top after the plan kernel's snapshot.)
+__device__ void update_pools(const thinkv_view& v, const AppendWs& ws, int* s_scan /*[5]*/) {
+  const int tid = threadIdx.x;
+  for (int k = 0; k < 3; ++k) {
+    int want = 0;
+    for (int t = tid; t < v.cfg.max_seqs; t += 256) want += ws.plan[t].need[k];
+    want = block_sum(want, s_scan);
+    const int avail = ws.avail_old[k];
+    if (tid == 0) v.free_top[k] = avail - (want < avail ? want : avail);
   }
+}
+
+// One block: masks, fill counts, page lists and counters of sequence s, once every place block
+// of the sequence has settled its slot.
+__device__ void commit_sequence(const thinkv_view& v, int layer, const AppendWs& ws, int s, int* s_scan /*[5]*/) {
+  const thinkv_config& c = v.cfg;
+  const int tid = threadIdx.x;
+  const SeqPlan pl = ws.plan[s];
   if (pl.lo >= pl.hi) return;
   int placed_all = 0, short_any = 0;
   for (int k = 0; k < 3; ++k) {
@@ -453,6 +485,13 @@ __global__ __launch_bounds__(256) void append_commit_kernel(thinkv_view v, int l
   }
 }
 
+// bulk calls: one block per sequence after the place kernel
+__global__ __launch_bounds__(256) void append_commit_kernel(thinkv_view v, int layer, AppendWs ws) {
+  __shared__ int s_scan[5];
+  if (blockIdx.x == 0) update_pools(v, ws, s_scan);
+  commit_sequence(v, layer, ws, blockIdx.x, s_scan);
+}
+
 int launch_append(const thinkv_view& v, int layer, const void* k_new, const void* v_new, const int32_t* tok_seq,
                   const int32_t* tok_pos, const uint8_t* tok_class, int32_t* tok_handle, int n_tok, int in_dtype,
                   void* workspace, hipStream_t st) {
@@ -465,13 +504,14 @@ int launch_append(const thinkv_view& v, int layer, const void* k_new, const void
   const int H = v.cfg.n_kv_heads, hp = v.cfg.head_dim == 128 ? 1 : 2;
   const int hpb = n_tok <= 4096 ? hp : ((H + hp - 1) / hp) * hp;
   const dim3 grid(n_tok, (H + hpb - 1) / hpb);
+  const int commit_here = n_tok <= 4096;   // else thousands of blocks would bump one sequence's counter
   if (v.cfg.head_dim == 128)
     hipLaunchKernelGGL(append_place_kernel<128>, grid, dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
-                       tok_class, tok_handle, n_tok, in_dtype, ws, hpb);
+                       tok_class, tok_handle, n_tok, in_dtype, ws, hpb, commit_here);
   else
     hipLaunchKernelGGL(append_place_kernel<64>, grid, dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
-                       tok_class, tok_handle, n_tok, in_dtype, ws, hpb);
-  hipLaunchKernelGGL(append_commit_kernel, dim3(S), dim3(256), 0, st, v, layer, ws);
+                       tok_class, tok_handle, n_tok, in_dtype, ws, hpb, commit_here);
+  if (!commit_here) hipLaunchKernelGGL(append_commit_kernel, dim3(S), dim3(256), 0, st, v, layer, ws);
   return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
 }
 

@@ -58,6 +58,7 @@ __global__ __launch_bounds__(256) void init_kernel(thinkv_view v) {
   for (int64_t i = tid; i < nsl * 3; i += stride) v.n_pages[i] = 0;
   for (int64_t i = tid; i < nsl; i += stride) v.n_live[i] = 0;
   for (int64_t i = tid; i < nsl + 1; i += stride) v.dev_status[i] = 0;
+  for (int64_t i = tid; i < c.max_seqs; i += stride) v.append_counters[i] = 0;
   for (int64_t i = tid; i < nsl * c.n_kv_heads * 4; i += stride) v.work_counters[i] = 0;
 }
 
