@@ -119,7 +119,8 @@ def select_evictions(cache, layer, tok_seq, tok_handle, seg_offset, seg_keep, ma
     return ev.astype(np.int32), margins
 
 
-def anneal_plan(seg_type, seg_live, transition_ended, n_live, budget, retention=RETENTION, importance=IMPORTANCE):
+def anneal_plan(seg_type, seg_live, transition_ended, n_live, budget, retention=RETENTION, importance=IMPORTANCE,
+                once=False, max_cuts=None):
     """Which segments of one (sequence, layer) are cut, and to how many tokens (Sec. 4.3).
 
     seg_type[i], seg_live[i]: thought type and live tokens of segment i, oldest first; the last
@@ -128,7 +129,9 @@ def anneal_plan(seg_type, seg_live, transition_ended, n_live, budget, retention=
     Case 1 (transition_ended): every preceding segment above the lowest retention value goes
     down one level.  Case 2: while more than `budget` tokens are live, the oldest segment of the
     least important type that can still shrink goes down one level.
-    Returns [(segment, keep)] in the order the cuts are made; a segment may appear twice."""
+    Returns [(segment, keep)] in the order the cuts are made; a segment may appear twice.
+    once=True: a segment is cut at most once per call (one K-means per segment and call; what is
+    still over budget is dealt with on the next call); max_cuts: at most that many cuts."""
     live = [int(v) for v in seg_live]
     total = int(n_live)
     cuts = []
@@ -140,18 +143,21 @@ def anneal_plan(seg_type, seg_live, transition_ended, n_live, budget, retention=
         return None
 
     last = len(live) - 1
+    done = set()
+    room = (lambda: True) if max_cuts is None else (lambda: len(cuts) < max_cuts)
     if transition_ended:
         for i in range(last):
             r = next_level(live[i])
-            if r is not None:
+            if r is not None and room():
                 cuts.append((i, r))
+                done.add(i)
                 total -= live[i] - r
                 live[i] = r
-    while total > budget:
+    while total > budget and room():
         pick = None
         for t in importance:
             for i in range(last):
-                if seg_type[i] == t and next_level(live[i]) is not None:
+                if seg_type[i] == t and next_level(live[i]) is not None and not (once and i in done):
                     pick = i
                     break
             if pick is not None:
@@ -160,6 +166,33 @@ def anneal_plan(seg_type, seg_live, transition_ended, n_live, budget, retention=
             break
         r = next_level(live[pick])
         cuts.append((pick, r))
+        done.add(pick)
         total -= live[pick] - r
         live[pick] = r
     return cuts
+
+
+def plan_evictions(cache, layer, seq, seg_start, seg_type, transition_ended, budget, max_cuts, retention=RETENTION):
+    """The plan over the cache as it stands: every live token of the sequence belongs to the
+    segment whose start is the largest one not above its position (the block table's start-index
+    column, Sec. 5.2); segments are counted, anneal_plan (one cut per segment and call) names the
+    cuts, and each cut comes with the handles of its live tokens in ascending position -- the
+    input of the survivor choice.  Returns [(segment, keep, handles)]."""
+    from .cache import make_handle, PAGE
+    seg_start = np.asarray(seg_start, dtype=np.int64)
+    n_seg = len(seg_start)
+    members = [[] for _ in range(n_seg)]
+    for c in range(3):
+        for pi in range(int(cache.n_pages[seq, layer, c])):
+            pid = int(cache.table[seq, layer, c, pi])
+            m = int(cache.valid[c][pid])
+            for slot in range(PAGE):
+                if m >> slot & 1:
+                    pos = int(cache.slot_pos[c][pid, slot])
+                    sg = int(np.searchsorted(seg_start, pos, side="right")) - 1
+                    if sg >= 0:
+                        members[sg].append((pos, make_handle(c, pi, slot)))
+    live = [len(m) for m in members]
+    cuts = anneal_plan(list(seg_type), live, bool(transition_ended), int(cache.n_live[seq, layer]), budget,
+                       retention=retention, once=True, max_cuts=max_cuts)
+    return [(i, r, [h for _, h in sorted(members[i])]) for i, r in cuts]

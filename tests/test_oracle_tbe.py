@@ -116,3 +116,35 @@ def test_anneal_plan_cases():
     assert total <= 400 and live[4] == 50
     # nothing can shrink any more: the plan stops even though the budget is not met
     assert tbe.anneal_plan([T, T, R], [4, 4, 500], False, 508, 100) == []
+
+
+def test_anneal_plan_one_cut_per_segment_and_capacity():
+    T, E, R = 0, 1, 2
+    # over budget by a lot: with once=True the transition segment is cut once, then the plan moves on to the next candidates
+    cuts = tbe.anneal_plan([R, E, T, E, R], [128, 128, 128, 128, 50], False, 562, 300, once=True)
+    assert cuts == [(2, 64), (1, 64), (3, 64), (0, 64)]
+    # capacity: stops after max_cuts cuts
+    assert tbe.anneal_plan([R, E, T, E, R], [128, 128, 128, 128, 50], False, 562, 300, once=True, max_cuts=2) == [(2, 64), (1, 64)]
+    # Case 1 and Case 2 in one call: the transition cut is not repeated by Case 2
+    cuts = tbe.anneal_plan([T, R, T, E], [100, 100, 20, 9], True, 229, 60, once=True)
+    assert cuts == [(0, 64), (1, 64), (2, 16)]
+
+
+def test_plan_evictions_groups_live_tokens_by_segment_start():
+    cfg = oc.OracleConfig(1, 8, 2, 64, (8, 2, 4), 1, 64, (64, 64, 64))
+    c = oc.OracleCache(cfg)
+    rng = np.random.default_rng(5)
+    n = 300
+    types = np.array([2] * 100 + [0] * 80 + [1] * 120, np.uint8)          # three segments: R, T, E (the last one open)
+    k = rng.standard_normal((n, 2, 64)).astype(np.float16).astype(np.float32)
+    h = np.asarray(c.append(0, k, k, np.zeros(n, np.int64), np.arange(n), types))
+    c.evict_slots(0, [0] * 10, h[5:15])                                    # ten tokens of segment 0 are gone already
+    plan = tbe.plan_evictions(c, 0, 0, [0, 100, 180], [2, 0, 1], True, 10 ** 9, 8)
+    assert [(i, r) for i, r, _ in plan] == [(0, 64), (1, 64)]
+    assert plan[0][2] == [int(x) for x in np.r_[h[:5], h[15:100]]]         # live tokens of the segment, ascending position
+    assert plan[1][2] == [int(x) for x in h[100:180]]
+    # no trigger, within budget: nothing
+    assert tbe.plan_evictions(c, 0, 0, [0, 100, 180], [2, 0, 1], False, 290, 8) == []
+    # over budget: the transition segment first (least important), then execution is open, so reasoning
+    plan = tbe.plan_evictions(c, 0, 0, [0, 100, 180], [2, 0, 1], False, 200, 8)
+    assert [(i, r) for i, r, _ in plan] == [(1, 64), (0, 64)]
