@@ -15,10 +15,11 @@
 //              two members the earlier one: both are equally near their mean)
 //
 // Two kernels.  gather: one workgroup per token writes its key row [Hkv * D] into the workspace.
-// kmeans: one workgroup of 256 threads per segment, thread i owns point i (segments hold at
-// most 256 live tokens, the schedule keeps at most 64): the N x K distances are accumulated
-// tile by tile (32 channels of all points and all centroids staged in LDS, 64 accumulators per
-// thread), the update sums the members of a cluster in index order (fixed summation order, so
+// kmeans: one workgroup of 256 threads per segment (segments hold at most 256 live tokens, the
+// schedule keeps at most 64): lane L of every wave owns points L, L + 64, ..., wave w clusters
+// 16w .. 16w + 15, so all threads are busy whatever the segment's size; the N x K distances are
+// accumulated tile by tile (32 channels of all points and all centroids staged in LDS, up to 64
+// accumulators per thread), the update sums the members of a cluster in index order (fixed summation order, so
 // the result is the same on every run), and the survivor of a cluster is found with a 64-bit
 // LDS minimum over (distance bits, index).  Plain binary32 FMAs on the vector ALU: the event is
 // rare (segments are annealed when a transition thought ends or the budget is exceeded).
@@ -84,31 +85,46 @@ __global__ __launch_bounds__(256) void tbe_gather_kernel(thinkv_view v, TbeArgs 
 }
 
 // ---- kmeans
-// squared distances of point `me` (this thread's) to all centroids, accumulated over the channels
-__device__ inline void distances(const float* __restrict__ x, const float* __restrict__ cent, int n, int k, int dim, float (*xs)[kPad],
-                                 float (*cs)[kPad], float* acc /*[kTbeMaxKeep]*/) {
-  const int tid = threadIdx.x;
+constexpr int kPT = kTbeMaxTokens / 64;   // points per thread at most: lane L owns points L, L + 64, ...
+constexpr int kKT = kTbeMaxKeep / 4;      // clusters per thread: wave w owns clusters kKT*w .. kKT*w + kKT-1
+
+// Squared distances of this lane's points to this wave's clusters, accumulated over the channels.
+// A wave reads the centroid rows as LDS broadcasts (all its lanes want the same cluster) and every
+// lane its own point rows; pt = ceil(n / 64) points per lane are live.
+__device__ inline void distances(const float* __restrict__ x, const float* __restrict__ cent, int n, int k, int dim, int pt,
+                                 float (*xs)[kPad], float (*cs)[kPad], float (*acc)[kKT]) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 #pragma unroll
-  for (int j = 0; j < kTbeMaxKeep; ++j) acc[j] = 0.f;
+  for (int q = 0; q < kPT; ++q)
+#pragma unroll
+    for (int j = 0; j < kKT; ++j) acc[q][j] = 0.f;
   for (int d0 = 0; d0 < dim; d0 += kTile) {
     __syncthreads();
-    for (int idx = tid; idx < kTbeMaxTokens * kTile; idx += 256) {
-      const int r = idx / kTile, cc = idx % kTile;
-      xs[r][cc] = r < n ? x[(int64_t)r * dim + d0 + cc] : 0.f;
+    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int idx = tid; idx < 64 * pt * (kTile / 4); idx += 256) {
+      const int r = idx / (kTile / 4), c4 = idx % (kTile / 4);
+      *(float4*)&xs[r][4 * c4] = r < n ? *(const float4*)&x[(int64_t)r * dim + d0 + 4 * c4] : zero4;
     }
-    for (int idx = tid; idx < kTbeMaxKeep * kTile; idx += 256) {
-      const int r = idx / kTile, cc = idx % kTile;
-      cs[r][cc] = r < k ? cent[(int64_t)r * dim + d0 + cc] : 0.f;
+    for (int idx = tid; idx < kTbeMaxKeep * (kTile / 4); idx += 256) {
+      const int r = idx / (kTile / 4), c4 = idx % (kTile / 4);
+      *(float4*)&cs[r][4 * c4] = r < k ? *(const float4*)&cent[(int64_t)r * dim + d0 + 4 * c4] : zero4;
     }
     __syncthreads();
-#pragma unroll
+#pragma unroll 2
     for (int c4 = 0; c4 < kTile / 4; ++c4) {
-      const float4 xv = *(const float4*)&xs[tid][4 * c4];
+      float4 xv[kPT];
 #pragma unroll
-      for (int j = 0; j < kTbeMaxKeep; ++j) {
-        const float4 cv = *(const float4*)&cs[j][4 * c4];
-        const float e0 = xv.x - cv.x, e1 = xv.y - cv.y, e2 = xv.z - cv.z, e3 = xv.w - cv.w;
-        acc[j] = fmaf(e3, e3, fmaf(e2, e2, fmaf(e1, e1, fmaf(e0, e0, acc[j]))));
+      for (int q = 0; q < kPT; ++q)
+        if (q < pt) xv[q] = *(const float4*)&xs[lane + 64 * q][4 * c4];
+#pragma unroll
+      for (int j = 0; j < kKT; ++j) {
+        const float4 cv = *(const float4*)&cs[kKT * wave + j][4 * c4];
+#pragma unroll
+        for (int q = 0; q < kPT; ++q)
+          if (q < pt) {
+            const float e0 = xv[q].x - cv.x, e1 = xv[q].y - cv.y, e2 = xv[q].z - cv.z, e3 = xv[q].w - cv.w;
+            acc[q][j] = fmaf(e3, e3, fmaf(e2, e2, fmaf(e1, e1, fmaf(e0, e0, acc[q][j]))));
+          }
       }
     }
   }
@@ -116,7 +132,7 @@ __device__ inline void distances(const float* __restrict__ x, const float* __res
 
 __global__ __launch_bounds__(256) void tbe_kmeans_kernel(thinkv_view v, TbeArgs a) {
   const thinkv_config& c = v.cfg;
-  const int seg = blockIdx.x, tid = threadIdx.x;
+  const int seg = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = a.seg_offset[seg], hi = a.seg_offset[seg + 1];
   const int n = hi - lo, want = a.seg_keep[seg];
   if (n <= 0) return;
@@ -130,11 +146,13 @@ __global__ __launch_bounds__(256) void tbe_kmeans_kernel(thinkv_view v, TbeArgs 
     for (int i = tid; i < n; i += 256) a.ev_handle[lo + i] = -1;
     return;
   }
-  const int k = want, dim = a.dim;
+  const int k = want, dim = a.dim, pt = (n + 63) / 64;
   const float* x = a.x + (int64_t)lo * dim;
   float* cent = a.cent + (int64_t)seg * kTbeMaxKeep * dim;
   __shared__ __attribute__((aligned(16))) float xs[kTbeMaxTokens][kPad];
   __shared__ __attribute__((aligned(16))) float cs[kTbeMaxKeep][kPad];
+  __shared__ float s_bd[4][kTbeMaxTokens];   // per wave (cluster quarter): best distance of every point ...
+  __shared__ int s_bj[4][kTbeMaxTokens];     // ... and the cluster it belongs to
   __shared__ int s_assign[kTbeMaxTokens], s_order[kTbeMaxTokens];
   __shared__ int s_cnt[kTbeMaxKeep], s_start[kTbeMaxKeep];
   __shared__ unsigned long long s_best[kTbeMaxKeep];
@@ -143,30 +161,65 @@ __global__ __launch_bounds__(256) void tbe_kmeans_kernel(thinkv_view v, TbeArgs 
     const int j = idx / dim, d = idx % dim;
     cent[idx] = x[(int64_t)((j * n) / k) * dim + d];
   }
-  float acc[kTbeMaxKeep];
-  int mine = -1;
-  for (int it = 0; it < a.max_iters; ++it) {
-    __threadfence_block();
-    distances(x, cent, n, k, dim, xs, cs, acc);
-    int best = 0;
-    float bd = acc[0];
+  float acc[kPT][kKT];
+  int mine[kPT];
 #pragma unroll
-    for (int j = 1; j < kTbeMaxKeep; ++j)
-      if (j < k && acc[j] < bd) {
-        bd = acc[j];
-        best = j;
-      }
-    const int changed = tid < n && best != mine;
-    mine = best;
+  for (int q = 0; q < kPT; ++q) mine[q] = -1;
+  // nearest cluster of this lane's points: best of this wave's quarter, then best of the four quarters
+  // (ties go to the lowest cluster: quarters and clusters are scanned in ascending order)
+  auto assign = [&](int* out) {
+#pragma unroll
+    for (int q = 0; q < kPT; ++q) {
+      float bd = INFINITY;
+      int bj = 0;
+#pragma unroll
+      for (int j = 0; j < kKT; ++j)
+        if (kKT * wave + j < k && acc[q][j] < bd) {
+          bd = acc[q][j];
+          bj = kKT * wave + j;
+        }
+      s_bd[wave][lane + 64 * q] = bd;
+      s_bj[wave][lane + 64 * q] = bj;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < kPT; ++q) {
+      float bd = s_bd[0][lane + 64 * q];
+      int bj = s_bj[0][lane + 64 * q];
+#pragma unroll
+      for (int w = 1; w < 4; ++w)
+        if (s_bd[w][lane + 64 * q] < bd) {
+          bd = s_bd[w][lane + 64 * q];
+          bj = s_bj[w][lane + 64 * q];
+        }
+      out[q] = bj;
+    }
+  };
+  for (int it = 0; it < a.max_iters; ++it) {
+    distances(x, cent, n, k, dim, pt, xs, cs, acc);
+    int now[kPT];
+    assign(now);
+    int changed = 0;
+#pragma unroll
+    for (int q = 0; q < kPT; ++q) {
+      changed |= (lane + 64 * q < n) && now[q] != mine[q];
+      mine[q] = now[q];
+    }
     if (!__syncthreads_or(changed)) break;
     // ---- update: members of every cluster in index order
     if (tid < kTbeMaxKeep) s_cnt[tid] = 0;
-    if (tid < n) s_assign[tid] = mine;
+    if (wave == 0) {
+#pragma unroll
+      for (int q = 0; q < kPT; ++q)
+        if (lane + 64 * q < n) s_assign[lane + 64 * q] = mine[q];
+    }
     __syncthreads();
-    int rank = 0;
     if (tid < n) {
-      for (int i = 0; i < tid; ++i) rank += s_assign[i] == mine;
-      atomicAdd(&s_cnt[mine], 1);
+      const int cl = s_assign[tid];
+      int rank = 0;
+      for (int i = 0; i < tid; ++i) rank += s_assign[i] == cl;
+      atomicAdd(&s_cnt[cl], 1);
+      s_order[tid] = rank;   // position among the cluster's members, for now
     }
     __syncthreads();
     if (tid == 0) {
@@ -177,7 +230,10 @@ __global__ __launch_bounds__(256) void tbe_kmeans_kernel(thinkv_view v, TbeArgs 
       }
     }
     __syncthreads();
-    if (tid < n) s_order[s_start[mine] + rank] = tid;
+    int slot = -1;
+    if (tid < n) slot = s_start[s_assign[tid]] + s_order[tid];
+    __syncthreads();
+    if (tid < n) s_order[slot] = tid;
     __syncthreads();
     for (int j = 0; j < k; ++j) {
       const int m = s_cnt[j];
@@ -192,29 +248,38 @@ __global__ __launch_bounds__(256) void tbe_kmeans_kernel(thinkv_view v, TbeArgs 
     __syncthreads();
   }
   // ---- survivors: nearest member of every cluster under the final centroids
-  __threadfence_block();
-  distances(x, cent, n, k, dim, xs, cs, acc);
+  distances(x, cent, n, k, dim, pt, xs, cs, acc);
   if (tid < kTbeMaxKeep) {
     s_cnt[tid] = 0;
     s_start[tid] = kTbeMaxTokens;   // here: lowest index among the cluster's members
     s_best[tid] = ~0ull;
   }
   __syncthreads();
-  float own = 0.f;
 #pragma unroll
-  for (int j = 0; j < kTbeMaxKeep; ++j)
-    if (j == mine) own = acc[j];
-  if (tid < n) {
-    atomicAdd(&s_cnt[mine], 1);
-    atomicMin(&s_start[mine], tid);
-    // distances are not negative, so their bit patterns order like the numbers; the index breaks ties
-    atomicMin(&s_best[mine], ((unsigned long long)__builtin_bit_cast(uint32_t, own) << 32) | (unsigned)tid);
+  for (int q = 0; q < kPT; ++q) {
+    const int p = lane + 64 * q;
+    if (p < n && mine[q] / kKT == wave) {   // the wave that holds the distance to the point's own cluster
+      float own = 0.f;
+#pragma unroll
+      for (int j = 0; j < kKT; ++j)
+        if (j == mine[q] % kKT) own = acc[q][j];
+      atomicAdd(&s_cnt[mine[q]], 1);
+      atomicMin(&s_start[mine[q]], p);
+      // distances are not negative, so their bit patterns order like the numbers; the index breaks ties
+      atomicMin(&s_best[mine[q]], ((unsigned long long)__builtin_bit_cast(uint32_t, own) << 32) | (unsigned)p);
+    }
   }
   __syncthreads();
-  if (tid < n) {
-    // two members are equally near their mean whatever the rounding says: the earlier one stays
-    const bool keep = s_cnt[mine] <= 2 ? tid == s_start[mine] : (int)(s_best[mine] & 0xFFFFFFFFull) == tid;
-    a.ev_handle[lo + tid] = keep ? -1 : a.tok_handle[lo + tid];
+  if (wave == 0) {
+#pragma unroll
+    for (int q = 0; q < kPT; ++q) {
+      const int p = lane + 64 * q;
+      if (p < n) {
+        // two members are equally near their mean whatever the rounding says: the earlier one stays
+        const bool keep = s_cnt[mine[q]] <= 2 ? p == s_start[mine[q]] : (int)(s_best[mine[q]] & 0xFFFFFFFFull) == p;
+        a.ev_handle[lo + p] = keep ? -1 : a.tok_handle[lo + p];
+      }
+    }
   }
 }
 
