@@ -211,6 +211,38 @@ def main():
         tbe = {"segments": len(off) - 1, "tokens_per_segment": 128, "keep": 64, "max_iters": 8,
                "us_median": float(np.median([a_.elapsed_time(b_) for a_, b_ in tm]) * 1e3),
                "survivors": int((d_ev == -1).sum().item())}
+    # the eviction plan on the device: every sequence's segment table (runs of one thought type, at most 192 tokens),
+    # a transition has just ended everywhere, so every closed segment above the floor is listed with its live tokens
+    plan = None
+    if args.variant == "fast":
+        max_segs = 2048
+        seg_start = np.zeros((args.batch, max_segs), np.int32)
+        seg_type = np.zeros((args.batch, max_segs), np.uint8)
+        n_segs = np.zeros(args.batch, np.int32)
+        for s in range(args.batch):
+            cls = wl.classes[s][:ntok0[s]]
+            edges = np.r_[0, np.flatnonzero(np.diff(cls)) + 1, len(cls)]
+            starts = np.concatenate([np.arange(a0, b0, 192) for a0, b0 in zip(edges[:-1], edges[1:])])[:max_segs]
+            n_segs[s] = len(starts)
+            seg_start[s, :len(starts)] = starts
+            seg_type[s, :len(starts)] = cls[starts]
+        cap_seg, cap_tok = args.batch * 256, args.batch * 256 * 192
+        p_out = [torch.empty(cap_tok, dtype=torch.int32, device=dev), torch.empty(cap_tok, dtype=torch.int32, device=dev),
+                 torch.empty(cap_seg + 1, dtype=torch.int32, device=dev), torch.empty(cap_seg, dtype=torch.int32, device=dev),
+                 torch.empty(2, dtype=torch.int32, device=dev)]
+        p_in = [ev_seq, torch.from_numpy(seg_start).to(dev), torch.from_numpy(seg_type).to(dev), torch.from_numpy(n_segs).to(dev),
+                torch.ones(args.batch, dtype=torch.uint8, device=dev)]
+        tm = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+        B.thinkv_tbe_plan(gc, 0, *p_in, 10 ** 9, 256, *p_out)
+        for a_, b_ in tm:
+            a_.record()
+            B.thinkv_tbe_plan(gc, 0, *p_in, 10 ** 9, 256, *p_out)
+            b_.record()
+        torch.cuda.synchronize()
+        cnts = p_out[4].cpu().numpy()
+        plan = {"sequences": args.batch, "segments_per_sequence": float(n_segs.mean()), "cuts": int(cnts[0]), "tokens_listed": int(cnts[1]),
+                "us_median": float(np.median([a_.elapsed_time(b_) for a_, b_ in tm]) * 1e3)}
+        del p_out
     torch.cuda.synchronize()
     attn_sparsity_us = float(np.median([a.elapsed_time(b) for a, b in smarks]) * 1e3) if args.variant == "fast" else None
     evict_us = float(np.median([m[0].elapsed_time(m[1]) for m in marks]) * 1e3)
@@ -239,7 +271,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "us_per_step": ms_step * 1e3, "attn_us_mean": float(attn_ms.mean() * 1e3), "attn_us_min": float(attn_ms.min() * 1e3),
         "attn_us_median": float(np.median(attn_ms) * 1e3), "evict_us_median": evict_us, "append_us_median": append_us,
-        "attn_with_sparsity_statistic_us_median": attn_sparsity_us, "tbe_select": tbe, "bulk_append": bulk,
+        "attn_with_sparsity_statistic_us_median": attn_sparsity_us, "tbe_select": tbe, "tbe_plan": plan, "bulk_append": bulk,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16" if args.variant == "fast" else "f32",
         "data": "synthetic",
         "config": {"workload": wl.name + " (R1-Llama-8B layer: 32 q / 8 kv heads, head_dim 128, bf16; T8/R4/E2, 30% E + 10% R evicted and refilled)",

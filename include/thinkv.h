@@ -54,6 +54,7 @@ typedef enum {
 #define THINKV_PAGE_SIZE 16
 #define THINKV_TBE_MAX_SEGMENT 256 /* live tokens of one segment handed to thinkv_tbe_select */
 #define THINKV_TBE_MAX_KEEP 64     /* largest retention level (the paper's schedule starts at 64) */
+#define THINKV_TBE_MAX_SEGS 2048   /* segments of one sequence thinkv_tbe_plan looks at          */
 #define THINKV_GROUP_SIZE 32
 
 /* Static geometry; host memory, passed by value inside thinkv_view. */
@@ -236,6 +237,42 @@ int thinkv_decode_attention_valu(const thinkv_view* view, int32_t layer, const v
  * last word of dev_status) for a segment outside the limits (nothing of it is evicted).
  */
 size_t thinkv_tbe_workspace_bytes(const thinkv_config* cfg, int32_t n_tok, int32_t n_seg);
+
+/*
+ * Thought-adaptive eviction, the plan (Sec. 4.3): which segments of the examined sequences are
+ * cut now, and to how many tokens; the output is the input of thinkv_tbe_select.
+ * Case 1: where transition_ended[b] is set (a transition segment of the sequence has just
+ * ended), every preceding segment goes down one level of the retention schedule {64,32,16,8,4}.
+ * Case 2: while the sequence holds more than `budget` live tokens, the oldest segment of the
+ * least important type (0 = transition, then 1 = execution, then 2 = reasoning) that can still
+ * shrink goes down one level.  The level of a segment follows from its live size (it is cut to
+ * the largest schedule value below that size); a segment is cut at most once per call; the
+ * last (open) segment is never touched; a segment with more than THINKV_TBE_MAX_SEGMENT live
+ * tokens is left alone and reported (THINKV_ST_BAD_SEGMENT in the last word of dev_status).
+ * A live token belongs to the segment whose start is the largest one not above its position
+ * (the block table's start-index column, Sec. 5.2 "Block Table").
+ *
+ *   seq_ids           DEVICE [B] sequences to examine (each at most once)
+ *   seg_start         DEVICE [max_seqs][max_segs] first position of every segment of a sequence,
+ *                     ascending; row = sequence id.  max_segs <= THINKV_TBE_MAX_SEGS
+ *   seg_type          DEVICE [max_seqs][max_segs] thought type of the segment
+ *   n_segs            DEVICE [max_seqs] segments the sequence has so far
+ *   transition_ended  DEVICE [B], may be NULL (no Case 1 anywhere)
+ *   max_cuts          cuts per sequence and call at most (1..256); what is left waits for the next call
+ *   cap_seg, cap_tok  capacity of the output lists; cuts that no longer fit are left for the next call
+ *   tok_seq, tok_handle  DEVICE [cap_tok] out: the live tokens of the cut segments, segment after
+ *                     segment, ascending position inside a segment
+ *   seg_offset        DEVICE [cap_seg + 1] out; seg_keep DEVICE [cap_seg] out
+ *   counts            DEVICE [2] out: number of cuts, number of listed tokens (the n_seg and n_tok
+ *                     of the thinkv_tbe_select call that follows)
+ *   workspace         at least thinkv_tbe_plan_workspace_bytes(B, max_cuts)
+ */
+size_t thinkv_tbe_plan_workspace_bytes(int32_t B, int32_t max_cuts);
+int thinkv_tbe_plan(const thinkv_view* view, int32_t layer, const int32_t* seq_ids, const int32_t* seg_start,
+                    const uint8_t* seg_type, const int32_t* n_segs, const uint8_t* transition_ended, int32_t B,
+                    int32_t max_segs, int32_t budget, int32_t max_cuts, int32_t cap_seg, int32_t cap_tok,
+                    int32_t* tok_seq, int32_t* tok_handle, int32_t* seg_offset, int32_t* seg_keep, int32_t* counts,
+                    void* workspace, size_t workspace_bytes, void* stream);
 int thinkv_tbe_select(const thinkv_view* view, int32_t layer, const int32_t* tok_seq, const int32_t* tok_handle,
                       const int32_t* seg_offset, const int32_t* seg_keep, int32_t n_seg, int32_t n_tok,
                       int32_t max_iters, int32_t* ev_handle, void* workspace, size_t workspace_bytes, void* stream);

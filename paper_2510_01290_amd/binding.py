@@ -16,7 +16,8 @@ ST_NOPAGES, ST_BAD_CLASS, ST_BAD_SLOT, ST_EVICT_DEAD, ST_BAD_SEQ, ST_BAD_SEGMENT
 EXPORTS = ["thinkv_block_bytes", "thinkv_page_bytes", "thinkv_append_workspace_bytes",
            "thinkv_decode_workspace_bytes", "thinkv_init_view", "thinkv_append_quantized", "thinkv_evict",
            "thinkv_decode_attention", "thinkv_decode_attention_valu", "thinkv_decode_sparsity_workspace_bytes",
-           "thinkv_decode_attention_sparsity", "thinkv_tbe_workspace_bytes", "thinkv_tbe_select", "thinkv_status_string"]
+           "thinkv_decode_attention_sparsity", "thinkv_tbe_workspace_bytes", "thinkv_tbe_select", "thinkv_tbe_plan_workspace_bytes", "thinkv_tbe_plan",
+           "thinkv_status_string"]
 
 
 class Config(C.Structure):
@@ -68,6 +69,10 @@ def load():
     lib.thinkv_tbe_workspace_bytes.argtypes = [C.POINTER(Config), i32, i32]
     lib.thinkv_tbe_select.restype = C.c_int
     lib.thinkv_tbe_select.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp]
+    lib.thinkv_tbe_plan_workspace_bytes.restype = sz
+    lib.thinkv_tbe_plan_workspace_bytes.argtypes = [i32, i32]
+    lib.thinkv_tbe_plan.restype = C.c_int
+    lib.thinkv_tbe_plan.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.thinkv_status_string.restype = C.c_char_p
     lib.thinkv_status_string.argtypes = [C.c_int]
     _lib = lib
@@ -202,6 +207,27 @@ def _decode(fn, cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale
 def thinkv_decode_attention(cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale, max_ctx_pages, stream=None):
     _decode(load().thinkv_decode_attention, cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale,
             max_ctx_pages, stream)
+
+
+def thinkv_tbe_plan(cache, layer, seq_ids, seg_start, seg_type, n_segs, transition_ended, budget, max_cuts, tok_seq, tok_handle,
+                    seg_offset, seg_keep, counts, stream=None):
+    """seg_start [max_seqs, max_segs] int32, seg_type [max_seqs, max_segs] uint8, n_segs [max_seqs] int32, seq_ids [B] int32,
+    transition_ended [B] uint8 or None; outputs tok_seq / tok_handle [cap_tok], seg_offset [cap_seg + 1], seg_keep [cap_seg],
+    counts [2], all int32 device tensors."""
+    B, max_segs = int(seq_ids.numel()), int(seg_start.shape[1])
+    cap_tok, cap_seg = int(tok_handle.numel()), int(seg_keep.numel())
+    assert seg_start.dtype == torch.int32 and seg_type.dtype == torch.uint8 and n_segs.dtype == torch.int32
+    assert seg_start.is_contiguous() and seg_type.is_contiguous() and tuple(seg_type.shape) == tuple(seg_start.shape)
+    assert tok_seq.numel() == cap_tok and seg_offset.numel() == cap_seg + 1 and counts.numel() == 2
+    for t in (seq_ids, tok_seq, tok_handle, seg_offset, seg_keep, counts):
+        assert t.dtype == torch.int32 and t.is_contiguous()
+    assert transition_ended is None or (transition_ended.dtype == torch.uint8 and transition_ended.numel() == B)
+    nb = load().thinkv_tbe_plan_workspace_bytes(B, int(max_cuts))
+    ws = cache.workspace(nb)
+    _check(load().thinkv_tbe_plan(C.byref(cache.view), layer, _ptr(seq_ids), _ptr(seg_start), _ptr(seg_type), _ptr(n_segs),
+                                  _ptr(transition_ended), B, max_segs, int(budget), int(max_cuts), cap_seg, cap_tok, _ptr(tok_seq),
+                                  _ptr(tok_handle), _ptr(seg_offset), _ptr(seg_keep), _ptr(counts), _ptr(ws), ws.numel(),
+                                  _stream(stream)), "thinkv_tbe_plan")
 
 
 def thinkv_tbe_select(cache, layer, tok_seq, tok_handle, seg_offset, seg_keep, ev_handle, max_iters=8, stream=None):

@@ -304,4 +304,271 @@ int launch_tbe_select(const thinkv_view& v, int layer, const int32_t* tok_seq, c
   return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
 }
 
+// ---------------------------------------------------------------------------------------------
+// The plan: which segments of which sequences are cut, and to how many tokens (Sec. 4.3: Case 1,
+// every preceding segment goes down one retention level when a transition segment has ended;
+// Case 2, while the sequence holds more live tokens than the budget, the oldest segment of the
+// least important type that can still shrink goes down one level).  A segment is cut at most
+// once per call (one K-means per segment and call); its level follows from its live size: it is
+// cut to the largest retention value below that size.  The open (last) segment is never touched.
+// A live token belongs to the segment whose start is the largest one not above its position
+// (the block table's start-index column, Sec. 5.2).
+//
+// Three kernels.  count (one workgroup per examined sequence): live tokens per segment (every
+// thread takes pages of the sequence's three lists; binary search of each live slot's position
+// in the segment starts, held in LDS), then one thread walks the plan and leaves the sequence's
+// cuts in a staging area.  offsets (one workgroup): exclusive sums over the sequences give every
+// cut its place in the dense output lists; cuts that no longer fit the caller's buffers are
+// dropped from the end.  fill (one workgroup per sequence): the live tokens of the cut segments
+// are dealt to their lists and each list is put in ascending position by a rank sort in LDS, so
+// the output does not depend on the order in which threads got there.
+constexpr int kMaxSegs = THINKV_TBE_MAX_SEGS;
+constexpr int kRetention[5] = {64, 32, 16, 8, 4};
+
+struct PlanArgs {
+  const int32_t* seq_ids;
+  const int32_t* seg_start;
+  const uint8_t* seg_type;
+  const int32_t* n_segs;
+  const uint8_t* transition_ended;
+  int32_t* tok_seq;
+  int32_t* tok_handle;
+  int32_t* seg_offset;
+  int32_t* seg_keep;
+  int32_t* counts;
+  // staging: per examined sequence max_cuts entries of (segment, keep, live tokens), the number of cuts,
+  // and the sequence's first cut / first token in the dense lists
+  int32_t* st_seg;
+  int32_t* st_keep;
+  int32_t* st_cnt;
+  int32_t* st_ncuts;
+  int32_t* st_seg_base;
+  int32_t* st_tok_base;
+  int layer, B, max_segs, budget, max_cuts, cap_seg, cap_tok;
+};
+
+size_t tbe_plan_ws_bytes(int B, int max_cuts) {
+  return ((size_t)(B > 0 ? B : 1) * (3 * (size_t)max_cuts + 3)) * sizeof(int32_t) + 256;
+}
+
+__device__ inline int next_level(int size) {
+#pragma unroll
+  for (int i = 0; i < 5; ++i)
+    if (kRetention[i] < size) return kRetention[i];
+  return 0;
+}
+
+// segment of position pos: index of the last start <= pos, -1 if there is none
+__device__ inline int segment_of(const int* starts, int n, int pos) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (starts[mid] <= pos) lo = mid + 1; else hi = mid;
+  }
+  return lo - 1;
+}
+
+// calls f(segment, position, handle) for every live token of the sequence; every thread takes pages
+template <typename F>
+__device__ inline void for_live_tokens(const thinkv_view& v, int seq, int layer, const int* s_start, int ns, F f) {
+  const thinkv_config& c = v.cfg;
+  for (int k = 0; k < 3; ++k) {
+    const int np = v.n_pages[npages_index(c, seq, layer, k)];
+    const int64_t tb = table_base(c, seq, layer, k);
+    for (int pi = threadIdx.x; pi < np; pi += blockDim.x) {
+      uint32_t m = v.slot_mask[tb + pi] & 0xFFFFu;
+      if (!m) continue;
+      const int pid = v.block_table[tb + pi];
+      const int32_t* sp = v.slot_pos[k] + (int64_t)pid * kPage;
+      while (m) {
+        const int slot = __ffs(m) - 1;
+        m &= m - 1;
+        const int pos = sp[slot];
+        const int sg = segment_of(s_start, ns, pos);
+        if (sg >= 0) f(sg, pos, THINKV_HANDLE(k, pi, slot));
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void tbe_count_plan_kernel(thinkv_view v, PlanArgs a) {
+  const thinkv_config& c = v.cfg;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  __shared__ int s_start[kMaxSegs];
+  __shared__ int s_cnt[kMaxSegs];
+  const int seq = a.seq_ids[b];
+  if (seq < 0 || seq >= c.max_seqs) {
+    if (tid == 0) {
+      atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEQ);
+      a.st_ncuts[b] = 0;
+    }
+    return;
+  }
+  int ns = a.n_segs[seq];
+  ns = ns < 0 ? 0 : (ns > a.max_segs ? a.max_segs : ns);
+  const int32_t* starts = a.seg_start + (int64_t)seq * a.max_segs;
+  const uint8_t* types = a.seg_type + (int64_t)seq * a.max_segs;
+  for (int i = tid; i < ns; i += 256) {
+    s_start[i] = starts[i];
+    s_cnt[i] = 0;
+  }
+  __syncthreads();
+  for_live_tokens(v, seq, a.layer, s_start, ns, [&](int sg, int, int) { atomicAdd(&s_cnt[sg], 1); });
+  __syncthreads();
+  if (tid != 0) return;
+  int total = v.n_live[sl_index(c, seq, a.layer)];
+  int n_cuts = 0;
+  bool oversize = false;
+  int32_t* o_seg = a.st_seg + (int64_t)b * a.max_cuts;
+  int32_t* o_keep = a.st_keep + (int64_t)b * a.max_cuts;
+  int32_t* o_cnt = a.st_cnt + (int64_t)b * a.max_cuts;
+  auto cut = [&](int i, int r) {
+    o_seg[n_cuts] = i;
+    o_keep[n_cuts] = r;
+    o_cnt[n_cuts] = s_cnt[i];
+    ++n_cuts;
+    total -= s_cnt[i] - r;
+    s_cnt[i] = -r;          // negative: cut in this call, now holding r tokens
+  };
+  const int last = ns - 1;
+  if (a.transition_ended && a.transition_ended[b]) {
+    for (int i = 0; i < last && n_cuts < a.max_cuts; ++i) {
+      const int r = next_level(s_cnt[i]);
+      if (!r) continue;
+      if (s_cnt[i] > kTbeMaxTokens) {
+        oversize = true;
+        continue;
+      }
+      cut(i, r);
+    }
+  }
+  while (total > a.budget && n_cuts < a.max_cuts) {
+    int pick = -1;
+    for (int t = 0; t < 3 && pick < 0; ++t)
+      for (int i = 0; i < last; ++i) {
+        if (types[i] != t || s_cnt[i] < 0) continue;
+        if (!next_level(s_cnt[i])) continue;
+        if (s_cnt[i] > kTbeMaxTokens) {
+          oversize = true;
+          continue;
+        }
+        pick = i;
+        break;
+      }
+    if (pick < 0) break;
+    cut(pick, next_level(s_cnt[pick]));
+  }
+  a.st_ncuts[b] = n_cuts;
+  if (oversize) atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEGMENT);
+}
+
+__global__ __launch_bounds__(256) void tbe_offsets_kernel(PlanArgs a) {
+  // one thread: B is the number of sequences of a decode batch
+  if (threadIdx.x != 0) return;
+  int n_seg = 0, n_tok = 0;
+  for (int b = 0; b < a.B; ++b) {
+    a.st_seg_base[b] = n_seg;
+    a.st_tok_base[b] = n_tok;
+    int kept = 0;
+    for (int i = 0; i < a.st_ncuts[b]; ++i) {
+      const int cnt = a.st_cnt[(int64_t)b * a.max_cuts + i];
+      if (n_seg >= a.cap_seg || n_tok + cnt > a.cap_tok) break;   // the caller's buffers are full: the rest waits for the next call
+      a.seg_offset[n_seg] = n_tok;
+      a.seg_keep[n_seg] = a.st_keep[(int64_t)b * a.max_cuts + i];
+      ++n_seg;
+      n_tok += cnt;
+      ++kept;
+    }
+    a.st_ncuts[b] = kept;
+  }
+  a.seg_offset[n_seg] = n_tok;
+  a.counts[0] = n_seg;
+  a.counts[1] = n_tok;
+}
+
+__global__ __launch_bounds__(256) void tbe_fill_kernel(thinkv_view v, PlanArgs a) {
+  const thinkv_config& c = v.cfg;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int n_cuts = a.st_ncuts[b];
+  if (n_cuts == 0) return;
+  __shared__ int s_start[kMaxSegs];
+  __shared__ int s_cut[kMaxSegs];                 // cut number of a segment, -1 = not cut
+  __shared__ int s_fill[kTbeMaxTokens];           // tokens dealt to a cut so far (cuts per sequence <= capacity checked on the host)
+  __shared__ int s_pos[kTbeMaxTokens], s_h[kTbeMaxTokens];
+  const int seq = a.seq_ids[b];
+  int ns = a.n_segs[seq];
+  ns = ns < 0 ? 0 : (ns > a.max_segs ? a.max_segs : ns);
+  const int32_t* starts = a.seg_start + (int64_t)seq * a.max_segs;
+  for (int i = tid; i < ns; i += 256) {
+    s_start[i] = starts[i];
+    s_cut[i] = -1;
+  }
+  for (int i = tid; i < n_cuts; i += 256) s_fill[i] = 0;
+  __syncthreads();
+  for (int i = tid; i < n_cuts; i += 256) s_cut[a.st_seg[(int64_t)b * a.max_cuts + i]] = i;
+  __syncthreads();
+  const int seg_base = a.st_seg_base[b];
+  // deal the tokens: position into tok_seq for now, handle into tok_handle
+  for_live_tokens(v, seq, a.layer, s_start, ns, [&](int sg, int pos, int h) {
+    const int cu = s_cut[sg];
+    if (cu < 0) return;
+    const int at = a.seg_offset[seg_base + cu] + atomicAdd(&s_fill[cu], 1);
+    a.tok_seq[at] = pos;
+    a.tok_handle[at] = h;
+  });
+  __syncthreads();
+  // ascending position inside every list
+  for (int cu = 0; cu < n_cuts; ++cu) {
+    const int lo = a.seg_offset[seg_base + cu], n = a.seg_offset[seg_base + cu + 1] - lo;
+    if (tid < n) {
+      s_pos[tid] = a.tok_seq[lo + tid];
+      s_h[tid] = a.tok_handle[lo + tid];
+    }
+    __syncthreads();
+    if (tid < n) {
+      int rank = 0;
+      const int mine = s_pos[tid];
+      for (int i = 0; i < n; ++i) rank += s_pos[i] < mine || (s_pos[i] == mine && i < tid);
+      a.tok_handle[lo + rank] = s_h[tid];
+      a.tok_seq[lo + rank] = seq;
+    }
+    __syncthreads();
+  }
+}
+
+int launch_tbe_plan(const thinkv_view& v, int layer, const int32_t* seq_ids, const int32_t* seg_start, const uint8_t* seg_type,
+                    const int32_t* n_segs, const uint8_t* transition_ended, int B, int max_segs, int budget, int max_cuts,
+                    int cap_seg, int cap_tok, int32_t* tok_seq, int32_t* tok_handle, int32_t* seg_offset, int32_t* seg_keep,
+                    int32_t* counts, void* workspace, hipStream_t st) {
+  PlanArgs a;
+  a.seq_ids = seq_ids;
+  a.seg_start = seg_start;
+  a.seg_type = seg_type;
+  a.n_segs = n_segs;
+  a.transition_ended = transition_ended;
+  a.tok_seq = tok_seq;
+  a.tok_handle = tok_handle;
+  a.seg_offset = seg_offset;
+  a.seg_keep = seg_keep;
+  a.counts = counts;
+  int32_t* w = (int32_t*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
+  a.st_seg = w;
+  a.st_keep = w + (size_t)B * max_cuts;
+  a.st_cnt = w + 2 * (size_t)B * max_cuts;
+  a.st_ncuts = w + 3 * (size_t)B * max_cuts;
+  a.st_seg_base = a.st_ncuts + B;
+  a.st_tok_base = a.st_seg_base + B;
+  a.layer = layer;
+  a.B = B;
+  a.max_segs = max_segs;
+  a.budget = budget;
+  a.max_cuts = max_cuts;
+  a.cap_seg = cap_seg;
+  a.cap_tok = cap_tok;
+  hipLaunchKernelGGL(tbe_count_plan_kernel, dim3(B), dim3(256), 0, st, v, a);
+  hipLaunchKernelGGL(tbe_offsets_kernel, dim3(1), dim3(64), 0, st, a);
+  hipLaunchKernelGGL(tbe_fill_kernel, dim3(B), dim3(256), 0, st, v, a);
+  return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
+}
+
 }  // namespace thinkv

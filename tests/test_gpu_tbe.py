@@ -236,3 +236,152 @@ def test_tbe_driven_budgeted_decode():
     out, lse = parity.gpu_attention(gc, wl, None, 0)
     assert np.abs(out - ref).max() <= parity.TOL
     _say({"cuts": n_cuts, "clear": n_clear, "equal_to_oracle": n_same, "live": live_now.tolist()})
+
+
+# ------------------------------------------------------------------------------ the plan on the device
+def _tables(classes_segs, max_seqs, max_segs, upto):
+    """segment starts / types / counts of every sequence from the generator's segment ids, tokens [0, upto[s])"""
+    st = np.zeros((max_seqs, max_segs), np.int32)
+    ty = np.zeros((max_seqs, max_segs), np.uint8)
+    ns = np.zeros(max_seqs, np.int32)
+    for s, (cls, seg) in enumerate(classes_segs):
+        seg = seg[:upto[s]]
+        first = np.r_[0, np.flatnonzero(np.diff(seg)) + 1]
+        ns[s] = len(first)
+        st[s, :len(first)] = first
+        ty[s, :len(first)] = cls[first]
+    return st, ty, ns
+
+
+def _device_plan(gc, layer, seq_ids, st, ty, ns, trans, budget, max_cuts, cap_seg, cap_tok):
+    from paper_2510_01290_amd import binding as B
+    d = gc.device
+    out = dict(tok_seq=torch.full((cap_tok,), -7, dtype=torch.int32, device=d), tok_handle=torch.full((cap_tok,), -7, dtype=torch.int32, device=d),
+               seg_offset=torch.full((cap_seg + 1,), -7, dtype=torch.int32, device=d), seg_keep=torch.full((cap_seg,), -7, dtype=torch.int32, device=d),
+               counts=torch.full((2,), -7, dtype=torch.int32, device=d))
+    B.thinkv_tbe_plan(gc, layer, torch.tensor(seq_ids, dtype=torch.int32, device=d), torch.from_numpy(st).to(d), torch.from_numpy(ty).to(d),
+                      torch.from_numpy(ns).to(d), None if trans is None else torch.tensor(trans, dtype=torch.uint8, device=d), budget, max_cuts,
+                      out["tok_seq"], out["tok_handle"], out["seg_offset"], out["seg_keep"], out["counts"])
+    torch.cuda.synchronize()
+    return {k: v.cpu().numpy() for k, v in out.items()}
+
+
+def _oracle_plan(oc, layer, seq_ids, st, ty, ns, trans, budget, max_cuts, cap_seg, cap_tok):
+    """the per-sequence plans put together the way the library does: sequence after sequence, cuts that do not fit are left out"""
+    tok_seq, tok_handle, off, keep = [], [], [0], []
+    for b, s in enumerate(seq_ids):
+        plan = otbe.plan_evictions(oc, layer, s, st[s, :ns[s]], ty[s, :ns[s]], bool(trans[b]) if trans is not None else False, budget, max_cuts)
+        for sg, r, hs in plan:
+            if len(hs) > 256:
+                continue
+            if len(keep) >= cap_seg or len(tok_handle) + len(hs) > cap_tok:
+                break
+            tok_seq += [s] * len(hs)
+            tok_handle += hs
+            off.append(len(tok_handle))
+            keep.append(r)
+    return np.array(tok_seq, np.int32), np.array(tok_handle, np.int32), np.array(off, np.int32), np.array(keep, np.int32)
+
+
+def test_tbe_plan_on_device_matches_the_oracle():
+    _say("the eviction plan computed on the device: Case 1, Case 2, both, capacity limits")
+    from paper_2510_01290_amd import binding as B
+    geom = synth.Geometry(1, 8, 2, 64, "f16", (8, 2, 4))
+    S, n_tok = 4, [1500, 300, 900, 40]
+    rng = np.random.default_rng(41)
+    cs = [synth.thought_classes(rng, n) for n in n_tok]
+    wl = synth.Workload("tbe-plan", geom, 41, S, [c for c, _ in cs], [], (0,), np.array(n_tok, np.int32) - 1)
+    gc = parity.make_gpu_cache(wl, arena_pages=(200, 200, 200), max_pages=120)
+    ob = parity.make_oracle(wl, arena_pages=(200, 200, 200), max_pages=120)
+    gb = parity.GpuBackend(gc)
+    handles = []
+    for s in range(S):
+        k = synth.kv_rows(wl.seed, 0, s, 0, 0, n_tok[s], geom, torch.device("cpu"))
+        h = gb.append(0, k.to(gc.device), k.to(gc.device), np.full(n_tok[s], s), np.arange(n_tok[s]), cs[s][0])
+        assert np.array_equal(h, ob.append(0, k, k, np.full(n_tok[s], s), np.arange(n_tok[s]), cs[s][0]))
+        handles.append(h)
+    # some tokens are gone already (sizes no longer round), and the freed slots of sequence 0 were reused by later positions
+    ev = rng.choice(1500, size=200, replace=False)
+    gb.evict(0, np.zeros(200, np.int64), handles[0][ev])
+    ob.evict(0, np.zeros(200, np.int64), handles[0][ev])
+    st, ty, ns = _tables(cs, S, 64, n_tok)
+    for name, seq_ids, trans, budget, max_cuts, cap_seg, cap_tok in [
+            ("case 1 everywhere", [0, 1, 2, 3], [1, 1, 1, 1], 10 ** 6, 32, 128, 8192),
+            ("case 2 only", [2, 0, 1], None, 250, 32, 128, 8192),
+            ("both, few cuts per sequence", [3, 1, 0, 2], [0, 1, 0, 1], 200, 3, 128, 8192),
+            ("output lists too short", [0, 1, 2], [1, 1, 1], 10 ** 6, 32, 5, 700)]:
+        got = _device_plan(gc, 0, seq_ids, st, ty, ns, trans, budget, max_cuts, cap_seg, cap_tok)
+        w_seq, w_h, w_off, w_keep = _oracle_plan(ob.cache, 0, seq_ids, st, ty, ns, trans, budget, max_cuts, cap_seg, cap_tok)
+        n_seg, n_t = int(got["counts"][0]), int(got["counts"][1])
+        assert (n_seg, n_t) == (len(w_keep), len(w_h)), (name, n_seg, n_t, len(w_keep), len(w_h))
+        assert np.array_equal(got["seg_keep"][:n_seg], w_keep) and np.array_equal(got["seg_offset"][:n_seg + 1], w_off), name
+        assert np.array_equal(got["tok_handle"][:n_t], w_h) and np.array_equal(got["tok_seq"][:n_t], w_seq), name
+        assert n_seg > 0
+        _say((name, "cuts", n_seg, "tokens", n_t))
+    assert int(gc.dev_status.abs().sum().item()) == 0
+    # a sequence id that does not exist, and a segment too large for the survivor choice
+    st2, ty2, ns2 = st.copy(), ty.copy(), ns.copy()
+    st2[2, :2] = [0, 880]
+    ns2[2] = 2                                              # sequence 2: one segment of 880 tokens, then the open one
+    got = _device_plan(gc, 0, [2, 9], st2, ty2, ns2, [1, 1], 10 ** 6, 8, 16, 4096)
+    assert got["counts"].tolist() == [0, 0]
+    flags = gc.dev_status.cpu().numpy()[-1]
+    assert flags & B.ST_BAD_SEGMENT and flags & B.ST_BAD_SEQ
+
+
+def test_tbe_whole_loop_on_the_device():
+    """decode under a budget with plan, survivor choice and eviction all from device-side lists; the host only keeps the
+    segment table up to date (the thought type of each step is its input) and reads the two counts"""
+    _say("budgeted decode: plan -> K-means -> evict, all on the device, against the oracle's loop")
+    from paper_2510_01290_amd import binding as B
+    geom = synth.Geometry(1, 8, 2, 64, "bf16", (8, 2, 4))
+    S, steps, per_call, budget = 3, 1200, 8, 350
+    rng = np.random.default_rng(43)
+    cs = [synth.thought_classes(rng, steps) for _ in range(S)]
+    wl = synth.Workload("tbe-loop", geom, 43, S, [c for c, _ in cs], [], (0,), np.full(S, steps - 1, np.int32))
+    pages = steps // 16 + 8
+    gc = parity.make_gpu_cache(wl, arena_pages=(S * pages,) * 3, max_pages=pages)
+    ob = parity.make_oracle(wl, arena_pages=(S * pages,) * 3, max_pages=pages)
+    gb = parity.GpuBackend(gc)
+    dev = gc.device
+    cap_seg, cap_tok = 64, 64 * 200
+    n_calls = n_cuts = n_same = 0
+    for t0 in range(0, steps, per_call):
+        n = min(per_call, steps - t0)
+        seqs = np.repeat(np.arange(S), n)
+        pos = np.tile(np.arange(t0, t0 + n), S)
+        cls = np.concatenate([cs[s][0][t0:t0 + n] for s in range(S)]).astype(np.uint8)
+        k = torch.cat([synth.kv_rows(wl.seed, 0, s, 0, t0, t0 + n, geom, torch.device("cpu")) for s in range(S)])
+        assert np.array_equal(gb.append(0, k.to(dev), k.to(dev), seqs, pos, cls), ob.append(0, k, k, seqs, pos, cls))
+        st, ty, ns = _tables(cs, S, 32, [t0 + n] * S)
+        # a transition segment ended inside this call?
+        trans = []
+        for s in range(S):
+            seg = cs[s][1]
+            ended = [seg[p - 1] for p in range(max(t0, 1), t0 + n) if seg[p] != seg[p - 1]]
+            trans.append(int(any(cs[s][0][np.flatnonzero(seg == e)[0]] == synth.T for e in ended)))
+        got = _device_plan(gc, 0, list(range(S)), st, ty, ns, trans, budget, 8, cap_seg, cap_tok)
+        w_seq, w_h, w_off, w_keep = _oracle_plan(ob.cache, 0, list(range(S)), st, ty, ns, trans, budget, 8, cap_seg, cap_tok)
+        n_seg, n_t = int(got["counts"][0]), int(got["counts"][1])
+        assert n_seg == len(w_keep) and np.array_equal(got["tok_handle"][:n_t], w_h) and np.array_equal(got["seg_keep"][:n_seg], w_keep)
+        if n_seg == 0:
+            continue
+        ev = _gpu_select(gc, 0, got["tok_seq"][:n_t].copy(), got["tok_handle"][:n_t].copy(), got["seg_offset"][:n_seg + 1].copy(),
+                         got["seg_keep"][:n_seg].copy())
+        want, margins = otbe.select_evictions(ob.cache, 0, w_seq, w_h, w_off, w_keep)
+        for sg, (a, b) in enumerate(zip(w_off[:-1], w_off[1:])):
+            eq = np.array_equal(ev[a:b], want[a:b])
+            assert eq or margins[sg] <= MIN_MARGIN
+            n_same += int(eq)
+        n_cuts += n_seg
+        n_calls += 1
+        B.thinkv_evict(gc, 0, torch.from_numpy(w_seq).to(dev), torch.from_numpy(ev).to(dev))
+        ob.cache.evict_slots(0, w_seq, ev)
+    parity.compare_bookkeeping_full(ob.cache, gc)
+    assert int(gc.dev_status.abs().sum().item()) == 0
+    live = gc.n_live[:, 0].cpu().numpy()
+    assert np.all(live <= budget + per_call) and n_cuts > 30
+    ref, _ = parity.oracle_attention(ob.cache, wl, 0, list(range(S)), list(range(S)))
+    out, _ = parity.gpu_attention(gc, wl, None, 0)
+    assert np.abs(out - ref).max() <= parity.TOL
+    _say({"calls_with_cuts": n_calls, "cuts": n_cuts, "equal_to_oracle": n_same, "live": live.tolist()})
