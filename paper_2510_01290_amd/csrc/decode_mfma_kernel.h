@@ -313,26 +313,22 @@ struct ClassRunner {
     }
     if constexpr (STAT) {
       // pooled scores: maximum over the heads of the group, i.e. over the GP lanes of a slice (all
-      // slices hold the same totals); the lanes of column 0 store their four slots of each page
-      float ua[4], ub[4];
+      // slices hold the same totals); the lanes of column 0 store their four slots of each page.
+      // One page after the other, so that only four more values are live at a time.
+      auto pooled = [&](const float* sc, int idx) {
+        float u[4];
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        ua[r4] = head_ok ? sa[r4] * kappa : -INFINITY;
-        ub[r4] = head_ok ? sb[r4] * kappa : -INFINITY;
-        // a quad of lanes, then (eight heads) the quad four lanes on: the row of 16 holds CS
-        // identical slices, so rotating the row by four reaches the other half of the slice
-        ua[r4] = max_dpp<0x4E>(max_dpp<0xB1>(ua[r4]));
-        ub[r4] = max_dpp<0x4E>(max_dpp<0xB1>(ub[r4]));
-        if constexpr (GP == 8) {
-          ua[r4] = max_dpp<0x124>(ua[r4]);
-          ub[r4] = max_dpp<0x124>(ub[r4]);
+        for (int r4 = 0; r4 < 4; ++r4) {
+          u[r4] = head_ok ? sc[r4] * kappa : -INFINITY;
+          // a quad of lanes, then (eight heads) the quad four lanes on: the row of 16 holds CS
+          // identical slices, so rotating the row by four reaches the other half of the slice
+          u[r4] = max_dpp<0x4E>(max_dpp<0xB1>(u[r4]));
+          if constexpr (GP == 8) u[r4] = max_dpp<0x124>(u[r4]);
         }
-      }
-      if (n == 0) {
-        if (id.idx_a < stat_room) *(float4*)(stat + (int64_t)id.idx_a * kPage + 4 * qd) = make_float4(ua[0], ua[1], ua[2], ua[3]);
-        if (id.idx_b >= 0 && id.idx_b < stat_room)
-          *(float4*)(stat + (int64_t)id.idx_b * kPage + 4 * qd) = make_float4(ub[0], ub[1], ub[2], ub[3]);
-      }
+        if (n == 0 && idx >= 0 && idx < stat_room) *(float4*)(stat + (int64_t)idx * kPage + 4 * qd) = make_float4(u[0], u[1], u[2], u[3]);
+      };
+      pooled(sa, id.idx_a);
+      pooled(sb, id.idx_b);
     }
     // ---------------- online softmax over the 8 scores of this lane; the running maximum only
     // moves when some lane of the wave sees a score above it
