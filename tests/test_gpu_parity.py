@@ -203,3 +203,46 @@ def test_window_with_positions_out_of_order():
             assert np.array_equal(np.isfinite(lse), fin)
             assert not fin.any() or np.abs(lse[fin] - ref_lse[fin]).max() <= 1e-3
             assert fin.any() or not got.any()                      # nothing visible: zeros and -inf
+
+
+def test_decode_calls_replay_correctly_from_a_captured_graph():
+    _say("decode attention (plain and with the sparsity statistic) captured in a graph, replayed between eager calls")
+    from paper_2510_01290_amd import binding as B
+    geom = synth.Geometry(1, 8, 2, 128, "bf16", (8, 2, 4))
+    wl = synth.bulk_evict_refill("graph", geom, 13, 3, np.array([900, 40, 2500]), {synth.E: 0.3}, refill_chunk=4)
+    gc = parity.make_gpu_cache(wl)
+    synth.ScriptRunner(wl, parity.GpuBackend(gc)).run()
+    dev = gc.device
+    seqs = list(range(wl.n_seqs))
+    q = torch.stack([synth.query_rows(wl.seed, 0, s, 0, geom, dev) for s in seqs]).contiguous()
+    sid = torch.tensor(seqs, dtype=torch.int32, device=dev)
+    qp = torch.from_numpy(wl.q_pos.astype(np.int32)).to(dev)
+    mcp = int(gc.n_pages[:, 0].sum(-1).max().item())
+    scale = geom.head_dim ** -0.5
+    outs = [torch.empty(q.shape, dtype=torch.float32, device=dev) for _ in range(3)]
+    lses = [torch.empty((len(seqs), geom.n_q_heads), dtype=torch.float32, device=dev) for _ in range(3)]
+    sps = [torch.empty(len(seqs), dtype=torch.float32, device=dev) for _ in range(2)]
+    # eager reference (also sizes the workspace, so nothing is allocated while capturing)
+    B.thinkv_decode_attention_sparsity(gc, 0, q, outs[0], lses[0], sps[0], sid, qp, 0, scale, mcp)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            B.thinkv_decode_attention(gc, 0, q, outs[1], lses[1], sid, qp, 0, scale, mcp)
+            B.thinkv_decode_attention_sparsity(gc, 0, q, outs[2], lses[2], sps[1], sid, qp, 0, scale, mcp)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in outs[1:] + lses[1:] + sps[1:]:
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for o in outs[1:]:
+            assert float((o - outs[0]).abs().max()) <= 1e-4, rep          # the split of the work differs from run to run
+        assert torch.equal(sps[1], sps[0]), rep
+        assert int(gc.work_counters.abs().sum().item()) == 0, "work counters not back at zero"
+        # eager work between the replays
+        B.thinkv_decode_attention(gc, 0, q, outs[0].clone(), None, sid, qp, 0, scale, mcp)
+        torch.cuda.synchronize()
