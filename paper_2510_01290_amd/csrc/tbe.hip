@@ -314,16 +314,19 @@ int launch_tbe_select(const thinkv_view& v, int layer, const int32_t* tok_seq, c
 // A live token belongs to the segment whose start is the largest one not above its position
 // (the block table's start-index column, Sec. 5.2).
 //
-// Three kernels.  count (one workgroup per examined sequence): live tokens per segment (every
-// thread takes pages of the sequence's three lists; binary search of each live slot's position
-// in the segment starts, held in LDS), then one thread walks the plan and leaves the sequence's
-// cuts in a staging area.  offsets (one workgroup): exclusive sums over the sequences give every
-// cut its place in the dense output lists; cuts that no longer fit the caller's buffers are
-// dropped from the end.  fill (one workgroup per sequence): the live tokens of the cut segments
-// are dealt to their lists and each list is put in ascending position by a rank sort in LDS, so
-// the output does not depend on the order in which threads got there.
+// Four kernels.  count (one workgroup per examined sequence): live tokens per segment (every
+// thread takes pages of the sequence's three lists and reads a page's sixteen positions as four
+// vectors; binary search of each live slot's position in the segment starts, held in LDS), then
+// one thread walks the plan and leaves the sequence's cuts in a staging area.  offsets (one
+// workgroup): every sequence's place in the dense output lists; a sequence whose cuts no longer
+// all fit the caller's buffers keeps the leading ones that do (the rest waits for the next call).
+// fill (one workgroup per sequence): list offsets of the sequence's cuts by a prefix sum, then its
+// live tokens are dealt to their lists.  sort (one wave per cut): each list is put in ascending
+// position by a rank sort in LDS, so the output does not depend on the order in which threads
+// got there.
 constexpr int kMaxSegs = THINKV_TBE_MAX_SEGS;
 constexpr int kRetention[5] = {64, 32, 16, 8, 4};
+constexpr int kPlanThreads = 1024;
 
 struct PlanArgs {
   const int32_t* seq_ids;
@@ -336,19 +339,22 @@ struct PlanArgs {
   int32_t* seg_offset;
   int32_t* seg_keep;
   int32_t* counts;
-  // staging: per examined sequence max_cuts entries of (segment, keep, live tokens), the number of cuts,
-  // and the sequence's first cut / first token in the dense lists
+  // staging: per examined sequence max_cuts entries of (segment, keep, live tokens); the number of
+  // cuts and of their tokens; the sequence's first cut / first token in the dense lists; per cut of
+  // the dense lists the sequence it belongs to
   int32_t* st_seg;
   int32_t* st_keep;
   int32_t* st_cnt;
   int32_t* st_ncuts;
+  int32_t* st_total;
   int32_t* st_seg_base;
   int32_t* st_tok_base;
+  int32_t* st_cut_seq;
   int layer, B, max_segs, budget, max_cuts, cap_seg, cap_tok;
 };
 
 size_t tbe_plan_ws_bytes(int B, int max_cuts) {
-  return ((size_t)(B > 0 ? B : 1) * (3 * (size_t)max_cuts + 3)) * sizeof(int32_t) + 256;
+  return ((size_t)(B > 0 ? B : 1) * (4 * (size_t)max_cuts + 4)) * sizeof(int32_t) + 256;
 }
 
 __device__ inline int next_level(int size) {
@@ -376,31 +382,38 @@ __device__ inline void for_live_tokens(const thinkv_view& v, int seq, int layer,
     const int np = v.n_pages[npages_index(c, seq, layer, k)];
     const int64_t tb = table_base(c, seq, layer, k);
     for (int pi = threadIdx.x; pi < np; pi += blockDim.x) {
-      uint32_t m = v.slot_mask[tb + pi] & 0xFFFFu;
+      const uint32_t m = v.slot_mask[tb + pi] & 0xFFFFu;
       if (!m) continue;
       const int pid = v.block_table[tb + pi];
-      const int32_t* sp = v.slot_pos[k] + (int64_t)pid * kPage;
-      while (m) {
-        const int slot = __ffs(m) - 1;
-        m &= m - 1;
-        const int pos = sp[slot];
-        const int sg = segment_of(s_start, ns, pos);
-        if (sg >= 0) f(sg, pos, THINKV_HANDLE(k, pi, slot));
+      const int4* sp = (const int4*)(v.slot_pos[k] + (int64_t)pid * kPage);
+      int pos[kPage];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int4 w = sp[q];
+        pos[4 * q] = w.x; pos[4 * q + 1] = w.y; pos[4 * q + 2] = w.z; pos[4 * q + 3] = w.w;
+      }
+#pragma unroll
+      for (int slot = 0; slot < kPage; ++slot) {
+        if (!(m >> slot & 1)) continue;
+        const int sg = segment_of(s_start, ns, pos[slot]);
+        if (sg >= 0) f(sg, pos[slot], THINKV_HANDLE(k, pi, slot));
       }
     }
   }
 }
 
-__global__ __launch_bounds__(256) void tbe_count_plan_kernel(thinkv_view v, PlanArgs a) {
+__global__ __launch_bounds__(kPlanThreads) void tbe_count_plan_kernel(thinkv_view v, PlanArgs a) {
   const thinkv_config& c = v.cfg;
   const int b = blockIdx.x, tid = threadIdx.x;
   __shared__ int s_start[kMaxSegs];
   __shared__ int s_cnt[kMaxSegs];
+  __shared__ uint8_t s_type[kMaxSegs];
   const int seq = a.seq_ids[b];
   if (seq < 0 || seq >= c.max_seqs) {
     if (tid == 0) {
       atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEQ);
       a.st_ncuts[b] = 0;
+      a.st_total[b] = 0;
     }
     return;
   }
@@ -408,8 +421,9 @@ __global__ __launch_bounds__(256) void tbe_count_plan_kernel(thinkv_view v, Plan
   ns = ns < 0 ? 0 : (ns > a.max_segs ? a.max_segs : ns);
   const int32_t* starts = a.seg_start + (int64_t)seq * a.max_segs;
   const uint8_t* types = a.seg_type + (int64_t)seq * a.max_segs;
-  for (int i = tid; i < ns; i += 256) {
+  for (int i = tid; i < ns; i += kPlanThreads) {
     s_start[i] = starts[i];
+    s_type[i] = types[i];
     s_cnt[i] = 0;
   }
   __syncthreads();
@@ -417,7 +431,7 @@ __global__ __launch_bounds__(256) void tbe_count_plan_kernel(thinkv_view v, Plan
   __syncthreads();
   if (tid != 0) return;
   int total = v.n_live[sl_index(c, seq, a.layer)];
-  int n_cuts = 0;
+  int n_cuts = 0, listed = 0;
   bool oversize = false;
   int32_t* o_seg = a.st_seg + (int64_t)b * a.max_cuts;
   int32_t* o_keep = a.st_keep + (int64_t)b * a.max_cuts;
@@ -427,6 +441,7 @@ __global__ __launch_bounds__(256) void tbe_count_plan_kernel(thinkv_view v, Plan
     o_keep[n_cuts] = r;
     o_cnt[n_cuts] = s_cnt[i];
     ++n_cuts;
+    listed += s_cnt[i];
     total -= s_cnt[i] - r;
     s_cnt[i] = -r;          // negative: cut in this call, now holding r tokens
   };
@@ -442,98 +457,175 @@ __global__ __launch_bounds__(256) void tbe_count_plan_kernel(thinkv_view v, Plan
       cut(i, r);
     }
   }
-  while (total > a.budget && n_cuts < a.max_cuts) {
-    int pick = -1;
-    for (int t = 0; t < 3 && pick < 0; ++t)
-      for (int i = 0; i < last; ++i) {
-        if (types[i] != t || s_cnt[i] < 0) continue;
-        if (!next_level(s_cnt[i])) continue;
-        if (s_cnt[i] > kTbeMaxTokens) {
-          oversize = true;
-          continue;
-        }
-        pick = i;
-        break;
+  // Case 2.  A segment that cannot be cut now cannot be cut later in this call either (one cut per
+  // segment and call), so "the oldest segment of the least important type that can still shrink",
+  // asked again after every cut, is one walk over the types in order of importance and over the
+  // segments of each from the oldest on.
+  for (int t = 0; t < 3; ++t)
+    for (int i = 0; i < last && total > a.budget && n_cuts < a.max_cuts; ++i) {
+      if (s_type[i] != t || s_cnt[i] < 0) continue;
+      const int r = next_level(s_cnt[i]);
+      if (!r) continue;
+      if (s_cnt[i] > kTbeMaxTokens) {
+        oversize = true;
+        continue;
       }
-    if (pick < 0) break;
-    cut(pick, next_level(s_cnt[pick]));
-  }
+      cut(i, r);
+    }
   a.st_ncuts[b] = n_cuts;
+  a.st_total[b] = listed;
   if (oversize) atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEGMENT);
 }
 
-__global__ __launch_bounds__(256) void tbe_offsets_kernel(PlanArgs a) {
-  // one thread: B is the number of sequences of a decode batch
-  if (threadIdx.x != 0) return;
-  int n_seg = 0, n_tok = 0;
-  for (int b = 0; b < a.B; ++b) {
-    a.st_seg_base[b] = n_seg;
-    a.st_tok_base[b] = n_tok;
-    int kept = 0;
-    for (int i = 0; i < a.st_ncuts[b]; ++i) {
-      const int cnt = a.st_cnt[(int64_t)b * a.max_cuts + i];
-      if (n_seg >= a.cap_seg || n_tok + cnt > a.cap_tok) break;   // the caller's buffers are full: the rest waits for the next call
-      a.seg_offset[n_seg] = n_tok;
-      a.seg_keep[n_seg] = a.st_keep[(int64_t)b * a.max_cuts + i];
-      ++n_seg;
-      n_tok += cnt;
-      ++kept;
-    }
-    a.st_ncuts[b] = kept;
+// exclusive prefix sum over one value per lane of wave 0 times four (values [4 * lane, 4 * lane + 4) of a
+// list of at most 256); returns the four exclusive sums through ex[] and the total
+__device__ inline int wave_scan4(const int* val, int* ex) {
+  const int lane = threadIdx.x & 63;
+  int inc = val[0] + val[1] + val[2] + val[3];
+  const int mine = inc;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int o = __shfl_up(inc, d, 64);
+    if (lane >= d) inc += o;
   }
-  a.seg_offset[n_seg] = n_tok;
-  a.counts[0] = n_seg;
-  a.counts[1] = n_tok;
+  const int total = __shfl(inc, 63, 64);
+  int run = inc - mine;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    ex[q] = run;
+    run += val[q];
+  }
+  return total;
 }
 
-__global__ __launch_bounds__(256) void tbe_fill_kernel(thinkv_view v, PlanArgs a) {
-  const thinkv_config& c = v.cfg;
+__global__ __launch_bounds__(64) void tbe_offsets_kernel(PlanArgs a) {
+  // one wave: sequences in order (their number is that of a decode batch); a sequence whose cuts all
+  // fit is placed from its two totals, only one that does not is looked at cut by cut
+  const int lane = threadIdx.x;
+  int n_seg = 0, n_tok = 0;
+  for (int b = 0; b < a.B; ++b) {
+    const int nc = a.st_ncuts[b], tot = a.st_total[b];
+    int kept = nc, kept_tok = tot;
+    if (n_seg + nc > a.cap_seg || (int64_t)n_tok + tot > a.cap_tok) {
+      // leading cuts that still fit (the lists only grow, so the first that does not fit ends them)
+      int val[4], ex[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) val[q] = 4 * lane + q < nc ? a.st_cnt[(int64_t)b * a.max_cuts + 4 * lane + q] : 0;
+      wave_scan4(val, ex);
+      int fits = 0, fits_tok = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int i = 4 * lane + q;
+        if (i < nc && n_seg + i < a.cap_seg && (int64_t)n_tok + ex[q] + val[q] <= a.cap_tok) {
+          ++fits;
+          fits_tok += val[q];
+        }
+      }
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) {
+        fits += __shfl_xor(fits, d, 64);
+        fits_tok += __shfl_xor(fits_tok, d, 64);
+      }
+      kept = fits;
+      kept_tok = fits_tok;
+    }
+    if (lane == 0) {
+      a.st_seg_base[b] = n_seg;
+      a.st_tok_base[b] = n_tok;
+      a.st_ncuts[b] = kept;
+    }
+    n_seg += kept;
+    n_tok += kept_tok;
+  }
+  if (lane == 0) {
+    a.seg_offset[n_seg] = n_tok;
+    a.counts[0] = n_seg;
+    a.counts[1] = n_tok;
+  }
+}
+
+__global__ __launch_bounds__(kPlanThreads) void tbe_fill_kernel(thinkv_view v, PlanArgs a) {
   const int b = blockIdx.x, tid = threadIdx.x;
   const int n_cuts = a.st_ncuts[b];
   if (n_cuts == 0) return;
   __shared__ int s_start[kMaxSegs];
   __shared__ int s_cut[kMaxSegs];                 // cut number of a segment, -1 = not cut
-  __shared__ int s_fill[kTbeMaxTokens];           // tokens dealt to a cut so far (cuts per sequence <= capacity checked on the host)
-  __shared__ int s_pos[kTbeMaxTokens], s_h[kTbeMaxTokens];
+  __shared__ int s_fill[kTbeMaxTokens];           // tokens dealt to a cut so far (cuts per sequence <= 256, checked on the host)
+  __shared__ int s_off[kTbeMaxTokens];            // first token of a cut's list
   const int seq = a.seq_ids[b];
   int ns = a.n_segs[seq];
   ns = ns < 0 ? 0 : (ns > a.max_segs ? a.max_segs : ns);
   const int32_t* starts = a.seg_start + (int64_t)seq * a.max_segs;
-  for (int i = tid; i < ns; i += 256) {
+  for (int i = tid; i < ns; i += kPlanThreads) {
     s_start[i] = starts[i];
     s_cut[i] = -1;
   }
-  for (int i = tid; i < n_cuts; i += 256) s_fill[i] = 0;
+  const int seg_base = a.st_seg_base[b], tok_base = a.st_tok_base[b];
+  if (tid < 64) {
+    int val[4], ex[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) val[q] = 4 * tid + q < n_cuts ? a.st_cnt[(int64_t)b * a.max_cuts + 4 * tid + q] : 0;
+    wave_scan4(val, ex);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int i = 4 * tid + q;
+      if (i < n_cuts) {
+        s_off[i] = tok_base + ex[q];
+        s_fill[i] = 0;
+        a.seg_offset[seg_base + i] = tok_base + ex[q];
+        a.seg_keep[seg_base + i] = a.st_keep[(int64_t)b * a.max_cuts + i];
+        a.st_cut_seq[seg_base + i] = seq;
+      }
+    }
+  }
   __syncthreads();
-  for (int i = tid; i < n_cuts; i += 256) s_cut[a.st_seg[(int64_t)b * a.max_cuts + i]] = i;
+  for (int i = tid; i < n_cuts; i += kPlanThreads) s_cut[a.st_seg[(int64_t)b * a.max_cuts + i]] = i;
   __syncthreads();
-  const int seg_base = a.st_seg_base[b];
   // deal the tokens: position into tok_seq for now, handle into tok_handle
   for_live_tokens(v, seq, a.layer, s_start, ns, [&](int sg, int pos, int h) {
     const int cu = s_cut[sg];
     if (cu < 0) return;
-    const int at = a.seg_offset[seg_base + cu] + atomicAdd(&s_fill[cu], 1);
+    const int at = s_off[cu] + atomicAdd(&s_fill[cu], 1);
     a.tok_seq[at] = pos;
     a.tok_handle[at] = h;
   });
-  __syncthreads();
-  // ascending position inside every list
-  for (int cu = 0; cu < n_cuts; ++cu) {
-    const int lo = a.seg_offset[seg_base + cu], n = a.seg_offset[seg_base + cu + 1] - lo;
-    if (tid < n) {
-      s_pos[tid] = a.tok_seq[lo + tid];
-      s_h[tid] = a.tok_handle[lo + tid];
-    }
-    __syncthreads();
-    if (tid < n) {
-      int rank = 0;
-      const int mine = s_pos[tid];
-      for (int i = 0; i < n; ++i) rank += s_pos[i] < mine || (s_pos[i] == mine && i < tid);
-      a.tok_handle[lo + rank] = s_h[tid];
-      a.tok_seq[lo + rank] = seq;
-    }
-    __syncthreads();
+}
+
+// one wave per cut of the dense lists: ascending position inside the list
+__global__ __launch_bounds__(256) void tbe_sort_kernel(PlanArgs a) {
+  __shared__ int s_pos[4][kTbeMaxTokens];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int cu = blockIdx.x * 4 + wave;
+  const bool live = cu < a.counts[0];
+  int lo = 0, n = 0, pos[kPT], h[kPT];
+  if (live) {
+    lo = a.seg_offset[cu];
+    n = a.seg_offset[cu + 1] - lo;   // at most kTbeMaxTokens: larger segments are never cut
+#pragma unroll
+    for (int q = 0; q < kPT; ++q)
+      if (lane + 64 * q < n) {
+        pos[q] = a.tok_seq[lo + lane + 64 * q];
+        h[q] = a.tok_handle[lo + lane + 64 * q];
+        s_pos[wave][lane + 64 * q] = pos[q];
+      }
   }
+  __syncthreads();
+  if (!live) return;
+  const int seq = a.st_cut_seq[cu];
+  int rank[kPT];
+#pragma unroll
+  for (int q = 0; q < kPT; ++q) rank[q] = 0;
+  for (int i = 0; i < n; ++i) {
+    const int other = s_pos[wave][i];
+#pragma unroll
+    for (int q = 0; q < kPT; ++q) rank[q] += other < pos[q] || (other == pos[q] && i < lane + 64 * q);
+  }
+#pragma unroll
+  for (int q = 0; q < kPT; ++q)
+    if (lane + 64 * q < n) {
+      a.tok_handle[lo + rank[q]] = h[q];
+      a.tok_seq[lo + rank[q]] = seq;
+    }
 }
 
 int launch_tbe_plan(const thinkv_view& v, int layer, const int32_t* seq_ids, const int32_t* seg_start, const uint8_t* seg_type,
@@ -555,8 +647,10 @@ int launch_tbe_plan(const thinkv_view& v, int layer, const int32_t* seq_ids, con
   a.st_seg = w;
   a.st_keep = w + (size_t)B * max_cuts;
   a.st_cnt = w + 2 * (size_t)B * max_cuts;
-  a.st_ncuts = w + 3 * (size_t)B * max_cuts;
-  a.st_seg_base = a.st_ncuts + B;
+  a.st_cut_seq = w + 3 * (size_t)B * max_cuts;
+  a.st_ncuts = w + 4 * (size_t)B * max_cuts;
+  a.st_total = a.st_ncuts + B;
+  a.st_seg_base = a.st_total + B;
   a.st_tok_base = a.st_seg_base + B;
   a.layer = layer;
   a.B = B;
@@ -565,9 +659,11 @@ int launch_tbe_plan(const thinkv_view& v, int layer, const int32_t* seq_ids, con
   a.max_cuts = max_cuts;
   a.cap_seg = cap_seg;
   a.cap_tok = cap_tok;
-  hipLaunchKernelGGL(tbe_count_plan_kernel, dim3(B), dim3(256), 0, st, v, a);
+  if (B > 0) hipLaunchKernelGGL(tbe_count_plan_kernel, dim3(B), dim3(kPlanThreads), 0, st, v, a);
   hipLaunchKernelGGL(tbe_offsets_kernel, dim3(1), dim3(64), 0, st, a);
-  hipLaunchKernelGGL(tbe_fill_kernel, dim3(B), dim3(256), 0, st, v, a);
+  if (B > 0) hipLaunchKernelGGL(tbe_fill_kernel, dim3(B), dim3(kPlanThreads), 0, st, v, a);
+  const int64_t most = (int64_t)B * max_cuts < cap_seg ? (int64_t)B * max_cuts : cap_seg;
+  if (most > 0) hipLaunchKernelGGL(tbe_sort_kernel, dim3((unsigned)((most + 3) / 4)), dim3(256), 0, st, a);
   return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
 }
 
