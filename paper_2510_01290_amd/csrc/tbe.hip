@@ -15,22 +15,22 @@
 //              two members the earlier one: both are equally near their mean)
 //
 // Two kernels.  gather: one workgroup per token writes its key row [Hkv * D] into the workspace.
-// kmeans: one workgroup of 256 threads per segment (segments hold at most 256 live tokens, the
-// schedule keeps at most 64): lane L of every wave owns points L, L + 64, ..., wave w clusters
-// 16w .. 16w + 15, so all threads are busy whatever the segment's size; the N x K distances are
-// accumulated tile by tile (32 channels of all points and all centroids staged in LDS, up to 64
-// accumulators per thread), the update sums the members of a cluster in index order (fixed summation order, so
-// the result is the same on every run), and the survivor of a cluster is found with a 64-bit
-// LDS minimum over (distance bits, index).  Plain binary32 FMAs on the vector ALU: the event is
-// rare (segments are annealed when a transition thought ends or the budget is exceeded).
+// kmeans: one workgroup of eight waves per segment (segments hold at most 256 live tokens, the
+// schedule keeps at most 64).  Squared distances are taken as |x|^2 - 2 x.c + |c|^2 with the
+// products x.c of all points with all centroids on the matrix cores in binary32 (the error of the
+// expansion is of the order of 1e-6 of |x|^2, far below the gaps that separate genuine decisions);
+// an assignment only needs |c|^2 - 2 x.c.  The channels go through LDS 64 at a time, the centroid
+// update is folded into the next pass over the channels (a cluster's members are summed from the
+// point tile that is in LDS anyway, in index order, so the result is the same on every run), and
+// the survivor of a cluster is found with a 64-bit LDS minimum over (distance bits, index).
 #include "common.h"
 
 namespace thinkv {
 
 constexpr int kTbeMaxTokens = THINKV_TBE_MAX_SEGMENT;   // live tokens of one segment
 constexpr int kTbeMaxKeep = THINKV_TBE_MAX_KEEP;        // largest retention level
-constexpr int kTile = 32;                               // channels per LDS tile
-constexpr int kPad = 36;                                // row stride of a tile in floats (odd multiple of 16 bytes)
+constexpr int kTile = 64;                               // channels per LDS tile
+constexpr int kPad = 68;                                // row stride of a tile in floats (odd multiple of 16 bytes)
 
 struct TbeArgs {
   const int32_t* tok_seq;
@@ -85,52 +85,143 @@ __global__ __launch_bounds__(256) void tbe_gather_kernel(thinkv_view v, TbeArgs 
 }
 
 // ---- kmeans
-constexpr int kPT = kTbeMaxTokens / 64;   // points per thread at most: lane L owns points L, L + 64, ...
-constexpr int kKT = kTbeMaxKeep / 4;      // clusters per thread: wave w owns clusters kKT*w .. kKT*w + kKT-1
+constexpr int kPT = kTbeMaxTokens / 64;   // points per lane at most: lane L looks after points L, L + 64, ...
+constexpr int kRB = kTbeMaxTokens / 16;   // 16-point row blocks of the distance matrix at most
+constexpr int kKmThreads = 512;           // eight waves: two per SIMD, so that one multiplies while the other waits for LDS
+constexpr int kRBW = kRB / 2;             // row blocks per wave: wave w takes blocks 2 t + w / 4
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// Squared distances of this lane's points to this wave's clusters, accumulated over the channels.
-// A wave reads the centroid rows as LDS broadcasts (all its lanes want the same cluster) and every
-// lane its own point rows; pt = ceil(n / 64) points per lane are live.
-__device__ inline void distances(const float* __restrict__ x, const float* __restrict__ cent, int n, int k, int dim, int pt,
-                                 float (*xs)[kPad], float (*cs)[kPad], float (*acc)[kKT]) {
+struct KmScratch {
+  float xs[kTbeMaxTokens][kPad];    // one tile: 64 channels of every point ...
+  float cs[kTbeMaxKeep][kPad];      // ... and of every centroid
+  float xx[kTbeMaxTokens];          // squared norms of the points
+  float cc[kTbeMaxKeep];            // squared norms of the centroids
+  int cnt[kTbeMaxKeep];             // members of every cluster,
+  int start[kTbeMaxKeep];           // where its members begin in order[],
+  int order[kTbeMaxTokens];         // and the points cluster by cluster, in index order inside a cluster
+};
+
+// One pass over the channels, 64 at a time through LDS (the loads of the next tile are in flight
+// while the current one is worked on):
+//   update  the centroid of every cluster that has members moves to their mean (sum from zero in
+//           index order, times 1 / count), tile by tile, from the point tile that is in LDS anyway;
+//           the moved rows go back to cent[] so that a cluster that later loses all its members
+//           still finds its centroid there
+//   dots    dot[p][j] of all points with all centroids on the matrix cores
+//           (v_mfma_f32_16x16x4_f32, binary32 in and out): wave w owns clusters 16 (w % 4) ..
+//           + 15 and every second row block of 16 points (blocks 2 t + w / 4); after the call lane l
+//           holds, in acc[t][i], the product of point 16 (2 t + w / 4) + 4 (l / 16) + i with cluster
+//           16 (w % 4) + l % 16
+//   norms   squared norms of the centroids, and of the points when first is set (they do not move)
+__device__ inline void pass_over_channels(const float* __restrict__ x, float* __restrict__ cent, int n, int k, int dim, bool first,
+                                          bool update, KmScratch& sm, f32x4 (&acc)[kRBW]) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, g = lane >> 4;
+  const int rbs = (n + 15) >> 4;
+  constexpr int kC4 = kTile / 4;                          // float4 per tile row
+  const int xq = (rbs * 16 * kC4 + kKmThreads - 1) / kKmThreads;   // float4 loads per thread for the points' tile
+  constexpr int kXQ = kTbeMaxTokens * kC4 / kKmThreads;
+  constexpr int kCQ = kTbeMaxKeep * kC4 / kKmThreads;
+  const int cb = wave & 3, half = wave >> 2;
 #pragma unroll
-  for (int q = 0; q < kPT; ++q)
+  for (int t = 0; t < kRBW; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float nx = 0.f, nc = 0.f;
+  float4 px[kXQ], pc[kCQ];
+  const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto fetch = [&](int d0) {
 #pragma unroll
-    for (int j = 0; j < kKT; ++j) acc[q][j] = 0.f;
+    for (int q = 0; q < kXQ; ++q)
+      if (q < xq) {
+        const int idx = tid + kKmThreads * q, row = idx / kC4, c4 = idx % kC4;
+        px[q] = row < n ? *(const float4*)&x[(int64_t)row * dim + d0 + 4 * c4] : zero4;
+      }
+#pragma unroll
+    for (int q = 0; q < kCQ; ++q) {
+      const int idx = tid + kKmThreads * q, row = idx / kC4, c4 = idx % kC4;
+      pc[q] = row < k ? *(const float4*)&cent[(int64_t)row * dim + d0 + 4 * c4] : zero4;
+    }
+  };
+  // the update: thread (cluster tid / 8, part tid % 8) owns 8 channels of the cluster's row
+  const int uj = tid >> 3, upart = tid & 7;
+  const int um = update && uj < k ? sm.cnt[uj] : 0, ust = uj < k ? sm.start[uj] : 0;
+  const float uinv = um > 0 ? 1.0f / (float)um : 0.f;
+  fetch(0);
   for (int d0 = 0; d0 < dim; d0 += kTile) {
-    __syncthreads();
-    const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int idx = tid; idx < 64 * pt * (kTile / 4); idx += 256) {
-      const int r = idx / (kTile / 4), c4 = idx % (kTile / 4);
-      *(float4*)&xs[r][4 * c4] = r < n ? *(const float4*)&x[(int64_t)r * dim + d0 + 4 * c4] : zero4;
+    __syncthreads();   // the previous tile has been used
+#pragma unroll
+    for (int q = 0; q < kXQ; ++q)
+      if (q < xq) {
+        const int idx = tid + kKmThreads * q;
+        *(float4*)&sm.xs[idx / kC4][4 * (idx % kC4)] = px[q];
+      }
+#pragma unroll
+    for (int q = 0; q < kCQ; ++q) {
+      const int idx = tid + kKmThreads * q;
+      *(float4*)&sm.cs[idx / kC4][4 * (idx % kC4)] = pc[q];
     }
-    for (int idx = tid; idx < kTbeMaxKeep * (kTile / 4); idx += 256) {
-      const int r = idx / (kTile / 4), c4 = idx % (kTile / 4);
-      *(float4*)&cs[r][4 * c4] = r < k ? *(const float4*)&cent[(int64_t)r * dim + d0 + 4 * c4] : zero4;
-    }
     __syncthreads();
-#pragma unroll 2
-    for (int c4 = 0; c4 < kTile / 4; ++c4) {
-      float4 xv[kPT];
+    if (d0 + kTile < dim) fetch(d0 + kTile);
+    if (update) {
+      if (um > 0) {
+        float4 sum[2];
 #pragma unroll
-      for (int q = 0; q < kPT; ++q)
-        if (q < pt) xv[q] = *(const float4*)&xs[lane + 64 * q][4 * c4];
+        for (int c4 = 0; c4 < 2; ++c4) sum[c4] = zero4;
+        for (int i = 0; i < um; ++i) {
+          const int row = sm.order[ust + i];
 #pragma unroll
-      for (int j = 0; j < kKT; ++j) {
-        const float4 cv = *(const float4*)&cs[kKT * wave + j][4 * c4];
+          for (int c4 = 0; c4 < 2; ++c4) {
+            const float4 t = *(const float4*)&sm.xs[row][8 * upart + 4 * c4];
+            sum[c4].x += t.x; sum[c4].y += t.y; sum[c4].z += t.z; sum[c4].w += t.w;
+          }
+        }
 #pragma unroll
-        for (int q = 0; q < kPT; ++q)
-          if (q < pt) {
-            const float e0 = xv[q].x - cv.x, e1 = xv[q].y - cv.y, e2 = xv[q].z - cv.z, e3 = xv[q].w - cv.w;
-            acc[q][j] = fmaf(e3, e3, fmaf(e2, e2, fmaf(e1, e1, fmaf(e0, e0, acc[q][j]))));
+        for (int c4 = 0; c4 < 2; ++c4) {
+          const float4 m = make_float4(sum[c4].x * uinv, sum[c4].y * uinv, sum[c4].z * uinv, sum[c4].w * uinv);
+          *(float4*)&sm.cs[uj][8 * upart + 4 * c4] = m;
+          *(float4*)&cent[(int64_t)uj * dim + d0 + 8 * upart + 4 * c4] = m;
+        }
+      }
+      __syncthreads();
+    }
+    if (first && tid < n) {
+#pragma unroll
+      for (int c4 = 0; c4 < kC4; ++c4) {
+        const float4 t = *(const float4*)&sm.xs[tid][4 * c4];
+        nx = fmaf(t.w, t.w, fmaf(t.z, t.z, fmaf(t.y, t.y, fmaf(t.x, t.x, nx))));
+      }
+    }
+    if (tid < k) {
+#pragma unroll
+      for (int c4 = 0; c4 < kC4; ++c4) {
+        const float4 t = *(const float4*)&sm.cs[tid][4 * c4];
+        nc = fmaf(t.w, t.w, fmaf(t.z, t.z, fmaf(t.y, t.y, fmaf(t.x, t.x, nc))));
+      }
+    }
+    if (16 * cb < k) {
+#pragma unroll
+      for (int kk = 0; kk < kTile / 16; ++kk) {
+        // lane (r, g) holds channels 16 kk + 4 g .. + 3 of its row: component c of every lane forms one
+        // four-channel step, the same channels on both sides
+        const float4 bv = *(const float4*)&sm.cs[16 * cb + r][16 * kk + 4 * g];
+#pragma unroll
+        for (int t = 0; t < kRBW; ++t)
+          if (2 * t + half < rbs) {
+            const float4 av = *(const float4*)&sm.xs[16 * (2 * t + half) + r][16 * kk + 4 * g];
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, bv.x, acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, bv.y, acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.z, bv.z, acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.w, bv.w, acc[t], 0, 0, 0);
           }
       }
     }
   }
+  __syncthreads();
+  if (first && tid < n) sm.xx[tid] = nx;
+  if (tid < kTbeMaxKeep) sm.cc[tid] = tid < k ? nc : 0.f;
+  __syncthreads();
 }
 
-__global__ __launch_bounds__(256) void tbe_kmeans_kernel(thinkv_view v, TbeArgs a) {
+__global__ __launch_bounds__(kKmThreads) void tbe_kmeans_kernel(thinkv_view v, TbeArgs a) {
   const thinkv_config& c = v.cfg;
   const int seg = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lo = a.seg_offset[seg], hi = a.seg_offset[seg + 1];
@@ -139,64 +230,80 @@ __global__ __launch_bounds__(256) void tbe_kmeans_kernel(thinkv_view v, TbeArgs 
   if (n > kTbeMaxTokens || want > kTbeMaxKeep || want < 1 || lo < 0 || hi > a.n_tok) {
     // outside what this kernel covers: nothing is evicted, and the caller is told
     if (tid == 0) atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEGMENT);
-    for (int i = tid; i < n && lo >= 0 && lo + i < a.n_tok; i += 256) a.ev_handle[lo + i] = -1;
+    for (int i = tid; i < n && lo >= 0 && lo + i < a.n_tok; i += kKmThreads) a.ev_handle[lo + i] = -1;
     return;
   }
   if (want >= n) {
-    for (int i = tid; i < n; i += 256) a.ev_handle[lo + i] = -1;
+    for (int i = tid; i < n; i += kKmThreads) a.ev_handle[lo + i] = -1;
     return;
   }
-  const int k = want, dim = a.dim, pt = (n + 63) / 64;
+  const int k = want, dim = a.dim, pt = (n + 63) / 64, rbs = (n + 15) >> 4;
   const float* x = a.x + (int64_t)lo * dim;
   float* cent = a.cent + (int64_t)seg * kTbeMaxKeep * dim;
-  __shared__ __attribute__((aligned(16))) float xs[kTbeMaxTokens][kPad];
-  __shared__ __attribute__((aligned(16))) float cs[kTbeMaxKeep][kPad];
-  __shared__ float s_bd[4][kTbeMaxTokens];   // per wave (cluster quarter): best distance of every point ...
+  __shared__ __attribute__((aligned(16))) KmScratch sm;
+  __shared__ float s_bd[4][kTbeMaxTokens];   // per cluster quarter: best distance of every point ...
   __shared__ int s_bj[4][kTbeMaxTokens];     // ... and the cluster it belongs to
-  __shared__ int s_assign[kTbeMaxTokens], s_order[kTbeMaxTokens];
-  __shared__ int s_cnt[kTbeMaxKeep], s_start[kTbeMaxKeep];
+  __shared__ int s_assign[kTbeMaxTokens];
+  __shared__ int s_cnt[kTbeMaxKeep], s_start[kTbeMaxKeep];   // survivors: members and lowest index of every cluster
   __shared__ unsigned long long s_best[kTbeMaxKeep];
   // initial centroids: evenly spaced points
-  for (int idx = tid; idx < k * dim; idx += 256) {
+  for (int idx = tid; idx < k * dim; idx += kKmThreads) {
     const int j = idx / dim, d = idx % dim;
     cent[idx] = x[(int64_t)((j * n) / k) * dim + d];
   }
-  float acc[kPT][kKT];
+  __syncthreads();
+  f32x4 acc[kRBW];
   int mine[kPT];
 #pragma unroll
   for (int q = 0; q < kPT; ++q) mine[q] = -1;
-  // nearest cluster of this lane's points: best of this wave's quarter, then best of the four quarters
-  // (ties go to the lowest cluster: quarters and clusters are scanned in ascending order)
+  const int r = lane & 15, g = lane >> 4, cb = wave & 3, half = wave >> 2, my_cl = 16 * cb + r;
+  // nearest cluster of every point: |c|^2 - 2 x.c decides (|x|^2 is common to a point's candidates);
+  // best of the sixteen clusters of this wave by exchanges among the sixteen lanes that hold a point's
+  // row, then best of the four cluster quarters (ties go to the lowest cluster)
   auto assign = [&](int* out) {
+    const float ccj = my_cl < k ? sm.cc[my_cl] : 0.f;
 #pragma unroll
-    for (int q = 0; q < kPT; ++q) {
-      float bd = INFINITY;
-      int bj = 0;
+    for (int t = 0; t < kRBW; ++t)
+      if (2 * t + half < rbs) {
+        const int rb = 2 * t + half;
 #pragma unroll
-      for (int j = 0; j < kKT; ++j)
-        if (kKT * wave + j < k && acc[q][j] < bd) {
-          bd = acc[q][j];
-          bj = kKT * wave + j;
+        for (int i = 0; i < 4; ++i) {
+          float bd = my_cl < k ? fmaf(-2.f, acc[t][i], ccj) : INFINITY;
+          int bj = my_cl;
+#pragma unroll
+          for (int d = 1; d < 16; d <<= 1) {
+            const float od = __shfl_xor(bd, d, 64);
+            const int oj = __shfl_xor(bj, d, 64);
+            if (od < bd || (od == bd && oj < bj)) {
+              bd = od;
+              bj = oj;
+            }
+          }
+          if (r == 0) {
+            s_bd[cb][16 * rb + 4 * g + i] = bd;
+            s_bj[cb][16 * rb + 4 * g + i] = bj;
+          }
         }
-      s_bd[wave][lane + 64 * q] = bd;
-      s_bj[wave][lane + 64 * q] = bj;
-    }
+      }
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < kPT; ++q) {
-      float bd = s_bd[0][lane + 64 * q];
-      int bj = s_bj[0][lane + 64 * q];
+      const int p = lane + 64 * q;
+      float bd = s_bd[0][p];
+      int bj = s_bj[0][p];
 #pragma unroll
       for (int w = 1; w < 4; ++w)
-        if (s_bd[w][lane + 64 * q] < bd) {
-          bd = s_bd[w][lane + 64 * q];
-          bj = s_bj[w][lane + 64 * q];
+        if (s_bd[w][p] < bd) {
+          bd = s_bd[w][p];
+          bj = s_bj[w][p];
         }
-      out[q] = bj;
+      out[q] = q < pt ? bj : -1;
     }
   };
+  bool converged = false;
   for (int it = 0; it < a.max_iters; ++it) {
-    distances(x, cent, n, k, dim, pt, xs, cs, acc);
+    // centroids: the initial ones, later the means under the previous assignment; then all products
+    pass_over_channels(x, cent, n, k, dim, it == 0, it > 0, sm, acc);
     int now[kPT];
     assign(now);
     int changed = 0;
@@ -205,69 +312,66 @@ __global__ __launch_bounds__(256) void tbe_kmeans_kernel(thinkv_view v, TbeArgs 
       changed |= (lane + 64 * q < n) && now[q] != mine[q];
       mine[q] = now[q];
     }
-    if (!__syncthreads_or(changed)) break;
-    // ---- update: members of every cluster in index order
-    if (tid < kTbeMaxKeep) s_cnt[tid] = 0;
+    if (!__syncthreads_or(changed)) {
+      converged = true;   // the products at hand are those with the final centroids
+      break;
+    }
+    // ---- members of every cluster in index order, for the next pass
+    if (tid < kTbeMaxKeep) sm.cnt[tid] = 0;
     if (wave == 0) {
 #pragma unroll
       for (int q = 0; q < kPT; ++q)
         if (lane + 64 * q < n) s_assign[lane + 64 * q] = mine[q];
     }
     __syncthreads();
+    int rank = 0;
     if (tid < n) {
       const int cl = s_assign[tid];
-      int rank = 0;
       for (int i = 0; i < tid; ++i) rank += s_assign[i] == cl;
-      atomicAdd(&s_cnt[cl], 1);
-      s_order[tid] = rank;   // position among the cluster's members, for now
+      atomicAdd(&sm.cnt[cl], 1);
     }
     __syncthreads();
     if (tid == 0) {
       int run = 0;
       for (int j = 0; j < k; ++j) {
-        s_start[j] = run;
-        run += s_cnt[j];
+        sm.start[j] = run;
+        run += sm.cnt[j];
       }
     }
     __syncthreads();
-    int slot = -1;
-    if (tid < n) slot = s_start[s_assign[tid]] + s_order[tid];
-    __syncthreads();
-    if (tid < n) s_order[slot] = tid;
-    __syncthreads();
-    for (int j = 0; j < k; ++j) {
-      const int m = s_cnt[j];
-      if (m == 0) continue;
-      const float inv = 1.0f / (float)m;
-      for (int d = tid; d < dim; d += 256) {
-        float sum = 0.f;
-        for (int r = 0; r < m; ++r) sum += x[(int64_t)s_order[s_start[j] + r] * dim + d];
-        cent[(int64_t)j * dim + d] = sum * inv;
-      }
-    }
+    if (tid < n) sm.order[sm.start[s_assign[tid]] + rank] = tid;
     __syncthreads();
   }
   // ---- survivors: nearest member of every cluster under the final centroids
-  distances(x, cent, n, k, dim, pt, xs, cs, acc);
+  if (!converged) pass_over_channels(x, cent, n, k, dim, false, true, sm, acc);
   if (tid < kTbeMaxKeep) {
     s_cnt[tid] = 0;
     s_start[tid] = kTbeMaxTokens;   // here: lowest index among the cluster's members
     s_best[tid] = ~0ull;
   }
+  if (wave == 0) {
+#pragma unroll
+    for (int q = 0; q < kPT; ++q)
+      if (lane + 64 * q < n) s_assign[lane + 64 * q] = mine[q];
+  }
   __syncthreads();
+  if (my_cl < k) {
+    const float ccj = sm.cc[my_cl];
 #pragma unroll
-  for (int q = 0; q < kPT; ++q) {
-    const int p = lane + 64 * q;
-    if (p < n && mine[q] / kKT == wave) {   // the wave that holds the distance to the point's own cluster
-      float own = 0.f;
+    for (int t = 0; t < kRBW; ++t)
+      if (2 * t + half < rbs) {
 #pragma unroll
-      for (int j = 0; j < kKT; ++j)
-        if (j == mine[q] % kKT) own = acc[q][j];
-      atomicAdd(&s_cnt[mine[q]], 1);
-      atomicMin(&s_start[mine[q]], p);
-      // distances are not negative, so their bit patterns order like the numbers; the index breaks ties
-      atomicMin(&s_best[mine[q]], ((unsigned long long)__builtin_bit_cast(uint32_t, own) << 32) | (unsigned)p);
-    }
+        for (int i = 0; i < 4; ++i) {
+          const int p = 16 * (2 * t + half) + 4 * g + i;
+          if (p < n && s_assign[p] == my_cl) {   // this lane holds the point's product with its own cluster
+            const float own = fmaxf(fmaf(-2.f, acc[t][i], sm.xx[p]) + ccj, 0.f);
+            atomicAdd(&s_cnt[my_cl], 1);
+            atomicMin(&s_start[my_cl], p);
+            // distances are not negative, so their bit patterns order like the numbers; the index breaks ties
+            atomicMin(&s_best[my_cl], ((unsigned long long)__builtin_bit_cast(uint32_t, own) << 32) | (unsigned)p);
+          }
+        }
+      }
   }
   __syncthreads();
   if (wave == 0) {
@@ -300,7 +404,7 @@ int launch_tbe_select(const thinkv_view& v, int layer, const int32_t* tok_seq, c
   a.n_tok = n_tok;
   a.max_iters = max_iters;
   hipLaunchKernelGGL(tbe_gather_kernel, dim3(n_tok), dim3(256), 0, st, v, a);
-  hipLaunchKernelGGL(tbe_kmeans_kernel, dim3(n_seg), dim3(256), 0, st, v, a);
+  hipLaunchKernelGGL(tbe_kmeans_kernel, dim3(n_seg), dim3(kKmThreads), 0, st, v, a);
   return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
 }
 
