@@ -20,8 +20,9 @@
 // an arrival counter of its sequence (view->append_counters), and the block that completes the
 // count commits the sequence before it goes on to quantise its own token.  Reads-before-writes
 // is all that has to hold, so no fence is involved (a release fence costs an L2 write-back here).
-// A bulk call (more than 4,096 tokens: thousands of blocks would bump one sequence's counter) keeps
-// a commit kernel of its own.
+// A call of more than 64 tokens (a prefill, a refill: hundreds of blocks would bump one sequence's
+// counter) keeps a commit kernel of its own and places its tokens sixteen to a block (see
+// append_place_bulk_kernel).
 // The grant of new pages (exclusive sum of the needs of the sequences before s, against what the
 // pool held when the call began) is a sum over at most max_seqs small numbers: every block that
 // wants it works it out for itself rather than waiting for a kernel of its own.  A decode step
@@ -43,6 +44,8 @@ struct SeqPlan {
   int pad;
 };
 static_assert(sizeof(SeqPlan) == 24 * 4, "SeqPlan layout");
+
+constexpr int kBulkFrom = 64;   // calls of more tokens take the bulk kernels
 
 struct AppendWs {
   SeqPlan* plan;     // [max_seqs]
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(256) void append_plan_kernel(thinkv_view v, int lay
   __shared__ int s_scan[5];
   const thinkv_config& c = v.cfg;
   const int s = blockIdx.x, tid = threadIdx.x;
-  if (n_tok <= 4096) {
+  if (n_tok <= kBulkFrom) {
     // small call (decode-style): every thread looks at a few tokens and the two that see the
     // sequence's first and last token publish the range
     if (tid == 0) s_rng[0] = s_rng[1] = 0;
@@ -485,6 +488,285 @@ __device__ void commit_sequence(const thinkv_view& v, int layer, const AppendWs&
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Bulk calls (prefill-style: thousands of tokens).  One block per token pays the slot selection and
+// eight short load-quantise-store passes for every token; here a block takes sixteen consecutive
+// tokens of the call: sixteen threads settle their slots side by side, then every pass quantises
+// one (kv-head, K or V) row of all sixteen tokens, eight channels per thread (one 16-byte load).
+// K codes go straight from registers to the page: the eight channels of a thread are the fields
+// of one 8-channel piece of a group, which the layout keeps together (8, 4 or 2 x 1 bytes).  V
+// codes are transposed through LDS (a V chunk holds channels 16 apart).  The grants of new pages
+// are worked out once, by a small kernel between plan and place.
+__global__ __launch_bounds__(256) void append_grant_kernel(thinkv_view v, AppendWs ws) {
+  __shared__ int s_scan[5];
+  const int S = v.cfg.max_seqs, tid = threadIdx.x;
+  for (int k = 0; k < 3; ++k) {
+    const int avail = ws.avail_old[k];
+    int run = 0;
+    for (int s0 = 0; s0 < S; s0 += 256) {
+      const int s = s0 + tid;
+      const int need = s < S ? ws.plan[s].need[k] : 0;
+      int ex;
+      const int tot = block_excl_scan(need, &ex, s_scan);
+      if (s < S) {
+        const int before = run + ex, left = avail - before;
+        ws.plan[s].base[k] = before < avail ? before : avail;
+        ws.plan[s].grant[k] = left < 0 ? 0 : (left < need ? left : need);
+      }
+      run += tot;
+    }
+  }
+}
+
+constexpr int kBulkTokens = 16;   // tokens per block of the bulk place kernel
+
+template <int D>
+__global__ __launch_bounds__(256) void append_place_bulk_kernel(thinkv_view v, int layer, const void* __restrict__ k_new,
+                                                                const void* __restrict__ v_new, const int32_t* __restrict__ tok_seq,
+                                                                const int32_t* __restrict__ tok_pos,
+                                                                const uint8_t* __restrict__ tok_class, int32_t* __restrict__ tok_handle,
+                                                                int n_tok, int in_dtype, AppendWs ws, int heads_per_block) {
+  constexpr int NG = D / kGroup;        // groups per row
+  constexpr int NM = D / 16;            // 16-channel blocks per row
+  constexpr int TPR = D / 8;            // threads per row
+  constexpr int RPP = 256 / TPR;        // rows per pass: 16 (one (head, K or V) of all tokens) or 32 (one head, K and V)
+  __shared__ int s_cls[kBulkTokens], s_pid[kBulkTokens], s_slot[kBulkTokens], s_ok[kBulkTokens], s_pi[kBulkTokens];
+  __shared__ int s_find[kBulkTokens], s_seq[kBulkTokens], s_rank[kBulkTokens];
+  __shared__ __attribute__((aligned(8))) uint8_t s_codes[2][kBulkTokens][D];
+  const thinkv_config& c = v.cfg;
+  const int tid = threadIdx.x, i0 = blockIdx.x * kBulkTokens;
+  // this block's share of the kv-heads; the first input rows are requested before the slots are settled
+  const int H = c.n_kv_heads;
+  const int h_lo = blockIdx.y * heads_per_block, h_hi = h_lo + heads_per_block < H ? h_lo + heads_per_block : H;
+  const int rsub = tid / TPR, cpiece = tid % TPR;          // row inside the pass, 8-channel piece of the row
+  const int grp = cpiece >> 2, j = cpiece & 3;             // group of the piece, piece inside the group
+  const int n_pass = (2 * (h_hi - h_lo) * kBulkTokens) / RPP;
+  // row of this thread in pass p: token, head, K or V
+  auto row_of = [&](int p, int* t, int* h, int* kind) {
+    const int row = p * RPP + rsub, hk = row / kBulkTokens;
+    *t = row % kBulkTokens;
+    *h = h_lo + (hk >> 1);
+    *kind = hk & 1;
+  };
+  // the eight input values of this thread in pass p (two 16-byte words; 16-bit inputs fill the first)
+  auto fetch = [&](int p, uint4* r0, uint4* r1) {
+    int t, h, kind;
+    row_of(p, &t, &h, &kind);
+    if (p >= n_pass || i0 + t >= n_tok) return;   // (a token without a slot is loaded too: its slot is not known yet at the first call)
+    const int64_t at = ((int64_t)(i0 + t) * H + h) * D + 8 * cpiece;
+    const void* src = kind ? v_new : k_new;
+    if (in_dtype == THINKV_F32) {
+      *r0 = *(const uint4*)((const float*)src + at);
+      *r1 = *(const uint4*)((const float*)src + at + 4);
+    } else {
+      *r0 = *(const uint4*)((const uint16_t*)src + at);
+    }
+  };
+  uint4 n0 = uint4{0u, 0u, 0u, 0u}, n1 = n0;
+  fetch(0, &n0, &n1);
+  // ---- slots: every case that is a closed form is settled by the token's own thread
+  if (tid < kBulkTokens) {
+    const int i = i0 + tid;
+    int ok = 0, cls = 0, pid = 0, slot = 0, pi = 0, find = 0, k = 0, s = -1;
+    if (i < n_tok) {
+      s = tok_seq[i];
+      if (s < 0 || s >= c.max_seqs) {
+        atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEQ);
+      } else {
+        cls = tok_class[i];
+        const SeqPlan& pl = ws.plan[s];
+        if (cls > 2) {
+          atomicOr(&v.dev_status[sl_index(c, s, layer)], THINKV_ST_BAD_CLASS);
+        } else if (i >= pl.lo && i < pl.hi) {
+          k = ws.tok_rank[i];
+          const int32_t* tab = v.block_table + table_base(c, s, layer, cls);
+          const int R = pl.R[cls], tail = pl.tail[cls], np = pl.np_old[cls];
+          if (k < R) {
+            find = 1;   // the k-th reclaimable slot: searched by the whole block below
+          } else if (k < R + tail) {
+            pi = np - 1;
+            pid = tab[pi];
+            slot = (int)v.page_filled[cls][pid] + (k - R);
+            ok = 1;
+          } else {
+            const int kk = k - R - tail, npi = kk >> 4;
+            if (npi < pl.grant[cls]) {
+              pid = v.free_stack[cls][ws.avail_old[cls] - 1 - (pl.base[cls] + npi)];
+              slot = kk & 15;
+              pi = np + npi;
+              ok = 1;
+            }
+          }
+        }
+      }
+    }
+    s_cls[tid] = cls; s_pid[tid] = pid; s_slot[tid] = slot; s_ok[tid] = ok; s_pi[tid] = pi;
+    s_find[tid] = find; s_seq[tid] = s; s_rank[tid] = k;
+  }
+  __syncthreads();
+  for (int t = 0; t < kBulkTokens; ++t) {
+    if (s_find[t] != 1) continue;   // the same for all threads
+    const int s = s_seq[t], cls = s_cls[t], k = s_rank[t];
+    const int np = ws.plan[s].np_old[cls];
+    const int64_t tb = table_base(c, s, layer, cls);
+    const int* pre = ws.pre + ((int64_t)s * 3 + cls) * c.max_pages;
+    for (int pi = tid; pi < np; pi += 256) {
+      uint32_t e = v.slot_mask[tb + pi] >> 16;
+      const int first = pre[pi];
+      if (k >= first && k < first + __popc(e)) {   // exactly one page of the list
+        for (int j = k - first; j > 0; --j) e &= e - 1;
+        s_pid[t] = v.block_table[tb + pi];
+        s_slot[t] = __ffs(e) - 1;
+        s_ok[t] = 1;
+        s_pi[t] = pi;
+      }
+    }
+  }
+  __syncthreads();
+  if (tid < kBulkTokens && i0 + tid < n_tok && blockIdx.y == 0) {
+    const int i = i0 + tid, cls = s_cls[tid], pid = s_pid[tid], slot = s_slot[tid], ok = s_ok[tid];
+    if (ok) {
+      v.slot_pos[cls][(int64_t)pid * kPage + slot] = tok_pos[i];
+      atomicMax(&v.page_pos_max[cls][pid], tok_pos[i]);
+    }
+    if (tok_handle) tok_handle[i] = ok ? THINKV_HANDLE(cls, s_pi[tid], slot) : -1;
+  }
+  // ---- quantise and store
+  for (int p = 0; p < n_pass; ++p) {
+    int t, h, kind;
+    row_of(p, &t, &h, &kind);
+    const uint4 r0 = n0, r1 = n1;
+    fetch(p + 1, &n0, &n1);
+    const bool has_v = RPP > kBulkTokens || (p & 1);       // some rows of this pass are V rows (the same for all threads)
+    const int buf = (RPP > kBulkTokens ? p : p >> 1) & 1;
+    const bool ok = s_ok[t] != 0;
+    const int cls = s_cls[t], slot = s_slot[t];
+    const int bits = c.bits_of_class[cls];
+    const BlockGeom gm = block_geom(bits, D);
+    uint8_t* blk = v.arena[cls] + ((int64_t)s_pid[t] * H + h) * gm.block_bytes;
+    if (ok) {
+      float x[8];
+      const uint32_t w[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+      if (in_dtype == THINKV_F32) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = __builtin_bit_cast(float, w[e]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint16_t u = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+          x[e] = in_dtype == THINKV_F16 ? (float)__builtin_bit_cast(_Float16, u) : __builtin_bit_cast(float, (uint32_t)u << 16);
+        }
+      }
+      float mn = x[0], mx = x[0];
+#pragma unroll
+      for (int e = 1; e < 8; ++e) {
+        mn = fminf(mn, x[e]);
+        mx = fmaxf(mx, x[e]);
+      }
+#pragma unroll
+      for (int d = 1; d <= 2; d <<= 1) {   // the four threads of a group are neighbours
+        mn = fminf(mn, __shfl_xor(mn, d, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, d, 64));
+      }
+      const float qmax = (float)((1 << bits) - 1);
+      const _Float16 zp = (_Float16)(mn + 0.0f);
+      const float s32 = (mx - mn) / qmax;
+      _Float16 sc = (_Float16)s32;
+      if ((float)sc < s32) {
+        uint16_t u = __builtin_bit_cast(uint16_t, sc);
+        sc = __builtin_bit_cast(_Float16, (uint16_t)(u + 1));
+      }
+      const float sf = (float)sc, zf = (float)zp;
+      uint32_t code[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float q = 0.0f;
+        if (sf > 0.0f) {
+          q = rintf((x[e] - zf) / sf);
+          q = fminf(fmaxf(q, 0.0f), qmax);
+        }
+        code[e] = (uint32_t)(int)q;
+      }
+      if (j == 0) {
+        uint16_t* meta = (uint16_t*)(blk + (kind ? gm.v_meta : gm.k_meta));
+        meta[meta_index(slot, grp)] = __builtin_bit_cast(uint16_t, sc);
+        meta[meta_index(slot, grp) + 4] = __builtin_bit_cast(uint16_t, zp);
+      }
+      if (!kind) {
+        // K: channel 32 grp + 8 j + e is field 4 grp + e / 2, half e % 2, of chunk 16 j + slot
+        uint8_t* chunk = blk + gm.k_codes + (16 * j + slot) * gm.chunk_bytes;
+        if (bits == 8) {          // fields 4 grp .. + 3 are words 2 grp and 2 grp + 1
+          uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            w0 |= code[e] << (16 * (e & 1) + 8 * (e >> 1));
+            w1 |= code[4 + e] << (16 * (e & 1) + 8 * (e >> 1));
+          }
+          *(uint2*)(chunk + 8 * grp) = uint2{w0, w1};
+        } else if (bits == 4) {   // word grp
+          uint32_t w0 = 0;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) w0 |= code[e] << (16 * (e & 1) + 4 * (e >> 1));
+          *(uint32_t*)(chunk + 4 * grp) = w0;
+        } else {                  // a quarter of each half of word grp / 2
+          uint32_t lo = 0, hi = 0;
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            lo |= code[e] << e;
+            hi |= code[e + 1] << e;
+          }
+          chunk[4 * (grp >> 1) + (grp & 1)] = (uint8_t)lo;
+          chunk[4 * (grp >> 1) + 2 + (grp & 1)] = (uint8_t)hi;
+        }
+      } else {
+        uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          w0 |= code[e] << (8 * e);
+          w1 |= code[4 + e] << (8 * e);
+        }
+        *(uint2*)&s_codes[buf][t][8 * cpiece] = uint2{w0, w1};
+      }
+    }
+    if (has_v) {
+      __syncthreads();
+      // V: chunk 16 (slot / 4) + m holds channels m, m + 16, ... of four slots.  Thread (token, m)
+      // packs the token's NM codes of the chunk: field u NM + mb of half hh (u, hh from the slot), i.e.
+      // whole 16-bit halves of consecutive words, or one byte when a row has fewer fields than a half.
+      const int hv = h_lo + (RPP > kBulkTokens ? p : p >> 1);   // the head whose V rows were just staged
+      const int tv = tid >> 4, m = tid & 15;
+      if (s_ok[tv]) {
+        const int clv = s_cls[tv], bv = c.bits_of_class[clv], slv = s_slot[tv];
+        const BlockGeom gv = block_geom(bv, D);
+        uint32_t cd[NM];
+#pragma unroll
+        for (int mb = 0; mb < NM; ++mb) cd[mb] = s_codes[buf][tv][16 * mb + m];
+        const int u = (slv >> 1) & 1, hh = slv & 1;
+        uint8_t* chunk = v.arena[clv] + ((int64_t)s_pid[tv] * H + hv) * gv.block_bytes + gv.v_codes +
+                         (16 * (slv >> 2) + m) * gv.chunk_bytes;
+        if (bv == 8) {
+#pragma unroll
+          for (int w = 0; w < NM / 2; ++w)
+            *(uint16_t*)(chunk + 4 * (u * (NM / 2) + w) + 2 * hh) = (uint16_t)(cd[2 * w] | cd[2 * w + 1] << 8);
+        } else if (bv == 4) {
+#pragma unroll
+          for (int w = 0; w < NM / 4; ++w)
+            *(uint16_t*)(chunk + 4 * (u * (NM / 4) + w) + 2 * hh) =
+                (uint16_t)(cd[4 * w] | cd[4 * w + 1] << 4 | cd[4 * w + 2] << 8 | cd[4 * w + 3] << 12);
+        } else {
+          uint32_t val = 0;
+#pragma unroll
+          for (int mb = 0; mb < NM; ++mb) val |= cd[mb] << (2 * mb);
+          if (NM == 8)
+            *(uint16_t*)(chunk + 4 * u + 2 * hh) = (uint16_t)val;
+          else
+            chunk[2 * hh + u] = (uint8_t)val;
+        }
+      }
+    }
+  }
+}
+
 // bulk calls: one block per sequence after the place kernel
 __global__ __launch_bounds__(256) void append_commit_kernel(thinkv_view v, int layer, AppendWs ws) {
   __shared__ int s_scan[5];
@@ -498,19 +780,35 @@ int launch_append(const thinkv_view& v, int layer, const void* k_new, const void
   AppendWs ws = carve(v.cfg, n_tok, workspace);
   const int S = v.cfg.max_seqs;
   hipLaunchKernelGGL(append_plan_kernel, dim3(S), dim3(256), 0, st, v, layer, tok_seq, tok_class, n_tok, ws);
-  // A decode-style call (few tokens) spreads the kv-heads of a token over several workgroups so
-  // that their load-quantise-store chains run side by side; a bulk call keeps one workgroup per
-  // token, which repeats the slot selection once instead of once per pass.
-  const int H = v.cfg.n_kv_heads, hp = v.cfg.head_dim == 128 ? 1 : 2;
-  const int hpb = n_tok <= 4096 ? hp : ((H + hp - 1) / hp) * hp;
-  const dim3 grid(n_tok, (H + hpb - 1) / hpb);
-  const int commit_here = n_tok <= 4096;   // else thousands of blocks would bump one sequence's counter
-  if (v.cfg.head_dim == 128)
-    hipLaunchKernelGGL(append_place_kernel<128>, grid, dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
-                       tok_class, tok_handle, n_tok, in_dtype, ws, hpb, commit_here);
-  else
-    hipLaunchKernelGGL(append_place_kernel<64>, grid, dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
-                       tok_class, tok_handle, n_tok, in_dtype, ws, hpb, commit_here);
+  const int commit_here = n_tok <= kBulkFrom;   // else thousands of blocks would bump one sequence's counter
+  const bool aligned = (((uintptr_t)k_new | (uintptr_t)v_new) & 15) == 0;
+  if (!commit_here && aligned) {
+    hipLaunchKernelGGL(append_grant_kernel, dim3(1), dim3(256), 0, st, v, ws);
+    // enough blocks to fill the chip: a mid-sized call spreads the kv-heads of its token groups over blocks
+    const int H = v.cfg.n_kv_heads, groups = (n_tok + kBulkTokens - 1) / kBulkTokens;
+    int hpb = (int)(((int64_t)H * groups + 4095) / 4096);
+    hpb = hpb < 1 ? 1 : (hpb > H ? H : hpb);
+    const dim3 grid(groups, (H + hpb - 1) / hpb);
+    if (v.cfg.head_dim == 128)
+      hipLaunchKernelGGL(append_place_bulk_kernel<128>, grid, dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
+                         tok_class, tok_handle, n_tok, in_dtype, ws, hpb);
+    else
+      hipLaunchKernelGGL(append_place_bulk_kernel<64>, grid, dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
+                         tok_class, tok_handle, n_tok, in_dtype, ws, hpb);
+  } else {
+    // A decode-style call (few tokens) spreads the kv-heads of a token over several workgroups so
+    // that their load-quantise-store chains run side by side; a bulk call whose rows are not
+    // 16-byte aligned keeps one workgroup per token.
+    const int H = v.cfg.n_kv_heads, hp = v.cfg.head_dim == 128 ? 1 : 2;
+    const int hpb = commit_here ? hp : ((H + hp - 1) / hp) * hp;
+    const dim3 grid(n_tok, (H + hpb - 1) / hpb);
+    if (v.cfg.head_dim == 128)
+      hipLaunchKernelGGL(append_place_kernel<128>, grid, dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
+                         tok_class, tok_handle, n_tok, in_dtype, ws, hpb, commit_here);
+    else
+      hipLaunchKernelGGL(append_place_kernel<64>, grid, dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
+                         tok_class, tok_handle, n_tok, in_dtype, ws, hpb, commit_here);
+  }
   if (!commit_here) hipLaunchKernelGGL(append_commit_kernel, dim3(S), dim3(256), 0, st, v, layer, ws);
   return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
 }

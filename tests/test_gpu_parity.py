@@ -246,3 +246,52 @@ def test_decode_calls_replay_correctly_from_a_captured_graph():
         # eager work between the replays
         B.thinkv_decode_attention(gc, 0, q, outs[0].clone(), None, sid, qp, 0, scale, mcp)
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("D,dtype,shift", [(128, torch.float32, 0), (64, torch.float32, 0), (128, torch.bfloat16, 1),
+                                           (64, torch.float16, 3), (128, torch.float32, 1)])
+def test_bulk_append_input_formats(D, dtype, shift):
+    _say(f"bulk append: D={D} {dtype}, rows start {shift} elements off a 16-byte boundary, types mixed token by token, "
+         "evictions between two calls")
+    H, n_tok = 3, 700
+    geom = synth.Geometry(1, 2 * H, H, D, "f16", (8, 2, 4))
+    rng = np.random.default_rng(77 + D + shift)
+    cls = rng.integers(0, 3, n_tok).astype(np.uint8)
+    wl = synth.Workload("bulk-formats", geom, 0, 2, [np.concatenate([cls, cls]), np.concatenate([cls, cls])], [])
+    gc = parity.make_gpu_cache(wl)
+    ob = parity.make_oracle(wl)
+    gb = parity.GpuBackend(gc)
+
+    def rows(seed):
+        g = torch.Generator().manual_seed(seed)
+        flat = (torch.randn(2 * n_tok * H * D + 8, generator=g) * 3).to(dtype)
+        return flat[shift:shift + 2 * n_tok * H * D].view(2 * n_tok, H, D)      # a view: not contiguous-copied below
+
+    ts = np.repeat(np.arange(2, dtype=np.int32), n_tok)
+    tp = np.tile(np.arange(n_tok, dtype=np.int32), 2)
+    tc = np.tile(cls, 2)
+    for call in range(2):
+        k, v = rows(10 + call), rows(20 + call)
+        kd, vd = k.cuda(), v.cuda()
+        if shift:   # .cuda() of a view keeps no offset: rebuild the offset on the device
+            fk = torch.empty(kd.numel() + 8, dtype=dtype, device="cuda")
+            fv = torch.empty(kd.numel() + 8, dtype=dtype, device="cuda")
+            fk[shift:shift + kd.numel()] = kd.reshape(-1)
+            fv[shift:shift + vd.numel()] = vd.reshape(-1)
+            kd, vd = fk[shift:shift + kd.numel()].view(k.shape), fv[shift:shift + vd.numel()].view(v.shape)
+            assert kd.data_ptr() % 16 != 0
+        from paper_2510_01290_amd import binding as B
+        d = gc.device
+        h = torch.empty(len(ts), dtype=torch.int32, device=d)
+        B.thinkv_append_quantized(gc, 0, kd, vd, torch.from_numpy(ts).to(d), torch.from_numpy(tp + call * n_tok).to(d),
+                                  torch.from_numpy(tc).to(d), h)
+        hg = h.cpu().numpy()
+        ho = ob.append(0, k, v, ts, tp + call * n_tok, tc)
+        assert np.array_equal(hg, ho), call
+        if call == 0:   # free a third of the slots: the second call reuses them in place before it takes new pages
+            pick = rng.random(len(hg)) < 0.33
+            gb.evict(0, ts[pick], hg[pick])
+            ob.evict(0, ts[pick], ho[pick])
+    assert int(gc.dev_status.abs().sum().item()) == 0
+    parity.compare_bookkeeping_full(ob.cache, gc)
+    parity.compare_sequences(ob.cache, gc, [(0, 0, 0), (1, 1, 0)], check_bytes=True)
