@@ -520,7 +520,7 @@ __global__ __launch_bounds__(256) void append_grant_kernel(thinkv_view v, Append
 
 constexpr int kBulkTokens = 16;   // tokens per block of the bulk place kernel
 
-template <int D>
+template <int D, bool F32>
 __global__ __launch_bounds__(256) void append_place_bulk_kernel(thinkv_view v, int layer, const void* __restrict__ k_new,
                                                                 const void* __restrict__ v_new, const int32_t* __restrict__ tok_seq,
                                                                 const int32_t* __restrict__ tok_pos,
@@ -541,29 +541,42 @@ __global__ __launch_bounds__(256) void append_place_bulk_kernel(thinkv_view v, i
   const int rsub = tid / TPR, cpiece = tid % TPR;          // row inside the pass, 8-channel piece of the row
   const int grp = cpiece >> 2, j = cpiece & 3;             // group of the piece, piece inside the group
   const int n_pass = (2 * (h_hi - h_lo) * kBulkTokens) / RPP;
-  // row of this thread in pass p: token, head, K or V
-  auto row_of = [&](int p, int* t, int* h, int* kind) {
-    const int row = p * RPP + rsub, hk = row / kBulkTokens;
-    *t = row % kBulkTokens;
+  // row of this thread in pass p: always the same token (a pass holds whole runs of sixteen rows);
+  // head and K or V change from pass to pass
+  const int t = rsub % kBulkTokens;
+  auto row_of = [&](int p, int* h, int* kind) {
+    const int hk = (p * RPP + rsub) / kBulkTokens;
     *h = h_lo + (hk >> 1);
     *kind = hk & 1;
   };
-  // the eight input values of this thread in pass p (two 16-byte words; 16-bit inputs fill the first)
-  auto fetch = [&](int p, uint4* r0, uint4* r1) {
-    int t, h, kind;
-    row_of(p, &t, &h, &kind);
+  // the eight input values of this thread in pass p (16-bit inputs: one 16-byte word, binary32: two)
+  const int64_t row_at = (int64_t)(i0 + t) * H * D + 8 * cpiece;
+  constexpr int kW = F32 ? 2 : 1;
+  struct Raw {
+    uint4 w[kW];
+  };
+  auto fetch = [&](int p, Raw* r) {
+    int h, kind;
+    row_of(p, &h, &kind);
     if (p >= n_pass || i0 + t >= n_tok) return;   // (a token without a slot is loaded too: its slot is not known yet at the first call)
-    const int64_t at = ((int64_t)(i0 + t) * H + h) * D + 8 * cpiece;
+    const int64_t at = row_at + h * D;
     const void* src = kind ? v_new : k_new;
-    if (in_dtype == THINKV_F32) {
-      *r0 = *(const uint4*)((const float*)src + at);
-      *r1 = *(const uint4*)((const float*)src + at + 4);
+    if (F32) {
+      r->w[0] = *(const uint4*)((const float*)src + at);
+      r->w[kW - 1] = *(const uint4*)((const float*)src + at + 4);
     } else {
-      *r0 = *(const uint4*)((const uint16_t*)src + at);
+      r->w[0] = *(const uint4*)((const uint16_t*)src + at);
     }
   };
-  uint4 n0 = uint4{0u, 0u, 0u, 0u}, n1 = n0;
-  fetch(0, &n0, &n1);
+  // four passes are requested ahead: a pass is short, and one pass is not enough to cover a load
+  constexpr int kAhead = 4;
+  Raw cur[kAhead], nxt[kAhead];
+#pragma unroll
+  for (int q = 0; q < kAhead; ++q) {
+#pragma unroll
+    for (int i = 0; i < kW; ++i) cur[q].w[i] = nxt[q].w[i] = uint4{0u, 0u, 0u, 0u};
+    fetch(q, &cur[q]);
+  }
   // ---- slots: every case that is a closed form is settled by the token's own thread
   if (tid < kBulkTokens) {
     const int i = i0 + tid;
@@ -632,22 +645,32 @@ __global__ __launch_bounds__(256) void append_place_bulk_kernel(thinkv_view v, i
     if (tok_handle) tok_handle[i] = ok ? THINKV_HANDLE(cls, s_pi[tid], slot) : -1;
   }
   // ---- quantise and store
-  for (int p = 0; p < n_pass; ++p) {
-    int t, h, kind;
-    row_of(p, &t, &h, &kind);
-    const uint4 r0 = n0, r1 = n1;
-    fetch(p + 1, &n0, &n1);
+  // what does not change from pass to pass: this thread's token as a quantiser thread ...
+  const bool ok = s_ok[t] != 0;
+  const int slot = s_slot[t];
+  const int bits = c.bits_of_class[s_cls[t]];
+  const BlockGeom gm = block_geom(bits, D);
+  uint8_t* const page = v.arena[s_cls[t]] + (int64_t)s_pid[t] * H * gm.block_bytes;
+  const float qmax = (float)((1 << bits) - 1);
+  // ... and its (token, chunk) as a thread that packs V codes
+  const int tv = tid >> 4, m = tid & 15;
+  const bool v_ok = s_ok[tv] != 0;
+  const int bv = c.bits_of_class[s_cls[tv]], slv = s_slot[tv];
+  const BlockGeom gv = block_geom(bv, D);
+  uint8_t* const v_chunk = v.arena[s_cls[tv]] + (int64_t)s_pid[tv] * H * gv.block_bytes + gv.v_codes +
+                           (16 * (slv >> 2) + m) * gv.chunk_bytes + 2 * (slv & 1);
+  const int v_u = (slv >> 1) & 1;
+  auto pass = [&](int p, const Raw& raw) {
+    int h, kind;
+    row_of(p, &h, &kind);
     const bool has_v = RPP > kBulkTokens || (p & 1);       // some rows of this pass are V rows (the same for all threads)
     const int buf = (RPP > kBulkTokens ? p : p >> 1) & 1;
-    const bool ok = s_ok[t] != 0;
-    const int cls = s_cls[t], slot = s_slot[t];
-    const int bits = c.bits_of_class[cls];
-    const BlockGeom gm = block_geom(bits, D);
-    uint8_t* blk = v.arena[cls] + ((int64_t)s_pid[t] * H + h) * gm.block_bytes;
+    uint8_t* blk = page + h * gm.block_bytes;
     if (ok) {
       float x[8];
+      const uint4 r0 = raw.w[0], r1 = raw.w[kW - 1];
       const uint32_t w[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
-      if (in_dtype == THINKV_F32) {
+      if (F32) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] = __builtin_bit_cast(float, w[e]);
       } else {
@@ -668,7 +691,6 @@ __global__ __launch_bounds__(256) void append_place_bulk_kernel(thinkv_view v, i
         mn = fminf(mn, __shfl_xor(mn, d, 64));
         mx = fmaxf(mx, __shfl_xor(mx, d, 64));
       }
-      const float qmax = (float)((1 << bits) - 1);
       const _Float16 zp = (_Float16)(mn + 0.0f);
       const float s32 = (mx - mn) / qmax;
       _Float16 sc = (_Float16)s32;
@@ -734,36 +756,39 @@ __global__ __launch_bounds__(256) void append_place_bulk_kernel(thinkv_view v, i
       // packs the token's NM codes of the chunk: field u NM + mb of half hh (u, hh from the slot), i.e.
       // whole 16-bit halves of consecutive words, or one byte when a row has fewer fields than a half.
       const int hv = h_lo + (RPP > kBulkTokens ? p : p >> 1);   // the head whose V rows were just staged
-      const int tv = tid >> 4, m = tid & 15;
-      if (s_ok[tv]) {
-        const int clv = s_cls[tv], bv = c.bits_of_class[clv], slv = s_slot[tv];
-        const BlockGeom gv = block_geom(bv, D);
+      if (v_ok) {
         uint32_t cd[NM];
 #pragma unroll
         for (int mb = 0; mb < NM; ++mb) cd[mb] = s_codes[buf][tv][16 * mb + m];
-        const int u = (slv >> 1) & 1, hh = slv & 1;
-        uint8_t* chunk = v.arena[clv] + ((int64_t)s_pid[tv] * H + hv) * gv.block_bytes + gv.v_codes +
-                         (16 * (slv >> 2) + m) * gv.chunk_bytes;
+        uint8_t* chunk = v_chunk + hv * gv.block_bytes;        // already at the half word of the slot
         if (bv == 8) {
 #pragma unroll
-          for (int w = 0; w < NM / 2; ++w)
-            *(uint16_t*)(chunk + 4 * (u * (NM / 2) + w) + 2 * hh) = (uint16_t)(cd[2 * w] | cd[2 * w + 1] << 8);
+          for (int w = 0; w < NM / 2; ++w) *(uint16_t*)(chunk + 4 * (v_u * (NM / 2) + w)) = (uint16_t)(cd[2 * w] | cd[2 * w + 1] << 8);
         } else if (bv == 4) {
 #pragma unroll
           for (int w = 0; w < NM / 4; ++w)
-            *(uint16_t*)(chunk + 4 * (u * (NM / 4) + w) + 2 * hh) =
+            *(uint16_t*)(chunk + 4 * (v_u * (NM / 4) + w)) =
                 (uint16_t)(cd[4 * w] | cd[4 * w + 1] << 4 | cd[4 * w + 2] << 8 | cd[4 * w + 3] << 12);
         } else {
           uint32_t val = 0;
 #pragma unroll
           for (int mb = 0; mb < NM; ++mb) val |= cd[mb] << (2 * mb);
           if (NM == 8)
-            *(uint16_t*)(chunk + 4 * u + 2 * hh) = (uint16_t)val;
+            *(uint16_t*)(chunk + 4 * v_u) = (uint16_t)val;
           else
-            chunk[2 * hh + u] = (uint8_t)val;
+            chunk[v_u] = (uint8_t)val;
         }
       }
     }
+  };
+  for (int p0 = 0; p0 < n_pass; p0 += kAhead) {
+#pragma unroll
+    for (int q = 0; q < kAhead; ++q) fetch(p0 + kAhead + q, &nxt[q]);
+#pragma unroll
+    for (int q = 0; q < kAhead; ++q)
+      if (p0 + q < n_pass) pass(p0 + q, cur[q]);
+#pragma unroll
+    for (int q = 0; q < kAhead; ++q) cur[q] = nxt[q];
   }
 }
 
@@ -789,12 +814,16 @@ int launch_append(const thinkv_view& v, int layer, const void* k_new, const void
     int hpb = (int)(((int64_t)H * groups + 4095) / 4096);
     hpb = hpb < 1 ? 1 : (hpb > H ? H : hpb);
     const dim3 grid(groups, (H + hpb - 1) / hpb);
-    if (v.cfg.head_dim == 128)
-      hipLaunchKernelGGL(append_place_bulk_kernel<128>, grid, dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
-                         tok_class, tok_handle, n_tok, in_dtype, ws, hpb);
-    else
-      hipLaunchKernelGGL(append_place_bulk_kernel<64>, grid, dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos,
-                         tok_class, tok_handle, n_tok, in_dtype, ws, hpb);
+    const bool f32 = in_dtype == THINKV_F32;
+#define THINKV_BULK(DD, FF)                                                                                                   \
+  hipLaunchKernelGGL((append_place_bulk_kernel<DD, FF>), grid, dim3(256), 0, st, v, layer, k_new, v_new, tok_seq, tok_pos, \
+                     tok_class, tok_handle, n_tok, in_dtype, ws, hpb)
+    if (v.cfg.head_dim == 128) {
+      if (f32) THINKV_BULK(128, true); else THINKV_BULK(128, false);
+    } else {
+      if (f32) THINKV_BULK(64, true); else THINKV_BULK(64, false);
+    }
+#undef THINKV_BULK
   } else {
     // A decode-style call (few tokens) spreads the kv-heads of a token over several workgroups so
     // that their load-quantise-store chains run side by side; a bulk call whose rows are not
