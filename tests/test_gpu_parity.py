@@ -295,3 +295,84 @@ def test_bulk_append_input_formats(D, dtype, shift):
     assert int(gc.dev_status.abs().sum().item()) == 0
     parity.compare_bookkeeping_full(ob.cache, gc)
     parity.compare_sequences(ob.cache, gc, [(0, 0, 0), (1, 1, 0)], check_bytes=True)
+
+
+@pytest.mark.parametrize("seed,D", [(1, 64), (2, 128), (3, 64), (4, 128)])
+def test_random_operation_sequences(seed, D):
+    _say(f"random appends (1 .. 300 tokens a call, both append paths) and evictions (live, dead, repeated, placeholder handles) "
+         f"on small pools and short page lists, seed {seed}, D={D}")
+    from paper_2510_01290_amd import binding as B
+    H, S = 2, 5
+    geom = synth.Geometry(1, 2 * H, H, D, "f16", (8, 2, 4) if seed % 2 else (2, 4, 8))
+    wl = synth.Workload("fuzz", geom, seed, S, [np.zeros(16, np.uint8)] * S, [], (0,), np.zeros(S, np.int32))
+    arena, max_pages = (14, 10, 12), 6                       # both the pools and the page lists run out now and then
+    gc = parity.make_gpu_cache(wl, arena_pages=arena, max_pages=max_pages)
+    ob = parity.make_oracle(wl, arena_pages=arena, max_pages=max_pages)
+    gb = parity.GpuBackend(gc)
+    rng = np.random.default_rng(1000 + seed)
+    next_pos = np.zeros(S, np.int64)
+    live = [dict() for _ in range(S)]                        # handle -> True, per sequence, as the calls returned them
+    dead = [[] for _ in range(S)]
+    n_calls = {"small": 0, "bulk": 0, "evict": 0, "tokens_without_a_slot": 0}
+    for op in range(36):
+        if op % 3 != 2 or not any(live):
+            seqs, cls = [], []
+            for s in sorted(rng.choice(S, size=int(rng.integers(1, S + 1)), replace=False).tolist()):
+                n = int(rng.choice([1, 1, 1, 2, 5, 17, 40, 120]))
+                seqs += [s] * n
+                bias = rng.dirichlet([1.0, 1.0, 1.0])
+                cls += rng.choice(3, size=n, p=bias).tolist()
+            n = len(seqs)
+            seqs, cls = np.array(seqs, np.int32), np.array(cls, np.uint8)
+            pos = np.empty(n, np.int32)
+            for s in range(S):
+                m = seqs == s
+                pos[m] = next_pos[s] + np.arange(int(m.sum()))
+                next_pos[s] += int(m.sum())
+            g = torch.Generator().manual_seed(seed * 1000 + op)
+            k = (torch.randn((n, H, D), generator=g) * float(rng.uniform(0.1, 8))).to(torch.float16)
+            v = (torch.randn((n, H, D), generator=g) * float(rng.uniform(0.1, 8))).to(torch.float16)
+            hg = gb.append(0, k.to(gc.device), v.to(gc.device), seqs, pos, cls)
+            ho = ob.append(0, k, v, seqs, pos, cls)
+            assert np.array_equal(hg, ho), ("handles", op, n)
+            n_calls["small" if n <= 64 else "bulk"] += 1
+            n_calls["tokens_without_a_slot"] += int((hg == -1).sum())
+            for s, h in zip(seqs.tolist(), hg.tolist()):
+                if h != -1:
+                    live[s][h] = True
+        else:
+            es, eh = [], []
+            for s in range(S):
+                hs = np.array(list(live[s].keys()), dtype=np.int64)
+                if hs.size:
+                    pick = hs[rng.random(hs.size) < rng.choice([0.1, 0.5, 0.9])]
+                    es += [s] * pick.size
+                    eh += pick.tolist()
+                    for h in pick.tolist():
+                        del live[s][h]
+                        dead[s].append(h)
+                if dead[s] and rng.random() < 0.3:             # a slot that is already dead, and a placeholder
+                    es += [s, s]
+                    eh += [int(rng.choice(dead[s])), -1]
+            if eh and rng.random() < 0.5:                      # the same live handle twice in one call counts once
+                es.append(es[0])
+                eh.append(eh[0])
+            order = rng.permutation(len(eh))
+            es, eh = np.array(es, np.int32)[order], np.array(eh, np.int32)[order]
+            gb.evict(0, es, eh)
+            ob.evict(0, es, eh)
+            n_calls["evict"] += 1
+            # (a "dead" handle whose slot was refilled meanwhile kills a live token, on both sides alike;
+            # the lists above only steer the choice of handles)
+        if op % 6 == 5:
+            parity.compare_bookkeeping_full(ob.cache, gc)
+    parity.compare_bookkeeping_full(ob.cache, gc)
+    parity.compare_sequences(ob.cache, gc, [(s, s, 0) for s in range(S)], check_bytes=True)
+    assert n_calls["small"] and n_calls["bulk"] and n_calls["evict"] and n_calls["tokens_without_a_slot"], n_calls
+    # attention over what is left, both kernels
+    wl.q_pos = next_pos.astype(np.int32)
+    ref, ref_lse = parity.oracle_attention(ob.cache, wl, 0, list(range(S)), list(range(S)))
+    for variant in ("fast", "valu"):
+        got, lse = parity.gpu_attention(gc, wl, None, 0, torch.float32, variant)
+        assert float(np.abs(got - ref).max()) <= parity.TOL, variant
+    _say(n_calls)
