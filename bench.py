@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--replicas", type=int, default=3,
                     help="identical copies of the cache the steps rotate over, so that the data of a step was last touched "
                          "replicas steps ago (3 x 0.75 GB is far beyond the 256 MB memory-side cache)")
+    ap.add_argument("--contrast", action="store_true",
+                    help="also time what in-place slot reuse avoids: compaction of a contiguous binary16 cache by a gather "
+                         "after an eviction, alone and running beside decode attention on a second stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -244,6 +247,10 @@ def main():
                 "us_median": float(np.median([a_.elapsed_time(b_) for a_, b_ in tm]) * 1e3)}
         del p_out
     torch.cuda.synchronize()
+    contrast = None
+    if args.contrast:
+        contrast = gather_contrast(args, np, torch, dev, g,
+                                   lambda j: decode(gcs[j % len(gcs)], 0, q_all[nsteps - 1], out, lse, ev_seq, t_pos[nsteps - 1], 0, scale, max_ctx_pages))
     attn_sparsity_us = float(np.median([a.elapsed_time(b) for a, b in smarks]) * 1e3) if args.variant == "fast" else None
     evict_us = float(np.median([m[0].elapsed_time(m[1]) for m in marks]) * 1e3)
     append_us = float(np.median([m[1].elapsed_time(m[2]) for m in marks]) * 1e3)
@@ -283,6 +290,8 @@ def main():
                      "traffic": TRAFFIC_DEFAULT_BYTES if (args.ctx == 32768 and args.batch == 16 and args.variant == "fast") else None, "algorithmic_bytes_per_launch": attn_bytes},
         "host_wall_ms_per_step": wall / args.steps * 1e3,
     }
+    if contrast is not None:
+        line["gather_compaction_contrast"] = contrast
     if args.copy_calibration:
         # 2^28 int16 elements: reads 512 MiB, writes 512 MiB per call, in an elementwise kernel
         # whose name (a unary functor on short) no other kernel of this run shares
@@ -294,6 +303,58 @@ def main():
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, args, nsteps, ev_handles, new_cls, np, torch, synth, parity)
     print(json.dumps(line))
+
+
+def gather_contrast(args, np, torch, dev, g, attention):
+    """What eviction costs when the cache is kept contiguous (Sec. 5.1 of the paper, its Observations on gather-based
+    compaction): after an eviction the survivors of every sequence are gathered into a dense buffer.  Here: a binary16
+    cache [batch * ctx][Hkv * D] for K and for V, 30 % of the tokens of every sequence evicted, the rest gathered row by
+    row (torch.index_select: plain device plumbing, 2 x Hkv * D * 2 bytes per token).  Timed alone, and looping on a second
+    stream while decode attention over the quantised paged cache runs on the first."""
+    n_tok, row = args.batch * args.ctx, g.n_kv_heads * g.head_dim
+    gen = torch.Generator(device=dev).manual_seed(5)
+    kv = [torch.empty((n_tok, row), dtype=torch.float16, device=dev).normal_(generator=gen) for _ in range(2)]
+    keep = torch.rand(n_tok, device=dev, generator=gen) >= 0.3
+    rows = torch.nonzero(keep).flatten()
+    dst = [torch.empty((int(rows.numel()), row), dtype=torch.float16, device=dev) for _ in range(2)]
+
+    def gather():
+        for a, b in zip(kv, dst):
+            torch.index_select(a, 0, rows, out=b)
+
+    def timed(fn, n, stream=None):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for j, (a, b) in enumerate(ev):
+            a.record(stream)
+            fn(j)
+            b.record(stream)
+        return ev
+
+    def med(ev):
+        return float(np.median([a.elapsed_time(b) for a, b in ev]) * 1e3)
+
+    for j in range(3):
+        gather()
+        attention(j)
+    torch.cuda.synchronize()
+    g_alone = timed(lambda j: gather(), 10)
+    a_alone = timed(attention, 30)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        g_beside = timed(lambda j: gather(), 40, side)        # about 40 x the time of one attention call each
+    a_beside = timed(attention, 60)                            # all of them start while the gathers are still running
+    still_running = not g_beside[-1][1].query()
+    torch.cuda.synchronize()
+    moved = 2 * int(rows.numel()) * row * 2 * 2               # read + written
+    ga, aa, gb, ab = med(g_alone), med(a_alone), med(g_beside), med(a_beside)
+    return {"contiguous_f16_cache_GB": 2 * n_tok * row * 2 / 1e9, "evicted_fraction": 0.3, "bytes_moved_per_compaction": moved,
+            "gather_us_alone": ga, "gather_GB_per_s_alone": moved / ga / 1e3, "attention_us_alone": aa,
+            "attention_us_beside_gather": ab, "attention_slowdown_beside_gather": ab / aa, "gather_us_beside_attention": gb,
+            "gathers_outlasted_the_attention_calls": bool(still_running),
+            "step_us_if_compacted_every_step_sequential": ga + aa, "slowdown_if_compacted_every_step": (ga + aa) / aa,
+            "in_place_reuse_bytes_moved": 0}
 
 
 def attention_only(args, np, torch, B, synth, parity, dev):
