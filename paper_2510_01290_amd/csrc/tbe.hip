@@ -533,13 +533,69 @@ __global__ __launch_bounds__(kPlanThreads) void tbe_count_plan_kernel(thinkv_vie
   __syncthreads();
   for_live_tokens(v, seq, a.layer, s_start, ns, [&](int sg, int, int) { atomicAdd(&s_cnt[sg], 1); });
   __syncthreads();
-  if (tid != 0) return;
-  int total = v.n_live[sl_index(c, seq, a.layer)];
-  int n_cuts = 0, listed = 0;
-  bool oversize = false;
   int32_t* o_seg = a.st_seg + (int64_t)b * a.max_cuts;
   int32_t* o_keep = a.st_keep + (int64_t)b * a.max_cuts;
   int32_t* o_cnt = a.st_cnt + (int64_t)b * a.max_cuts;
+  const int last = ns - 1;
+  // Case 1: every closed segment that can still shrink, in ascending order, is independent of the
+  // others: all threads, with a prefix sum for the place of each cut in the list
+  __shared__ int s_wave[3][kPlanThreads / 64];
+  __shared__ int s_c1[4];   // cuts, tokens listed, tokens dropped, a segment too large for one workgroup was met
+  if (tid < 4) s_c1[tid] = 0;
+  __syncthreads();
+  if (a.transition_ended && a.transition_ended[b]) {
+    for (int i0 = 0; i0 < last; i0 += kPlanThreads) {
+      const int i = i0 + tid, lane = tid & 63, wave = tid >> 6;
+      const int cnt = i < last ? s_cnt[i] : 0;
+      const int r = next_level(cnt);
+      const bool big = r && cnt > kTbeMaxTokens;
+      const int flag = r && !big;
+      int inc = flag;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += o;
+      }
+      if (lane == 63) s_wave[0][wave] = inc;
+      __syncthreads();
+      int before = s_c1[0];
+      for (int w = 0; w < wave; ++w) before += s_wave[0][w];
+      const int at = before + inc - flag;
+      const bool take = flag && at < a.max_cuts;
+      if (take) {
+        o_seg[at] = i;
+        o_keep[at] = r;
+        o_cnt[at] = cnt;
+        s_cnt[i] = -r;          // negative: cut in this call, now holding r tokens
+      }
+      int n_take = take, listed = take ? cnt : 0, dropped = take ? cnt - r : 0;
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) {
+        n_take += __shfl_xor(n_take, d, 64);
+        listed += __shfl_xor(listed, d, 64);
+        dropped += __shfl_xor(dropped, d, 64);
+      }
+      __syncthreads();   // s_wave[0] and s_c1[0] have been read
+      if (lane == 0) {
+        s_wave[0][wave] = n_take;
+        s_wave[1][wave] = listed;
+        s_wave[2][wave] = dropped;
+      }
+      if (big) s_c1[3] = 1;
+      __syncthreads();
+      if (tid == 0)
+        for (int w = 0; w < kPlanThreads / 64; ++w) {
+          s_c1[0] += s_wave[0][w];
+          s_c1[1] += s_wave[1][w];
+          s_c1[2] += s_wave[2][w];
+        }
+      __syncthreads();
+    }
+  }
+  if (tid != 0) return;
+  int total = v.n_live[sl_index(c, seq, a.layer)] - s_c1[2];
+  int n_cuts = s_c1[0], listed = s_c1[1];
+  bool oversize = s_c1[3] != 0;
   auto cut = [&](int i, int r) {
     o_seg[n_cuts] = i;
     o_keep[n_cuts] = r;
@@ -549,18 +605,6 @@ __global__ __launch_bounds__(kPlanThreads) void tbe_count_plan_kernel(thinkv_vie
     total -= s_cnt[i] - r;
     s_cnt[i] = -r;          // negative: cut in this call, now holding r tokens
   };
-  const int last = ns - 1;
-  if (a.transition_ended && a.transition_ended[b]) {
-    for (int i = 0; i < last && n_cuts < a.max_cuts; ++i) {
-      const int r = next_level(s_cnt[i]);
-      if (!r) continue;
-      if (s_cnt[i] > kTbeMaxTokens) {
-        oversize = true;
-        continue;
-      }
-      cut(i, r);
-    }
-  }
   // Case 2.  A segment that cannot be cut now cannot be cut later in this call either (one cut per
   // segment and call), so "the oldest segment of the least important type that can still shrink",
   // asked again after every cut, is one walk over the types in order of importance and over the
