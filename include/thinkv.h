@@ -161,6 +161,8 @@ int thinkv_init_view(const thinkv_view* view, void* stream /* hipStream_t */);
  * binary16(min), scale = smallest binary16 >= (max-min)/(2^b-1), code = clamp(rint((x-zp)/
  * scale), 0, 2^b-1) in binary32 with IEEE division and round-half-even.
  * Skipped tokens: invalid sequence or type, or no page available (flags in dev_status).
+ * No alignment is required of k_new and v_new; calls of more than 64 tokens are faster when both
+ * are 16-byte aligned.
  */
 int thinkv_append_quantized(const thinkv_view* view, int32_t layer, const void* k_new, const void* v_new,
                             const int32_t* tok_seq, const int32_t* tok_pos, const uint8_t* tok_class,
@@ -231,8 +233,9 @@ int thinkv_decode_attention_valu(const thinkv_view* view, int32_t layer, const v
  *                        survives -- ready for thinkv_evict(view, layer, tok_seq, ev_handle, n_tok),
  *                        which skips entries of -1
  *   workspace            at least thinkv_tbe_workspace_bytes(cfg, n_tok, n_seg)
- * Arithmetic is binary32; a decision between two candidates closer than rounding may differ
- * from a binary64 evaluation.  Device-side errors: THINKV_ST_BAD_SLOT / BAD_SEQ for a token that
+ * Arithmetic is binary32, squared distances taken as |x|^2 - 2 x.c + |c|^2; a decision between
+ * two candidates whose distances differ by less than about 1e-5 of the points' mean squared norm
+ * may differ from a binary64 evaluation.  Device-side errors: THINKV_ST_BAD_SLOT / BAD_SEQ for a token that
  * does not exist (it clusters as the origin and is never evicted), THINKV_ST_BAD_SEGMENT (in the
  * last word of dev_status) for a segment outside the limits (nothing of it is evicted).
  */
