@@ -241,6 +241,13 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
   __shared__ uint32_t s_meta[HP][2][NG];
   const thinkv_config& c = v.cfg;
   const int i = blockIdx.x, tid = threadIdx.x;
+  // the first input value of this thread is requested before the slot is settled: the slot takes a
+  // chain of dependent loads, and a decode-style call is nothing but latency
+  const int hs = tid / (2 * D), r = tid % (2 * D), kind = r / D, ch = r % D;
+  const int h_first = blockIdx.y * heads_per_block + hs;
+  const int h_end = (int)(blockIdx.y + 1) * heads_per_block < c.n_kv_heads ? (int)(blockIdx.y + 1) * heads_per_block : c.n_kv_heads;
+  float x_first = 0.f;
+  if (h_first < h_end) x_first = load_as_f32(kind ? v_new : k_new, ((int64_t)i * c.n_kv_heads + h_first) * D + ch, in_dtype);
   // slot selection.  Thread 0 settles every case that is a closed form; the page of the k-th
   // reclaimable slot (k < R) is found by all threads, each testing a stride of the page list.
   __shared__ int s_find[4];   // 1 = search wanted / 2 = grant wanted, sequence, type, rank
@@ -344,13 +351,11 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
   uint8_t* page = v.arena[cls] + (int64_t)pid * H * g.block_bytes;
   const int CB = g.chunk_bytes, FPH = 16 / bits, CPB = 8 / bits;  // codes per byte
 
-  const int hs = tid / (2 * D), r = tid % (2 * D), kind = r / D, ch = r % D;
-  const int h_end = (int)(blockIdx.y + 1) * heads_per_block < H ? (int)(blockIdx.y + 1) * heads_per_block : H;
   for (int h0 = blockIdx.y * heads_per_block; h0 < h_end; h0 += HP) {
     const int h = h0 + hs;
     if (h < h_end) {
       const void* src = kind ? v_new : k_new;
-      const float x = load_as_f32(src, ((int64_t)i * H + h) * D + ch, in_dtype);
+      const float x = h == h_first ? x_first : load_as_f32(src, ((int64_t)i * H + h) * D + ch, in_dtype);
       float mn = x, mx = x;
 #pragma unroll
       for (int d = 16; d >= 1; d >>= 1) {
