@@ -385,3 +385,32 @@ def test_tbe_whole_loop_on_the_device():
     out, _ = parity.gpu_attention(gc, wl, None, 0)
     assert np.abs(out - ref).max() <= parity.TOL
     _say({"calls_with_cuts": n_calls, "cuts": n_cuts, "equal_to_oracle": n_same, "live": live.tolist()})
+
+
+def test_tbe_largest_segments_and_every_keep():
+    _say("K-means survivors at the limits: segments of 256, 255, 241, 17, 16 and 5 live tokens, keep 64 .. 1, channels 1,024 and 128")
+    for geom, n_ctx in ((synth.Geometry(1, 32, 8, 128, "bf16", (8, 2, 4)), 1400), (synth.Geometry(1, 4, 2, 64, "f16", (2, 4, 8)), 1400)):
+        wl = synth.bulk_evict_refill("tbe-big", geom, 31, 1, np.array([n_ctx]), {synth.E: 0.1}, refill_chunk=3)
+        gc = parity.make_gpu_cache(wl)
+        gr = synth.ScriptRunner(wl, parity.GpuBackend(gc)).run()
+        ob = parity.make_oracle(wl)
+        synth.ScriptRunner(wl, ob).run()
+        dead = _dead(wl)[0]
+        hs = gr.handle[(0, 0)]
+        live = np.array([int(hs[p]) for p in range(int(wl.q_pos[0]) + 1) if hs[p] != -1 and not dead[p]], np.int32)
+        sizes = [256, 255, 241, 17, 16, 5, 256, 100]
+        keeps = [64, 32, 4, 16, 8, 1, 3, 50]
+        off = np.r_[0, np.cumsum(sizes)].astype(np.int32)
+        assert off[-1] <= len(live)
+        th, ts, keep = live[:off[-1]], np.zeros(off[-1], np.int32), np.array(keeps, np.int32)
+        want, margins = otbe.select_evictions(ob.cache, 0, ts, th, off, keep, 8)
+        got = _gpu_select(gc, 0, ts, th, off, keep)
+        n_clear = 0
+        for sg, (a, b) in enumerate(zip(off[:-1], off[1:])):
+            kept = got[a:b] == -1
+            assert 1 <= kept.sum() <= keeps[sg] and np.array_equal(got[a:b][~kept], th[a:b][~kept]), sg
+            if margins[sg] > MIN_MARGIN:
+                n_clear += 1
+                assert np.array_equal(got[a:b], want[a:b]), (sg, margins[sg])
+        assert n_clear >= 5, margins
+        assert int(gc.dev_status.abs().sum().item()) == 0
