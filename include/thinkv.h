@@ -182,6 +182,18 @@ int thinkv_evict(const thinkv_view* view, int32_t layer, const int32_t* ev_seq, 
                  int32_t n_ev, void* stream);
 
 /*
+ * The two calls of a decode step in one (Sec. 5.2: a step marks the tokens its eviction policy
+ * chose and the newly generated token takes a freed slot): the same result, tables, bytes and
+ * flags as thinkv_evict(ev_seq, ev_handle, n_ev) followed by thinkv_append_quantized(...) with
+ * the same arguments, with one kernel launch less (the evictions of a sequence are applied by
+ * the workgroup that plans the sequence's appends).
+ */
+int thinkv_evict_append(const thinkv_view* view, int32_t layer, const int32_t* ev_seq, const int32_t* ev_handle, int32_t n_ev,
+                        const void* k_new, const void* v_new, const int32_t* tok_seq, const int32_t* tok_pos,
+                        const uint8_t* tok_class, int32_t* tok_handle, int32_t n_tok, thinkv_dtype in_dtype, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+/*
  * Decode attention (appendix "Decode": O = softmax(q K^T / sqrt(d)) V over every cached
  * token; "Grouped-Query Attention": the n_q_heads / n_kv_heads query heads of a group share
  * one K/V head, each with its own softmax).  K^ and V^ are zp + code * scale from the stored

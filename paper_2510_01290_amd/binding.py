@@ -14,7 +14,7 @@ F16, BF16, F32 = 0, 1, 2
 _DT = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
 ST_NOPAGES, ST_BAD_CLASS, ST_BAD_SLOT, ST_EVICT_DEAD, ST_BAD_SEQ, ST_BAD_SEGMENT = 1, 2, 4, 8, 16, 32
 EXPORTS = ["thinkv_block_bytes", "thinkv_page_bytes", "thinkv_append_workspace_bytes",
-           "thinkv_decode_workspace_bytes", "thinkv_init_view", "thinkv_append_quantized", "thinkv_evict",
+           "thinkv_decode_workspace_bytes", "thinkv_init_view", "thinkv_append_quantized", "thinkv_evict", "thinkv_evict_append",
            "thinkv_decode_attention", "thinkv_decode_attention_valu", "thinkv_decode_sparsity_workspace_bytes",
            "thinkv_decode_attention_sparsity", "thinkv_tbe_workspace_bytes", "thinkv_tbe_select", "thinkv_tbe_plan_workspace_bytes", "thinkv_tbe_plan",
            "thinkv_status_string"]
@@ -56,6 +56,8 @@ def load():
     lib.thinkv_append_quantized.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, vp, vp, i32, C.c_int, vp, sz, vp]
     lib.thinkv_evict.restype = C.c_int
     lib.thinkv_evict.argtypes = [C.POINTER(View), i32, vp, vp, i32, vp]
+    lib.thinkv_evict_append.restype = C.c_int
+    lib.thinkv_evict_append.argtypes = [C.POINTER(View), i32, vp, vp, i32, vp, vp, vp, vp, vp, vp, i32, C.c_int, vp, sz, vp]
     for name in ("thinkv_decode_attention", "thinkv_decode_attention_valu"):
         fn = getattr(lib, name)
         fn.restype = C.c_int
@@ -183,6 +185,20 @@ def thinkv_append_quantized(cache, layer, k_new, v_new, tok_seq, tok_pos, tok_cl
     _check(load().thinkv_append_quantized(C.byref(cache.view), layer, _ptr(k_new), _ptr(v_new), _ptr(tok_seq),
                                           _ptr(tok_pos), _ptr(tok_class), _ptr(tok_handle), n_tok, _DT[k_new.dtype],
                                           _ptr(ws), ws.numel(), _stream(stream)), "thinkv_append_quantized")
+
+
+def thinkv_evict_append(cache, layer, ev_seq, ev_handle, k_new, v_new, tok_seq, tok_pos, tok_class, tok_handle=None, stream=None):
+    """thinkv_evict followed by thinkv_append_quantized, in one call"""
+    n_tok = int(tok_seq.numel())
+    assert ev_seq.dtype == torch.int32 and ev_handle.dtype == torch.int32 and ev_seq.numel() == ev_handle.numel()
+    assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.dtype == v_new.dtype
+    assert tok_seq.dtype == torch.int32 and tok_pos.dtype == torch.int32 and tok_class.dtype == torch.uint8
+    assert tuple(k_new.shape) == (n_tok, cache.cfg.n_kv_heads, cache.cfg.head_dim) == tuple(v_new.shape)
+    nb = thinkv_append_workspace_bytes(cache.cfg, n_tok)
+    ws = cache.workspace(nb)
+    _check(load().thinkv_evict_append(C.byref(cache.view), layer, _ptr(ev_seq), _ptr(ev_handle), int(ev_seq.numel()),
+                                      _ptr(k_new), _ptr(v_new), _ptr(tok_seq), _ptr(tok_pos), _ptr(tok_class), _ptr(tok_handle),
+                                      n_tok, _DT[k_new.dtype], _ptr(ws), ws.numel(), _stream(stream)), "thinkv_evict_append")
 
 
 def thinkv_evict(cache, layer, ev_seq, ev_handle, stream=None):

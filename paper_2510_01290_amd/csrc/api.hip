@@ -7,7 +7,7 @@ namespace thinkv {
 size_t append_ws_bytes(const thinkv_config& c, int n_tok);
 int launch_append(const thinkv_view& v, int layer, const void* k_new, const void* v_new, const int32_t* tok_seq,
                   const int32_t* tok_pos, const uint8_t* tok_class, int32_t* tok_handle, int n_tok, int in_dtype,
-                  void* workspace, hipStream_t st);
+                  void* workspace, hipStream_t st, const int32_t* ev_seq, const int32_t* ev_handle, int n_ev);
 int launch_evict(const thinkv_view& v, int layer, const int32_t* ev_seq, const int32_t* ev_handle, int n_ev, hipStream_t st);
 int launch_init(const thinkv_view& v, hipStream_t st);
 int launch_decode_simple(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
@@ -191,7 +191,28 @@ int thinkv_append_quantized(const thinkv_view* view, int32_t layer, const void* 
   if (in_dtype != THINKV_F16 && in_dtype != THINKV_BF16 && in_dtype != THINKV_F32) return THINKV_E_UNSUPPORTED;
   if (workspace_bytes < append_ws_bytes(view->cfg, n_tok)) return THINKV_E_WORKSPACE;
   return launch_append(*view, layer, k_new, v_new, tok_seq, tok_pos, tok_class, tok_handle, n_tok, (int)in_dtype,
-                       workspace, (hipStream_t)stream);
+                       workspace, (hipStream_t)stream, nullptr, nullptr, 0);
+}
+
+int thinkv_evict_append(const thinkv_view* view, int32_t layer, const int32_t* ev_seq, const int32_t* ev_handle, int32_t n_ev,
+                        const void* k_new, const void* v_new, const int32_t* tok_seq, const int32_t* tok_pos,
+                        const uint8_t* tok_class, int32_t* tok_handle, int32_t n_tok, thinkv_dtype in_dtype, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  // a long eviction list, or no tokens to append: the two calls one after the other
+  if (n_tok <= 0 || n_ev <= 0 || n_ev > 4096) {
+    const int rc = thinkv_evict(view, layer, ev_seq, ev_handle, n_ev, stream);
+    if (rc) return rc;
+    return thinkv_append_quantized(view, layer, k_new, v_new, tok_seq, tok_pos, tok_class, tok_handle, n_tok, in_dtype, workspace,
+                                   workspace_bytes, stream);
+  }
+  int rc = check_view(view);
+  if (rc) return rc;
+  if (layer < 0 || layer >= view->cfg.n_layers) return THINKV_E_INVALID_ARG;
+  if (!ev_seq || !ev_handle || !k_new || !v_new || !tok_seq || !tok_pos || !tok_class || !workspace) return THINKV_E_INVALID_ARG;
+  if (in_dtype != THINKV_F16 && in_dtype != THINKV_BF16 && in_dtype != THINKV_F32) return THINKV_E_UNSUPPORTED;
+  if (workspace_bytes < append_ws_bytes(view->cfg, n_tok)) return THINKV_E_WORKSPACE;
+  return launch_append(*view, layer, k_new, v_new, tok_seq, tok_pos, tok_class, tok_handle, n_tok, (int)in_dtype, workspace,
+                       (hipStream_t)stream, ev_seq, ev_handle, n_ev);
 }
 
 int thinkv_evict(const thinkv_view* view, int32_t layer, const int32_t* ev_seq, const int32_t* ev_handle, int32_t n_ev,

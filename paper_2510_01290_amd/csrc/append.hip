@@ -108,11 +108,25 @@ __device__ inline int block_excl_scan(int v, int* excl, int* lds /*[5]*/) {
 }
 
 __global__ __launch_bounds__(256) void append_plan_kernel(thinkv_view v, int layer, const int32_t* __restrict__ tok_seq,
-                                                          const uint8_t* __restrict__ tok_class, int n_tok, AppendWs ws) {
+                                                          const uint8_t* __restrict__ tok_class, int n_tok, AppendWs ws,
+                                                          const int32_t* __restrict__ ev_seq, const int32_t* __restrict__ ev_handle,
+                                                          int n_ev) {
   __shared__ int s_rng[2];
   __shared__ int s_scan[5];
   const thinkv_config& c = v.cfg;
   const int s = blockIdx.x, tid = threadIdx.x;
+  // Evictions that come with the call (thinkv_evict_append): an eviction touches the tables of its
+  // own sequence only, and so does the plan of a sequence, so the block of sequence s applies the
+  // handles of sequence s and goes on; no block waits for another.
+  if (n_ev > 0) {
+    for (int i = tid; i < n_ev; i += 256) {
+      const int es = ev_seq[i];
+      if (es == s) evict_one(v, layer, s, ev_handle[i]);
+      else if (s == 0 && (es < 0 || es >= c.max_seqs)) atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEQ);
+    }
+    __threadfence_block();
+    __syncthreads();
+  }
   if (n_tok <= kBulkFrom) {
     // small call (decode-style): every thread looks at a few tokens and the two that see the
     // sequence's first and last token publish the range
@@ -806,10 +820,10 @@ __global__ __launch_bounds__(256) void append_commit_kernel(thinkv_view v, int l
 
 int launch_append(const thinkv_view& v, int layer, const void* k_new, const void* v_new, const int32_t* tok_seq,
                   const int32_t* tok_pos, const uint8_t* tok_class, int32_t* tok_handle, int n_tok, int in_dtype,
-                  void* workspace, hipStream_t st) {
+                  void* workspace, hipStream_t st, const int32_t* ev_seq, const int32_t* ev_handle, int n_ev) {
   AppendWs ws = carve(v.cfg, n_tok, workspace);
   const int S = v.cfg.max_seqs;
-  hipLaunchKernelGGL(append_plan_kernel, dim3(S), dim3(256), 0, st, v, layer, tok_seq, tok_class, n_tok, ws);
+  hipLaunchKernelGGL(append_plan_kernel, dim3(S), dim3(256), 0, st, v, layer, tok_seq, tok_class, n_tok, ws, ev_seq, ev_handle, n_ev);
   const int commit_here = n_tok <= kBulkFrom;   // else thousands of blocks would bump one sequence's counter
   const bool aligned = (((uintptr_t)k_new | (uintptr_t)v_new) & 15) == 0;
   if (!commit_here && aligned) {

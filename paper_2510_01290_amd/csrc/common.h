@@ -51,6 +51,30 @@ __device__ inline int npages_index(const thinkv_config& c, int seq, int layer, i
 }
 __device__ inline int sl_index(const thinkv_config& c, int seq, int layer) { return seq * c.n_layers + layer; }
 
+// Soft eviction of one handle of sequence s (a valid sequence id).  The live bit is cleared with
+// one atomic; only the thread that saw it set goes on to mark the slot reclaimable, so duplicates
+// and dead slots count once.
+__device__ inline void evict_one(const thinkv_view& v, int layer, int s, int32_t h) {
+  const thinkv_config& c = v.cfg;
+  if (h == -1) return;   // placeholder: no token
+  const uint32_t uh = (uint32_t)h;
+  const int cls = uh >> 28, pi = (uh >> 4) & 0xFFFFFF, slot = uh & 15;
+  uint32_t* status = &v.dev_status[sl_index(c, s, layer)];
+  if (h < 0 || cls > 2 || pi >= v.n_pages[npages_index(c, s, layer, cls)]) {
+    atomicOr(status, THINKV_ST_BAD_SLOT);
+    return;
+  }
+  uint32_t* mask = &v.slot_mask[table_base(c, s, layer, cls) + pi];
+  const uint32_t bit = 1u << slot;
+  const uint32_t old = atomicAnd(mask, ~bit);
+  if (old & bit) {
+    atomicOr(mask, bit << 16);
+    atomicSub(&v.n_live[sl_index(c, s, layer)], 1);
+  } else {
+    atomicOr(status, THINKV_ST_EVICT_DEAD);
+  }
+}
+
 // widen one element of a 16/32-bit float array exactly to binary32
 __device__ inline float load_as_f32(const void* p, int64_t i, int dtype) {
   if (dtype == THINKV_F16) {

@@ -3,8 +3,7 @@
 
 namespace thinkv {
 
-// One thread per handle.  The live bit is cleared with one atomic; only the thread that saw
-// it set goes on to mark the slot reclaimable, so duplicates and dead slots count once.
+// One thread per handle.
 __global__ __launch_bounds__(256) void evict_kernel(thinkv_view v, int layer, const int32_t* __restrict__ ev_seq,
                                                     const int32_t* __restrict__ ev_handle, int n_ev) {
   const thinkv_config& c = v.cfg;
@@ -15,24 +14,7 @@ __global__ __launch_bounds__(256) void evict_kernel(thinkv_view v, int layer, co
     atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEQ);
     return;
   }
-  const int32_t h = ev_handle[i];
-  if (h == -1) return;   // placeholder: no token
-  const uint32_t uh = (uint32_t)h;
-  const int cls = uh >> 28, pi = (uh >> 4) & 0xFFFFFF, slot = uh & 15;
-  uint32_t* status = &v.dev_status[sl_index(c, s, layer)];
-  if (h < 0 || cls > 2 || pi >= v.n_pages[npages_index(c, s, layer, cls)]) {
-    atomicOr(status, THINKV_ST_BAD_SLOT);
-    return;
-  }
-  uint32_t* mask = &v.slot_mask[table_base(c, s, layer, cls) + pi];
-  const uint32_t bit = 1u << slot;
-  const uint32_t old = atomicAnd(mask, ~bit);
-  if (old & bit) {
-    atomicOr(mask, bit << 16);
-    atomicSub(&v.n_live[sl_index(c, s, layer)], 1);
-  } else {
-    atomicOr(status, THINKV_ST_EVICT_DEAD);
-  }
+  evict_one(v, layer, s, ev_handle[i]);
 }
 
 __global__ __launch_bounds__(256) void init_kernel(thinkv_view v) {

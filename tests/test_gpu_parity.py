@@ -297,10 +297,10 @@ def test_bulk_append_input_formats(D, dtype, shift):
     parity.compare_sequences(ob.cache, gc, [(0, 0, 0), (1, 1, 0)], check_bytes=True)
 
 
-@pytest.mark.parametrize("seed,D", [(1, 64), (2, 128), (3, 64), (4, 128)])
-def test_random_operation_sequences(seed, D):
+@pytest.mark.parametrize("seed,D,fused", [(1, 64, False), (2, 128, False), (3, 64, True), (4, 128, True), (5, 128, True)])
+def test_random_operation_sequences(seed, D, fused):
     _say(f"random appends (1 .. 300 tokens a call, both append paths) and evictions (live, dead, repeated, placeholder handles) "
-         f"on small pools and short page lists, seed {seed}, D={D}")
+         f"on small pools and short page lists, seed {seed}, D={D}" + (", evictions handed over with the next append (thinkv_evict_append)" if fused else ""))
     from paper_2510_01290_amd import binding as B
     H, S = 2, 5
     geom = synth.Geometry(1, 2 * H, H, D, "f16", (8, 2, 4) if seed % 2 else (2, 4, 8))
@@ -313,7 +313,8 @@ def test_random_operation_sequences(seed, D):
     next_pos = np.zeros(S, np.int64)
     live = [dict() for _ in range(S)]                        # handle -> True, per sequence, as the calls returned them
     dead = [[] for _ in range(S)]
-    n_calls = {"small": 0, "bulk": 0, "evict": 0, "tokens_without_a_slot": 0}
+    n_calls = {"small": 0, "bulk": 0, "evict": 0, "fused": 0, "tokens_without_a_slot": 0}
+    pending = None
     for op in range(36):
         if op % 3 != 2 or not any(live):
             seqs, cls = [], []
@@ -332,7 +333,17 @@ def test_random_operation_sequences(seed, D):
             g = torch.Generator().manual_seed(seed * 1000 + op)
             k = (torch.randn((n, H, D), generator=g) * float(rng.uniform(0.1, 8))).to(torch.float16)
             v = (torch.randn((n, H, D), generator=g) * float(rng.uniform(0.1, 8))).to(torch.float16)
-            hg = gb.append(0, k.to(gc.device), v.to(gc.device), seqs, pos, cls)
+            if pending is not None:
+                d = gc.device
+                h = torch.empty(n, dtype=torch.int32, device=d)
+                B.thinkv_evict_append(gc, 0, torch.from_numpy(pending[0]).to(d), torch.from_numpy(pending[1]).to(d),
+                                      k.to(d), v.to(d), torch.from_numpy(seqs).to(d), torch.from_numpy(pos).to(d),
+                                      torch.from_numpy(cls).to(d), h)
+                hg = h.cpu().numpy()
+                pending = None
+                n_calls["fused"] += 1
+            else:
+                hg = gb.append(0, k.to(gc.device), v.to(gc.device), seqs, pos, cls)
             ho = ob.append(0, k, v, seqs, pos, cls)
             assert np.array_equal(hg, ho), ("handles", op, n)
             n_calls["small" if n <= 64 else "bulk"] += 1
@@ -357,18 +368,27 @@ def test_random_operation_sequences(seed, D):
             if eh and rng.random() < 0.5:                      # the same live handle twice in one call counts once
                 es.append(es[0])
                 eh.append(eh[0])
+            if rng.random() < 0.3:                             # a sequence that does not exist
+                es.append(S + 3)
+                eh.append(0)
             order = rng.permutation(len(eh))
             es, eh = np.array(es, np.int32)[order], np.array(eh, np.int32)[order]
-            gb.evict(0, es, eh)
+            if fused and len(eh):
+                pending = (es, eh)          # the device gets them with the next append
+            else:
+                gb.evict(0, es, eh)
             ob.evict(0, es, eh)
             n_calls["evict"] += 1
             # (a "dead" handle whose slot was refilled meanwhile kills a live token, on both sides alike;
             # the lists above only steer the choice of handles)
-        if op % 6 == 5:
+        if op % 6 == 5 and pending is None:
             parity.compare_bookkeeping_full(ob.cache, gc)
+    if pending is not None:
+        gb.evict(0, *pending)
     parity.compare_bookkeeping_full(ob.cache, gc)
     parity.compare_sequences(ob.cache, gc, [(s, s, 0) for s in range(S)], check_bytes=True)
     assert n_calls["small"] and n_calls["bulk"] and n_calls["evict"] and n_calls["tokens_without_a_slot"], n_calls
+    assert bool(n_calls["fused"]) == fused
     # attention over what is left, both kernels
     wl.q_pos = next_pos.astype(np.int32)
     ref, ref_lse = parity.oracle_attention(ob.cache, wl, 0, list(range(S)), list(range(S)))
