@@ -104,7 +104,9 @@ def main():
     t_pos = torch.stack([torch.arange(ntok0[s], ntok0[s] + nsteps, dtype=torch.int32) for s in range(args.batch)], 1).contiguous().to(dev)
     k_new = torch.stack([synth.kv_rows(wl.seed, 0, s, 0, ntok0[s], ntok0[s] + nsteps, g, dev) for s in range(args.batch)], 1).contiguous()
     v_new = torch.stack([synth.kv_rows(wl.seed, 0, s, 1, ntok0[s], ntok0[s] + nsteps, g, dev) for s in range(args.batch)], 1).contiguous()
-    q_all = torch.stack([torch.stack([synth.query_rows(wl.seed, 0, s, st, g, dev) for s in range(args.batch)]) for st in range(nsteps)]).contiguous()
+    # (generated on the host and moved once: a few thousand tiny device launches less)
+    cpu = torch.device("cpu")
+    q_all = torch.stack([torch.stack([synth.query_rows(wl.seed, 0, s, st, g, cpu) for s in range(args.batch)]) for st in range(nsteps)]).contiguous().to(dev)
     out = torch.empty((args.batch, g.n_q_heads, g.head_dim), dtype=torch.bfloat16, device=dev)
     lse = torch.empty((args.batch, g.n_q_heads), dtype=torch.float32, device=dev)
     h_out = torch.empty(args.batch, dtype=torch.int32, device=dev)
