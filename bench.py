@@ -22,7 +22,7 @@ HBM_PEAK = 8.0e12
 # HBM bytes of one decode-attention launch (split-K kernel + merge) on the default workload, from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a copy of known size
 # (profiles/decode_attention_cfg2_32k_hbm_traffic.txt); other workloads report null
-TRAFFIC_DEFAULT_BYTES = 734.5e6
+TRAFFIC_DEFAULT_BYTES = 734.7e6
 
 
 def main():
