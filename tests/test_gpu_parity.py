@@ -396,3 +396,73 @@ def test_random_operation_sequences(seed, D, fused):
         got, lse = parity.gpu_attention(gc, wl, None, 0, torch.float32, variant)
         assert float(np.abs(got - ref).max()) <= parity.TOL, variant
     _say(n_calls)
+
+
+def test_whole_decode_step_replays_correctly_from_a_captured_graph():
+    _say("evict + append (one call) + decode attention captured in a graph on one cache, replayed three times; "
+         "the same steps run eagerly on a twin cache")
+    from paper_2510_01290_amd import binding as B
+    geom = synth.Geometry(1, 8, 2, 128, "bf16", (8, 2, 4))
+    wl = synth.bulk_evict_refill("graph-step", geom, 17, 3, np.array([700, 90, 1500]), {synth.E: 0.2}, refill_chunk=4)
+    twins = []
+    for _ in range(2):
+        gc = parity.make_gpu_cache(wl)
+        gr = synth.ScriptRunner(wl, parity.GpuBackend(gc)).run()
+        twins.append(gc)
+    eager, graphed = twins
+    dev, S = eager.device, wl.n_seqs
+    # static inputs of the captured step; their contents change between replays
+    hs = [gr.handle[(0, s)] for s in range(S)]
+    live = [[int(h) for h in hs[s][:60] if h != -1] for s in range(S)]
+    ev_seq = torch.arange(S, dtype=torch.int32, device=dev)
+    ev_h = torch.zeros(S, dtype=torch.int32, device=dev)
+    k = torch.zeros((S, geom.n_kv_heads, geom.head_dim), dtype=torch.bfloat16, device=dev)
+    v = torch.zeros_like(k)
+    pos = torch.zeros(S, dtype=torch.int32, device=dev)
+    cls = torch.zeros(S, dtype=torch.uint8, device=dev)
+    q = torch.zeros((S, geom.n_q_heads, geom.head_dim), dtype=torch.bfloat16, device=dev)
+    mcp = int(eager.n_pages[:, 0].sum(-1).max().item()) + 2
+    scale = geom.head_dim ** -0.5
+    outs = {c: torch.empty(q.shape, dtype=torch.float32, device=dev) for c in ("eager", "graph")}
+    hnd = {c: torch.empty(S, dtype=torch.int32, device=dev) for c in ("eager", "graph")}
+
+    def step(gc, tag):
+        B.thinkv_evict_append(gc, 0, ev_seq, ev_h, k, v, ev_seq, pos, cls, hnd[tag])
+        B.thinkv_decode_attention(gc, 0, q, outs[tag], None, ev_seq, pos, 0, scale, mcp)
+
+    def set_inputs(i):
+        ev_h.copy_(torch.tensor([live[s][i] for s in range(S)], dtype=torch.int32))
+        k.copy_(torch.stack([synth.kv_rows(wl.seed, 0, s, 0, 5000 + i, 5001 + i, geom, dev)[0] for s in range(S)]))
+        v.copy_(torch.stack([synth.kv_rows(wl.seed, 0, s, 1, 5000 + i, 5001 + i, geom, dev)[0] for s in range(S)]))
+        pos.copy_(torch.tensor([int(wl.q_pos[s]) + 1 + i for s in range(S)], dtype=torch.int32))
+        cls.copy_(torch.tensor([(s + i) % 3 for s in range(S)], dtype=torch.uint8))
+        q.copy_(torch.stack([synth.query_rows(wl.seed, 0, s, 100 + i, geom, dev) for s in range(S)]))
+
+    set_inputs(0)
+    step(eager, "eager")                       # also sizes the workspaces, so nothing is allocated while capturing
+    graphed.workspace(max(int(eager._ws.numel()) if getattr(eager, "_ws", None) is not None else 0, 1 << 20))
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.thinkv_decode_attention(graphed, 0, q, outs["graph"], None, ev_seq, pos, 0, scale, mcp)   # warm-up on the side stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step(graphed, "graph")
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for i in range(3):
+        if i:
+            set_inputs(i)
+            step(eager, "eager")
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(hnd["eager"], hnd["graph"]), i
+        assert float((outs["eager"] - outs["graph"]).abs().max()) <= 1e-4, i
+        for name in ("block_table", "slot_mask", "n_pages", "n_live", "dev_status", "free_top", "work_counters", "append_counters"):
+            assert torch.equal(getattr(eager, name), getattr(graphed, name)), (name, i)
+        for c in range(3):
+            assert torch.equal(eager.arena[c], graphed.arena[c]), ("arena", c, i)
+            assert torch.equal(eager.slot_pos[c], graphed.slot_pos[c]), ("slot_pos", c, i)
+    assert int(eager.dev_status.abs().sum().item()) == 0
