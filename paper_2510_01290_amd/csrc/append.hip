@@ -224,7 +224,7 @@ __global__ __launch_bounds__(256) void append_plan_kernel(thinkv_view v, int lay
 // New pages of type k granted to sequence s: base = pages wanted by the sequences before s
 // (pop order), grant = what the pool (avail pages when the call began) still covers of s's own
 // need.  Called by every thread of the block.
-__device__ inline void grant_of(const thinkv_view& v, const AppendWs& ws, int s, int k, int* base, int* grant, int* lds /*[5]*/) {
+__device__ inline void grant_of(const AppendWs& ws, int s, int k, int* base, int* grant, int* lds /*[5]*/) {
   const int avail = ws.avail_old[k];
   int before = 0;
   for (int t = threadIdx.x; t < s; t += 256) before += ws.plan[t].need[k];
@@ -306,7 +306,7 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
     for (int pi = tid; pi < np; pi += 256) {
       uint32_t e = v.slot_mask[tb + pi] >> 16;
       const int first = pre[pi];
-      if (k >= first && k < first + __popc(e)) {   // exactly one page of the list
+      if (k >= first && k < first + (int)__popc(e)) {   // exactly one page of the list
         for (int j = k - first; j > 0; --j) e &= e - 1;
         s_place[1] = v.block_table[tb + pi];
         s_place[2] = __ffs(e) - 1;
@@ -319,7 +319,7 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
   if (s_find[0] == 2) {
     const int s = s_find[1], cls = s_find[2], k = s_find[3];
     int base, grant;
-    grant_of(v, ws, s, cls, &base, &grant, s_scan);
+    grant_of(ws, s, cls, &base, &grant, s_scan);
     if (tid == 0) {
       const SeqPlan& pl = ws.plan[s];
       const int kk = k - pl.R[cls] - pl.tail[cls], npi = kk >> 4;
@@ -461,7 +461,7 @@ __device__ void commit_sequence(const thinkv_view& v, int layer, const AppendWs&
     const int n = pl.n[k], R = pl.R[k], tail = pl.tail[k], np = pl.np_old[k];
     if (n == 0) continue;
     int base = 0, grant = 0;
-    if (pl.need[k] > 0) grant_of(v, ws, s, k, &base, &grant, s_scan);
+    if (pl.need[k] > 0) grant_of(ws, s, k, &base, &grant, s_scan);
     int32_t* tab = v.block_table + table_base(c, s, layer, k);
     uint32_t* msk = v.slot_mask + table_base(c, s, layer, k);
     const int* pre = ws.pre + ((int64_t)s * 3 + k) * c.max_pages;
@@ -545,7 +545,6 @@ __global__ __launch_bounds__(256) void append_place_bulk_kernel(thinkv_view v, i
                                                                 const int32_t* __restrict__ tok_pos,
                                                                 const uint8_t* __restrict__ tok_class, int32_t* __restrict__ tok_handle,
                                                                 int n_tok, int in_dtype, AppendWs ws, int heads_per_block) {
-  constexpr int NG = D / kGroup;        // groups per row
   constexpr int NM = D / 16;            // 16-channel blocks per row
   constexpr int TPR = D / 8;            // threads per row
   constexpr int RPP = 256 / TPR;        // rows per pass: 16 (one (head, K or V) of all tokens) or 32 (one head, K and V)
@@ -645,7 +644,7 @@ __global__ __launch_bounds__(256) void append_place_bulk_kernel(thinkv_view v, i
     for (int pi = tid; pi < np; pi += 256) {
       uint32_t e = v.slot_mask[tb + pi] >> 16;
       const int first = pre[pi];
-      if (k >= first && k < first + __popc(e)) {   // exactly one page of the list
+      if (k >= first && k < first + (int)__popc(e)) {   // exactly one page of the list
         for (int j = k - first; j > 0; --j) e &= e - 1;
         s_pid[t] = v.block_table[tb + pi];
         s_slot[t] = __ffs(e) - 1;
