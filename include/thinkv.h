@@ -245,7 +245,7 @@ int thinkv_decode_attention_valu(const thinkv_view* view, int32_t layer, const v
  *                        survives -- ready for thinkv_evict(view, layer, tok_seq, ev_handle, n_tok),
  *                        which skips entries of -1
  *   workspace            at least thinkv_tbe_workspace_bytes(cfg, n_tok, n_seg)
- * Arithmetic is binary32, squared distances taken as |x|^2 - 2 x.c + |c|^2; a decision between
+ * Arithmetic is binary32 (products of 22-bit operands), squared distances taken as |x|^2 - 2 x.c + |c|^2; a decision between
  * two candidates whose distances differ by less than about 1e-5 of the points' mean squared norm
  * may differ from a binary64 evaluation.  Device-side errors: THINKV_ST_BAD_SLOT / BAD_SEQ for a token that
  * does not exist (it clusters as the origin and is never evicted), THINKV_ST_BAD_SEGMENT (in the

@@ -17,8 +17,10 @@
 // Two kernels.  gather: one workgroup per token writes its key row [Hkv * D] into the workspace.
 // kmeans: one workgroup of eight waves per segment (segments hold at most 256 live tokens, the
 // schedule keeps at most 64).  Squared distances are taken as |x|^2 - 2 x.c + |c|^2 with the
-// products x.c of all points with all centroids on the matrix cores in binary32 (the error of the
-// expansion is of the order of 1e-6 of |x|^2, far below the gaps that separate genuine decisions);
+// products x.c of all points with all centroids on the matrix cores; a dequantised key does not
+// fit binary16 and the binary32 matrix instruction is slow, so every number enters as the sum of
+// two binary16 parts (22 significant bits) and a product is three binary16 MFMAs.  The error of
+// all this is of the order of 1e-6 of |x|^2, far below the gaps that separate genuine decisions;
 // an assignment only needs |c|^2 - 2 x.c.  The channels go through LDS 64 at a time, the centroid
 // update is folded into the next pass over the channels (a cluster's members are summed from the
 // point tile that is in LDS anyway, in index order, so the result is the same on every run), and
@@ -30,7 +32,6 @@ namespace thinkv {
 constexpr int kTbeMaxTokens = THINKV_TBE_MAX_SEGMENT;   // live tokens of one segment
 constexpr int kTbeMaxKeep = THINKV_TBE_MAX_KEEP;        // largest retention level
 constexpr int kTile = 64;                               // channels per LDS tile
-constexpr int kPad = 68;                                // row stride of a tile in floats (odd multiple of 16 bytes)
 
 struct TbeArgs {
   const int32_t* tok_seq;
@@ -91,15 +92,35 @@ constexpr int kKmThreads = 512;           // eight waves: two per SIMD, so that 
 constexpr int kRBW = kRB / 2;             // row blocks per wave: wave w takes blocks 2 t + w / 4
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+constexpr int kPadH = 2 * kTile + 8;   // binary16 numbers per tile row: high parts, low parts, padding (an odd multiple of 16 bytes)
+
 struct KmScratch {
-  float xs[kTbeMaxTokens][kPad];    // one tile: 64 channels of every point ...
-  float cs[kTbeMaxKeep][kPad];      // ... and of every centroid
-  float xx[kTbeMaxTokens];          // squared norms of the points
-  float cc[kTbeMaxKeep];            // squared norms of the centroids
-  int cnt[kTbeMaxKeep];             // members of every cluster,
-  int start[kTbeMaxKeep];           // where its members begin in order[],
-  int order[kTbeMaxTokens];         // and the points cluster by cluster, in index order inside a cluster
+  _Float16 xs[kTbeMaxTokens][kPadH];   // one tile: 64 channels of every point, each as high + low binary16 part ...
+  _Float16 cs[kTbeMaxKeep][kPadH];     // ... and of every centroid
+  float xx[kTbeMaxTokens];             // squared norms of the points
+  float cc[kTbeMaxKeep];               // squared norms of the centroids
+  int cnt[kTbeMaxKeep];                // members of every cluster,
+  int start[kTbeMaxKeep];              // where its members begin in order[],
+  int order[kTbeMaxTokens];            // and the points cluster by cluster, in index order inside a cluster
 };
+
+// four channels into a tile row: x = hi + lo with hi = binary16(x), lo = binary16(x - hi), 22 significant bits
+__device__ inline void store_split(_Float16* row, int c, float4 v) {
+  const f16x4 hi = {(_Float16)v.x, (_Float16)v.y, (_Float16)v.z, (_Float16)v.w};
+  const f16x4 lo = {(_Float16)(v.x - (float)hi[0]), (_Float16)(v.y - (float)hi[1]), (_Float16)(v.z - (float)hi[2]),
+                    (_Float16)(v.w - (float)hi[3])};
+  *(f16x4*)&row[c] = hi;
+  *(f16x4*)&row[kTile + c] = lo;
+}
+
+// eight channels of a tile row back as binary32 (hi + lo)
+__device__ inline void load_joined(const _Float16* row, int c, float* out) {
+  const f16x8 hi = *(const f16x8*)&row[c], lo = *(const f16x8*)&row[kTile + c];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) out[e] = (float)hi[e] + (float)lo[e];
+}
 
 // One pass over the channels, 64 at a time through LDS (the loads of the next tile are in flight
 // while the current one is worked on):
@@ -107,11 +128,14 @@ struct KmScratch {
 //           index order, times 1 / count), tile by tile, from the point tile that is in LDS anyway;
 //           the moved rows go back to cent[] so that a cluster that later loses all its members
 //           still finds its centroid there
-//   dots    dot[p][j] of all points with all centroids on the matrix cores
-//           (v_mfma_f32_16x16x4_f32, binary32 in and out): wave w owns clusters 16 (w % 4) ..
-//           + 15 and every second row block of 16 points (blocks 2 t + w / 4); after the call lane l
-//           holds, in acc[t][i], the product of point 16 (2 t + w / 4) + 4 (l / 16) + i with cluster
-//           16 (w % 4) + l % 16
+//   dots    dot[p][j] of all points with all centroids on the matrix cores.  The binary32 matrix
+//           instruction is slow (a sixteenth of the binary16 rate), and binary16 alone cannot hold a
+//           dequantised key, so every number enters as the sum of two binary16 parts and a product
+//           is taken as hi.hi + hi.lo + lo.hi on v_mfma_f32_16x16x32_f16 (exact products, binary32
+//           sums; what is dropped is of the order of 2^-22 of |x||c|).  Wave w owns clusters
+//           16 (w % 4) .. + 15 and every second row block of 16 points (blocks 2 t + w / 4); after
+//           the call lane l holds, in acc[t][i], the product of point 16 (2 t + w / 4) + 4 (l / 16) + i
+//           with cluster 16 (w % 4) + l % 16
 //   norms   squared norms of the centroids, and of the points when first is set (they do not move)
 __device__ inline void pass_over_channels(const float* __restrict__ x, float* __restrict__ cent, int n, int k, int dim, bool first,
                                           bool update, KmScratch& sm, f32x4 (&acc)[kRBW]) {
@@ -152,72 +176,76 @@ __device__ inline void pass_over_channels(const float* __restrict__ x, float* __
     for (int q = 0; q < kXQ; ++q)
       if (q < xq) {
         const int idx = tid + kKmThreads * q;
-        *(float4*)&sm.xs[idx / kC4][4 * (idx % kC4)] = px[q];
+        store_split(sm.xs[idx / kC4], 4 * (idx % kC4), px[q]);
       }
 #pragma unroll
     for (int q = 0; q < kCQ; ++q) {
       const int idx = tid + kKmThreads * q;
-      *(float4*)&sm.cs[idx / kC4][4 * (idx % kC4)] = pc[q];
+      store_split(sm.cs[idx / kC4], 4 * (idx % kC4), pc[q]);
     }
     __syncthreads();
     if (d0 + kTile < dim) fetch(d0 + kTile);
     if (update) {
       if (um > 0) {
-        float4 sum[2];
+        float sum[8];
 #pragma unroll
-        for (int c4 = 0; c4 < 2; ++c4) sum[c4] = zero4;
+        for (int e = 0; e < 8; ++e) sum[e] = 0.f;
         for (int i = 0; i < um; ++i) {
-          const int row = sm.order[ust + i];
+          float t[8];
+          load_joined(sm.xs[sm.order[ust + i]], 8 * upart, t);
 #pragma unroll
-          for (int c4 = 0; c4 < 2; ++c4) {
-            const float4 t = *(const float4*)&sm.xs[row][8 * upart + 4 * c4];
-            sum[c4].x += t.x; sum[c4].y += t.y; sum[c4].z += t.z; sum[c4].w += t.w;
-          }
+          for (int e = 0; e < 8; ++e) sum[e] += t[e];
         }
-#pragma unroll
-        for (int c4 = 0; c4 < 2; ++c4) {
-          const float4 m = make_float4(sum[c4].x * uinv, sum[c4].y * uinv, sum[c4].z * uinv, sum[c4].w * uinv);
-          *(float4*)&sm.cs[uj][8 * upart + 4 * c4] = m;
-          *(float4*)&cent[(int64_t)uj * dim + d0 + 8 * upart + 4 * c4] = m;
-        }
+        const float4 m0 = make_float4(sum[0] * uinv, sum[1] * uinv, sum[2] * uinv, sum[3] * uinv);
+        const float4 m1 = make_float4(sum[4] * uinv, sum[5] * uinv, sum[6] * uinv, sum[7] * uinv);
+        store_split(sm.cs[uj], 8 * upart, m0);
+        store_split(sm.cs[uj], 8 * upart + 4, m1);
+        *(float4*)&cent[(int64_t)uj * dim + d0 + 8 * upart] = m0;
+        *(float4*)&cent[(int64_t)uj * dim + d0 + 8 * upart + 4] = m1;
       }
       __syncthreads();
     }
     if (first && tid < n) {
 #pragma unroll
-      for (int c4 = 0; c4 < kC4; ++c4) {
-        const float4 t = *(const float4*)&sm.xs[tid][4 * c4];
-        nx = fmaf(t.w, t.w, fmaf(t.z, t.z, fmaf(t.y, t.y, fmaf(t.x, t.x, nx))));
+      for (int c8 = 0; c8 < kTile / 8; ++c8) {
+        float t[8];
+        load_joined(sm.xs[tid], 8 * c8, t);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) nx = fmaf(t[e], t[e], nx);
       }
     }
-    if (tid < k) {
+    if (uj < k) {   // the eight channels of thread (cluster, part), as the products will see them
+      float t[8];
+      load_joined(sm.cs[uj], 8 * upart, t);
 #pragma unroll
-      for (int c4 = 0; c4 < kC4; ++c4) {
-        const float4 t = *(const float4*)&sm.cs[tid][4 * c4];
-        nc = fmaf(t.w, t.w, fmaf(t.z, t.z, fmaf(t.y, t.y, fmaf(t.x, t.x, nc))));
-      }
+      for (int e = 0; e < 8; ++e) nc = fmaf(t[e], t[e], nc);
     }
     if (16 * cb < k) {
 #pragma unroll
-      for (int kk = 0; kk < kTile / 16; ++kk) {
-        // lane (r, g) holds channels 16 kk + 4 g .. + 3 of its row: component c of every lane forms one
-        // four-channel step, the same channels on both sides
-        const float4 bv = *(const float4*)&sm.cs[16 * cb + r][16 * kk + 4 * g];
+      for (int ks = 0; ks < kTile / 32; ++ks) {
+        // lane (r, g) holds channels 32 ks + 8 g .. + 7 of its row, on both sides
+        const f16x8 bh = *(const f16x8*)&sm.cs[16 * cb + r][32 * ks + 8 * g];
+        const f16x8 bl = *(const f16x8*)&sm.cs[16 * cb + r][kTile + 32 * ks + 8 * g];
 #pragma unroll
         for (int t = 0; t < kRBW; ++t)
           if (2 * t + half < rbs) {
-            const float4 av = *(const float4*)&sm.xs[16 * (2 * t + half) + r][16 * kk + 4 * g];
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.x, bv.x, acc[t], 0, 0, 0);
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.y, bv.y, acc[t], 0, 0, 0);
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.z, bv.z, acc[t], 0, 0, 0);
-            acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av.w, bv.w, acc[t], 0, 0, 0);
+            const _Float16* row = sm.xs[16 * (2 * t + half) + r];
+            const f16x8 ah = *(const f16x8*)&row[32 * ks + 8 * g];
+            const f16x8 al = *(const f16x8*)&row[kTile + 32 * ks + 8 * g];
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh, acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bl, acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al, bh, acc[t], 0, 0, 0);
           }
       }
     }
   }
   __syncthreads();
   if (first && tid < n) sm.xx[tid] = nx;
-  if (tid < kTbeMaxKeep) sm.cc[tid] = tid < k ? nc : 0.f;
+  // the eight parts of a cluster's norm sit in eight neighbouring lanes
+  nc += __shfl_xor(nc, 1, 64);
+  nc += __shfl_xor(nc, 2, 64);
+  nc += __shfl_xor(nc, 4, 64);
+  if (upart == 0) sm.cc[uj] = uj < k ? nc : 0.f;
   __syncthreads();
 }
 
