@@ -15,7 +15,7 @@
 //              two members the earlier one: both are equally near their mean)
 //
 // Two kernels.  gather: one workgroup per token writes its key row [Hkv * D] into the workspace.
-// kmeans: one workgroup of eight waves per segment (segments hold at most 256 live tokens, the
+// kmeans: one workgroup of sixteen waves per segment (segments hold at most 256 live tokens, the
 // schedule keeps at most 64).  Squared distances are taken as |x|^2 - 2 x.c + |c|^2 with the
 // products x.c of all points with all centroids on the matrix cores; a dequantised key does not
 // fit binary16 and the binary32 matrix instruction is slow, so every number enters as the sum of
@@ -88,8 +88,9 @@ __global__ __launch_bounds__(256) void tbe_gather_kernel(thinkv_view v, TbeArgs 
 // ---- kmeans
 constexpr int kPT = kTbeMaxTokens / 64;   // points per lane at most: lane L looks after points L, L + 64, ...
 constexpr int kRB = kTbeMaxTokens / 16;   // 16-point row blocks of the distance matrix at most
-constexpr int kKmThreads = 512;           // eight waves: two per SIMD, so that one multiplies while the other waits for LDS
-constexpr int kRBW = kRB / 2;             // row blocks per wave: wave w takes blocks 2 t + w / 4
+constexpr int kKmThreads = 1024;          // sixteen waves, four per SIMD: the staging of a tile is mostly waiting
+constexpr int kRowSplit = kKmThreads / 256;   // waves that share a cluster quarter and split the row blocks
+constexpr int kRBW = kRB / kRowSplit;     // row blocks per wave: wave w takes blocks kRowSplit t + w / 4
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -133,8 +134,8 @@ __device__ inline void load_joined(const _Float16* row, int c, float* out) {
 //           dequantised key, so every number enters as the sum of two binary16 parts and a product
 //           is taken as hi.hi + hi.lo + lo.hi on v_mfma_f32_16x16x32_f16 (exact products, binary32
 //           sums; what is dropped is of the order of 2^-22 of |x||c|).  Wave w owns clusters
-//           16 (w % 4) .. + 15 and every second row block of 16 points (blocks 2 t + w / 4); after
-//           the call lane l holds, in acc[t][i], the product of point 16 (2 t + w / 4) + 4 (l / 16) + i
+//           16 (w % 4) .. + 15 and every fourth row block of 16 points (blocks 4 t + w / 4); after
+//           the call lane l holds, in acc[t][i], the product of point 16 (4 t + w / 4) + 4 (l / 16) + i
 //           with cluster 16 (w % 4) + l % 16
 //   norms   squared norms of the centroids, and of the points when first is set (they do not move)
 __device__ inline void pass_over_channels(const float* __restrict__ x, float* __restrict__ cent, int n, int k, int dim, bool first,
@@ -228,8 +229,8 @@ __device__ inline void pass_over_channels(const float* __restrict__ x, float* __
         const f16x8 bl = *(const f16x8*)&sm.cs[16 * cb + r][kTile + 32 * ks + 8 * g];
 #pragma unroll
         for (int t = 0; t < kRBW; ++t)
-          if (2 * t + half < rbs) {
-            const _Float16* row = sm.xs[16 * (2 * t + half) + r];
+          if (kRowSplit * t + half < rbs) {
+            const _Float16* row = sm.xs[16 * (kRowSplit * t + half) + r];
             const f16x8 ah = *(const f16x8*)&row[32 * ks + 8 * g];
             const f16x8 al = *(const f16x8*)&row[kTile + 32 * ks + 8 * g];
             acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh, acc[t], 0, 0, 0);
@@ -245,7 +246,7 @@ __device__ inline void pass_over_channels(const float* __restrict__ x, float* __
   nc += __shfl_xor(nc, 1, 64);
   nc += __shfl_xor(nc, 2, 64);
   nc += __shfl_xor(nc, 4, 64);
-  if (upart == 0) sm.cc[uj] = uj < k ? nc : 0.f;
+  if (upart == 0 && uj < kTbeMaxKeep) sm.cc[uj] = uj < k ? nc : 0.f;
   __syncthreads();
 }
 
@@ -292,8 +293,8 @@ __global__ __launch_bounds__(kKmThreads) void tbe_kmeans_kernel(thinkv_view v, T
     const float ccj = my_cl < k ? sm.cc[my_cl] : 0.f;
 #pragma unroll
     for (int t = 0; t < kRBW; ++t)
-      if (2 * t + half < rbs) {
-        const int rb = 2 * t + half;
+      if (kRowSplit * t + half < rbs) {
+        const int rb = kRowSplit * t + half;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           float bd = my_cl < k ? fmaf(-2.f, acc[t][i], ccj) : INFINITY;
@@ -387,10 +388,10 @@ __global__ __launch_bounds__(kKmThreads) void tbe_kmeans_kernel(thinkv_view v, T
     const float ccj = sm.cc[my_cl];
 #pragma unroll
     for (int t = 0; t < kRBW; ++t)
-      if (2 * t + half < rbs) {
+      if (kRowSplit * t + half < rbs) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int p = 16 * (2 * t + half) + 4 * g + i;
+          const int p = 16 * (kRowSplit * t + half) + 4 * g + i;
           if (p < n && s_assign[p] == my_cl) {   // this lane holds the point's product with its own cluster
             const float own = fmaxf(fmaf(-2.f, acc[t][i], sm.xx[p]) + ccj, 0.f);
             atomicAdd(&s_cnt[my_cl], 1);
