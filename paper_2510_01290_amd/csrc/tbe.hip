@@ -49,39 +49,59 @@ size_t tbe_ws_bytes(const thinkv_config& c, int n_tok, int n_seg) {
   return ((size_t)(n_tok > 0 ? n_tok : 1) * dim + (size_t)(n_seg > 0 ? n_seg : 1) * kTbeMaxKeep * dim) * sizeof(float) + 256;
 }
 
-// ---- gather: x[i][hd * D + ch] = the stored key of token i
+// ---- gather: x[i][hd * D + ch] = the stored key of token i.  A workgroup takes kGatherTokens tokens:
+// one thread per token walks the chain handle -> page list -> page, then all threads extract codes.
+constexpr int kGatherTokens = 8;
+
 __global__ __launch_bounds__(256) void tbe_gather_kernel(thinkv_view v, TbeArgs a) {
   const thinkv_config& c = v.cfg;
-  const int i = blockIdx.x, tid = threadIdx.x;
-  const int D = c.head_dim, H = c.n_kv_heads;
-  float* row = a.x + (int64_t)i * a.dim;
-  const int s = a.tok_seq[i];
-  const uint32_t uh = (uint32_t)a.tok_handle[i];
-  const int cls = uh >> 28, pi = (uh >> 4) & 0xFFFFFF, slot = uh & 15;
-  bool ok = s >= 0 && s < c.max_seqs;
-  if (!ok && tid == 0) atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEQ);
-  if (ok && (a.tok_handle[i] < 0 || cls > 2 || pi >= v.n_pages[npages_index(c, s, a.layer, cls)])) {
-    ok = false;
-    if (tid == 0) atomicOr(&v.dev_status[sl_index(c, s, a.layer)], THINKV_ST_BAD_SLOT);
+  const int tid = threadIdx.x, i0 = blockIdx.x * kGatherTokens;
+  const int D = c.head_dim, H = c.n_kv_heads, ld = D == 128 ? 7 : 6;
+  __shared__ int s_ok[kGatherTokens], s_cls[kGatherTokens], s_slot[kGatherTokens], s_pid[kGatherTokens];
+  if (tid < kGatherTokens) {
+    const int i = i0 + tid;
+    int ok = 0, cls = 0, slot = 0, pid = 0;
+    if (i < a.n_tok) {
+      const int s = a.tok_seq[i];
+      const int32_t h = a.tok_handle[i];
+      const uint32_t uh = (uint32_t)h;
+      cls = uh >> 28;
+      slot = uh & 15;
+      const int pi = (uh >> 4) & 0xFFFFFF;
+      if (s < 0 || s >= c.max_seqs) {
+        atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEQ);
+      } else if (h < 0 || cls > 2 || pi >= v.n_pages[npages_index(c, s, a.layer, cls)]) {
+        atomicOr(&v.dev_status[sl_index(c, s, a.layer)], THINKV_ST_BAD_SLOT);
+      } else {
+        pid = v.block_table[table_base(c, s, a.layer, cls) + pi];
+        ok = 1;
+      }
+    }
+    s_ok[tid] = ok; s_cls[tid] = cls; s_slot[tid] = slot; s_pid[tid] = pid;
   }
-  if (!ok) {   // a token that does not exist clusters as the origin and is never evicted
-    for (int idx = tid; idx < a.dim; idx += 256) row[idx] = 0.f;
-    return;
-  }
-  const int bits = c.bits_of_class[cls], FPH = 16 / bits;
-  const uint32_t mask = (1u << bits) - 1u;
-  const BlockGeom g = block_geom(bits, D);
-  const int pid = v.block_table[table_base(c, s, a.layer, cls) + pi];
-  const uint8_t* page = v.arena[cls] + (int64_t)pid * H * g.block_bytes;
-  for (int idx = tid; idx < a.dim; idx += 256) {
-    const int hd = idx / D, ch = idx % D;
-    const uint8_t* blk = page + (int64_t)hd * g.block_bytes;
-    const int grp = ch >> 5, chunk = 16 * ((ch & 31) >> 3) + slot;
-    const int f = 4 * grp + ((ch & 7) >> 1), bit = 32 * (f / FPH) + 16 * (ch & 1) + bits * (f % FPH);
-    const uint32_t word = ((const uint32_t*)(blk + g.k_codes + chunk * g.chunk_bytes))[bit >> 5];
-    const float code = (float)((word >> (bit & 31)) & mask);
-    const _Float16* meta = (const _Float16*)(blk + g.k_meta);
-    row[idx] = fmaf(code, (float)meta[meta_index(slot, grp)], (float)meta[meta_index(slot, grp) + 4]);
+  __syncthreads();
+  for (int t = 0; t < kGatherTokens && i0 + t < a.n_tok; ++t) {
+    float* row = a.x + (int64_t)(i0 + t) * a.dim;
+    if (!s_ok[t]) {   // a token that does not exist clusters as the origin and is never evicted
+      for (int idx = tid; idx < a.dim; idx += 256) row[idx] = 0.f;
+      continue;
+    }
+    const int cls = s_cls[t], slot = s_slot[t];
+    const int bits = c.bits_of_class[cls];
+    const int lb = bits == 8 ? 3 : (bits == 4 ? 2 : 1), lf = 4 - lb;   // log2 of the bits per code and of the fields per half word
+    const uint32_t mask = (1u << bits) - 1u;
+    const BlockGeom g = block_geom(bits, D);
+    const uint8_t* page = v.arena[cls] + (int64_t)s_pid[t] * H * g.block_bytes;
+    for (int idx = tid; idx < a.dim; idx += 256) {
+      const int hd = idx >> ld, ch = idx & (D - 1);
+      const uint8_t* blk = page + (int64_t)hd * g.block_bytes;
+      const int grp = ch >> 5, chunk = 16 * ((ch & 31) >> 3) + slot;
+      const int f = 4 * grp + ((ch & 7) >> 1), bit = 32 * (f >> lf) + 16 * (ch & 1) + ((f & ((1 << lf) - 1)) << lb);
+      const uint32_t word = ((const uint32_t*)(blk + g.k_codes + chunk * g.chunk_bytes))[bit >> 5];
+      const float code = (float)((word >> (bit & 31)) & mask);
+      const _Float16* meta = (const _Float16*)(blk + g.k_meta);
+      row[idx] = fmaf(code, (float)meta[meta_index(slot, grp)], (float)meta[meta_index(slot, grp) + 4]);
+    }
   }
 }
 
@@ -432,7 +452,7 @@ int launch_tbe_select(const thinkv_view& v, int layer, const int32_t* tok_seq, c
   a.n_seg = n_seg;
   a.n_tok = n_tok;
   a.max_iters = max_iters;
-  hipLaunchKernelGGL(tbe_gather_kernel, dim3(n_tok), dim3(256), 0, st, v, a);
+  hipLaunchKernelGGL(tbe_gather_kernel, dim3((n_tok + kGatherTokens - 1) / kGatherTokens), dim3(256), 0, st, v, a);
   hipLaunchKernelGGL(tbe_kmeans_kernel, dim3(n_seg), dim3(kKmThreads), 0, st, v, a);
   return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
 }
