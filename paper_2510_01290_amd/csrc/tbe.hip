@@ -527,29 +527,55 @@ __device__ inline int segment_of(const int* starts, int n, int pos) {
   return lo - 1;
 }
 
-// calls f(segment, position, handle) for every live token of the sequence; every thread takes pages
+// calls f(segment, position, handle) for every live token of the sequence; every thread takes pages.
+// The walk is a chain of dependent loads (page count -> live mask and page id -> the page's sixteen
+// positions) and little else, so the chains of the three page lists run side by side.
 template <typename F>
 __device__ inline void for_live_tokens(const thinkv_view& v, int seq, int layer, const int* s_start, int ns, F f) {
   const thinkv_config& c = v.cfg;
-  for (int k = 0; k < 3; ++k) {
-    const int np = v.n_pages[npages_index(c, seq, layer, k)];
-    const int64_t tb = table_base(c, seq, layer, k);
-    for (int pi = threadIdx.x; pi < np; pi += blockDim.x) {
-      const uint32_t m = v.slot_mask[tb + pi] & 0xFFFFu;
-      if (!m) continue;
-      const int pid = v.block_table[tb + pi];
-      const int4* sp = (const int4*)(v.slot_pos[k] + (int64_t)pid * kPage);
-      int pos[kPage];
+  int np[3], most = 0;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int4 w = sp[q];
-        pos[4 * q] = w.x; pos[4 * q + 1] = w.y; pos[4 * q + 2] = w.z; pos[4 * q + 3] = w.w;
+  for (int k = 0; k < 3; ++k) {
+    np[k] = v.n_pages[npages_index(c, seq, layer, k)];
+    most = np[k] > most ? np[k] : most;
+  }
+  for (int pi = threadIdx.x; pi < most; pi += blockDim.x) {
+    uint32_t m[3];
+    int pid[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      const bool in = pi < np[k];
+      const int64_t at = table_base(c, seq, layer, k) + (in ? pi : 0);
+      m[k] = in ? v.slot_mask[at] & 0xFFFFu : 0u;
+      pid[k] = in ? v.block_table[at] : 0;
+    }
+    int pos[3][kPage];
+#pragma unroll
+    for (int k = 0; k < 3; ++k)
+      if (m[k]) {
+        const int4* sp = (const int4*)(v.slot_pos[k] + (int64_t)pid[k] * kPage);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int4 w = sp[q];
+          pos[k][4 * q] = w.x; pos[k][4 * q + 1] = w.y; pos[k][4 * q + 2] = w.z; pos[k][4 * q + 3] = w.w;
+        }
       }
 #pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      if (!m[k]) continue;
+      // neighbours in a page are mostly neighbours in the sequence: the segment of the slot before is
+      // tried first (two LDS reads), the binary search (eleven dependent ones) only when that fails
+      int sg = -1, lo_pos = 0, hi_pos = -1;   // [lo_pos, hi_pos): positions of segment sg
+#pragma unroll
       for (int slot = 0; slot < kPage; ++slot) {
-        if (!(m >> slot & 1)) continue;
-        const int sg = segment_of(s_start, ns, pos[slot]);
-        if (sg >= 0) f(sg, pos[slot], THINKV_HANDLE(k, pi, slot));
+        if (!(m[k] >> slot & 1)) continue;
+        const int p = pos[k][slot];
+        if (p < lo_pos || p >= hi_pos) {
+          sg = segment_of(s_start, ns, p);
+          lo_pos = sg >= 0 ? s_start[sg] : 0;
+          hi_pos = sg >= 0 ? (sg + 1 < ns ? s_start[sg + 1] : 0x7fffffff) : -1;
+        }
+        if (sg >= 0) f(sg, p, THINKV_HANDLE(k, pi, slot));
       }
     }
   }
