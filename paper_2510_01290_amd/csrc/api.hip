@@ -121,6 +121,7 @@ static int decode_common(const thinkv_view* view, int32_t layer, const void* q, 
   a.stat = nullptr;
   a.stat_stride = 0;
   a.sparsity = sparsity;
+  a.direct = fast && !sparsity && a.max_split == 1;   // short contexts: one item per query, no merge launch
   hipStream_t st = (hipStream_t)stream;
   if (sparsity) {
     // pooled scores behind the partials (whose size is a multiple of 16 bytes)
@@ -135,7 +136,7 @@ static int decode_common(const thinkv_view* view, int32_t layer, const void* q, 
     return launch_stat_count(*view, a, st);
   }
   rc = fast ? launch_decode_mfma(*view, a, st) : launch_decode_simple(*view, a, st);
-  if (rc) return rc;
+  if (rc || a.direct) return rc;
   return launch_decode_merge(*view, a, st);
 }
 

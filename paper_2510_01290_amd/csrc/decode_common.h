@@ -30,6 +30,7 @@ struct DecodeArgs {
   float* stat;          // [B][n_kv_heads][stat_stride] pooled scores, 16 per page in page-list order (types 0, 1, 2)
   int64_t stat_stride;  // floats per (query, kv-head): 16 * max_ctx_pages
   float* sparsity;      // [B]
+  int direct;           // 1: every query has a single item (max_split == 1) and the attention kernel writes out / lse itself
 };
 
 struct ItemPlan {

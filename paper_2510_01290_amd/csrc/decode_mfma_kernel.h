@@ -522,7 +522,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
     np_total += np[k];
   }
   const ItemPlan plan = plan_items(a.ppi, a.max_split, np_total);
-  if (item_j >= plan.n_items) return;
+  if (item_j >= plan.n_items) {
+    if (a.direct && item_j == 0) {   // no pages at all, and no merge kernel to say so
+      const int Hq0 = c.n_q_heads, G0 = Hq0 / c.n_kv_heads;
+      for (int i = threadIdx.x; i < G0 * D; i += 256) store_from_f32(a.out, ((int64_t)b * Hq0 + hkv * G0) * D + i, a.out_dtype, 0.f);
+      if (a.lse && threadIdx.x < G0) a.lse[(int64_t)b * Hq0 + hkv * G0 + threadIdx.x] = -INFINITY;
+    }
+    return;
+  }
   const int split = item_j;   // the item's row among the partials
   int u0, u1;
   item_units(plan, split, &u0, &u1);
@@ -630,6 +637,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
       L += lds.l[w][g] * f;
       A += lds.acc[w][g][ch] * f;
     }
+    if (a.direct) {   // the only item of its query: this is the result
+      store_from_f32(a.out, ((int64_t)b * Hq + hkv * G + g) * D + ch, a.out_dtype, L > 0.f ? A / L : 0.f);
+      if (a.lse && ch == 0) a.lse[(int64_t)b * Hq + hkv * G + g] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
+      continue;
+    }
     float* dst = a.partial + partial_index(a, Hq, D, b, hkv * G + g, split);
     dst[2 + ch] = A;
     if (ch == 0) {
@@ -637,6 +649,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
       dst[1] = L;
     }
   }
+  // (direct) the work queues of this (query, kv-head) are left empty for the next call: no other workgroup shares them
+  if (a.direct && tid < 4) v.work_counters[(((int64_t)a.layer * c.max_seqs + b) * c.n_kv_heads + hkv) * 4 + tid] = 0u;
 }
 
 template <int D, bool WIN, bool STAT>
