@@ -199,8 +199,9 @@ int thinkv_evict_append(const thinkv_view* view, int32_t layer, const int32_t* e
                         const void* k_new, const void* v_new, const int32_t* tok_seq, const int32_t* tok_pos,
                         const uint8_t* tok_class, int32_t* tok_handle, int32_t n_tok, thinkv_dtype in_dtype, void* workspace,
                         size_t workspace_bytes, void* stream) {
-  // a long eviction list, or no tokens to append: the two calls one after the other
-  if (n_tok <= 0 || n_ev <= 0 || n_ev > 4096) {
+  // a long eviction list (every plan workgroup reads all of it: one workgroup per sequence slot of the view), or no
+  // tokens to append: the two calls one after the other
+  if (n_tok <= 0 || n_ev <= 0 || n_ev > 4096 || (view && (int64_t)n_ev * view->cfg.max_seqs > (1 << 20))) {
     const int rc = thinkv_evict(view, layer, ev_seq, ev_handle, n_ev, stream);
     if (rc) return rc;
     return thinkv_append_quantized(view, layer, k_new, v_new, tok_seq, tok_pos, tok_class, tok_handle, n_tok, in_dtype, workspace,
