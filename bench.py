@@ -16,7 +16,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK = 8.0e12
 # HBM bytes of one decode-attention launch (split-K kernel + merge) on the default workload, from
@@ -54,13 +53,12 @@ def main():
     import torch
     from paper_2510_01290_amd import binding as B
     from paper_2510_01290_amd import synth
-    import backends
-    import parity
+    from paper_2510_01290_amd import harness
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.workload != "cfg2-32k":
-        print(json.dumps(attention_only(args, np, torch, B, synth, parity, dev)))
+        print(json.dumps(attention_only(args, np, torch, B, synth, harness, dev)))
         return
     n_extra = 20   # steps after the timed region, with every call bracketed by events
     nsteps = args.steps + args.warmup + 2 * n_extra
@@ -68,13 +66,13 @@ def main():
                                     name=f"cfg2-shape B={args.batch} ctx={args.ctx}")
     g = wl.geom
     # room for the timed appends
-    arena = tuple(int(x + args.batch * (nsteps // 16 + 2)) for x in backends.arena_need(wl))
-    maxp = backends.max_pages_need(wl) + nsteps // 16 + 2
+    arena = tuple(int(x + args.batch * (nsteps // 16 + 2)) for x in harness.arena_need(wl))
+    maxp = harness.max_pages_need(wl) + nsteps // 16 + 2
     t0 = time.time()
     gcs = []
     for _ in range(max(1, args.replicas)):
-        gc_r = parity.make_gpu_cache(wl, arena_pages=arena, max_pages=maxp)
-        gr = synth.ScriptRunner(wl, parity.GpuBackend(gc_r)).run()       # the same script: same handles in every copy
+        gc_r = harness.make_gpu_cache(wl, arena_pages=arena, max_pages=maxp)
+        gr = synth.ScriptRunner(wl, harness.GpuBackend(gc_r)).run()       # the same script: same handles in every copy
         gcs.append(gc_r)
     gc = gcs[0]
     torch.cuda.synchronize()
@@ -312,7 +310,7 @@ def main():
             torch.add(src, 1, out=dst)
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(wl, args, nsteps, ev_handles, new_cls, np, torch, synth, parity)
+        line["cpu_baseline"] = cpu_baseline(wl, args, nsteps, ev_handles, new_cls, np, torch, synth)
     print(json.dumps(line))
 
 
@@ -368,7 +366,7 @@ def gather_contrast(args, np, torch, dev, g, attention):
             "in_place_reuse_bytes_moved": 0}
 
 
-def attention_only(args, np, torch, B, synth, parity, dev):
+def attention_only(args, np, torch, B, synth, harness, dev):
     """Decode attention alone on one of the other configurations: the cache is built by the
     configuration's own script (bulk append, eviction, refill or budgeted decode), then a step is
     one attention call per built layer for the whole batch."""
@@ -379,8 +377,8 @@ def attention_only(args, np, torch, B, synth, parity, dev):
           "cfg5": lambda: synth.config_stress(n_layers=2, n_steps=32)}[args.workload]()
     g = wl.geom
     t0 = time.time()
-    gc = parity.make_gpu_cache(wl)
-    synth.ScriptRunner(wl, parity.GpuBackend(gc)).run()
+    gc = harness.make_gpu_cache(wl)
+    synth.ScriptRunner(wl, harness.GpuBackend(gc)).run()
     torch.cuda.synchronize()
     assert int(gc.dev_status.abs().sum().item()) == 0, "device flags set while building the cache"
     # Copies of the cache to rotate over, so that a call does not find its pages in the 256 MB
@@ -389,8 +387,8 @@ def attention_only(args, np, torch, B, synth, parity, dev):
     n_rep = int(min(4, max(1, -(-(1 << 30) // max(stored, 1)))))
     gcs = [gc]
     for _ in range(n_rep - 1):
-        gcs.append(parity.make_gpu_cache(wl))
-        synth.ScriptRunner(wl, parity.GpuBackend(gcs[-1])).run()
+        gcs.append(harness.make_gpu_cache(wl))
+        synth.ScriptRunner(wl, harness.GpuBackend(gcs[-1])).run()
     torch.cuda.synchronize()
     build_s = time.time() - t0
     L, S = g.n_layers, wl.n_seqs
@@ -475,7 +473,7 @@ def attention_only(args, np, torch, B, synth, parity, dev):
     }
 
 
-def cpu_baseline(wl, args, nsteps, ev_handles, new_cls, np, torch, synth, parity):
+def cpu_baseline(wl, args, nsteps, ev_handles, new_cls, np, torch, synth):
     """The oracle as it stands, timed on this machine's host cores on ONE sequence of the same
     workload (sequence 0: its full build is replayed untimed, then whole steps are timed)."""
     from oracle import attention as oattn
@@ -505,7 +503,7 @@ def cpu_baseline(wl, args, nsteps, ev_handles, new_cls, np, torch, synth, parity
         live = oc.stored_bytes_live(0, 0)
         done += 1
     dt = time.perf_counter() - t0
-    return {"value": live * done / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+    return {"value": live * done / dt / 1e9, "unit": "GB/s", "cores": cores, "blas_threads": blas_threads, "kind": "oracle",
             "seconds_per_sequence_step": dt / done,
             "sample": f"{done} whole steps (evict 1, append 1, binary64 attention) of sequence 0 of the same workload "
                       f"({int(oc.n_live[0, 0])} live tokens); a batch step costs {args.batch}x this"}
