@@ -54,35 +54,68 @@ static int check_view(const thinkv_view* v) {
   return THINKV_OK;
 }
 
-// Work-item sizes.  A compute unit holds three workgroups of the decode kernel, so the chip
-// holds 768, and every item pays a fixed price (query set-up, three type switches, fold) worth
-// about a fifth of a 180-page item.  Where the launch has few (query, kv-head) pairs the items
-// are therefore sized so that the workgroups of the longest sequences fill the chip exactly
-// once; where it has many, so that the launch runs about four rounds of equal items, whose
-// end is levelled well enough by their number.  The floor keeps the set-up small against the item.
-constexpr int kMinPagesPerItem = 32;
-
+// Work-item sizes.  The fast kernel's items are single waves (TKV_WAVES of them per SIMD); the
+// plain kernel's are workgroups of four waves, three to a compute unit.  An item pays a fixed
+// price (query set-up, three type switches, its partial row), so it is given at least a few page
+// pairs.  Where the launch has few (query, kv-head) pairs, the items of the longest sequence fill
+// the machine exactly once; where it has many, an item per so many pages, about sixteen rounds of
+// them if every sequence were as long as the host's bound: on full-attention layers the items of
+// a head share its queues, so late items simply find less to do.
 // A sliding-window layer is another matter: only the pages that hold one of the last W positions
 // are worked on, the rest of the page list is merely scanned (a few bytes a page), so the fixed
-// price of an item dominates.  There an item scans at least 256 pages (64 per wave), and a
-// (query, kv-head) gets several items only while that still fills the chip once.
-static int pages_per_item(const thinkv_config& c, int B, int max_ctx_pages, int window) {
-  const int64_t heads = (int64_t)B * c.n_kv_heads;
-  int64_t n_items = heads <= 384 ? 768 / heads : (4 * 768 + heads - 1) / heads;   // items per (query, kv-head)
-  if (window > 0) {
-    n_items = 768 / heads;
-    const int64_t most = (max_ctx_pages + 255) / 256;
-    if (n_items > most) n_items = most;
+// price of an item dominates: an item scans at least 64 pages per wave.
+static int compute_units() {
+  static int cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+  if (cached[dev] == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    cached[dev] = cus;
   }
-  if (n_items < 1) n_items = 1;
-  int ppi = (int)((max_ctx_pages + n_items - 1) / n_items);
-  return ppi < kMinPagesPerItem ? kMinPagesPerItem : ppi;
+  return cached[dev];
 }
 
-// grid extents for sequences of at most max_ctx_pages pages
-static int split_bound(int max_ctx_pages, int ppi) {
-  const ItemPlan p = plan_items(ppi, 1 << 30, max_ctx_pages);
-  return p.n_items > 0 ? p.n_items : 1;
+struct ItemSizing {
+  int n_rows, per_head, ppi;
+};
+
+static ItemSizing size_items(const thinkv_config& c, int B, int max_ctx_pages, int window, bool fast) {
+  const int64_t heads = (int64_t)B * c.n_kv_heads;
+  const int64_t resident = fast ? (int64_t)compute_units() * 4 * TKV_WAVES : (int64_t)compute_units() * 3;
+  const int least = window > 0 ? (fast ? 64 : 256) : (fast ? 16 : 32);   // fewest pages worth an item
+  int64_t cap = ((int64_t)max_ctx_pages + least - 1) / least;
+  if (cap < 1) cap = 1;
+  if (cap > kMaxRowsPerHead) cap = kMaxRowsPerHead;
+  int64_t per_head;
+  if (heads * 2 <= resident || window > 0)
+    per_head = resident / heads;
+  else
+    per_head = ((fast ? 16 : 4) * resident + heads - 1) / heads;
+  if (per_head > cap) per_head = cap;
+  if (per_head < 1) per_head = 1;
+  ItemSizing z;
+  z.per_head = (int)per_head;
+  z.n_rows = (int)(per_head * heads);
+  z.ppi = (int)(((int64_t)max_ctx_pages + per_head - 1) / per_head);
+  if (z.ppi < 1) z.ppi = 1;
+  return z;
+}
+
+// partial rows any decode call with these bounds can need
+static int64_t rows_bound(const thinkv_config& c, int B, int max_ctx_pages) {
+  int64_t most = 1;
+  for (int fast = 0; fast < 2; ++fast)
+    for (int window = 0; window < 2; ++window) {
+      const ItemSizing z = size_items(c, B, max_ctx_pages, window, fast != 0);
+      if (z.n_rows > most) most = z.n_rows;
+    }
+  return most;
+}
+
+static size_t partial_bytes_of(const thinkv_config& c, int64_t rows) {
+  const int G = c.n_q_heads / c.n_kv_heads;
+  return (size_t)rows * G * (c.head_dim + kRowPad) * sizeof(float);
 }
 
 static int decode_common(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
@@ -98,10 +131,10 @@ static int decode_common(const thinkv_view* view, int32_t layer, const void* q, 
   if (!q || !out || !seq_ids || !workspace || (window > 0 && !q_pos)) return THINKV_E_INVALID_ARG;
   if (q_dtype != THINKV_F16 && q_dtype != THINKV_BF16) return THINKV_E_UNSUPPORTED;
   if (out_dtype != THINKV_F16 && out_dtype != THINKV_BF16 && out_dtype != THINKV_F32) return THINKV_E_UNSUPPORTED;
-  const size_t partial_bytes = thinkv_decode_workspace_bytes(&view->cfg, B, max_ctx_pages);
-  if (workspace_bytes < (sparsity ? thinkv_decode_sparsity_workspace_bytes(&view->cfg, B, max_ctx_pages) : partial_bytes)) return THINKV_E_WORKSPACE;
   fast = fast && decode_mfma_supported(view->cfg);
   if (sparsity && !fast) return THINKV_E_UNSUPPORTED;
+  const size_t partial_bytes = thinkv_decode_workspace_bytes(&view->cfg, B, max_ctx_pages);
+  if (workspace_bytes < (sparsity ? thinkv_decode_sparsity_workspace_bytes(&view->cfg, B, max_ctx_pages) : partial_bytes)) return THINKV_E_WORKSPACE;
   DecodeArgs a;
   a.q = q;
   a.out = out;
@@ -114,14 +147,17 @@ static int decode_common(const thinkv_view* view, int32_t layer, const void* q, 
   a.window = window;
   a.q_dtype = q_dtype;
   a.out_dtype = out_dtype;
-  a.ppi = pages_per_item(view->cfg, B, max_ctx_pages, window);
-  a.max_split = split_bound(max_ctx_pages, a.ppi);
-  if (a.max_split > 1024) return THINKV_E_SHAPE;   // merge kernel keeps one weight per item in LDS
+  const ItemSizing z = size_items(view->cfg, B, max_ctx_pages, window, fast);
+  a.n_rows = z.n_rows;
+  a.per_head = z.per_head;
+  a.ppi = z.ppi;
+  // the heads' first rows and row counts behind the partial rows
+  a.alloc = (int32_t*)((char*)workspace + ((partial_bytes_of(view->cfg, rows_bound(view->cfg, B, max_ctx_pages)) + 255) & ~(size_t)255));
   a.scale_log2e = softmax_scale * 1.4426950408889634f;
   a.stat = nullptr;
   a.stat_stride = 0;
   a.sparsity = sparsity;
-  a.direct = fast && !sparsity && a.max_split == 1;   // short contexts: one item per query, no merge launch
+  a.direct = fast && !sparsity && a.per_head == 1;   // short contexts or huge batches: one item per head, no merge launch
   hipStream_t st = (hipStream_t)stream;
   if (sparsity) {
     // pooled scores behind the partials (whose size is a multiple of 16 bytes)
@@ -162,9 +198,9 @@ size_t thinkv_append_workspace_bytes(const thinkv_config* cfg, int32_t n_tok) {
 
 size_t thinkv_decode_workspace_bytes(const thinkv_config* cfg, int32_t B, int32_t max_ctx_pages) {
   if (check_config(cfg) || B < 0 || max_ctx_pages < 0) return 0;
-  // the item size never drops below kMinPagesPerItem pages, whatever the batch
-  const int ms = split_bound(max_ctx_pages, kMinPagesPerItem);
-  return (size_t)(B > 0 ? B : 1) * cfg->n_q_heads * ms * (cfg->head_dim + 2) * sizeof(float);
+  // partial rows, then two words per (query, kv-head)
+  const int b1 = B > 0 ? B : 1;
+  return ((partial_bytes_of(*cfg, rows_bound(*cfg, b1, max_ctx_pages)) + 255) & ~(size_t)255) + (size_t)b1 * cfg->n_kv_heads * 2 * sizeof(int32_t) + 256;
 }
 
 size_t thinkv_decode_sparsity_workspace_bytes(const thinkv_config* cfg, int32_t B, int32_t max_ctx_pages) {

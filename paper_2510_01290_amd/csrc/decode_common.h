@@ -1,17 +1,23 @@
 // Split-K bookkeeping shared by the decode-attention kernels and the merge kernel.
 //
-// The context of one (query, kv-head) is cut into work items.  Item sizes are counted in
-// quarter units: the sequence's pages make U = ceil(4 * pages / ppi) units, dealt four at a time
-// to ceil(U / 4) items (about ppi pages each; the last item may be shorter).  An item takes the
-// same fraction [u0 / U, u1 / U) of each of the three per-type page lists, so items of one
-// sequence cost the same per unit whatever the precision mix.  (On full-attention layers the
-// fast kernel only uses the item count: there the workgroups of a (query, kv-head) draw their
-// pages from shared queues.)  ppi is chosen on the host; item counts are derived on the device
-// from the page counts, identically in the attention and merge kernels.  Each item writes, per
-// query head, a partial (m, l, acc[D]): running maximum of the scaled scores in the log2
-// domain, sum of 2^(score - m), and the unnormalised weighted value sum.
+// The context of one (query, kv-head) -- a "head" below -- is worked on by several items; each
+// item leaves, per query head of the group, one partial row (acc[D], m, l, two words of padding):
+// the unnormalised weighted value sum, the running maximum of the scaled scores in the log2
+// domain, and the sum of 2^(score - m).  The merge kernel folds the rows of a head.
+//
+// How many items a head gets is decided on the device from its page count, identically by every
+// kernel of a call: an item per `ppi` pages, at most `per_head` (both chosen by the host); the items
+// of a head that is short do not exist (their waves leave at once).  On full-attention layers the
+// fast kernel's items do not own pages: the items of a head draw page pairs from shared queues, so
+// an item is a worker and its count a share of the machine.  Elsewhere item j of n takes the same
+// fraction [j/n, (j+1)/n) of each of the three per-type lists.
 #pragma once
 #include "common.h"
+
+// waves per SIMD the fast kernel is built for (its register budget); the host sizes launches with the same number
+#ifndef TKV_WAVES
+#define TKV_WAVES 2
+#endif
 
 namespace thinkv {
 
@@ -21,53 +27,64 @@ struct DecodeArgs {
   float* lse;
   const int32_t* seq_ids;
   const int32_t* q_pos;
-  float* partial;       // [B][Hq][max_split][D + 2]
+  float* partial;       // [n_rows][G][D + 4]
+  int32_t* alloc;       // [B * n_kv_heads][2]: first row and number of rows of each head, written by its item 0
   int layer, B, window, q_dtype, out_dtype;
+  int n_rows;           // items (grid extent of the fast kernel, in waves), = per_head * B * n_kv_heads
+  int per_head;         // the most items a head can have
   int ppi;              // pages per item
-  int max_split;        // grid extent: items, hence partial rows, per (query, head) (>= the count of any sequence)
   float scale_log2e;    // softmax_scale * log2(e)
   // sparsity statistic (null / 0 on plain attention calls)
   float* stat;          // [B][n_kv_heads][stat_stride] pooled scores, 16 per page in page-list order (types 0, 1, 2)
   int64_t stat_stride;  // floats per (query, kv-head): 16 * max_ctx_pages
   float* sparsity;      // [B]
-  int direct;           // 1: every query has a single item (max_split == 1) and the attention kernel writes out / lse itself
+  int direct;           // 1: every head has a single item and the attention kernel writes out / lse itself
 };
 
-struct ItemPlan {
-  int n_items, units;
+constexpr int kMaxRowsPerHead = 1024;
+
+struct ItemLoc {
+  int b, hkv;   // the head
+  int j, n;     // item j of n
+  int row0;     // the head's first partial row
 };
 
-__host__ __device__ inline ItemPlan plan_items(int ppi, int max_items, int np_total) {
-  ItemPlan p;
-  p.units = (int)(((int64_t)np_total * 4 + ppi - 1) / ppi);
-  p.n_items = (p.units + 3) / 4;
-  if (p.n_items > max_items) p.n_items = max_items;   // never on a launch sized by the host's bound
-  return p;
+__device__ inline int seq_pages(const thinkv_view& v, int layer, int seq, int* np) {
+  const thinkv_config& c = v.cfg;
+  int tot = 0;
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    np[k] = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, layer, k)] : 0;
+    tot += np[k];
+  }
+  return tot;
 }
 
-// item i of the plan covers units [u0, u1) of p.units
-__device__ inline void item_units(const ItemPlan& p, int i, int* u0, int* u1) {
-  *u0 = 4 * i;
-  *u1 = 4 * i + 4 < p.units ? 4 * i + 4 : p.units;
-}
-
-// Workgroup id -> (query, kv-head, item j), item-major: ids [j * heads, (j + 1) * heads) are item
-// j of every head, and head h's item j sits at offset (h + j) mod heads of that run; the caller
-// checks j against the sequence's plan.  Two things follow.  The hardware starts workgroups in id order and a SIMD favours
-// its oldest wave, so the workgroups of the first third of a chip-filling launch run visibly faster
-// than those of the last third: item-major order gives every head workgroups of every age.  And
-// ids go round the XCDs (id mod 8), so the shift by j puts the items of a head on different XCDs.
-__device__ inline void locate_workgroup(const DecodeArgs& a, int n_kv_heads, int id, int* b, int* hkv, int* j) {
-  const int heads = n_kv_heads * a.B;
-  *j = id / heads;
-  int rest = id % heads - *j % heads;
+// Item id -> head, item number, item count, first row.  Item-major: ids [j * heads, (j + 1) * heads) are item j of every
+// head (the hardware starts workgroups in id order and a SIMD favours its oldest wave: every head gets workers of every
+// age), shifted by j so that the items of a head land on different XCDs (ids go round the XCDs).
+__device__ inline ItemLoc locate_item(const thinkv_view& v, const DecodeArgs& a, int id) {
+  const thinkv_config& c = v.cfg;
+  const int H = c.n_kv_heads, heads = H * a.B;
+  ItemLoc it;
+  it.j = id / heads;
+  int rest = id % heads - it.j % heads;
   if (rest < 0) rest += heads;
-  *hkv = rest % n_kv_heads;
-  *b = rest / n_kv_heads;
+  it.hkv = rest % H;
+  it.b = rest / H;
+  int np[3];
+  const int tot = seq_pages(v, a.layer, a.seq_ids[it.b], np);
+  int n = (int)(((int64_t)tot + a.ppi - 1) / a.ppi);
+  n = n < 1 ? 1 : (n > a.per_head ? a.per_head : n);
+  it.n = n;
+  it.row0 = rest * a.per_head;
+  return it;
 }
 
-__device__ inline int64_t partial_index(const DecodeArgs& a, int Hq, int D, int b, int hq, int split) {
-  return (((int64_t)b * Hq + hq) * a.max_split + split) * (D + 2);
+constexpr int kRowPad = 4;   // a partial row: acc[D], m, l, two unused words (rows stay 16-byte aligned)
+
+__device__ inline float* partial_row(const DecodeArgs& a, int G, int D, int row, int g) {
+  return a.partial + ((int64_t)row * G + g) * (D + kRowPad);
 }
 
 }  // namespace thinkv

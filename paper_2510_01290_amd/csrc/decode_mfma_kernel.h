@@ -41,6 +41,13 @@
 #pragma once
 #include "decode_common.h"
 
+#ifndef TKV_ABL
+#define TKV_ABL 0
+#endif
+#ifndef TKV_CHUNK
+#define TKV_CHUNK 4
+#endif
+
 namespace thinkv {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -130,9 +137,24 @@ struct PageRegs {
   uint4 km[NSET], vm[NSET];   // (scale 0|1, scale 2|3, zero-point 0|1, zero-point 2|3)
 };
 
+#ifndef TKV_NT
+#define TKV_NT 7   // bit 0: 2-bit pages, bit 1: 4-bit pages, bit 2: 8-bit pages read with non-temporal loads
+#endif
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+template <bool NT> __device__ __forceinline__ uint4 ld16(const void* p) {
+  if constexpr (NT) { const u32x4 w = __builtin_nontemporal_load((const u32x4*)p); return make_uint4(w.x, w.y, w.z, w.w); }
+  else return *(const uint4*)p;
+}
+template <bool NT> __device__ __forceinline__ uint2 ld8(const void* p) {
+  if constexpr (NT) { const u32x2 w = __builtin_nontemporal_load((const u32x2*)p); return make_uint2(w.x, w.y); }
+  else return *(const uint2*)p;
+}
+
 template <int D, int BITS, int NSET>
 __device__ __forceinline__ void load_page(PageRegs<D, BITS, NSET>& r, const uint8_t* blk, int lane, const int* meta_off) {
   constexpr int CW = PageRegs<D, BITS, NSET>::CW;
+  constexpr bool NT = ((TKV_NT >> (BITS == 2 ? 0 : (BITS == 4 ? 1 : 2))) & 1) != 0;
   const BlockGeom g = block_geom(BITS, D);
   const uint32_t* kc = (const uint32_t*)(blk + g.k_codes) + lane * CW;
   const uint32_t* vc = (const uint32_t*)(blk + g.v_codes) + lane * CW;
@@ -140,28 +162,28 @@ __device__ __forceinline__ void load_page(PageRegs<D, BITS, NSET>& r, const uint
     r.kw[0] = kc[0];
     r.vw[0] = vc[0];
   } else if constexpr (CW == 2) {
-    const uint2 a = *(const uint2*)kc, b = *(const uint2*)vc;
+    const uint2 a = ld8<NT>(kc), b = ld8<NT>(vc);
     r.kw[0] = a.x; r.kw[1] = a.y;
     r.vw[0] = b.x; r.vw[1] = b.y;
   } else {
 #pragma unroll
     for (int i = 0; i < CW; i += 4) {
-      const uint4 a = *(const uint4*)(kc + i), b = *(const uint4*)(vc + i);
+      const uint4 a = ld16<NT>(kc + i), b = ld16<NT>(vc + i);
       r.kw[i] = a.x; r.kw[i + 1] = a.y; r.kw[i + 2] = a.z; r.kw[i + 3] = a.w;
       r.vw[i] = b.x; r.vw[i + 1] = b.y; r.vw[i + 2] = b.z; r.vw[i + 3] = b.w;
     }
   }
 #pragma unroll
   for (int s = 0; s < NSET; ++s) {
-    r.km[s] = *(const uint4*)(blk + g.k_meta + meta_off[s]);
-    r.vm[s] = *(const uint4*)(blk + g.v_meta + meta_off[s]);
+    r.km[s] = ld16<NT>(blk + g.k_meta + meta_off[s]);
+    r.vm[s] = ld16<NT>(blk + g.v_meta + meta_off[s]);
   }
 }
 
 template <int D, int NSET>
 struct WaveState {
   static constexpr int NM = D / 16;
-  float4v o[NM];    // o[mb][r]: channel 16*mb + 4*qd + r of column n, in units of the class
+  float4v o[NM];    // o[mb][r]: channel 16*mb + 4*qd + r of column n (while a type is walked: in its units, and lifted)
   float oz[NSET];   // this lane's share of sum_t p_t zp_V(t, group of the lane's slice)
   float l;          // this lane's share of sum_t p_t
   float m;          // running maximum (log2 domain) of column n; -inf before the first live token
@@ -189,7 +211,15 @@ struct PairRegs {
   PageRegs<D, BITS, NSET> a, b;
 };
 
-// One wave's share of an item: page pairs wave, wave+4, ... of tab[p0..p1).
+// What a lane keeps of the query for the whole item: per column set the eight binary16 values of
+// (its head, its slice's group, channels 8qd .. 8qd+7) and the sum of the group's 32 values.
+template <int NSET>
+struct QRegs {
+  H8 q[NSET];
+  float sum[NSET];
+};
+
+// The pages of one type, as one wave walks them.
 // STAT: besides attending, leave the group-pooled score of every visited slot (the maximum over
 // the query heads of the group of the scaled score, log2 domain; -inf for a dead or invisible
 // slot) in a[.].stat, for the attention-sparsity statistic.
@@ -204,21 +234,24 @@ struct ClassRunner {
   const DecodeArgs& a;
   const int cls, hkv, qpos;
   const int32_t* tab;
-  const int p0, p1, wave;
+  const int p0, p1;
   int lane, qd, n;
   int meta_off[NSET];  // byte offset, inside a meta region, of this lane's unit per column set
   H8 bq[NG];           // B operands of the score MFMAs: q of group g in slice g % CS, zeros elsewhere
   float qs[NSET];      // 2^(OMIN-24) * sum_{i in group} q_i of this lane's (slice group, head)
   float kappa;         // 2^(24-OMIN) * softmax_scale * log2(e): MFMA score units -> log2 domain
+  float lift;          // the weights of this type's pages are 2^lift times the softmax weights (kLift, or 0 after a scale too large for it)
   float neg1;          // -1, kept opaque so that x - (float)h stays one fused mixed-precision instruction
   float* stat;         // STAT: pooled scores of this type's page list, 16 per page
   int stat_room;       // STAT: pages of this list the buffer has room for (the host's bound on the context)
   bool head_ok;        // this lane's column belongs to a query head of the group
 
+  // qr: this lane's query slice per column set (binary16, channels 32g + 8qd + e of its head and slice group) and the
+  // group sums, as the kernel read them once per item
   __device__ __forceinline__ ClassRunner(WaveState<D, NSET>& st_, const thinkv_view& v_, const DecodeArgs& a_, int cls_,
-                                         const int32_t* tab_, int p0_, int p1_, int wave_, int hkv_, int G, const _Float16* s_q,
-                                         const float* s_qsum, int qpos_, float* stat_, int stat_room_)
-      : st(st_), v(v_), a(a_), cls(cls_), hkv(hkv_), qpos(qpos_), tab(tab_), p0(p0_), p1(p1_), wave(wave_), stat(stat_), stat_room(stat_room_) {
+                                         const int32_t* tab_, int p0_, int p1_, int hkv_, int G, const QRegs<NSET>& qr,
+                                         int qpos_, float* stat_, int stat_room_)
+      : st(st_), v(v_), a(a_), cls(cls_), hkv(hkv_), qpos(qpos_), tab(tab_), p0(p0_), p1(p1_), stat(stat_), stat_room(stat_room_) {
     lane = threadIdx.x & 63;
     qd = lane >> 4;
     n = lane & 15;
@@ -227,24 +260,22 @@ struct ClassRunner {
     head_ok = head < G;
     const int glc = gl < CS ? gl : CS - 1;   // unused slices read slice CS-1's unit (finite, multiplied by zeros)
     kappa = (float)(1 << (24 - F::OMIN)) * a.scale_log2e;
+    enter();
     neg1 = -1.0f;
     asm volatile("" : "+v"(neg1));
 #pragma unroll
     for (int s = 0; s < NSET; ++s) {
       const int g = s * CS + glc;
       meta_off[s] = (g * 4 + qd) * 16;
-      qs[s] = used ? s_qsum[head * NG + g] * (1.0f / (float)(1 << (24 - F::OMIN))) : 0.f;
+      qs[s] = used ? qr.sum[s] * (1.0f / (float)(1 << (24 - F::OMIN))) : 0.f;
     }
-    // q of this lane's head and slice group(s), channels 32g + 8qd + e: one 16-byte LDS read per
-    // column set, scaled down by the residual power of two the codes of those fields carry (exact:
+    // the query slice is scaled down by the residual power of two the codes of those fields carry (exact:
     // power-of-two scaling of binary16 values), then dealt to the group's operand; the operands of
-    // the other groups are zero in this lane.  Branch-free, so the reads are issued together.
+    // the other groups are zero in this lane
     H8 mine[NSET];
 #pragma unroll
     for (int s = 0; s < NSET; ++s) {
-      const int g = s * CS + glc;
-      const uint4 raw = *(const uint4*)(s_q + (used ? head : 0) * D + 32 * g + 8 * qd);
-      mine[s].u[0] = raw.x; mine[s].u[1] = raw.y; mine[s].u[2] = raw.z; mine[s].u[3] = raw.w;
+      mine[s] = qr.q[s];
 #pragma unroll
       for (int e = 0; e < 8; ++e) mine[s].h[e] *= (_Float16)(1.0f / (float)(1 << F::rel_of(e >> 1)));   // rel_of depends on the field's parity only
     }
@@ -254,6 +285,42 @@ struct ClassRunner {
 #pragma unroll
       for (int w = 0; w < 4; ++w) bq[g].u[w] = on ? mine[g / CS].u[w] : 0u;
     }
+  }
+
+  // The second operand of the value products, p * s_V, is a binary16 pair: 22 significant bits, but nothing
+  // below 2^-24.  With the weights taken relative to the running maximum (p <= 1), a head whose attention is
+  // peaked would have most of its tokens down where binary16 has few bits left or none.  So the weights of a
+  // type's pages are lifted by 2^kLift -- the softmax reference is lowered, which costs nothing: the
+  // denominator, the zero-point sums and the tiles carry the same factor until the type is left -- as far as
+  // scales of ordinary size allow (a scale of 2^(16 - kLift), i.e. a group range of about a thousand, would take
+  // the largest product out of binary16; every pair is checked, and such a pair ends the lift for the rest of
+  // the type).
+  static constexpr int kLift = BITS == 8 ? 14 : (BITS == 4 ? 10 : 8);
+  // the tiles are in the units of the type (its codes carry a power of two that depends on the bit width) and
+  // lifted while its pages are walked, in absolute units in between
+  __device__ static constexpr float tile_unit(int mb) { return (float)(1 << (BITS == 8 ? 0 : F::OMIN + F::rel_of(mb))); }
+  __device__ __forceinline__ void enter() {
+    const float up = (float)(1 << kLift);
+    lift = (float)kLift;
+    st.l *= up;
+#pragma unroll
+    for (int s = 0; s < NSET; ++s) st.oz[s] *= up;
+#pragma unroll
+    for (int mb = 0; mb < NM; ++mb) st.o[mb] *= up * tile_unit(mb);
+  }
+  __device__ __forceinline__ void drop_lift() {
+    const float down = __builtin_amdgcn_exp2f(-lift);
+    st.l *= down;
+#pragma unroll
+    for (int s = 0; s < NSET; ++s) st.oz[s] *= down;
+#pragma unroll
+    for (int mb = 0; mb < NM; ++mb) st.o[mb] *= down;
+    lift = 0.f;
+  }
+  __device__ __forceinline__ void leave() {
+    drop_lift();
+#pragma unroll
+    for (int mb = 0; mb < NM; ++mb) st.o[mb] *= 1.0f / tile_unit(mb);
   }
 
   __device__ __forceinline__ void issue_loads(Pair& r, const PairIds& id) const {
@@ -276,7 +343,7 @@ struct ClassRunner {
         const int g = set * CS + gl;
         H8 ka;
 #pragma unroll
-        for (int vv = 0; vv < 4; ++vv) ka.u[vv] = F::get(r.kw, 4 * g + vv);
+        for (int vv = 0; vv < 4; ++vv) ka.u[vv] = (TKV_ABL & 16) ? r.kw[(4 * g + vv) % PageRegs<D, BITS, NSET>::CW] : F::get(r.kw, 4 * g + vv);
         c[set] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka.h, bq[g].h, gl == 0 ? zero : c[set], 0, 0, 0);
       }
     }
@@ -288,8 +355,8 @@ struct ClassRunner {
       const float t = fmaf(half_of<R>(r.km[set].x, r.km[set].y), c[set][R], z);                  \
       acc = set == 0 ? t : acc + t;                                                              \
     }                                                                                            \
-    acc = add_row_ror<8>(acc);                                                                   \
-    if constexpr (GP == 4) acc = add_row_ror<4>(acc);                                            \
+    if (!(TKV_ABL & 64)) { acc = add_row_ror<8>(acc);                                                                   \
+    if constexpr (GP == 4) acc = add_row_ror<4>(acc); }                                           \
     s[R] = acc;                                                                                  \
   }
     TKV_SCORE(0) TKV_SCORE(1) TKV_SCORE(2) TKV_SCORE(3)
@@ -297,13 +364,23 @@ struct ClassRunner {
   }
 
   __device__ __forceinline__ void compute(const Pair& r, const PairIds& id) {
+    if constexpr ((TKV_ABL & 128) != 0) {   // loads only: fold every loaded word into the denominator
+      uint32_t x = 0;
+      constexpr int CWx = PageRegs<D, BITS, NSET>::CW;
+#pragma unroll
+      for (int i = 0; i < CWx; ++i) x ^= r.a.kw[i] ^ r.a.vw[i] ^ r.b.kw[i] ^ r.b.vw[i];
+#pragma unroll
+      for (int s2 = 0; s2 < NSET; ++s2) x ^= r.a.km[s2].x ^ r.a.km[s2].w ^ r.a.vm[s2].y ^ r.a.vm[s2].z ^ r.b.km[s2].x ^ r.b.km[s2].w ^ r.b.vm[s2].y ^ r.b.vm[s2].z;
+      st.l += __builtin_bit_cast(float, x & 0x3F800000u);
+      return;
+    }
     const uint32_t live_a = id.live_a, live_b = id.live_b;
     float sa[4], sb[4];
     page_scores(r.a, sa);
     page_scores(r.b, sb);
     // ---------------- dead slots: score -inf, hence p = 0.  Their scales and zero-points are finite
     // (stale, or zero in a slot never written: arenas start zero-filled), so they drop out of every sum.
-    if ((live_a & live_b) != 0xFFFFu) {
+    if (!(TKV_ABL & 1) && (live_a & live_b) != 0xFFFFu) {
       const uint32_t la = (live_a >> (4 * qd)) & 0xFu, lb = (live_b >> (4 * qd)) & 0xFu;
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
@@ -345,93 +422,203 @@ struct ClassRunner {
       st.m = m_new;
       st.m_sub = m_sub;
     }
+    // p = 2^(score - m + lift): the weights are lifted by a power of two (see kLift), and with them
+    // the denominator, the zero-point sums and the value tiles of this type
     float pa[4], pb[4];
+    const float mref = st.m_sub - lift;
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
-      pa[r4] = __builtin_amdgcn_exp2f(fmaf(sa[r4], kappa, -st.m_sub));
-      pb[r4] = __builtin_amdgcn_exp2f(fmaf(sb[r4], kappa, -st.m_sub));
+      pa[r4] = (TKV_ABL & 2) ? fmaf(sa[r4], kappa, -mref) : __builtin_amdgcn_exp2f(fmaf(sa[r4], kappa, -mref));
+      pb[r4] = (TKV_ABL & 2) ? fmaf(sb[r4], kappa, -mref) : __builtin_amdgcn_exp2f(fmaf(sb[r4], kappa, -mref));
     }
     st.l += ((pa[0] + pa[1]) + (pa[2] + pa[3])) + ((pb[0] + pb[1]) + (pb[2] + pb[3]));
     // ---------------- values, per column set: B = two-term split of p * s_V, A = V codes
+    float xa[NSET][4], xb[NSET][4];
 #pragma unroll
     for (int set = 0; set < NSET; ++set) {
-      float xa[4], xb[4], z = st.oz[set];
+#define TKV_X(R)                                                               \
+  {                                                                            \
+    xa[set][R] = fmaf(half_of<R>(r.a.vm[set].x, r.a.vm[set].y), pa[R], 0.0f);  \
+    xb[set][R] = fmaf(half_of<R>(r.b.vm[set].x, r.b.vm[set].y), pb[R], 0.0f);  \
+  }
+      TKV_X(0) TKV_X(1) TKV_X(2) TKV_X(3)
+#undef TKV_X
+    }
+    if (lift != 0.f) {
+      // would a lifted product leave binary16?  (scales this large are far outside what a cache holds in
+      // practice; then the rest of this type's pages is worked on without the lift)
+      float big = 0.f;
+#pragma unroll
+      for (int set = 0; set < NSET; ++set)
+        big = fmaxf(fmaxf(fmaxf(big, fmaxf(xa[set][0], xa[set][1])), fmaxf(fmaxf(xa[set][2], xa[set][3]), fmaxf(xb[set][0], xb[set][1]))),
+                    fmaxf(xb[set][2], xb[set][3]));
+      if (__any(big > 6.0e4f)) {
+        const float down = __builtin_amdgcn_exp2f(-lift);
+        drop_lift();   // the denominator already holds this pair's weights: they come down with it
+#pragma unroll
+        for (int set = 0; set < NSET; ++set) {
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4) {
+            xa[set][r4] *= down;
+            xb[set][r4] *= down;
+          }
+        }
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          pa[r4] *= down;
+          pb[r4] *= down;
+        }
+      }
+    }
+#pragma unroll
+    for (int set = 0; set < NSET; ++set) {
+      float z = st.oz[set];
 #define TKV_PV(R)                                                     \
   {                                                                   \
     z = fmaf(half_of<R>(r.a.vm[set].z, r.a.vm[set].w), pa[R], z);           \
     z = fmaf(half_of<R>(r.b.vm[set].z, r.b.vm[set].w), pb[R], z);           \
-    xa[R] = fmaf(half_of<R>(r.a.vm[set].x, r.a.vm[set].y), pa[R], 0.0f);    \
-    xb[R] = fmaf(half_of<R>(r.b.vm[set].x, r.b.vm[set].y), pb[R], 0.0f);    \
   }
       TKV_PV(0) TKV_PV(1) TKV_PV(2) TKV_PV(3)
 #undef TKV_PV
       st.oz[set] = z;
       // k-slots 8qd+e: e<4 page a slots 4qd+e, e>=4 page b
       H8 hi, lo;
-      hi.u[0] = pack_rne(xa[0], xa[1]);
-      hi.u[1] = pack_rne(xa[2], xa[3]);
-      hi.u[2] = pack_rne(xb[0], xb[1]);
-      hi.u[3] = pack_rne(xb[2], xb[3]);
-      lo.u[0] = pack_rne(fmaf(neg1, half_lo(hi.u[0]), xa[0]), fmaf(neg1, half_hi(hi.u[0]), xa[1]));
-      lo.u[1] = pack_rne(fmaf(neg1, half_lo(hi.u[1]), xa[2]), fmaf(neg1, half_hi(hi.u[1]), xa[3]));
-      lo.u[2] = pack_rne(fmaf(neg1, half_lo(hi.u[2]), xb[0]), fmaf(neg1, half_hi(hi.u[2]), xb[1]));
-      lo.u[3] = pack_rne(fmaf(neg1, half_lo(hi.u[3]), xb[2]), fmaf(neg1, half_hi(hi.u[3]), xb[3]));
+      hi.u[0] = pack_rne(xa[set][0], xa[set][1]);
+      hi.u[1] = pack_rne(xa[set][2], xa[set][3]);
+      hi.u[2] = pack_rne(xb[set][0], xb[set][1]);
+      hi.u[3] = pack_rne(xb[set][2], xb[set][3]);
+      lo.u[0] = pack_rne(fmaf(neg1, half_lo(hi.u[0]), xa[set][0]), fmaf(neg1, half_hi(hi.u[0]), xa[set][1]));
+      lo.u[1] = pack_rne(fmaf(neg1, half_lo(hi.u[1]), xa[set][2]), fmaf(neg1, half_hi(hi.u[1]), xa[set][3]));
+      lo.u[2] = pack_rne(fmaf(neg1, half_lo(hi.u[2]), xb[set][0]), fmaf(neg1, half_hi(hi.u[2]), xb[set][1]));
+      lo.u[3] = pack_rne(fmaf(neg1, half_lo(hi.u[3]), xb[set][2]), fmaf(neg1, half_hi(hi.u[3]), xb[set][3]));
 #pragma unroll
       for (int mm = 0; mm < 2 * CS; ++mm) {
         const int mb = 2 * CS * set + mm;
         H8 va;
         // field f = u*NM + mb holds slots (2u, 2u+1) of the lane's slot quad
-        va.u[0] = F::get(r.a.vw, 0 * NM + mb);
-        va.u[1] = F::get(r.a.vw, 1 * NM + mb);
-        va.u[2] = F::get(r.b.vw, 0 * NM + mb);
-        va.u[3] = F::get(r.b.vw, 1 * NM + mb);
-        st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, hi.h, st.o[mb], 0, 0, 0);
-        st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, lo.h, st.o[mb], 0, 0, 0);
+        constexpr int CWv = PageRegs<D, BITS, NSET>::CW;
+        va.u[0] = (TKV_ABL & 8) ? r.a.vw[mb % CWv] : F::get(r.a.vw, 0 * NM + mb);
+        va.u[1] = (TKV_ABL & 8) ? r.a.vw[(mb + 1) % CWv] : F::get(r.a.vw, 1 * NM + mb);
+        va.u[2] = (TKV_ABL & 8) ? r.b.vw[mb % CWv] : F::get(r.b.vw, 0 * NM + mb);
+        va.u[3] = (TKV_ABL & 8) ? r.b.vw[(mb + 1) % CWv] : F::get(r.b.vw, 1 * NM + mb);
+        if (!(TKV_ABL & 32)) st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, hi.h, st.o[mb], 0, 0, 0);
+        else st.o[mb][0] += __builtin_bit_cast(float, va.u[0] ^ va.u[1] ^ va.u[2] ^ va.u[3] ^ hi.u[0] ^ hi.u[1] ^ hi.u[2] ^ hi.u[3]);
+        if (!(TKV_ABL & (4 | 32))) st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, lo.h, st.o[mb], 0, 0, 0);
+        else if (TKV_ABL & 32) st.o[mb][1] += __builtin_bit_cast(float, lo.u[0] ^ lo.u[1] ^ lo.u[2] ^ lo.u[3]);
       }
     }
   }
 
-  // Dynamic chunks: the type's whole page list tab[0 .. n_pages) is cut into chunks of kChunkPairs
-  // page pairs; *counter hands out chunk numbers to every wave of every workgroup of this
-  // (query, kv-head).  The next chunk number is requested before the current chunk is worked
-  // on, so the round trip of the atomic hides behind a chunk of compute.
-  static constexpr int kChunkPairs = 4;
-  __device__ __forceinline__ int take_chunk(uint32_t* counter) const {
+  // Shared queues: *counter hands out page pairs of the type's page list tab[0 .. n_pages) to every
+  // item of this (query, kv-head), kChunkPairs consecutive pairs per request.  A wave keeps the
+  // chunk it works on, the ids of the next one (requested when the current one was started, so
+  // they have long arrived when they are needed) and one more chunk on order; its pairs thus
+  // form one stream across chunk boundaries, and the loads of pair i + 1 are requested before
+  // pair i is worked on (two register sets, A and B, used in turn): a wave always has a pair in
+  // flight while it computes.  When the stream ends the pair in flight is a repeat (a cache hit)
+  // and is dropped.
+  static constexpr int kChunkPairs = TKV_CHUNK;
+  static_assert(kChunkPairs <= 8, "a chunk's page ids are held in sixteen scalars");
+  static constexpr int kChunkPages = 2 * kChunkPairs;
+  typedef const int32_t __attribute__((address_space(4))) * ConstI32;   // read-only for the whole launch: scalar loads
+  struct Stream {
+    ConstI32 tab, msk;
+    uint32_t* counter;
+    int n_pages, n_pairs;
+    int pg0, cnt, pr;             // current chunk: first page, pages, next pair
+    int vpid;                     // lane L: id of page L of the current chunk
+    int vmask;                    // lane L: mask word of that page (live bits in the low half)
+    int s_pid[kChunkPages];       // the next chunk's ids and mask words: scalar loads requested when the
+    int s_msk[kChunkPages];       //   current chunk was started (no traffic in the vector-memory queue)
+    int nj;                       // first pair of the next chunk (>= n_pairs: none)
+    int on_order;                 // lane 0: first pair of the chunk after that (atomic in flight)
+  };
+  // ids and masks of the chunk that starts at pair j -> scalars; entries past the end of the list repeat its last page (never used)
+  __device__ __forceinline__ void load_ids(Stream& q, int j) const {
+    const int pg0 = 2 * j;
+#pragma unroll
+    for (int i = 0; i < kChunkPages; ++i) {
+      const int at = pg0 + i < q.n_pages ? pg0 + i : q.n_pages - 1;
+      q.s_pid[i] = __builtin_amdgcn_readfirstlane(q.tab[at]);
+      q.s_msk[i] = __builtin_amdgcn_readfirstlane(q.msk[at]);
+    }
+  }
+  __device__ __forceinline__ void spread_ids(Stream& q) const {
+#pragma unroll
+    for (int i = 0; i < kChunkPages; ++i) {
+      asm("v_writelane_b32 %0, %1, %2" : "+v"(q.vpid) : "s"(__builtin_amdgcn_readfirstlane(q.s_pid[i])), "n"(i));
+      asm("v_writelane_b32 %0, %1, %2" : "+v"(q.vmask) : "s"(__builtin_amdgcn_readfirstlane(q.s_msk[i])), "n"(i));
+    }
+  }
+  // asks for the next chunk
+  __device__ __forceinline__ void order_chunk(Stream& q) const {
     int r = 0;
-    if (lane == 0) r = (int)atomicAdd(counter, 1u);
-    return r;   // valid in lane 0; read with readfirstlane when needed
+    if (lane == 0) r = (int)atomicAdd(q.counter, (uint32_t)kChunkPairs);
+    q.on_order = r;   // valid in lane 0
+  }
+  __device__ __forceinline__ void set_chunk(Stream& q, int j) const {
+    q.pg0 = 2 * j;
+    q.cnt = q.n_pages - q.pg0 < kChunkPages ? q.n_pages - q.pg0 : kChunkPages;
+    q.pr = 0;
+  }
+  // the next pair of the stream; false (and a repeat of page 0 of the current chunk with no live slot) at its end
+  __device__ __forceinline__ bool next_pair(Stream& q, PairIds& id) const {
+    bool have = true;
+    if (2 * q.pr >= q.cnt) {
+      if (q.nj < q.n_pairs) {
+        spread_ids(q);
+        set_chunk(q, q.nj);
+        q.nj = __builtin_amdgcn_readfirstlane(q.on_order);
+        if (q.nj < q.n_pairs) load_ids(q, q.nj);
+        order_chunk(q);
+      } else {
+        have = false;
+      }
+    }
+    const int ia = have ? 2 * q.pr : 0;
+    const bool two = have && 2 * q.pr + 1 < q.cnt;
+    const int ib = two ? 2 * q.pr + 1 : ia;
+    id.pid_a = __builtin_amdgcn_readlane(q.vpid, ia);
+    id.live_a = have ? (uint32_t)__builtin_amdgcn_readlane(q.vmask, ia) & 0xFFFFu : 0u;
+    id.pid_b = __builtin_amdgcn_readlane(q.vpid, ib);
+    id.live_b = two ? (uint32_t)__builtin_amdgcn_readlane(q.vmask, ib) & 0xFFFFu : 0u;
+    id.idx_a = q.pg0 + ia;
+    id.idx_b = two ? q.pg0 + ib : -1;
+    q.pr += have ? 1 : 0;
+    return have;
   }
   __device__ __forceinline__ void run_dynamic(int n_pages, uint32_t* counter) {
-    const int n_pairs = (n_pages + 1) >> 1;
-    const int n_chunks = (n_pairs + kChunkPairs - 1) / kChunkPairs;
-    const uint32_t* msk = v.slot_mask + (tab - v.block_table);
-    int j = __builtin_amdgcn_readfirstlane(take_chunk(counter));
-    while (j < n_chunks) {
-      const int pg0 = 2 * kChunkPairs * j;
-      const int cnt = n_pages - pg0 < 2 * kChunkPairs ? n_pages - pg0 : 2 * kChunkPairs;
-      int vpid = 0;
-      uint32_t vmask = 0;
-      if (lane < cnt) {
-        vpid = tab[pg0 + lane];
-        vmask = msk[pg0 + lane] & 0xFFFFu;
-      }
-      const int r_next = take_chunk(counter);
-      const int np2 = (cnt + 1) >> 1;
-      for (int pr = 0; pr < np2; ++pr) {
-        PairIds id;
-        id.pid_a = __builtin_amdgcn_readlane(vpid, 2 * pr);
-        id.live_a = __builtin_amdgcn_readlane(vmask, 2 * pr);
-        const int ib = 2 * pr + 1 < cnt ? 2 * pr + 1 : 2 * pr;
-        id.pid_b = __builtin_amdgcn_readlane(vpid, ib);
-        id.live_b = 2 * pr + 1 < cnt ? __builtin_amdgcn_readlane(vmask, ib) : 0u;
-        id.idx_a = pg0 + 2 * pr;
-        id.idx_b = 2 * pr + 1 < cnt ? pg0 + 2 * pr + 1 : -1;
-        if ((id.live_a | id.live_b) == 0) continue;
-        Pair r;
-        issue_loads(r, id);
-        compute(r, id);
-      }
-      j = __builtin_amdgcn_readfirstlane(r_next);
+    Stream q;
+    q.tab = (ConstI32)(uintptr_t)tab;
+    q.msk = (ConstI32)(uintptr_t)(v.slot_mask + (tab - v.block_table));
+    q.counter = counter;
+    q.n_pages = n_pages;
+    q.n_pairs = (n_pages + 1) >> 1;
+    order_chunk(q);
+    const int j0 = __builtin_amdgcn_readfirstlane(q.on_order);
+    if (j0 >= q.n_pairs) return;
+    order_chunk(q);
+    load_ids(q, j0);
+    q.vpid = 0;
+    q.vmask = 0;
+    spread_ids(q);
+    set_chunk(q, j0);
+    q.nj = __builtin_amdgcn_readfirstlane(q.on_order);
+    if (q.nj < q.n_pairs) load_ids(q, q.nj);
+    order_chunk(q);
+    PairIds ida, idb;
+    Pair ra, rb;
+    next_pair(q, ida);   // the first chunk has at least one page
+    issue_loads(ra, ida);
+    while (true) {
+      const bool more_b = next_pair(q, idb);
+      issue_loads(rb, idb);
+      if ((ida.live_a | ida.live_b) != 0) compute(ra, ida);
+      if (!more_b) break;
+      const bool more_a = next_pair(q, ida);
+      issue_loads(ra, ida);
+      if ((idb.live_a | idb.live_b) != 0) compute(rb, idb);
+      if (!more_a) break;
     }
   }
 
@@ -439,12 +626,11 @@ struct ClassRunner {
   // with one vector load each (lane L holds page p0 + base + L).  A page can hold a visible
   // token only if the largest position ever written into it lies inside the window, so one
   // word per page (page_pos_max) settles most pages; a lane reads the 16 positions of its page
-  // only when that test passes.  The four waves take every fourth run of 64 pages; the pages of
-  // a run that still have a visible slot are paired up, and ids and masks reach the pair code
-  // through v_readlane.
+  // only when that test passes.  The pages of a run of 64 that still have a visible slot are
+  // paired up, and ids and masks reach the pair code through v_readlane.
   __device__ __forceinline__ void run() {
     const int n_pages = p1 - p0;
-    for (int base = 64 * wave; base < n_pages; base += 256) {
+    for (int base = 0; base < n_pages; base += 64) {
       const int cnt = n_pages - base < 64 ? n_pages - base : 64;
       int vpid = 0;
       uint32_t vmask = 0;
@@ -490,66 +676,67 @@ struct ClassRunner {
   }
 };
 
-template <int D, int GP>
-struct ItemLds {
-  _Float16 q[GP * D];
-  float qsum[GP * (D / 32)];
-  float m[4][GP], l[4][GP];
-  float acc[4][GP][D];
-};
-
-template <int D>
-__device__ __forceinline__ float class_unit(int bits, int mb) {
-  // V codes of a b-bit class enter the MFMA as c * 2^(OMIN + rel(mb) - 24)
-  const int sh = bits == 2 ? Fld<2>::OMIN + Fld<2>::rel_of(mb) : (bits == 4 ? Fld<4>::OMIN + Fld<4>::rel_of(mb) : 0);
-  return (float)(1 << sh);
-}
-
-// One workgroup of four waves per (query, kv-head, item).  WIN: sliding-window layer (static shares).
+// One wave per item; a workgroup is four items that share nothing but the launch (the hardware starts a
+// four-wave workgroup as fast as a one-wave one, and a launch of thousands of single waves takes ten
+// microseconds to get going).  WIN: sliding-window layer (static shares).
 template <int D, int GP, bool WIN, bool STAT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void decode_mfma_kernel(thinkv_view v, DecodeArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TKV_WAVES, TKV_WAVES))) void decode_mfma_kernel(thinkv_view v, DecodeArgs a) {
   using CL = Cols<D, GP>;
   constexpr int NG = D / 32, NM = D / 16, CS = CL::CS, NSET = CL::NSET;
   const thinkv_config& c = v.cfg;
-  int b, hkv, item_j;
-  locate_workgroup(a, c.n_kv_heads, blockIdx.x, &b, &hkv, &item_j);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int item = blockIdx.x * 4 + wave;
+  if (item >= a.n_rows) return;
+  const ItemLoc it = locate_item(v, a, item);
+  if (it.j >= it.n) return;
+  const int b = it.b, hkv = it.hkv;
   const int seq = a.seq_ids[b];
-  __shared__ ItemLds<D, GP> lds;
-  int np[3], np_total = 0;
-#pragma unroll
-  for (int k = 0; k < 3; ++k) {
-    np[k] = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
-    np_total += np[k];
-  }
-  const ItemPlan plan = plan_items(a.ppi, a.max_split, np_total);
-  if (item_j >= plan.n_items) {
-    if (a.direct && item_j == 0) {   // no pages at all, and no merge kernel to say so
-      const int Hq0 = c.n_q_heads, G0 = Hq0 / c.n_kv_heads;
-      for (int i = threadIdx.x; i < G0 * D; i += 256) store_from_f32(a.out, ((int64_t)b * Hq0 + hkv * G0) * D + i, a.out_dtype, 0.f);
-      if (a.lse && threadIdx.x < G0) a.lse[(int64_t)b * Hq0 + hkv * G0 + threadIdx.x] = -INFINITY;
-    }
-    return;
-  }
-  const int split = item_j;   // the item's row among the partials
-  int u0, u1;
-  item_units(plan, split, &u0, &u1);
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  int np[3];
+  seq_pages(v, a.layer, seq, np);
+  const int lane = threadIdx.x & 63, qd = lane >> 4, n = lane & 15;
+  const int gl = n / GP, head = n % GP;
   const int Hq = c.n_q_heads, G = Hq / c.n_kv_heads;
-  for (int i = tid; i < G * D; i += 256)
-    lds.q[i] = (_Float16)load_as_f32(a.q, ((int64_t)b * Hq + hkv * G) * D + i, a.q_dtype);
-  __syncthreads();
-  if (tid < G * NG * 4) {
-    // four threads per (head, group) sum eight channels each
-    const int hg = tid >> 2, part = tid & 3;
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) s += (float)lds.q[(hg / NG) * D + 32 * (hg % NG) + 8 * part + i];
-    s += __shfl_xor(s, 1, 64);
-    s += __shfl_xor(s, 2, 64);
-    if (part == 0) lds.qsum[hg] = s;
+  if (it.j == 0 && lane == 0 && !a.direct) {
+    a.alloc[2 * (b * c.n_kv_heads + hkv)] = it.row0;
+    a.alloc[2 * (b * c.n_kv_heads + hkv) + 1] = it.n;
   }
-  __syncthreads();
+#ifdef TKV_STAMP
+  unsigned long long* stamps = (unsigned long long*)(a.alloc + 2 * a.B * c.n_kv_heads + 64) + (int64_t)item * 8;
+  const bool stamper = lane == 0;
+  if (stamper) { stamps[0] = wall_clock64(); stamps[6] = ((unsigned long long)b << 32) | (unsigned)(hkv * 1000 + it.j); }
+#endif
+
+  // ---- the query: lane (slice gl, head, row quad qd) reads, per column set, the eight values of
+  // channels 32g + 8qd .. of its head (g = the set's group of its slice), rounds them to binary16
+  // and adds them up; the four row quads complete the group's sum
+  QRegs<NSET> qr;
+  {
+    const bool used = gl < CS && head < G;
+    const int glc = gl < CS ? gl : CS - 1;
+#pragma unroll
+    for (int s = 0; s < NSET; ++s) {
+      const int g = s * CS + glc;
+      const int64_t at = ((int64_t)b * Hq + hkv * G + (used ? head : 0)) * D + 32 * g + 8 * qd;
+      float sum = 0.f;
+      if (a.q_dtype == THINKV_F16) {
+        const uint4 raw = *(const uint4*)((const _Float16*)a.q + at);
+        qr.q[s].u[0] = raw.x; qr.q[s].u[1] = raw.y; qr.q[s].u[2] = raw.z; qr.q[s].u[3] = raw.w;
+      } else {
+        const uint4 raw = *(const uint4*)((const uint16_t*)a.q + at);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t u = (e & 1) ? (w[e >> 1] & 0xFFFF0000u) : (w[e >> 1] << 16);
+          qr.q[s].h[e] = (_Float16)__builtin_bit_cast(float, u);
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum += (float)qr.q[s].h[e];
+      sum += __shfl_xor(sum, 16, 64);
+      sum += __shfl_xor(sum, 32, 64);
+      qr.sum[s] = sum;
+    }
+  }
 
   WaveState<D, NSET> st;
 #pragma unroll
@@ -560,47 +747,48 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   st.m = -INFINITY;
   st.m_sub = 0.f;
   const int qpos = WIN ? a.q_pos[b] : 0;
-  const int qd = lane >> 4, n = lane & 15;
+#ifdef TKV_STAMP
+  if (stamper) stamps[1] = wall_clock64();
+#endif
 
-  // The running output is kept in the units of the class being walked (its codes carry a
-  // power of two that depends on the bit width) and re-based at class boundaries.
-  // Waves and workgroups start on different types: a pair of 8-bit pages moves three times the
-  // bytes of a pair of 2-bit pages for the same arithmetic, so if every wave walked the types in
-  // the same order the whole chip would swing between bandwidth-bound and issue-bound phases.
-  const int rot = (wave + split + hkv + b) % 3;
+  // Items start on different types: a pair of 8-bit pages moves three times the bytes of a pair of
+  // 2-bit pages for the same arithmetic, so if every wave walked the types in the same order the
+  // whole chip would swing between bandwidth-bound and issue-bound phases.
+  const int rot = (it.j + hkv + b) % 3;
   for (int kk = 0; kk < 3; ++kk) {
     const int k = kk + rot < 3 ? kk + rot : kk + rot - 3;
     const int bits = c.bits_of_class[k];
     const int npk = k == 0 ? np[0] : (k == 1 ? np[1] : np[2]);
-    const int p0 = WIN ? (int)((int64_t)u0 * npk / plan.units) : 0, p1 = WIN ? (int)((int64_t)u1 * npk / plan.units) : npk;
-    if (p1 <= p0) continue;
-    const int32_t* tab = v.block_table + table_base(c, seq, a.layer, k);
-    uint32_t* counter = v.work_counters + (((int64_t)a.layer * c.max_seqs + b) * c.n_kv_heads + hkv) * 4 + k;
-    // STAT: the pooled scores of a (query, kv-head) lie in the order of the three page lists
-    float* stat = nullptr;
-    int stat_room = 0;
-    if constexpr (STAT) {
-      const int before = k == 0 ? 0 : (k == 1 ? np[0] : np[0] + np[1]);
-      stat = a.stat + ((int64_t)b * c.n_kv_heads + hkv) * a.stat_stride + (int64_t)before * kPage;
-      stat_room = (int)(a.stat_stride / kPage) - before;
-    }
-#pragma unroll
-    for (int mb = 0; mb < NM; ++mb) st.o[mb] *= class_unit<D>(bits, mb);
-#define TKV_RUN(B_)                                                                                        \
-  {                                                                                                        \
-    ClassRunner<D, B_, GP, STAT> cr(st, v, a, k, tab, p0, p1, wave, hkv, G, lds.q, lds.qsum, qpos, stat, stat_room); \
-    if constexpr (WIN) cr.run();                                                                           \
-    else cr.run_dynamic(npk, counter);                                                                     \
+    const int p0 = WIN ? (int)((int64_t)it.j * npk / it.n) : 0, p1 = WIN ? (int)((int64_t)(it.j + 1) * npk / it.n) : npk;
+    if (p1 > p0) {
+      const int32_t* tab = v.block_table + table_base(c, seq, a.layer, k);
+      uint32_t* counter = v.work_counters + (((int64_t)a.layer * c.max_seqs + b) * c.n_kv_heads + hkv) * 4 + k;
+      // STAT: the pooled scores of a (query, kv-head) lie in the order of the three page lists
+      float* stat = nullptr;
+      int stat_room = 0;
+      if constexpr (STAT) {
+        const int before = k == 0 ? 0 : (k == 1 ? np[0] : np[0] + np[1]);
+        stat = a.stat + ((int64_t)b * c.n_kv_heads + hkv) * a.stat_stride + (int64_t)before * kPage;
+        stat_room = (int)(a.stat_stride / kPage) - before;
+      }
+#define TKV_RUN(B_)                                                                                     \
+  {                                                                                                     \
+    ClassRunner<D, B_, GP, STAT> cr(st, v, a, k, tab, p0, p1, hkv, G, qr, qpos, stat, stat_room);        \
+    if constexpr (WIN) cr.run();                                                                        \
+    else cr.run_dynamic(npk, counter);                                                                  \
+    cr.leave();                                                                                         \
   }
-    if (bits == 2) TKV_RUN(2) else if (bits == 4) TKV_RUN(4) else TKV_RUN(8)
+      if (bits == 2) TKV_RUN(2) else if (bits == 4) TKV_RUN(4) else TKV_RUN(8)
 #undef TKV_RUN
-#pragma unroll
-    for (int mb = 0; mb < NM; ++mb) st.o[mb] *= 1.0f / class_unit<D>(bits, mb);
+    }
+#ifdef TKV_STAMP
+    if (stamper) stamps[2 + kk] = wall_clock64();
+#endif
   }
 
-  // ---- fold.  The four lanes of a column (row quads) each hold a share of the denominator
-  // and of the zero-point sums; the tile of channel block mb is valid in the slice of its group.
-  const int gl = n / GP, head = n % GP;
+  // ---- the item's partial row per query head.  The four lanes of a column (row quads) each hold a
+  // share of the denominator and of the zero-point sums; the tile of channel block mb is valid in
+  // the slice of its group, where lane (head, qd) holds channels 16 mb + 4 qd .. + 3.
   float l = st.l;
   l += __shfl_xor(l, 16, 64);
   l += __shfl_xor(l, 32, 64);
@@ -612,51 +800,50 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
     z += __shfl_xor(z, 32, 64);
     zsum[set] = z;
   }
+  if (head < G) {
+    if (a.direct) {   // the only item of its head: this is the result
+      const int64_t o_at = ((int64_t)b * Hq + hkv * G + head) * D;
 #pragma unroll
-  for (int mb = 0; mb < NM; ++mb) {
-    const int g = mb >> 1, set = g / CS;
-    if (gl == g % CS && head < G) {
+      for (int mb = 0; mb < NM; ++mb) {
+        const int g = mb >> 1, set = g / CS;
+        if (gl == g % CS) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) lds.acc[wave][head][16 * mb + 4 * qd + r] = st.o[mb][r] * 16777216.f + zsum[set];
+          for (int r = 0; r < 4; ++r)
+            store_from_f32(a.out, o_at + 16 * mb + 4 * qd + r, a.out_dtype, l > 0.f ? (st.o[mb][r] * 16777216.f + zsum[set]) / l : 0.f);
+        }
+      }
+      if (a.lse && qd == 0 && gl == 0) a.lse[(int64_t)b * Hq + hkv * G + head] = l > 0.f ? (st.m + log2f(l)) * 0.6931471805599453f : -INFINITY;
+    } else {
+      float* dst = partial_row(a, G, D, it.row0 + it.j, head);
+#pragma unroll
+      for (int mb = 0; mb < NM; ++mb) {
+        const int g = mb >> 1, set = g / CS;
+        if (gl == g % CS) {
+          float4 o4;
+          o4.x = st.o[mb][0] * 16777216.f + zsum[set];
+          o4.y = st.o[mb][1] * 16777216.f + zsum[set];
+          o4.z = st.o[mb][2] * 16777216.f + zsum[set];
+          o4.w = st.o[mb][3] * 16777216.f + zsum[set];
+          *(float4*)(dst + 16 * mb + 4 * qd) = o4;
+        }
+      }
+      if (qd == 0 && gl == 0) {
+        dst[D] = st.m;
+        dst[D + 1] = l;
+      }
     }
   }
-  if (qd == 0 && gl == 0 && head < G) {
-    lds.m[wave][head] = st.m;
-    lds.l[wave][head] = l;
-  }
-  __syncthreads();
-  for (int i = tid; i < G * D; i += 256) {
-    const int g = i / D, ch = i % D;
-    float M = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) M = fmaxf(M, lds.m[w][g]);
-    float L = 0.f, A = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float f = (lds.m[w][g] == -INFINITY) ? 0.f : exp2f(lds.m[w][g] - M);
-      L += lds.l[w][g] * f;
-      A += lds.acc[w][g][ch] * f;
-    }
-    if (a.direct) {   // the only item of its query: this is the result
-      store_from_f32(a.out, ((int64_t)b * Hq + hkv * G + g) * D + ch, a.out_dtype, L > 0.f ? A / L : 0.f);
-      if (a.lse && ch == 0) a.lse[(int64_t)b * Hq + hkv * G + g] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
-      continue;
-    }
-    float* dst = a.partial + partial_index(a, Hq, D, b, hkv * G + g, split);
-    dst[2 + ch] = A;
-    if (ch == 0) {
-      dst[0] = M;
-      dst[1] = L;
-    }
-  }
-  // (direct) the work queues of this (query, kv-head) are left empty for the next call: no other workgroup shares them
-  if (a.direct && tid < 4) v.work_counters[(((int64_t)a.layer * c.max_seqs + b) * c.n_kv_heads + hkv) * 4 + tid] = 0u;
+#ifdef TKV_STAMP
+  if (stamper) stamps[5] = wall_clock64();
+#endif
+  // (direct) the work queues of this head are left empty for the next call: no other item shares them
+  if (a.direct && lane < 4) v.work_counters[(((int64_t)a.layer * c.max_seqs + b) * c.n_kv_heads + hkv) * 4 + lane] = 0u;
 }
 
 template <int D, bool WIN, bool STAT>
 static int launch_dw(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {
   const int G = v.cfg.n_q_heads / v.cfg.n_kv_heads;
-  dim3 grid(a.max_split * v.cfg.n_kv_heads * a.B), blk(256);
+  dim3 grid((a.n_rows + 3) / 4), blk(256);
   if (G <= 4)
     hipLaunchKernelGGL((decode_mfma_kernel<D, 4, WIN, STAT>), grid, blk, 0, st, v, a);
   else if (G <= 8)

@@ -1,7 +1,7 @@
 // Decode attention, plain-VALU variant, and the split-K merge kernel.
 //
-// One workgroup (4 waves) per (query, kv-head, split).  A wave takes every fourth page of the
-// item.  For a page it dequantises K in binary32 straight from the packed chunks (lane (j,t)
+// One workgroup (4 waves) per item of a (query, kv-head); items are dealt by size and take static
+// shares of the page lists.  A wave takes every fourth page of the item.  For a page it dequantises K in binary32 straight from the packed chunks (lane (j,t)
 // owns slot t, channels 32g+8j..+7 of every group g), reduces the partial dot products over the
 // four j lanes, updates the running softmax, then walks the V chunks (lane (q,m) owns slots
 // 4q..4q+3, channels 16mb+m).  It is the simple, easily checked path; the MFMA kernel in
@@ -19,8 +19,9 @@ template <int D>
 __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, DecodeArgs a) {
   constexpr int NG = D / kGroup, NM = D / 16, GMAX = 8;
   const thinkv_config& c = v.cfg;
-  int b, hkv, item_j;
-  locate_workgroup(a, c.n_kv_heads, blockIdx.x, &b, &hkv, &item_j);
+  const ItemLoc it = locate_item(v, a, blockIdx.x);
+  if (it.j >= it.n) return;
+  const int b = it.b, hkv = it.hkv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int Hq = c.n_q_heads, H = c.n_kv_heads, G = Hq / H;
   const int seq = a.seq_ids[b];
@@ -28,16 +29,12 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
   __shared__ float s_m[4][GMAX], s_l[4][GMAX];
   __shared__ float s_acc[4][GMAX][D];
 
-  int np[3], np_total = 0;
-  for (int k = 0; k < 3; ++k) {
-    np[k] = (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
-    np_total += np[k];
+  int np[3];
+  seq_pages(v, a.layer, seq, np);
+  if (it.j == 0 && tid == 0) {
+    a.alloc[2 * (b * H + hkv)] = it.row0;
+    a.alloc[2 * (b * H + hkv) + 1] = it.n;
   }
-  const ItemPlan plan = plan_items(a.ppi, a.max_split, np_total);
-  if (item_j >= plan.n_items) return;
-  const int split = item_j;   // the item's row among the partials
-  int u0, u1;
-  item_units(plan, split, &u0, &u1);
   for (int i = tid; i < G * D; i += 256)
     s_q[i / D][i % D] = load_as_f32(a.q, ((int64_t)b * Hq + hkv * G) * D + i, a.q_dtype) * a.scale_log2e;
   __syncthreads();
@@ -55,7 +52,7 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
   for (int k = 0; k < 3; ++k) {
     const int bits = c.bits_of_class[k];
     const BlockGeom geo = block_geom(bits, D);
-    const int p0 = (int)((int64_t)u0 * np[k] / plan.units), p1 = (int)((int64_t)u1 * np[k] / plan.units);
+    const int p0 = (int)((int64_t)it.j * np[k] / it.n), p1 = (int)((int64_t)(it.j + 1) * np[k] / it.n);
     const int32_t* tab = v.block_table + table_base(c, seq, a.layer, k);
     const uint32_t* msk = v.slot_mask + table_base(c, seq, a.layer, k);
     for (int pi = p0 + wave; pi < p1; pi += 4) {
@@ -149,37 +146,35 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
       L += s_l[w][g] * f;
       A += s_acc[w][g][ch] * f;
     }
-    float* dst = a.partial + partial_index(a, Hq, D, b, hkv * G + g, split);
-    dst[2 + ch] = A;
+    float* dst = partial_row(a, G, D, it.row0 + it.j, g);
+    dst[ch] = A;
     if (ch == 0) {
-      dst[0] = M;
-      dst[1] = L;
+      dst[D] = M;
+      dst[D + 1] = L;
     }
   }
 }
 
-// One workgroup of D threads per (query, query head): log-sum-exp merge of the partials.
-// Maxima and weights are found with one split per thread; the weighted sum over splits is
-// unrolled so that several partial rows are in flight per thread.
-constexpr int kMaxSplit = 1024;
-
+// One workgroup of D threads per (query, query head): log-sum-exp merge of the head's partial rows
+// (first row and count as item 0 of the head left them).  Maxima and weights are found with one
+// row per thread; the weighted sum over rows is unrolled so that several rows are in flight per thread.
 template <int D>
 __global__ __launch_bounds__(D) void decode_merge_kernel(thinkv_view v, DecodeArgs a) {
   const thinkv_config& c = v.cfg;
   const int hq = blockIdx.x, b = blockIdx.y, ch = threadIdx.x;
-  const int Hq = c.n_q_heads;
-  const int seq = a.seq_ids[b];
-  __shared__ float s_w[kMaxSplit];
+  const int Hq = c.n_q_heads, G = Hq / c.n_kv_heads, hkv = hq / G;
+  __shared__ float s_w[kMaxRowsPerHead];
   __shared__ float s_red[D / 64];
-  int np_total = 0;
-  for (int k = 0; k < 3; ++k)
-    np_total += (seq >= 0 && seq < c.max_seqs) ? v.n_pages[npages_index(c, seq, a.layer, k)] : 0;
-  const int ns = plan_items(a.ppi, a.max_split, np_total).n_items;
-  const float* src = a.partial + partial_index(a, Hq, D, b, hq, 0);
-  // maximum over splits
+  const int row0 = a.alloc[2 * (b * c.n_kv_heads + hkv)];
+  int ns = a.alloc[2 * (b * c.n_kv_heads + hkv) + 1];
+  ns = ns > kMaxRowsPerHead ? kMaxRowsPerHead : ns;
+  constexpr int RS = D + kRowPad;
+  const float* src = partial_row(a, G, D, row0, hq % G);
+  const int64_t stride = (int64_t)G * RS;   // from one row of this query head to the next
+  // maximum over rows
   float m_loc = -INFINITY;
   for (int s = ch; s < ns; s += D) {
-    const float m = src[(int64_t)s * (D + 2)];
+    const float m = src[s * stride + D];
     s_w[s] = m;
     m_loc = fmaxf(m_loc, m);
   }
@@ -195,7 +190,7 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(thinkv_view v, DecodeAr
     const float m = s_w[s];
     const float f = (m == -INFINITY) ? 0.f : exp2f(m - M);
     s_w[s] = f;
-    l_loc = fmaf(src[(int64_t)s * (D + 2) + 1], f, l_loc);
+    l_loc = fmaf(src[s * stride + D + 1], f, l_loc);
   }
   for (int d = 32; d >= 1; d >>= 1) l_loc += __shfl_xor(l_loc, d, 64);
   if ((ch & 63) == 0) s_red[ch >> 6] = l_loc;
@@ -204,27 +199,27 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(thinkv_view v, DecodeAr
   for (int w = 1; w < D / 64; ++w) L += s_red[w];
   // weighted sum of the partial rows
   float A = 0.f;
-  const float* col = src + 2 + ch;
+  const float* col = src + ch;
   int s = 0;
   for (; s + 4 <= ns; s += 4) {
-    const float x0 = col[(int64_t)(s + 0) * (D + 2)], x1 = col[(int64_t)(s + 1) * (D + 2)];
-    const float x2 = col[(int64_t)(s + 2) * (D + 2)], x3 = col[(int64_t)(s + 3) * (D + 2)];
+    const float x0 = col[(s + 0) * stride], x1 = col[(s + 1) * stride];
+    const float x2 = col[(s + 2) * stride], x3 = col[(s + 3) * stride];
     A = fmaf(x0, s_w[s], A);
     A = fmaf(x1, s_w[s + 1], A);
     A = fmaf(x2, s_w[s + 2], A);
     A = fmaf(x3, s_w[s + 3], A);
   }
-  for (; s < ns; ++s) A = fmaf(col[(int64_t)s * (D + 2)], s_w[s], A);
+  for (; s < ns; ++s) A = fmaf(col[s * stride], s_w[s], A);
   // the work queues of this (query, kv-head) are left empty for the next call
-  if (ch < 4 && hq % (Hq / c.n_kv_heads) == 0 && b < c.max_seqs)
-    v.work_counters[(((int64_t)a.layer * c.max_seqs + b) * c.n_kv_heads + hq / (Hq / c.n_kv_heads)) * 4 + ch] = 0u;
+  if (ch < 4 && hq % G == 0 && b < c.max_seqs)
+    v.work_counters[(((int64_t)a.layer * c.max_seqs + b) * c.n_kv_heads + hkv) * 4 + ch] = 0u;
   const float o = L > 0.f ? A / L : 0.f;
   store_from_f32(a.out, ((int64_t)b * Hq + hq) * D + ch, a.out_dtype, o);
   if (a.lse && ch == 0) a.lse[(int64_t)b * Hq + hq] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : -INFINITY;
 }
 
 int launch_decode_simple(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {
-  dim3 grid(a.max_split * v.cfg.n_kv_heads * a.B);
+  dim3 grid(a.n_rows);
   if (v.cfg.head_dim == 128)
     hipLaunchKernelGGL(decode_simple_kernel<128>, grid, dim3(256), 0, st, v, a);
   else
