@@ -214,6 +214,24 @@ int thinkv_decode_attention(const thinkv_view* view, int32_t layer, const void* 
                             float softmax_scale, thinkv_dtype q_dtype, thinkv_dtype out_dtype,
                             int32_t max_ctx_pages, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * thinkv_decode_attention for callers that cannot allocate device memory or hand over a
+ * workspace: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same contract, arguments and kernels as thinkv_decode_attention, minus the
+ * workspace: the partial rows live in an array of THINKV_NOALLOC_SCRATCH_BYTES that is part of the
+ * library's device image (every GPU the library runs on holds its own copy until the process ends).
+ * The call allocates and frees nothing.  Launches whose partial rows do not fit (ask
+ * thinkv_decode_workspace_bytes with the same B and max_ctx_pages) return THINKV_E_WORKSPACE.
+ * All calls of a process on one GPU share that GPU's array: two calls that overlap in time on one
+ * GPU (different streams) race; calls on one stream are ordered and safe.  Nothing in the array
+ * needs clearing between calls (every word read was written by the same call).
+ */
+#define THINKV_NOALLOC_SCRATCH_BYTES (32u << 20)
+int thinkv_decode_attention_noalloc(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
+                                    const int32_t* seq_ids, const int32_t* q_pos, int32_t B, int32_t window,
+                                    float softmax_scale, thinkv_dtype q_dtype, thinkv_dtype out_dtype,
+                                    int32_t max_ctx_pages, void* stream);
+
 /* Same contract and arguments as thinkv_decode_attention, computed by the plain vector-ALU
  * kernel (binary32 dequantisation, no matrix cores).  Kept as a slow cross-check. */
 int thinkv_decode_attention_valu(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,

@@ -15,7 +15,7 @@ _DT = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
 ST_NOPAGES, ST_BAD_CLASS, ST_BAD_SLOT, ST_EVICT_DEAD, ST_BAD_SEQ, ST_BAD_SEGMENT = 1, 2, 4, 8, 16, 32
 EXPORTS = ["thinkv_block_bytes", "thinkv_page_bytes", "thinkv_append_workspace_bytes",
            "thinkv_decode_workspace_bytes", "thinkv_init_view", "thinkv_append_quantized", "thinkv_evict", "thinkv_evict_append",
-           "thinkv_decode_attention", "thinkv_decode_attention_valu", "thinkv_decode_sparsity_workspace_bytes",
+           "thinkv_decode_attention", "thinkv_decode_attention_noalloc", "thinkv_decode_attention_valu", "thinkv_decode_sparsity_workspace_bytes",
            "thinkv_decode_attention_sparsity", "thinkv_tbe_workspace_bytes", "thinkv_tbe_select", "thinkv_tbe_plan_workspace_bytes", "thinkv_tbe_plan",
            "thinkv_status_string"]
 
@@ -62,6 +62,8 @@ def load():
         fn = getattr(lib, name)
         fn.restype = C.c_int
         fn.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, vp, i32, i32, C.c_float, C.c_int, C.c_int, i32, vp, sz, vp]
+    lib.thinkv_decode_attention_noalloc.restype = C.c_int
+    lib.thinkv_decode_attention_noalloc.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, vp, i32, i32, C.c_float, C.c_int, C.c_int, i32, vp]
     lib.thinkv_decode_sparsity_workspace_bytes.restype = sz
     lib.thinkv_decode_sparsity_workspace_bytes.argtypes = [C.POINTER(Config), i32, i32]
     lib.thinkv_decode_attention_sparsity.restype = C.c_int
@@ -223,6 +225,21 @@ def _decode(fn, cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale
 def thinkv_decode_attention(cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale, max_ctx_pages, stream=None):
     _decode(load().thinkv_decode_attention, cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale,
             max_ctx_pages, stream)
+
+
+NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def thinkv_decode_attention_noalloc(cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale, max_ctx_pages, stream=None):
+    """thinkv_decode_attention without a workspace: the partial rows live in the library's own device array"""
+    B = int(q.shape[0])
+    assert q.is_contiguous() and out.is_contiguous() and tuple(q.shape) == tuple(out.shape)
+    assert tuple(q.shape[1:]) == (cache.cfg.n_q_heads, cache.cfg.head_dim)
+    assert seq_ids.dtype == torch.int32 and (q_pos is None or q_pos.dtype == torch.int32)
+    assert lse is None or (lse.dtype == torch.float32 and lse.numel() == B * cache.cfg.n_q_heads)
+    _check(load().thinkv_decode_attention_noalloc(C.byref(cache.view), layer, _ptr(q), _ptr(out), _ptr(lse), _ptr(seq_ids), _ptr(q_pos), B,
+                                                  window, float(softmax_scale), _DT[q.dtype], _DT[out.dtype], int(max_ctx_pages),
+                                                  _stream(stream)), "thinkv_decode_attention_noalloc")
 
 
 def thinkv_tbe_plan(cache, layer, seq_ids, seg_start, seg_type, n_segs, transition_ended, budget, max_cuts, tok_seq, tok_handle,

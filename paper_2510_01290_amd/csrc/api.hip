@@ -1,5 +1,6 @@
-// C ABI entry points: argument checks and kernel dispatch.  No allocation, no global state,
-// no synchronisation.
+// C ABI entry points: argument checks and kernel dispatch.  No allocation, no synchronisation; the
+// only state is what never changes (the device's compute-unit count, the address of the
+// library's own scratch array on each device).
 #include <cstdlib>
 #include "decode_common.h"
 
@@ -269,6 +270,29 @@ int thinkv_decode_attention(const thinkv_view* view, int32_t layer, const void* 
                             void* workspace, size_t workspace_bytes, void* stream) {
   return decode_common(view, layer, q, out, lse, seq_ids, q_pos, B, window, softmax_scale, (int)q_dtype, (int)out_dtype,
                        max_ctx_pages, workspace, workspace_bytes, stream, true);
+}
+
+// Partial rows of thinkv_decode_attention_noalloc.  In host code this name is only a stand-in for the
+// symbol: the array's address on a device comes from hipGetSymbolAddress (once per device, below).
+static __device__ __align__(256) unsigned char scratch[THINKV_NOALLOC_SCRATCH_BYTES];
+
+int thinkv_decode_attention_noalloc(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
+                                    const int32_t* seq_ids, const int32_t* q_pos, int32_t B, int32_t window,
+                                    float softmax_scale, thinkv_dtype q_dtype, thinkv_dtype out_dtype,
+                                    int32_t max_ctx_pages, void* stream) {
+  static void* scratch_of_device[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return THINKV_E_HIP;
+  if (scratch_of_device[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return THINKV_E_HIP;
+    scratch_of_device[dev] = p;
+  }
+  if (view && B > 0 && max_ctx_pages >= 0 && check_config(&view->cfg) == THINKV_OK &&
+      thinkv_decode_workspace_bytes(&view->cfg, B, max_ctx_pages) > (size_t)THINKV_NOALLOC_SCRATCH_BYTES)
+    return THINKV_E_WORKSPACE;
+  return decode_common(view, layer, q, out, lse, seq_ids, q_pos, B, window, softmax_scale, (int)q_dtype, (int)out_dtype,
+                       max_ctx_pages, scratch_of_device[dev], (size_t)THINKV_NOALLOC_SCRATCH_BYTES, stream, true);
 }
 
 int thinkv_decode_attention_valu(const thinkv_view* view, int32_t layer, const void* q, void* out, float* lse,
