@@ -1,13 +1,13 @@
 """Thought-adaptive eviction over the oracle cache: which tokens of a thought segment survive
 (test infrastructure; see oracle/__init__.py).
 
-Sec. 4.3 of the paper ("Think Before you Evict"): a segment of a thought type that is selected
-for eviction the n-th time is cut down to R_n tokens, R = {64, 32, 16, 8, 4}; the survivors are
-chosen by K-means over the segment's post-RoPE keys with K = min(|segment|, R_n): "the cluster
-centroids correspond to keys that are retained, and the corresponding value tokens are
-preserved" (appendix "TBE Eviction Policy": one representative key-value pair per cluster).
-Case 1 anneals every preceding segment when a transition segment ends; Case 2, when the cache
-is over its budget, anneals the oldest segment of the least important type until it fits.
+Sec. 4.3 of the paper ("Think Before you Evict"), problem statement "Thought-Adaptive Eviction":
+a segment that is selected for eviction the n-th time keeps min(|segment|, R_n) tokens,
+R = {64, 32, 16, 8, 4}; the survivors are chosen by K-means over the segment's post-RoPE keys
+with that K, one representative key of every cluster staying in the cache together with its
+value (appendix "TBE Eviction Policy").  Case 1 anneals every preceding segment when a
+transition segment ends; Case 2, when the cache is over its budget, anneals the oldest segment
+of the least important type until it fits.
 
 The paper fixes neither the K-means variant, its initialisation, its stopping rule nor any
 tie-break.  This reading (the kernels implement the same one):
@@ -119,65 +119,95 @@ def select_evictions(cache, layer, tok_seq, tok_handle, seg_offset, seg_keep, ma
     return ev.astype(np.int32), margins
 
 
+BY_COUNT, BY_SIZE = "count", "size"
+
+
 def anneal_plan(seg_type, seg_live, transition_ended, n_live, budget, retention=RETENTION, importance=IMPORTANCE,
-                once=False, max_cuts=None):
+                once=False, max_cuts=None, seg_count=None, rule=BY_COUNT):
     """Which segments of one (sequence, layer) are cut, and to how many tokens (Sec. 4.3).
 
     seg_type[i], seg_live[i]: thought type and live tokens of segment i, oldest first; the last
-    segment is the one being generated and is never touched.  The level of a segment follows
-    from its size: it is cut to the largest retention value below its size.
-    Case 1 (transition_ended): every preceding segment above the lowest retention value goes
-    down one level.  Case 2: while more than `budget` tokens are live, the oldest segment of the
-    least important type that can still shrink goes down one level.
-    Returns [(segment, keep)] in the order the cuts are made; a segment may appear twice.
-    once=True: a segment is cut at most once per call (one K-means per segment and call; what is
-    still over budget is dealt with on the next call); max_cuts: at most that many cuts."""
+    segment is the one being generated and is never touched.
+
+    rule BY_COUNT (the paper's statement of the problem): seg_count[i] = n, how often segment i has
+    been selected so far (updated in place; zeros when not given).  A selection keeps
+    min(live, R_n) tokens and makes the count n + 1; a segment can be selected while n is below
+    the number of retention levels.  A selection that removes nothing (the segment is no larger
+    than R_n) is not a cut: it only advances the count.
+    rule BY_SIZE (a reading for callers that keep no counts): the level follows from the
+    segment's size, which is cut to the largest retention value below it; seg_count is not used.
+
+    Case 1 (transition_ended): every preceding segment is selected once.  Case 2: while more than
+    `budget` tokens are live, the oldest segment of the least important type that can still be
+    selected is.  Returns [(segment, keep)] in the order the cuts are made; a segment may appear
+    twice.  once=True: a segment is cut at most once per call (one K-means per segment and call;
+    what is still over budget is dealt with on the next call); max_cuts: at most that many cuts
+    (a cut there is no room for is not made, and its selection does not count)."""
     live = [int(v) for v in seg_live]
     total = int(n_live)
     cuts = []
+    levels = len(retention)
+    if rule == BY_COUNT and seg_count is None:
+        seg_count = [0] * len(live)
 
-    def next_level(size):
-        for r in retention:
-            if r < size:
-                return r
-        return None
+    def selectable(i):
+        if rule == BY_COUNT:
+            return seg_count[i] < levels
+        return any(r < live[i] for r in retention)
+
+    def target(i):
+        """tokens segment i keeps if it is selected now"""
+        if rule == BY_COUNT:
+            return min(live[i], retention[seg_count[i]])
+        return next(r for r in retention if r < live[i])
 
     last = len(live) - 1
     done = set()
     room = (lambda: True) if max_cuts is None else (lambda: len(cuts) < max_cuts)
+
+    def select(i):
+        """True if the selection was made (a cut, or a selection that removes nothing)"""
+        nonlocal total
+        r = target(i)
+        if r < live[i]:
+            if not room():
+                return False
+            cuts.append((i, r))
+            done.add(i)
+            total -= live[i] - r
+            live[i] = r
+        if rule == BY_COUNT:
+            seg_count[i] += 1
+        return True
+
     if transition_ended:
         for i in range(last):
-            r = next_level(live[i])
-            if r is not None and room():
-                cuts.append((i, r))
-                done.add(i)
-                total -= live[i] - r
-                live[i] = r
+            if selectable(i):
+                select(i)
     while total > budget and room():
         pick = None
         for t in importance:
             for i in range(last):
-                if seg_type[i] == t and next_level(live[i]) is not None and not (once and i in done):
+                if seg_type[i] == t and selectable(i) and not (once and i in done):
                     pick = i
                     break
             if pick is not None:
                 break
         if pick is None:
             break
-        r = next_level(live[pick])
-        cuts.append((pick, r))
-        done.add(pick)
-        total -= live[pick] - r
-        live[pick] = r
+        if not select(pick):
+            break
     return cuts
 
 
-def plan_evictions(cache, layer, seq, seg_start, seg_type, transition_ended, budget, max_cuts, retention=RETENTION):
+def plan_evictions(cache, layer, seq, seg_start, seg_type, transition_ended, budget, max_cuts, retention=RETENTION,
+                   seg_count=None, rule=BY_COUNT):
     """The plan over the cache as it stands: every live token of the sequence belongs to the
     segment whose start is the largest one not above its position (the block table's start-index
     column, Sec. 5.2); segments are counted, anneal_plan (one cut per segment and call) names the
     cuts, and each cut comes with the handles of its live tokens in ascending position -- the
-    input of the survivor choice.  Returns [(segment, keep, handles)]."""
+    input of the survivor choice.  seg_count (rule BY_COUNT): the segments' selection counts, updated
+    in place.  Returns [(segment, keep, handles)]."""
     from .cache import make_handle, PAGE
     seg_start = np.asarray(seg_start, dtype=np.int64)
     n_seg = len(seg_start)
@@ -194,5 +224,5 @@ def plan_evictions(cache, layer, seq, seg_start, seg_type, transition_ended, bud
                         members[sg].append((pos, make_handle(c, pi, slot)))
     live = [len(m) for m in members]
     cuts = anneal_plan(list(seg_type), live, bool(transition_ended), int(cache.n_live[seq, layer]), budget,
-                       retention=retention, once=True, max_cuts=max_cuts)
+                       retention=retention, once=True, max_cuts=max_cuts, seg_count=seg_count, rule=rule)
     return [(i, r, [h for _, h in sorted(members[i])]) for i, r in cuts]
