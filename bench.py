@@ -244,10 +244,12 @@ def main():
         p_in = [ev_seq, torch.from_numpy(seg_start).to(dev), torch.from_numpy(seg_type).to(dev), torch.from_numpy(n_segs).to(dev),
                 torch.ones(args.batch, dtype=torch.uint8, device=dev)]
         tm = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
-        B.thinkv_tbe_plan(gc, 0, *p_in, 10 ** 9, 256, *p_out)
+        seg_cnt = torch.zeros((args.batch, max_segs), dtype=torch.int32, device=dev)      # every segment selected for the first time
+        B.thinkv_tbe_plan(gc, 0, *p_in, 10 ** 9, 256, *p_out, seg_count=seg_cnt)
         for a_, b_ in tm:
+            seg_cnt.zero_()
             a_.record()
-            B.thinkv_tbe_plan(gc, 0, *p_in, 10 ** 9, 256, *p_out)
+            B.thinkv_tbe_plan(gc, 0, *p_in, 10 ** 9, 256, *p_out, seg_count=seg_cnt)
             b_.record()
         torch.cuda.synchronize()
         cnts = p_out[4].cpu().numpy()

@@ -55,6 +55,8 @@ typedef enum {
 #define THINKV_TBE_MAX_SEGMENT 256 /* live tokens of one segment handed to thinkv_tbe_select */
 #define THINKV_TBE_MAX_KEEP 64     /* largest retention level (the paper's schedule starts at 64) */
 #define THINKV_TBE_MAX_SEGS 2048   /* segments of one sequence thinkv_tbe_plan looks at          */
+#define THINKV_TBE_BY_COUNT 0      /* thinkv_tbe_plan: retention level from the segment's selection count */
+#define THINKV_TBE_BY_SIZE 1       /* thinkv_tbe_plan: retention level from the segment's live size       */
 #define THINKV_GROUP_SIZE 32
 
 /* Static geometry; host memory, passed by value inside thinkv_view. */
@@ -275,13 +277,21 @@ size_t thinkv_tbe_workspace_bytes(const thinkv_config* cfg, int32_t n_tok, int32
  * Thought-adaptive eviction, the plan (Sec. 4.3): which segments of the examined sequences are
  * cut now, and to how many tokens; the output is the input of thinkv_tbe_select.
  * Case 1: where transition_ended[b] is set (a transition segment of the sequence has just
- * ended), every preceding segment goes down one level of the retention schedule {64,32,16,8,4}.
- * Case 2: while the sequence holds more than `budget` live tokens, the oldest segment of the
- * least important type (0 = transition, then 1 = execution, then 2 = reasoning) that can still
- * shrink goes down one level.  The level of a segment follows from its live size (it is cut to
- * the largest schedule value below that size); a segment is cut at most once per call; the
- * last (open) segment is never touched; a segment with more than THINKV_TBE_MAX_SEGMENT live
- * tokens is left alone and reported (THINKV_ST_BAD_SEGMENT in the last word of dev_status).
+ * ended), every preceding segment is selected.  Case 2: while the sequence holds more than
+ * `budget` live tokens, the oldest segment of the least important type (0 = transition, then
+ * 1 = execution, then 2 = reasoning) that can still be selected is.
+ * What a selection does (problem statement "Thought-Adaptive Eviction" of Sec. 4.3, retention
+ * schedule R = {64,32,16,8,4}):
+ *   THINKV_TBE_BY_COUNT  the paper's rule.  seg_count[seq][segment] = n, how often the segment has been
+ *                        selected so far; the selection keeps min(live tokens, R_n) and makes the count n + 1;
+ *                        a segment can be selected while n < 5.  A selection that removes nothing is not listed
+ *                        as a cut, it only advances the count.  The caller keeps the table (zero for a new segment).
+ *   THINKV_TBE_BY_SIZE   for callers that keep no counts: the level follows from the segment's live
+ *                        size, which is cut to the largest schedule value below it; seg_count is not used.
+ * A segment is cut at most once per call; the last (open) segment is never touched; a segment
+ * with more than THINKV_TBE_MAX_SEGMENT live tokens is left alone and reported
+ * (THINKV_ST_BAD_SEGMENT in the last word of dev_status).  A cut that does not fit the output
+ * lists is not made: its segment's count stays.
  * A live token belongs to the segment whose start is the largest one not above its position
  * (the block table's start-index column, Sec. 5.2 "Block Table").
  *
@@ -291,6 +301,8 @@ size_t thinkv_tbe_workspace_bytes(const thinkv_config* cfg, int32_t n_tok, int32
  *   seg_type          DEVICE [max_seqs][max_segs] thought type of the segment
  *   n_segs            DEVICE [max_seqs] segments the sequence has so far
  *   transition_ended  DEVICE [B], may be NULL (no Case 1 anywhere)
+ *   seg_count         DEVICE [max_seqs][max_segs] in/out (THINKV_TBE_BY_COUNT; may be NULL under BY_SIZE)
+ *   rule              THINKV_TBE_BY_COUNT or THINKV_TBE_BY_SIZE
  *   max_cuts          cuts per sequence and call at most (1..256); what is left waits for the next call
  *   cap_seg, cap_tok  capacity of the output lists; cuts that no longer fit are left for the next call
  *   tok_seq, tok_handle  DEVICE [cap_tok] out: the live tokens of the cut segments, segment after
@@ -302,7 +314,7 @@ size_t thinkv_tbe_workspace_bytes(const thinkv_config* cfg, int32_t n_tok, int32
  */
 size_t thinkv_tbe_plan_workspace_bytes(int32_t B, int32_t max_cuts);
 int thinkv_tbe_plan(const thinkv_view* view, int32_t layer, const int32_t* seq_ids, const int32_t* seg_start,
-                    const uint8_t* seg_type, const int32_t* n_segs, const uint8_t* transition_ended, int32_t B,
+                    const uint8_t* seg_type, const int32_t* n_segs, const uint8_t* transition_ended, int32_t* seg_count, int32_t rule, int32_t B,
                     int32_t max_segs, int32_t budget, int32_t max_cuts, int32_t cap_seg, int32_t cap_tok,
                     int32_t* tok_seq, int32_t* tok_handle, int32_t* seg_offset, int32_t* seg_keep, int32_t* counts,
                     void* workspace, size_t workspace_bytes, void* stream);

@@ -76,7 +76,7 @@ def load():
     lib.thinkv_tbe_plan_workspace_bytes.restype = sz
     lib.thinkv_tbe_plan_workspace_bytes.argtypes = [i32, i32]
     lib.thinkv_tbe_plan.restype = C.c_int
-    lib.thinkv_tbe_plan.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.thinkv_tbe_plan.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.thinkv_status_string.restype = C.c_char_p
     lib.thinkv_status_string.argtypes = [C.c_int]
     _lib = lib
@@ -242,9 +242,13 @@ def thinkv_decode_attention_noalloc(cache, layer, q, out, lse, seq_ids, q_pos, w
                                                   _stream(stream)), "thinkv_decode_attention_noalloc")
 
 
+TBE_BY_COUNT, TBE_BY_SIZE = 0, 1
+
+
 def thinkv_tbe_plan(cache, layer, seq_ids, seg_start, seg_type, n_segs, transition_ended, budget, max_cuts, tok_seq, tok_handle,
-                    seg_offset, seg_keep, counts, stream=None):
-    """seg_start [max_seqs, max_segs] int32, seg_type [max_seqs, max_segs] uint8, n_segs [max_seqs] int32, seq_ids [B] int32,
+                    seg_offset, seg_keep, counts, seg_count=None, rule=TBE_BY_COUNT, stream=None):
+    """seg_count [max_seqs, max_segs] int32 in/out (selections of every segment so far; rule TBE_BY_COUNT);
+    seg_start [max_seqs, max_segs] int32, seg_type [max_seqs, max_segs] uint8, n_segs [max_seqs] int32, seq_ids [B] int32,
     transition_ended [B] uint8 or None; outputs tok_seq / tok_handle [cap_tok], seg_offset [cap_seg + 1], seg_keep [cap_seg],
     counts [2], all int32 device tensors."""
     B, max_segs = int(seq_ids.numel()), int(seg_start.shape[1])
@@ -255,10 +259,11 @@ def thinkv_tbe_plan(cache, layer, seq_ids, seg_start, seg_type, n_segs, transiti
     for t in (seq_ids, tok_seq, tok_handle, seg_offset, seg_keep, counts):
         assert t.dtype == torch.int32 and t.is_contiguous()
     assert transition_ended is None or (transition_ended.dtype == torch.uint8 and transition_ended.numel() == B)
+    assert seg_count is None or (seg_count.dtype == torch.int32 and seg_count.is_contiguous() and tuple(seg_count.shape) == tuple(seg_start.shape))
     nb = load().thinkv_tbe_plan_workspace_bytes(B, int(max_cuts))
     ws = cache.workspace(nb)
     _check(load().thinkv_tbe_plan(C.byref(cache.view), layer, _ptr(seq_ids), _ptr(seg_start), _ptr(seg_type), _ptr(n_segs),
-                                  _ptr(transition_ended), B, max_segs, int(budget), int(max_cuts), cap_seg, cap_tok, _ptr(tok_seq),
+                                  _ptr(transition_ended), _ptr(seg_count), int(rule), B, max_segs, int(budget), int(max_cuts), cap_seg, cap_tok, _ptr(tok_seq),
                                   _ptr(tok_handle), _ptr(seg_offset), _ptr(seg_keep), _ptr(counts), _ptr(ws), ws.numel(),
                                   _stream(stream)), "thinkv_tbe_plan")
 

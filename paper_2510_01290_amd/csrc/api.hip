@@ -16,7 +16,7 @@ int launch_decode_mfma(const thinkv_view& v, const DecodeArgs& a, hipStream_t st
 size_t tbe_ws_bytes(const thinkv_config& c, int n_tok, int n_seg);
 size_t tbe_plan_ws_bytes(int B, int max_cuts);
 int launch_tbe_plan(const thinkv_view& v, int layer, const int32_t* seq_ids, const int32_t* seg_start, const uint8_t* seg_type,
-                    const int32_t* n_segs, const uint8_t* transition_ended, int B, int max_segs, int budget, int max_cuts,
+                    const int32_t* n_segs, const uint8_t* transition_ended, int32_t* seg_count, int rule, int B, int max_segs, int budget, int max_cuts,
                     int cap_seg, int cap_tok, int32_t* tok_seq, int32_t* tok_handle, int32_t* seg_offset, int32_t* seg_keep,
                     int32_t* counts, void* workspace, hipStream_t st);
 int launch_tbe_select(const thinkv_view& v, int layer, const int32_t* tok_seq, const int32_t* tok_handle, const int32_t* seg_offset,
@@ -336,7 +336,7 @@ size_t thinkv_tbe_plan_workspace_bytes(int32_t B, int32_t max_cuts) {
 }
 
 int thinkv_tbe_plan(const thinkv_view* view, int32_t layer, const int32_t* seq_ids, const int32_t* seg_start,
-                    const uint8_t* seg_type, const int32_t* n_segs, const uint8_t* transition_ended, int32_t B,
+                    const uint8_t* seg_type, const int32_t* n_segs, const uint8_t* transition_ended, int32_t* seg_count, int32_t rule, int32_t B,
                     int32_t max_segs, int32_t budget, int32_t max_cuts, int32_t cap_seg, int32_t cap_tok,
                     int32_t* tok_seq, int32_t* tok_handle, int32_t* seg_offset, int32_t* seg_keep, int32_t* counts,
                     void* workspace, size_t workspace_bytes, void* stream) {
@@ -346,8 +346,10 @@ int thinkv_tbe_plan(const thinkv_view* view, int32_t layer, const int32_t* seq_i
   if (max_segs < 1 || max_segs > THINKV_TBE_MAX_SEGS || max_cuts < 1 || max_cuts > THINKV_TBE_MAX_SEGMENT) return THINKV_E_INVALID_ARG;
   if (!seq_ids || !seg_start || !seg_type || !n_segs || !tok_seq || !tok_handle || !seg_offset || !seg_keep || !counts || !workspace)
     return THINKV_E_INVALID_ARG;
+  if (rule != THINKV_TBE_BY_COUNT && rule != THINKV_TBE_BY_SIZE) return THINKV_E_INVALID_ARG;
+  if (rule == THINKV_TBE_BY_COUNT && !seg_count) return THINKV_E_INVALID_ARG;
   if (workspace_bytes < tbe_plan_ws_bytes(B, max_cuts)) return THINKV_E_WORKSPACE;
-  return launch_tbe_plan(*view, layer, seq_ids, seg_start, seg_type, n_segs, transition_ended, B, max_segs, budget, max_cuts,
+  return launch_tbe_plan(*view, layer, seq_ids, seg_start, seg_type, n_segs, transition_ended, seg_count, rule, B, max_segs, budget, max_cuts,
                          cap_seg, cap_tok, tok_seq, tok_handle, seg_offset, seg_keep, counts, workspace, (hipStream_t)stream);
 }
 

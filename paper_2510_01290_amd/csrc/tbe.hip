@@ -462,8 +462,11 @@ int launch_tbe_select(const thinkv_view& v, int layer, const int32_t* tok_seq, c
 // every preceding segment goes down one retention level when a transition segment has ended;
 // Case 2, while the sequence holds more live tokens than the budget, the oldest segment of the
 // least important type that can still shrink goes down one level).  A segment is cut at most
-// once per call (one K-means per segment and call); its level follows from its live size: it is
-// cut to the largest retention value below that size.  The open (last) segment is never touched.
+// once per call (one K-means per segment and call).  Its level follows from the number n of times
+// it has been selected before (a column the caller keeps): it keeps min(live, R_n) tokens, and a
+// selection that removes nothing only advances n (problem statement "Thought-Adaptive Eviction");
+// or, as an option for callers without that column, from its live size: it is cut to the largest
+// retention value below that size.  The open (last) segment is never touched.
 // A live token belongs to the segment whose start is the largest one not above its position
 // (the block table's start-index column, Sec. 5.2).
 //
@@ -487,6 +490,8 @@ struct PlanArgs {
   const uint8_t* seg_type;
   const int32_t* n_segs;
   const uint8_t* transition_ended;
+  int32_t* seg_count;   // [max_seqs][max_segs] selections so far (rule THINKV_TBE_BY_COUNT)
+  int rule;
   int32_t* tok_seq;
   int32_t* tok_handle;
   int32_t* seg_offset;
@@ -587,6 +592,8 @@ __global__ __launch_bounds__(kPlanThreads) void tbe_count_plan_kernel(thinkv_vie
   __shared__ int s_start[kMaxSegs];
   __shared__ int s_cnt[kMaxSegs];
   __shared__ uint8_t s_type[kMaxSegs];
+  __shared__ uint8_t s_lvl[kMaxSegs];   // selections so far, capped at the number of levels
+  const bool by_count = a.rule == THINKV_TBE_BY_COUNT;
   const int seq = a.seq_ids[b];
   if (seq < 0 || seq >= c.max_seqs) {
     if (tid == 0) {
@@ -600,10 +607,13 @@ __global__ __launch_bounds__(kPlanThreads) void tbe_count_plan_kernel(thinkv_vie
   ns = ns < 0 ? 0 : (ns > a.max_segs ? a.max_segs : ns);
   const int32_t* starts = a.seg_start + (int64_t)seq * a.max_segs;
   const uint8_t* types = a.seg_type + (int64_t)seq * a.max_segs;
+  int32_t* sel = by_count ? a.seg_count + (int64_t)seq * a.max_segs : nullptr;
   for (int i = tid; i < ns; i += kPlanThreads) {
     s_start[i] = starts[i];
     s_type[i] = types[i];
     s_cnt[i] = 0;
+    const int n = by_count ? sel[i] : 0;
+    s_lvl[i] = (uint8_t)(n < 0 ? 0 : (n > 5 ? 5 : n));
   }
   __syncthreads();
   for_live_tokens(v, seq, a.layer, s_start, ns, [&](int sg, int, int) { atomicAdd(&s_cnt[sg], 1); });
@@ -622,7 +632,23 @@ __global__ __launch_bounds__(kPlanThreads) void tbe_count_plan_kernel(thinkv_vie
     for (int i0 = 0; i0 < last; i0 += kPlanThreads) {
       const int i = i0 + tid, lane = tid & 63, wave = tid >> 6;
       const int cnt = i < last ? s_cnt[i] : 0;
-      const int r = next_level(cnt);
+      // what the segment keeps if it is selected now (0: it cannot be selected, or nothing would go)
+      int r = 0;
+      if (i < last) {
+        if (by_count) {
+          const int n = s_lvl[i];
+          if (n < 5) {
+            r = cnt < kRetention[n] ? cnt : kRetention[n];
+            if (r >= cnt) {           // removes nothing: not a cut, the count moves on
+              s_lvl[i] = (uint8_t)(n + 1);
+              sel[i] = n + 1;
+              r = 0;
+            }
+          }
+        } else {
+          r = next_level(cnt);
+        }
+      }
       const bool big = r && cnt > kTbeMaxTokens;
       const int flag = r && !big;
       int inc = flag;
@@ -687,7 +713,21 @@ __global__ __launch_bounds__(kPlanThreads) void tbe_count_plan_kernel(thinkv_vie
   for (int t = 0; t < 3; ++t)
     for (int i = 0; i < last && total > a.budget && n_cuts < a.max_cuts; ++i) {
       if (s_type[i] != t || s_cnt[i] < 0) continue;
-      const int r = next_level(s_cnt[i]);
+      int r = 0;
+      if (by_count) {
+        // selections that remove nothing follow one another at once (each advances the count)
+        int n = s_lvl[i];
+        while (n < 5 && r == 0) {
+          const int keep = s_cnt[i] < kRetention[n] ? s_cnt[i] : kRetention[n];
+          if (keep < s_cnt[i]) r = keep; else ++n;
+        }
+        if (n != s_lvl[i]) {
+          s_lvl[i] = (uint8_t)n;
+          sel[i] = n;
+        }
+      } else {
+        r = next_level(s_cnt[i]);
+      }
       if (!r) continue;
       if (s_cnt[i] > kTbeMaxTokens) {
         oversize = true;
@@ -802,7 +842,12 @@ __global__ __launch_bounds__(kPlanThreads) void tbe_fill_kernel(thinkv_view v, P
     }
   }
   __syncthreads();
-  for (int i = tid; i < n_cuts; i += kPlanThreads) s_cut[a.st_seg[(int64_t)b * a.max_cuts + i]] = i;
+  for (int i = tid; i < n_cuts; i += kPlanThreads) {
+    const int sg = a.st_seg[(int64_t)b * a.max_cuts + i];
+    s_cut[sg] = i;
+    // the cut is made (it fitted the lists): this was a selection of the segment
+    if (a.rule == THINKV_TBE_BY_COUNT) a.seg_count[(int64_t)seq * a.max_segs + sg] += 1;
+  }
   __syncthreads();
   // deal the tokens: position into tok_seq for now, handle into tok_handle
   for_live_tokens(v, seq, a.layer, s_start, ns, [&](int sg, int pos, int h) {
@@ -852,7 +897,7 @@ __global__ __launch_bounds__(256) void tbe_sort_kernel(PlanArgs a) {
 }
 
 int launch_tbe_plan(const thinkv_view& v, int layer, const int32_t* seq_ids, const int32_t* seg_start, const uint8_t* seg_type,
-                    const int32_t* n_segs, const uint8_t* transition_ended, int B, int max_segs, int budget, int max_cuts,
+                    const int32_t* n_segs, const uint8_t* transition_ended, int32_t* seg_count, int rule, int B, int max_segs, int budget, int max_cuts,
                     int cap_seg, int cap_tok, int32_t* tok_seq, int32_t* tok_handle, int32_t* seg_offset, int32_t* seg_keep,
                     int32_t* counts, void* workspace, hipStream_t st) {
   PlanArgs a;
@@ -861,6 +906,8 @@ int launch_tbe_plan(const thinkv_view& v, int layer, const int32_t* seq_ids, con
   a.seg_type = seg_type;
   a.n_segs = n_segs;
   a.transition_ended = transition_ended;
+  a.seg_count = seg_count;
+  a.rule = rule;
   a.tok_seq = tok_seq;
   a.tok_handle = tok_handle;
   a.seg_offset = seg_offset;

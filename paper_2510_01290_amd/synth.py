@@ -262,12 +262,12 @@ def bulk_evict_refill(name, geom, seed, n_seqs, ctx_tokens, evict_frac, refill=N
 def budgeted_decode(name, geom, seed, n_seqs, n_steps, budget, steps_per_call=16,
                     retention=(64, 32, 16, 8, 4), evict_order=(E, R, T)):
     """Config 3: n_steps decode appends per sequence under a live-token budget.  Whenever a
-    sequence holds more than `budget` live tokens, the oldest segment of the least important
-    class that is still above the lowest retention level is cut down to the next level below
-    its current size by a seeded uniform choice (the paper's budget case of thought-adaptive
-    eviction, Sec. 4.3, with the K-means pick replaced by a random one).  The level follows from
-    the segment's size alone, so a segment that was cut while still growing can be cut again.
-    All layers share the token classes; eviction choices are drawn per layer."""
+    sequence holds more than `budget` live tokens, the oldest closed segment of the least
+    important class that can still be selected is: its n-th selection keeps min(size,
+    retention[n]) tokens, chosen by a seeded uniform pick (the paper's budget case of
+    thought-adaptive eviction, Sec. 4.3, with the K-means pick replaced by a random one); the
+    segment being generated is never touched.  All layers share the token classes; eviction
+    choices are drawn per layer."""
     rng = np.random.default_rng(seed)
     L = geom.n_layers
     classes, segs = [], []
@@ -280,6 +280,7 @@ def budgeted_decode(name, geom, seed, n_seqs, n_steps, budget, steps_per_call=16
     for l in range(L):
         # per sequence: segment id -> live positions
         live = [dict() for _ in range(n_seqs)]
+        selected = [dict() for _ in range(n_seqs)]     # segment id -> times selected so far
         n_live = np.zeros(n_seqs, dtype=np.int64)
         t = 0
         while t < n_steps:
@@ -291,23 +292,25 @@ def budgeted_decode(name, geom, seed, n_seqs, n_steps, budget, steps_per_call=16
                 for g in np.unique(sg).tolist():
                     live[s].setdefault(g, []).extend((t + np.flatnonzero(sg == g)).tolist())
                 n_live[s] += n
+                open_seg = int(segs[s][t + n - 1])
                 while n_live[s] > budget:
                     pick = None
                     for c in evict_order:
                         for g in sorted(live[s]):
-                            if classes[s][live[s][g][0]] != c:
+                            if g == open_seg or classes[s][live[s][g][0]] != c:
                                 continue
-                            lv = 0
-                            while lv < len(retention) and retention[lv] >= len(live[s][g]):
-                                lv += 1
-                            if lv < len(retention):
-                                pick = (g, lv)
+                            # selections that remove nothing only advance the segment's count
+                            while selected[s].get(g, 0) < len(retention) and retention[selected[s].get(g, 0)] >= len(live[s][g]):
+                                selected[s][g] = selected[s].get(g, 0) + 1
+                            if selected[s].get(g, 0) < len(retention):
+                                pick = (g, selected[s].get(g, 0))
                                 break
                         if pick:
                             break
                     if pick is None:
                         break
                     g, lv = pick
+                    selected[s][g] = lv + 1
                     keep = retention[lv]
                     cur = np.array(live[s][g])
                     drop = rng.choice(cur, size=len(cur) - keep, replace=False)

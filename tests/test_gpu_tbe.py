@@ -171,6 +171,7 @@ def test_tbe_driven_budgeted_decode():
     dev = gc.device
     handle = [np.full(steps, -1, np.int64) for _ in range(S)]
     alive = [np.zeros(steps, bool) for _ in range(S)]
+    selected = [dict() for _ in range(S)]         # run start -> times the segment has been selected (the paper's n)
     n_cuts = n_clear = n_same = 0
     for t0 in range(0, steps, per_call):
         n = min(per_call, steps - t0)
@@ -197,12 +198,11 @@ def test_tbe_driven_budgeted_decode():
             live = [int(alive[s][a:b].sum()) for a, b in runs]
             types = [int(c[a]) for a, _ in runs]
             ended = len(runs) >= 2 and types[-2] == synth.T and runs[-1][0] >= t0      # a transition segment ended in this call
-            plan = otbe.anneal_plan(types, live, ended, int(alive[s].sum()), budget)
-            seen = set()
+            cnt = [selected[s].get(a, 0) for a, _ in runs]
+            plan = otbe.anneal_plan(types, live, ended, int(alive[s].sum()), budget, once=True, seg_count=cnt)
+            for (a, _), c_ in zip(runs, cnt):
+                selected[s][a] = c_
             for i, r in plan:
-                if i in seen:
-                    continue                      # one cut per segment and call; the rest follows on the next call
-                seen.add(i)
                 a, b = runs[i]
                 p = a + np.flatnonzero(alive[s][a:b])
                 t_seq += [s] * len(p)
@@ -253,33 +253,47 @@ def _tables(classes_segs, max_seqs, max_segs, upto):
     return st, ty, ns
 
 
-def _device_plan(gc, layer, seq_ids, st, ty, ns, trans, budget, max_cuts, cap_seg, cap_tok):
+def _device_plan(gc, layer, seq_ids, st, ty, ns, trans, budget, max_cuts, cap_seg, cap_tok, seg_count=None, rule=0):
+    """seg_count: numpy [max_seqs, max_segs] int32, updated in place from the device's copy"""
     from paper_2510_01290_amd import binding as B
     d = gc.device
+    d_cnt = None if seg_count is None else torch.from_numpy(seg_count).to(d)
     out = dict(tok_seq=torch.full((cap_tok,), -7, dtype=torch.int32, device=d), tok_handle=torch.full((cap_tok,), -7, dtype=torch.int32, device=d),
                seg_offset=torch.full((cap_seg + 1,), -7, dtype=torch.int32, device=d), seg_keep=torch.full((cap_seg,), -7, dtype=torch.int32, device=d),
                counts=torch.full((2,), -7, dtype=torch.int32, device=d))
     B.thinkv_tbe_plan(gc, layer, torch.tensor(seq_ids, dtype=torch.int32, device=d), torch.from_numpy(st).to(d), torch.from_numpy(ty).to(d),
                       torch.from_numpy(ns).to(d), None if trans is None else torch.tensor(trans, dtype=torch.uint8, device=d), budget, max_cuts,
-                      out["tok_seq"], out["tok_handle"], out["seg_offset"], out["seg_keep"], out["counts"])
+                      out["tok_seq"], out["tok_handle"], out["seg_offset"], out["seg_keep"], out["counts"], seg_count=d_cnt, rule=rule)
     torch.cuda.synchronize()
+    if seg_count is not None:
+        seg_count[...] = d_cnt.cpu().numpy()
     return {k: v.cpu().numpy() for k, v in out.items()}
 
 
-def _oracle_plan(oc, layer, seq_ids, st, ty, ns, trans, budget, max_cuts, cap_seg, cap_tok):
-    """the per-sequence plans put together the way the library does: sequence after sequence, cuts that do not fit are left out"""
+def _oracle_plan(oc, layer, seq_ids, st, ty, ns, trans, budget, max_cuts, cap_seg, cap_tok, seg_count=None, rule=otbe.BY_COUNT):
+    """the per-sequence plans put together the way the library does: sequence after sequence, cuts that do not fit are left
+    out (a cut that is not made is no selection: its segment's count is taken back).  seg_count: numpy [max_seqs, max_segs],
+    updated in place."""
     tok_seq, tok_handle, off, keep = [], [], [0], []
     for b, s in enumerate(seq_ids):
-        plan = otbe.plan_evictions(oc, layer, s, st[s, :ns[s]], ty[s, :ns[s]], bool(trans[b]) if trans is not None else False, budget, max_cuts)
+        cnt = None if seg_count is None else [int(x) for x in seg_count[s, :ns[s]]]
+        plan = otbe.plan_evictions(oc, layer, s, st[s, :ns[s]], ty[s, :ns[s]], bool(trans[b]) if trans is not None else False, budget, max_cuts,
+                                   seg_count=cnt, rule=rule)
+        full = False
         for sg, r, hs in plan:
             if len(hs) > 256:
                 continue
-            if len(keep) >= cap_seg or len(tok_handle) + len(hs) > cap_tok:
-                break
+            if full or len(keep) >= cap_seg or len(tok_handle) + len(hs) > cap_tok:
+                full = True
+                if cnt is not None:
+                    cnt[sg] -= 1
+                continue
             tok_seq += [s] * len(hs)
             tok_handle += hs
             off.append(len(tok_handle))
             keep.append(r)
+        if cnt is not None:
+            seg_count[s, :ns[s]] = cnt
     return np.array(tok_seq, np.int32), np.array(tok_handle, np.int32), np.array(off, np.int32), np.array(keep, np.int32)
 
 
@@ -305,25 +319,35 @@ def test_tbe_plan_on_device_matches_the_oracle():
     gb.evict(0, np.zeros(200, np.int64), handles[0][ev])
     ob.evict(0, np.zeros(200, np.int64), handles[0][ev])
     st, ty, ns = _tables(cs, S, 64, n_tok)
+    cnt_dev, cnt_ora = np.zeros((S, 64), np.int32), np.zeros((S, 64), np.int32)
     for name, seq_ids, trans, budget, max_cuts, cap_seg, cap_tok in [
             ("case 1 everywhere", [0, 1, 2, 3], [1, 1, 1, 1], 10 ** 6, 32, 128, 8192),
             ("case 2 only", [2, 0, 1], None, 250, 32, 128, 8192),
             ("both, few cuts per sequence", [3, 1, 0, 2], [0, 1, 0, 1], 200, 3, 128, 8192),
-            ("output lists too short", [0, 1, 2], [1, 1, 1], 10 ** 6, 32, 5, 700)]:
-        got = _device_plan(gc, 0, seq_ids, st, ty, ns, trans, budget, max_cuts, cap_seg, cap_tok)
-        w_seq, w_h, w_off, w_keep = _oracle_plan(ob.cache, 0, seq_ids, st, ty, ns, trans, budget, max_cuts, cap_seg, cap_tok)
-        n_seg, n_t = int(got["counts"][0]), int(got["counts"][1])
-        assert (n_seg, n_t) == (len(w_keep), len(w_h)), (name, n_seg, n_t, len(w_keep), len(w_h))
-        assert np.array_equal(got["seg_keep"][:n_seg], w_keep) and np.array_equal(got["seg_offset"][:n_seg + 1], w_off), name
-        assert np.array_equal(got["tok_handle"][:n_t], w_h) and np.array_equal(got["tok_seq"][:n_t], w_seq), name
-        assert n_seg > 0
-        _say((name, "cuts", n_seg, "tokens", n_t))
+            ("output lists too short", [0, 1, 2], [1, 1, 1], 10 ** 6, 32, 5, 700),
+            ("case 1 again: the next level", [0, 1, 2, 3], [1, 1, 1, 1], 10 ** 6, 32, 128, 8192),
+            ("case 2 again", [1, 0, 2], None, 120, 32, 128, 8192)]:
+        # the size-derived option (no counts kept), then the paper's rule: the counts are carried from case to case on both
+        # sides (the cache itself does not change: a plan evicts nothing), so later cases see segments at every level
+        for rule_d, rule_o, c_d, c_o in ((B.TBE_BY_SIZE, otbe.BY_SIZE, None, None), (B.TBE_BY_COUNT, otbe.BY_COUNT, cnt_dev, cnt_ora)):
+            got = _device_plan(gc, 0, seq_ids, st, ty, ns, trans, budget, max_cuts, cap_seg, cap_tok, seg_count=c_d, rule=rule_d)
+            w_seq, w_h, w_off, w_keep = _oracle_plan(ob.cache, 0, seq_ids, st, ty, ns, trans, budget, max_cuts, cap_seg, cap_tok,
+                                                     seg_count=c_o, rule=rule_o)
+            n_seg, n_t = int(got["counts"][0]), int(got["counts"][1])
+            assert (n_seg, n_t) == (len(w_keep), len(w_h)), (name, rule_o, n_seg, n_t, len(w_keep), len(w_h))
+            assert np.array_equal(got["seg_keep"][:n_seg], w_keep) and np.array_equal(got["seg_offset"][:n_seg + 1], w_off), (name, rule_o)
+            assert np.array_equal(got["tok_handle"][:n_t], w_h) and np.array_equal(got["tok_seq"][:n_t], w_seq), (name, rule_o)
+            assert n_seg > 0 or rule_o == otbe.BY_COUNT
+            if c_d is not None:
+                assert np.array_equal(c_d, c_o), (name, "selection counts")
+            _say((name, rule_o, "cuts", n_seg, "tokens", n_t))
     assert int(gc.dev_status.abs().sum().item()) == 0
     # a sequence id that does not exist, and a segment too large for the survivor choice
     st2, ty2, ns2 = st.copy(), ty.copy(), ns.copy()
     st2[2, :2] = [0, 880]
     ns2[2] = 2                                              # sequence 2: one segment of 880 tokens, then the open one
-    got = _device_plan(gc, 0, [2, 9], st2, ty2, ns2, [1, 1], 10 ** 6, 8, 16, 4096)
+    assert cnt_dev.max() >= 2 and (cnt_dev[:, 0] > 0).any()
+    got = _device_plan(gc, 0, [2, 9], st2, ty2, ns2, [1, 1], 10 ** 6, 8, 16, 4096, rule=B.TBE_BY_SIZE)
     assert got["counts"].tolist() == [0, 0]
     flags = gc.dev_status.cpu().numpy()[-1]
     assert flags & B.ST_BAD_SEGMENT and flags & B.ST_BAD_SEQ
@@ -345,6 +369,7 @@ def test_tbe_whole_loop_on_the_device():
     gb = parity.GpuBackend(gc)
     dev = gc.device
     cap_seg, cap_tok = 64, 64 * 200
+    cnt_dev, cnt_ora = np.zeros((S, 32), np.int32), np.zeros((S, 32), np.int32)
     n_calls = n_cuts = n_same = 0
     for t0 in range(0, steps, per_call):
         n = min(per_call, steps - t0)
@@ -360,8 +385,9 @@ def test_tbe_whole_loop_on_the_device():
             seg = cs[s][1]
             ended = [seg[p - 1] for p in range(max(t0, 1), t0 + n) if seg[p] != seg[p - 1]]
             trans.append(int(any(cs[s][0][np.flatnonzero(seg == e)[0]] == synth.T for e in ended)))
-        got = _device_plan(gc, 0, list(range(S)), st, ty, ns, trans, budget, 8, cap_seg, cap_tok)
-        w_seq, w_h, w_off, w_keep = _oracle_plan(ob.cache, 0, list(range(S)), st, ty, ns, trans, budget, 8, cap_seg, cap_tok)
+        got = _device_plan(gc, 0, list(range(S)), st, ty, ns, trans, budget, 8, cap_seg, cap_tok, seg_count=cnt_dev)
+        w_seq, w_h, w_off, w_keep = _oracle_plan(ob.cache, 0, list(range(S)), st, ty, ns, trans, budget, 8, cap_seg, cap_tok, seg_count=cnt_ora)
+        assert np.array_equal(cnt_dev, cnt_ora), "selection counts"
         n_seg, n_t = int(got["counts"][0]), int(got["counts"][1])
         assert n_seg == len(w_keep) and np.array_equal(got["tok_handle"][:n_t], w_h) and np.array_equal(got["seg_keep"][:n_seg], w_keep)
         if n_seg == 0:
