@@ -112,8 +112,9 @@ class OracleCache:
         """k_new, v_new: [n_tok, Hkv, D] (values exactly representable in binary32).
         Tokens are applied in array order.  Returns int32 handles [n_tok] (-1 = skipped)."""
         cfg = self.cfg
-        k_new = np.asarray(k_new, dtype=np.float32)
-        v_new = np.asarray(v_new, dtype=np.float32)
+        if self.store_data:
+            k_new = np.asarray(k_new, dtype=np.float32)
+            v_new = np.asarray(v_new, dtype=np.float32)
         tok_class = np.asarray(tok_class)
         n_tok = len(tok_seq)
         handles = np.full(n_tok, -1, dtype=np.int32)

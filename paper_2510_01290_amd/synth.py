@@ -149,6 +149,7 @@ class ScriptRunner:
 
     def __init__(self, wl, backend, layers=None, seqs=None):
         self.wl, self.be = wl, backend
+        self.with_data = getattr(backend, "needs_data", True)     # a backend that keeps tables only is not sent K/V rows
         self.layers = set(range(wl.geom.n_layers)) if layers is None else set(layers)
         self.seqs = None if seqs is None else set(int(s) for s in seqs)
         self.handle = {(l, s): np.full(len(wl.classes[s]), -1, dtype=np.int32)
@@ -165,12 +166,13 @@ class ScriptRunner:
             ts.append(np.full(n, s, dtype=np.int32))
             tp.append(np.arange(t0, t0 + n, dtype=np.int32))
             tc.append(wl.classes[s][t0:t0 + n])
-            ks.append(kv_rows(wl.seed, op.layer, s, 0, t0, t0 + n, wl.geom, dev))
-            vs.append(kv_rows(wl.seed, op.layer, s, 1, t0, t0 + n, wl.geom, dev))
+            if self.with_data:
+                ks.append(kv_rows(wl.seed, op.layer, s, 0, t0, t0 + n, wl.geom, dev))
+                vs.append(kv_rows(wl.seed, op.layer, s, 1, t0, t0 + n, wl.geom, dev))
         if not ts:
             return None
         return (np.concatenate(ts), np.concatenate(tp), np.concatenate(tc).astype(np.uint8),
-                torch.cat(ks), torch.cat(vs))
+                torch.cat(ks) if self.with_data else None, torch.cat(vs) if self.with_data else None)
 
     def run(self, ops=None):
         for op in (self.wl.ops if ops is None else ops):

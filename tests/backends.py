@@ -11,8 +11,11 @@ class OracleBackend:
 
     def __init__(self, cfg, store_data=True):
         self.cache = ocache.OracleCache(cfg, store_data=store_data)
+        self.needs_data = store_data
 
     def append(self, layer, k, v, tok_seq, tok_pos, tok_class):
+        if not self.needs_data:
+            return self.cache.append(layer, None, None, tok_seq, tok_pos, tok_class)
         return self.cache.append(layer, k.float().numpy(), v.float().numpy(), tok_seq, tok_pos, tok_class)
 
     def evict(self, layer, ev_seq, ev_handle):

@@ -128,6 +128,8 @@ class Case:
     sample: list = None          # (seq, layer) pairs the oracle replays; None = everything
     variants: tuple = ("fast", "valu")
     cross_check_all: bool = False   # sampled cases: also compare the two device kernels on every sequence
+    full_tables: bool = False       # sampled cases: also replay EVERY sequence and layer on an oracle that keeps the tables
+                                    # only (no K/V data) and compare every handle, table, mask, counter and free pool
 
 
 def case_tiny(seed=0, bits=(8, 2, 4)):
@@ -175,6 +177,14 @@ def run_case(case, check_bytes=True, out_dtypes=(torch.float32,)):
             assert np.array_equal(gr.handle[(l, s)], orr.handle[(l, s)]), ("handles", s, l)
             compare_sequences(ob.cache, gc, [(s, s, l)], check_bytes)
             per_layer.setdefault(l, []).append((s, s, ob.cache))
+        if case.full_tables:
+            t0 = time.time()
+            ob = make_oracle(wl, store_data=False)
+            orr = synth.ScriptRunner(wl, ob).run()
+            for key in gr.handle:
+                assert np.array_equal(gr.handle[key], orr.handle[key]), ("handles", key)
+            compare_bookkeeping_full(ob.cache, gc)
+            res["all_tables_compared_seconds"] = round(time.time() - t0, 1)
     worst = {}
     for l, rows in per_layer.items():
         refs = {}
