@@ -264,7 +264,11 @@ int thinkv_decode_attention_valu(const thinkv_view* view, int32_t layer, const v
  *   ev_handle            DEVICE [n_tok] out: the token's handle if it is to be evicted, -1 if it
  *                        survives -- ready for thinkv_evict(view, layer, tok_seq, ev_handle, n_tok),
  *                        which skips entries of -1
- *   workspace            at least thinkv_tbe_workspace_bytes(cfg, n_tok, n_seg)
+ *   workspace            at least thinkv_tbe_workspace_bytes(cfg, n_tok, n_seg).  On return it holds, from its first
+ *                        256-byte boundary on: float x[n_tok][n_kv_heads * head_dim], the dequantised keys;
+ *                        float cent[n_seg][THINKV_TBE_MAX_KEEP][n_kv_heads * head_dim], the centroids after the last
+ *                        update; int32 assign[n_tok], every token's cluster at the last assignment (-1 where the
+ *                        segment was not clustered) -- for callers that want to inspect the clustering
  * Arithmetic is binary32 (products of 22-bit operands), squared distances taken as |x|^2 - 2 x.c + |c|^2; a decision between
  * two candidates whose distances differ by less than about 1e-5 of the points' mean squared norm
  * may differ from a binary64 evaluation.  Device-side errors: THINKV_ST_BAD_SLOT / BAD_SEQ for a token that

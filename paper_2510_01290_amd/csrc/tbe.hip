@@ -41,12 +41,14 @@ struct TbeArgs {
   int32_t* ev_handle;
   float* x;      // [n_tok][dim]
   float* cent;   // [n_seg][kTbeMaxKeep][dim]
+  int32_t* assign;   // [n_tok] cluster of every token at the last assignment (-1: its segment was not clustered)
   int layer, n_seg, n_tok, max_iters, dim;
 };
 
 size_t tbe_ws_bytes(const thinkv_config& c, int n_tok, int n_seg) {
   const size_t dim = (size_t)c.n_kv_heads * c.head_dim;
-  return ((size_t)(n_tok > 0 ? n_tok : 1) * dim + (size_t)(n_seg > 0 ? n_seg : 1) * kTbeMaxKeep * dim) * sizeof(float) + 256;
+  return ((size_t)(n_tok > 0 ? n_tok : 1) * dim + (size_t)(n_seg > 0 ? n_seg : 1) * kTbeMaxKeep * dim) * sizeof(float) +
+         (size_t)(n_tok > 0 ? n_tok : 1) * sizeof(int32_t) + 256;
 }
 
 // ---- gather: x[i][hd * D + ch] = the stored key of token i.  A workgroup takes kGatherTokens tokens:
@@ -279,11 +281,17 @@ __global__ __launch_bounds__(kKmThreads) void tbe_kmeans_kernel(thinkv_view v, T
   if (n > kTbeMaxTokens || want > kTbeMaxKeep || want < 1 || lo < 0 || hi > a.n_tok) {
     // outside what this kernel covers: nothing is evicted, and the caller is told
     if (tid == 0) atomicOr(&v.dev_status[c.max_seqs * c.n_layers], THINKV_ST_BAD_SEGMENT);
-    for (int i = tid; i < n && lo >= 0 && lo + i < a.n_tok; i += kKmThreads) a.ev_handle[lo + i] = -1;
+    for (int i = tid; i < n && lo >= 0 && lo + i < a.n_tok; i += kKmThreads) {
+      a.ev_handle[lo + i] = -1;
+      a.assign[lo + i] = -1;
+    }
     return;
   }
   if (want >= n) {
-    for (int i = tid; i < n; i += kKmThreads) a.ev_handle[lo + i] = -1;
+    for (int i = tid; i < n; i += kKmThreads) {
+      a.ev_handle[lo + i] = -1;
+      a.assign[lo + i] = -1;
+    }
     return;
   }
   const int k = want, dim = a.dim, pt = (n + 63) / 64, rbs = (n + 15) >> 4;
@@ -431,6 +439,7 @@ __global__ __launch_bounds__(kKmThreads) void tbe_kmeans_kernel(thinkv_view v, T
         // two members are equally near their mean whatever the rounding says: the earlier one stays
         const bool keep = s_cnt[mine[q]] <= 2 ? p == s_start[mine[q]] : (int)(s_best[mine[q]] & 0xFFFFFFFFull) == p;
         a.ev_handle[lo + p] = keep ? -1 : a.tok_handle[lo + p];
+        a.assign[lo + p] = mine[q];
       }
     }
   }
@@ -448,6 +457,7 @@ int launch_tbe_select(const thinkv_view& v, int layer, const int32_t* tok_seq, c
   a.dim = v.cfg.n_kv_heads * v.cfg.head_dim;
   a.x = (float*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
   a.cent = a.x + (size_t)n_tok * a.dim;
+  a.assign = (int32_t*)(a.cent + (size_t)n_seg * kTbeMaxKeep * a.dim);
   a.layer = layer;
   a.n_seg = n_seg;
   a.n_tok = n_tok;

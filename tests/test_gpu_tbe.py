@@ -54,14 +54,75 @@ def _dead(wl):
     return dead
 
 
-def _gpu_select(gc, layer, tok_seq, tok_handle, off, keep, max_iters=8):
+def _gpu_select(gc, layer, tok_seq, tok_handle, off, keep, max_iters=8, inspect=False):
+    """inspect: also return what the call left in its workspace (keys, centroids after the last update, last assignment)"""
     from paper_2510_01290_amd import binding as B
     d = gc.device
     ev = torch.full((len(tok_handle),), 12345, dtype=torch.int32, device=d)
     B.thinkv_tbe_select(gc, layer, torch.from_numpy(tok_seq).to(d), torch.from_numpy(tok_handle).to(d), torch.from_numpy(off).to(d),
                         torch.from_numpy(keep).to(d), ev, max_iters=max_iters)
     torch.cuda.synchronize()
-    return ev.cpu().numpy()
+    if not inspect:
+        return ev.cpu().numpy()
+    n_tok, n_seg, dim = len(tok_handle), len(keep), gc.cfg.n_kv_heads * gc.cfg.head_dim
+    base = (-gc._ws.data_ptr()) % 256
+    f = gc._ws[base:base + 4 * (n_tok * dim + n_seg * 64 * dim + n_tok)].view(torch.float32)
+    x = f[:n_tok * dim].view(n_tok, dim).cpu().numpy().astype(np.float64)
+    cent = f[n_tok * dim:n_tok * dim + n_seg * 64 * dim].view(n_seg, 64, dim).cpu().numpy().astype(np.float64)
+    assign = f[n_tok * dim + n_seg * 64 * dim:].view(torch.int32).cpu().numpy()
+    return ev.cpu().numpy(), x, cent, assign
+
+
+def _check_lloyd_step(x, k, assign, cent_before, cent_after, kept, tol):
+    """The device's last step, checked in binary64 on its own terms: x [N, dim] the segment's keys, assign [N] the device's
+    last assignment, cent_before [k, dim] the centroids that assignment was made against, cent_after [k, dim] the centroids
+    after the update that followed (the same as before when the run had converged), kept [N] bool the survivors.
+    tol: squared distance below which two candidates are a coin toss for binary32 arithmetic."""
+    n = x.shape[0]
+    assert assign.min() >= 0 and assign.max() < k
+    d = ((x[:, None, :] - cent_before[None, :, :]) ** 2).sum(-1)
+    own = d[np.arange(n), assign]
+    assert np.all(own <= d.min(1) + tol), ("a point is not with (one of) its nearest centroid(s)", float((own - d.min(1)).max()), tol)
+    scale = np.abs(x).max() + 1.0
+    for j in range(k):
+        members = np.flatnonzero(assign == j)
+        if members.size == 0:
+            assert np.array_equal(cent_after[j], cent_before[j]), "an emptied cluster moved its centroid"
+            assert not kept[members].any()
+            continue
+        assert np.abs(cent_after[j] - x[members].mean(0)).max() <= 1e-4 * scale, ("centroid is not the mean of its members", j)
+        assert kept[members].sum() == 1, ("survivors of cluster", j, int(kept[members].sum()))
+        surv = members[kept[members]][0]
+        if members.size <= 2:
+            assert surv == members[0]
+        else:
+            dj = ((x[members] - cent_after[j]) ** 2).sum(-1)
+            assert dj[kept[members]][0] <= dj.min() + tol, ("survivor is not (one of) the nearest member(s)", j)
+    assert kept.sum() == len(np.unique(assign))
+
+
+def _check_clustering(gc, ob, layer, tok_seq, tok_handle, off, keep, max_iters, got, x_dev, cent_after, assign):
+    """every clustered segment of a device call: its last Lloyd step and its survivors are valid (see _check_lloyd_step).  The
+    centroids the last assignment was made against are those a call with one assignment less leaves behind (the kernel is
+    deterministic), or the evenly spaced initial points when there was only one."""
+    if max_iters > 1:
+        _, _, cent_before, _ = _gpu_select(gc, layer, tok_seq, tok_handle, off, keep, max_iters - 1, inspect=True)
+    checked = 0
+    for sg, (a, b) in enumerate(zip(off[:-1], off[1:])):
+        n, k = int(b - a), int(keep[sg])
+        if n <= 0 or n > 256 or k < 1 or k > 64:
+            continue
+        kept = got[a:b] == -1
+        if k >= n:
+            assert kept.all() and (assign[a:b] == -1).all()
+            continue
+        x = otbe.segment_keys(ob.cache, layer, int(tok_seq[a]), tok_handle[a:b])
+        assert np.abs(x - x_dev[a:b]).max() <= 1e-5 * (np.abs(x).max() + 1.0)          # the keys the device clustered are the stored ones
+        before = cent_before[sg, :k] if max_iters > 1 else x_dev[a:b][(np.arange(k) * n) // k]
+        tol = MIN_MARGIN * max(float(np.mean((x * x).sum(-1))), 1e-300)
+        _check_lloyd_step(x, k, assign[a:b], before, cent_after[sg, :k], kept, tol)
+        checked += 1
+    return checked
 
 
 def _case(wl, keep_of, max_iters=8, layer=0):
@@ -74,7 +135,7 @@ def _case(wl, keep_of, max_iters=8, layer=0):
     sizes = np.diff(off)
     keep = np.array([keep_of(int(n)) for n in sizes], np.int32)
     want, margins = otbe.select_evictions(ob.cache, layer, tok_seq, tok_handle, off, keep, max_iters)
-    got = _gpu_select(gc, layer, tok_seq, tok_handle, off, keep, max_iters)
+    got, x_dev, cent_after, assign = _gpu_select(gc, layer, tok_seq, tok_handle, off, keep, max_iters, inspect=True)
     clear = margins > MIN_MARGIN
     assert clear.mean() >= 0.6, f"too many near-ties for a meaningful comparison ({clear.mean():.2f} clear)"
     same = 0
@@ -84,6 +145,8 @@ def _case(wl, keep_of, max_iters=8, layer=0):
         assert eq or not clear[sg], ("segment", sg, "margin", margins[sg], np.flatnonzero(got[a:b] != want[a:b])[:8])
         kept = got[a:b] == -1
         assert 1 <= kept.sum() <= min(b - a, keep[sg]) and np.array_equal(got[a:b][~kept], tok_handle[a:b][~kept])
+    # whether or not a segment came out as in the oracle: the device's own last step and its survivors are valid
+    n_valid = _check_clustering(gc, ob, layer, tok_seq, tok_handle, off, keep, max_iters, got, x_dev, cent_after, assign)
     want = got          # from here on both sides evict what the device chose
     margin = margins.min()
     # the list goes straight into the evict call; tables and attention afterwards agree with the oracle
@@ -96,7 +159,8 @@ def _case(wl, keep_of, max_iters=8, layer=0):
     out, lse = parity.gpu_attention(gc, wl, None, layer)
     assert np.abs(out - ref).max() <= parity.TOL
     return {"workload": wl.name, "segments": len(keep), "tokens": len(tok_handle), "evicted": int((got != -1).sum()),
-            "segments_equal_to_oracle": same, "segments_with_a_clear_margin": int(clear.sum()), "smallest_margin": float(margin)}
+            "segments_equal_to_oracle": same, "segments_with_a_clear_margin": int(clear.sum()), "smallest_margin": float(margin),
+            "segments_whose_last_step_was_validated": n_valid}
 
 
 def test_tbe_first_anneal_of_every_segment():
@@ -430,7 +494,8 @@ def test_tbe_largest_segments_and_every_keep():
         assert off[-1] <= len(live)
         th, ts, keep = live[:off[-1]], np.zeros(off[-1], np.int32), np.array(keeps, np.int32)
         want, margins = otbe.select_evictions(ob.cache, 0, ts, th, off, keep, 8)
-        got = _gpu_select(gc, 0, ts, th, off, keep)
+        got, x_dev, cent_after, assign = _gpu_select(gc, 0, ts, th, off, keep, inspect=True)
+        assert _check_clustering(gc, ob, 0, ts, th, off, keep, 8, got, x_dev, cent_after, assign) == len(keeps)
         n_clear = 0
         for sg, (a, b) in enumerate(zip(off[:-1], off[1:])):
             kept = got[a:b] == -1
