@@ -22,6 +22,7 @@ HBM_PEAK = 8.0e12
 # rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a copy of known size
 # (profiles/decode_attention_cfg2_32k_hbm_traffic.txt); other workloads report null
 TRAFFIC_DEFAULT_BYTES = 734.7e6
+TRAFFIC_SOURCE = "profiles/decode_attention_cfg2_32k_hbm_traffic.txt (rocprofv3 counters of an earlier run of this command, not measured live)"
 
 
 def main():
@@ -41,6 +42,10 @@ def main():
     ap.add_argument("--contrast", action="store_true",
                     help="also time what in-place slot reuse avoids: compaction of a contiguous binary16 cache by a gather "
                          "after an eviction, alone and running beside decode attention on a second stream")
+    ap.add_argument("--e2e", action="store_true",
+                    help="with --workload cfg5: the configuration as written -- 64 consecutive decode steps of {append one token "
+                         "per sequence on every layer, an eviction pass every 16th step, attention on every layer}")
+    ap.add_argument("--layers", type=int, default=32, help="layers built for --workload cfg5 --e2e (32 = the configuration; fewer is stated in the output)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -57,6 +62,9 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload == "cfg5" and args.e2e:
+        print(json.dumps(e2e_cfg5(args, np, torch, B, synth, harness, dev)))
+        return
     if args.workload != "cfg2-32k":
         print(json.dumps(attention_only(args, np, torch, B, synth, harness, dev)))
         return
@@ -261,6 +269,17 @@ def main():
     if args.contrast:
         contrast = gather_contrast(args, np, torch, dev, g,
                                    lambda j: decode(gcs[j % len(gcs)], 0, q_all[nsteps - 1], out, lse, ev_seq, t_pos[nsteps - 1], 0, scale, max_ctx_pages))
+    # what the memory system gives for this layout: the same (page, kv-head) blocks read by a kernel that does nothing else
+    chk = torch.zeros(1, dtype=torch.int32, device=dev)
+    pm = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+    for j in range(3):
+        B.thinkv_probe_stream_pages(gcs[j % len(gcs)], 0, ev_seq, chk)
+    for j, (a_, b_) in enumerate(pm):
+        a_.record()
+        B.thinkv_probe_stream_pages(gcs[j % len(gcs)], 0, ev_seq, chk)
+        b_.record()
+    torch.cuda.synchronize()
+    probe_us = float(np.mean([a_.elapsed_time(b_) for a_, b_ in pm]) * 1e3)
     attn_sparsity_us = float(np.median([a.elapsed_time(b) for a, b in smarks]) * 1e3) if args.variant == "fast" else None
     evict_us = float(np.median([m[0].elapsed_time(m[1]) for m in marks]) * 1e3)
     append_us = float(np.median([m[1].elapsed_time(m[2]) for m in marks]) * 1e3)
@@ -282,6 +301,8 @@ def main():
     step_bytes = attn_bytes + append_bytes + args.batch * 12
     attn_s = float(attn_ms.mean()) * 1e-3
     achieved = attn_bytes / attn_s / 1e9
+    page_bytes_read = sum(int(gc.n_pages[:, 0, c].sum().item()) * gc.page_bytes[c] for c in range(3))     # whole pages, dead slots included
+    ceiling = page_bytes_read / (probe_us * 1e-6) / 1e9
     line = {
         "metric": "hybrid-quant paged decode attn: \u00b5s/step + HBM GB/s (% of peak) at 32k ctx",
         "value": step_bytes / (ms_step * 1e-3) / 1e9,
@@ -298,7 +319,11 @@ def main():
                    "step": "evict 1 + append 1 (one call, thinkv_evict_append) + decode attention, per sequence"},
         "roofline": {"bound": "hbm", "kernel": "decode attention (split-K kernel + merge)", "achieved": achieved, "peak": HBM_PEAK / 1e9,
                      "unit": "GB/s", "frac": achieved * 1e9 / HBM_PEAK,
-                     "traffic": TRAFFIC_DEFAULT_BYTES if (args.ctx == 32768 and args.batch == 16 and args.variant == "fast") else None, "algorithmic_bytes_per_launch": attn_bytes},
+                     "traffic": TRAFFIC_DEFAULT_BYTES if (args.ctx == 32768 and args.batch == 16 and args.variant == "fast") else None,
+                     "traffic_source": TRAFFIC_SOURCE, "algorithmic_bytes_per_launch": attn_bytes,
+                     "stream_ceiling": {"GB/s": ceiling, "us": probe_us, "bytes": page_bytes_read, "frac_of_peak": ceiling * 1e9 / HBM_PEAK,
+                                        "what": "the pages of the same launch read by a kernel that only loads (thinkv_probe_stream_pages)"},
+                     "frac_of_stream_ceiling": achieved / ceiling},
         "host_wall_ms_per_step": wall / args.steps * 1e3,
     }
     if contrast is not None:
@@ -366,6 +391,136 @@ def gather_contrast(args, np, torch, dev, g, attention):
             "gathers_outlasted_the_attention_calls": bool(still_running),
             "step_us_if_compacted_every_step_sequential": ga + aa, "slowdown_if_compacted_every_step": (ga + aa) / aa,
             "in_place_reuse_bytes_moved": 0}
+
+
+def e2e_cfg5(args, np, torch, B, synth, harness, dev):
+    """Configuration 5 as written: the ragged batch of 256 (contexts log-uniform in 1k..64k) is bulk-built on `--layers`
+    layers of the 8B shape, then 64 consecutive decode steps run; a step appends one token per sequence on every layer,
+    every 16th step begins with an eviction pass that removes 5 % of the live tokens of the least important class (E,
+    seeded uniform choice per sequence and layer), and runs decode attention on every layer."""
+    n_steps, L = 64, args.layers
+    g = synth.Geometry(L, 32, 8, 128, "bf16")
+    ctx = synth.stress_contexts(4, 256)
+    wl = synth.stress_decode("cfg5-stress-8b", g, 4, ctx, 0)
+    S = wl.n_seqs
+    t0 = time.time()
+    need = np.array(harness.arena_need(wl, slack=1.0), dtype=np.int64)
+    arena = tuple(int(x * 1.03) + S * L * 8 for x in need)
+    gc = harness.make_gpu_cache(wl, arena_pages=arena, max_pages=harness.max_pages_need(wl) + 8)
+    gr = synth.ScriptRunner(wl, harness.GpuBackend(gc)).run()
+    torch.cuda.synchronize()
+    build_s = time.time() - t0
+    assert int(gc.dev_status.abs().sum().item()) == 0, "device flags set while building the cache"
+    # ---- inputs of the steps, resident before timing starts
+    gen = torch.Generator(device=dev).manual_seed(99)
+    rng = np.random.default_rng(99)
+    scale_ch = torch.ones(g.head_dim, device=dev)
+    scale_ch[list(synth.outlier_channels(g.head_dim))] = 8.0
+    kv_new = [(torch.randn((n_steps, S, g.n_kv_heads, g.head_dim), device=dev, generator=gen) * scale_ch).to(torch.bfloat16) for _ in range(2 * L)]
+    q = [torch.randn((S, g.n_q_heads, g.head_dim), device=dev, generator=gen).to(torch.bfloat16) for _ in range(L)]
+    new_cls = np.stack([synth.thought_classes(rng, n_steps)[0] for _ in range(S)], 1)          # [step][seq]
+    t_cls = torch.from_numpy(new_cls).to(dev)
+    t_pos = torch.from_numpy(np.stack([ctx + st for st in range(n_steps)]).astype(np.int32)).to(dev)
+    seqs = torch.arange(S, dtype=torch.int32, device=dev)
+    ev_lists = {}
+    for l in range(L):
+        cand = [np.flatnonzero(wl.classes[s_][:ctx[s_]] == synth.E) for s_ in range(S)]
+        for p_ in range(n_steps // 16):
+            es, eh = [], []
+            for s_ in range(S):
+                n = int(round(0.05 * len(cand[s_])))
+                if n == 0:
+                    continue
+                pick = rng.choice(len(cand[s_]), size=n, replace=False)
+                eh.append(gr.handle[(l, s_)][cand[s_][pick]])
+                es.append(np.full(n, s_, np.int32))
+                cand[s_] = np.delete(cand[s_], pick)
+            ev_lists[(l, p_)] = (torch.from_numpy(np.concatenate(es)).to(dev), torch.from_numpy(np.concatenate(eh).astype(np.int32)).to(dev))
+    out = torch.empty((S, g.n_q_heads, g.head_dim), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty((S, g.n_q_heads), dtype=torch.float32, device=dev)
+    h_out = torch.empty(S, dtype=torch.int32, device=dev)
+    mcp = [int(gc.n_pages[:, l].sum(-1).max().item()) + n_steps // 16 + 4 for l in range(L)]
+    scale = g.head_dim ** -0.5
+
+    def step(st, marks=None):
+        for l in range(L):
+            if marks is not None:
+                marks[l][0].record()
+            if st % 16 == 15:
+                B.thinkv_evict(gc, l, *ev_lists[(l, st // 16)])
+            if marks is not None:
+                marks[l][1].record()
+            B.thinkv_append_quantized(gc, l, kv_new[2 * l][st], kv_new[2 * l + 1][st], seqs, t_pos[st], t_cls[st], h_out)
+            if marks is not None:
+                marks[l][2].record()
+            B.thinkv_decode_attention(gc, l, q[l], out, lse, seqs, t_pos[st], 0, scale, mcp[l])
+            if marks is not None:
+                marks[l][3].record()
+
+    marks = [[[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(L)] for _ in range(n_steps)]
+    step_ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_steps + 1)]
+    torch.cuda.synchronize()
+    step_ev[0].record()
+    for st in range(n_steps):
+        step(st, marks[st])
+        step_ev[st + 1].record()
+    torch.cuda.synchronize()
+    assert int(gc.dev_status.abs().sum().item()) == 0, "device flags set during the steps"
+    step_ms = np.array([step_ev[i].elapsed_time(step_ev[i + 1]) for i in range(n_steps)])
+    ev_us = np.array([[m[0].elapsed_time(m[1]) * 1e3 for m in marks[st]] for st in range(n_steps)])
+    ap_us = np.array([[m[1].elapsed_time(m[2]) * 1e3 for m in marks[st]] for st in range(n_steps)])
+    at_us = np.array([[m[2].elapsed_time(m[3]) * 1e3 for m in marks[st]] for st in range(n_steps)])
+    # algorithmic bytes of a step, from the tables as they stand at the end
+    H, D, Hq = g.n_kv_heads, g.head_dim, g.n_q_heads
+    live_by_class = [0, 0, 0]
+    for l in range(L):
+        sm = (gc.slot_mask[:, l] & 0xFFFF).cpu().numpy().astype(np.uint16)
+        npg = gc.n_pages[:, l].cpu().numpy()
+        for c in range(3):
+            live_by_class[c] += int(sum(np.unpackbits(sm[s_, c, :npg[s_, c]].view(np.uint8)).sum() for s_ in range(S)))
+    kv_bytes = sum(n * H * 2 * (D * b // 8 + D // 32 * 4) for n, b in zip(live_by_class, g.bits_of_class))
+    attn_bytes = kv_bytes + int(gc.n_pages.sum().item()) * 8 + L * S * Hq * D * 4
+    append_bytes = L * S * (2 * H * D * 2 + H * 2 * (D * 4 // 8 + D // 32 * 4) + 12)
+    ms = float(step_ms.mean())
+    line = {
+        "metric": "hybrid-quant paged decode attn: \u00b5s/step + HBM GB/s (% of peak) at 32k ctx",
+        "value": (attn_bytes + append_bytes) / (ms * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": n_steps, "warmup": 0,
+        "ms_per_step": ms, "ms_per_step_min": float(step_ms.min()), "ms_per_step_with_eviction_pass": float(step_ms[15::16].mean()),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "cfg5 as written: ragged batch 256 (contexts log-uniform 1k..64k), 8B shape, 64 consecutive decode steps",
+                   "layers_built": L, "layers_of_the_configuration": 32, "scaled_down": L != 32, "batch": S,
+                   "live_tokens_per_layer": int(sum(live_by_class) / L), "build_seconds": round(build_s, 1),
+                   "step": "per layer: [every 16th step: evict 5% of the live E tokens of every sequence] + append 1 token per sequence + decode attention"},
+        "per_layer_us": {"attention_mean": float(at_us.mean()), "append_mean": float(ap_us.mean()),
+                         "evict_pass_mean": float(ev_us[15::16].mean()), "attention_GB_per_s": attn_bytes / L / (float(at_us.mean()) * 1e-6) / 1e9,
+                         "attention_frac_of_8TBps": attn_bytes / L / (float(at_us.mean()) * 1e-6) / HBM_PEAK},
+        "algorithmic_bytes_per_step": attn_bytes + append_bytes,
+    }
+    if not args.no_cpu_baseline:
+        # the oracle on ONE (sequence, layer) of the same workload: the sequence of median context, whole steps
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        import parity
+        from oracle import attention as oattn
+        s_ = int(np.argsort(ctx)[S // 2])
+        ob = parity.make_oracle(wl, max_seqs=S, arena_pages=tuple(int(x) + 16 for x in harness.arena_need_one(wl, s_)))
+        synth.ScriptRunner(wl, ob, layers=[0], seqs=[s_]).run()
+        oc = ob.cache
+        cpu = torch.device("cpu")
+        k1 = kv_new[0][:, s_].float().cpu().numpy()
+        v1 = kv_new[1][:, s_].float().cpu().numpy()
+        q1 = q[0][s_].float().cpu().numpy().astype(np.float64)[None]
+        t1 = time.perf_counter()
+        done = 0
+        while done < n_steps and (done < 1 or time.perf_counter() - t1 < args.cpu_seconds):
+            oc.append(0, k1[done:done + 1], v1[done:done + 1], [s_], [int(ctx[s_]) + done], [new_cls[done, s_]])
+            oattn.decode_attention(oc, 0, q1, [s_], [int(ctx[s_]) + done], 0, scale)
+            done += 1
+        dt = (time.perf_counter() - t1) / done
+        line["cpu_baseline"] = {"value": oc.stored_bytes_live(s_, 0) / dt / 1e9, "unit": "GB/s", "cores": len(os.sched_getaffinity(0)), "kind": "oracle",
+                                "seconds_per_sequence_layer_step": dt,
+                                "sample": f"{done} steps (append 1, binary64 attention) of one sequence (context {int(ctx[s_])}, the batch's median) on one layer; "
+                                          f"a whole step is {S} sequences x {L} layers of this"}
+    return line
 
 
 def attention_only(args, np, torch, B, synth, harness, dev):
@@ -477,13 +632,19 @@ def attention_only(args, np, torch, B, synth, harness, dev):
 
 def cpu_baseline(wl, args, nsteps, ev_handles, new_cls, np, torch, synth):
     """The oracle as it stands, timed on this machine's host cores on ONE sequence of the same
-    workload (sequence 0: its full build is replayed untimed, then whole steps are timed)."""
+    workload (sequence 0: its full build is replayed untimed, then whole steps are timed).
+    The only part of the default run that loads anything from oracle/ (through the test helpers)."""
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import parity
     from oracle import attention as oattn
+    # the host cores this process may run on; the oracle itself is NumPy (one Python thread, BLAS
+    # threads inside the matrix products)
+    cores = len(os.sched_getaffinity(0))
     try:
         from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
-        cores = 1
+        blas_threads = None
     g = wl.geom
     ob = parity.make_oracle(wl, max_seqs=1, arena_pages=tuple(int(x) + 8 for x in parity.backends.arena_need(wl)),
                             max_pages=parity.backends.max_pages_need(wl) + 8)

@@ -355,6 +355,16 @@ int thinkv_decode_attention_sparsity(const thinkv_view* view, int32_t layer, con
                                      thinkv_dtype out_dtype, int32_t max_ctx_pages, void* workspace,
                                      size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement aid (no part of the method): reads every (page, kv-head) block of the listed
+ * sequences' page lists of one layer -- exactly the cache bytes a full-attention
+ * thinkv_decode_attention call over the same sequences reads -- with plain streaming loads and no
+ * arithmetic, split over the machine the way the attention launch is.  Its duration is what the
+ * memory system gives for this layout.  checksum: DEVICE one word (any value; only ever xor-ed).
+ */
+int thinkv_probe_stream_pages(const thinkv_view* view, int32_t layer, const int32_t* seq_ids, int32_t B, uint32_t* checksum,
+                              void* stream);
+
 const char* thinkv_status_string(int status);
 
 #ifdef __cplusplus

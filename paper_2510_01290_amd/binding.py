@@ -16,7 +16,7 @@ ST_NOPAGES, ST_BAD_CLASS, ST_BAD_SLOT, ST_EVICT_DEAD, ST_BAD_SEQ, ST_BAD_SEGMENT
 EXPORTS = ["thinkv_block_bytes", "thinkv_page_bytes", "thinkv_append_workspace_bytes",
            "thinkv_decode_workspace_bytes", "thinkv_init_view", "thinkv_append_quantized", "thinkv_evict", "thinkv_evict_append",
            "thinkv_decode_attention", "thinkv_decode_attention_noalloc", "thinkv_decode_attention_valu", "thinkv_decode_sparsity_workspace_bytes",
-           "thinkv_decode_attention_sparsity", "thinkv_tbe_workspace_bytes", "thinkv_tbe_select", "thinkv_tbe_plan_workspace_bytes", "thinkv_tbe_plan",
+           "thinkv_decode_attention_sparsity", "thinkv_tbe_workspace_bytes", "thinkv_tbe_select", "thinkv_tbe_plan_workspace_bytes", "thinkv_tbe_plan", "thinkv_probe_stream_pages",
            "thinkv_status_string"]
 
 
@@ -77,6 +77,8 @@ def load():
     lib.thinkv_tbe_plan_workspace_bytes.argtypes = [i32, i32]
     lib.thinkv_tbe_plan.restype = C.c_int
     lib.thinkv_tbe_plan.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.thinkv_probe_stream_pages.restype = C.c_int
+    lib.thinkv_probe_stream_pages.argtypes = [C.POINTER(View), i32, vp, i32, vp, vp]
     lib.thinkv_status_string.restype = C.c_char_p
     lib.thinkv_status_string.argtypes = [C.c_int]
     _lib = lib
@@ -294,6 +296,13 @@ def thinkv_decode_attention_sparsity(cache, layer, q, out, lse, sparsity, seq_id
         C.byref(cache.view), layer, _ptr(q), _ptr(out), _ptr(lse), _ptr(sparsity), _ptr(seq_ids), _ptr(q_pos), B, window,
         float(softmax_scale), _DT[q.dtype], _DT[out.dtype], int(max_ctx_pages), _ptr(ws), ws.numel(), _stream(stream)),
         "thinkv_decode_attention_sparsity")
+
+
+def thinkv_probe_stream_pages(cache, layer, seq_ids, checksum, stream=None):
+    """measurement aid: stream the pages a full-attention decode call over seq_ids reads (checksum: one int32 device word)"""
+    assert seq_ids.dtype == torch.int32 and checksum.dtype == torch.int32 and checksum.numel() >= 1
+    _check(load().thinkv_probe_stream_pages(C.byref(cache.view), layer, _ptr(seq_ids), int(seq_ids.numel()), _ptr(checksum), _stream(stream)),
+           "thinkv_probe_stream_pages")
 
 
 def thinkv_decode_attention_valu(cache, layer, q, out, lse, seq_ids, q_pos, window, softmax_scale, max_ctx_pages, stream=None):

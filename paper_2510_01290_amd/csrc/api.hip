@@ -27,6 +27,7 @@ int launch_stat_fill(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
 int launch_stat_count(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
 int launch_decode_merge(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
 int decode_mfma_supported(const thinkv_config& c);
+int launch_probe_stream(const thinkv_view& v, int layer, const int32_t* seq_ids, int B, int per_head, uint32_t* checksum, hipStream_t st);
 
 
 static int check_config(const thinkv_config* c) {
@@ -351,6 +352,18 @@ int thinkv_tbe_plan(const thinkv_view* view, int32_t layer, const int32_t* seq_i
   if (workspace_bytes < tbe_plan_ws_bytes(B, max_cuts)) return THINKV_E_WORKSPACE;
   return launch_tbe_plan(*view, layer, seq_ids, seg_start, seg_type, n_segs, transition_ended, seg_count, rule, B, max_segs, budget, max_cuts,
                          cap_seg, cap_tok, tok_seq, tok_handle, seg_offset, seg_keep, counts, workspace, (hipStream_t)stream);
+}
+
+int thinkv_probe_stream_pages(const thinkv_view* view, int32_t layer, const int32_t* seq_ids, int32_t B, uint32_t* checksum, void* stream) {
+  int rc = check_view(view);
+  if (rc) return rc;
+  if (B < 0 || layer < 0 || layer >= view->cfg.n_layers || B > view->cfg.max_seqs) return THINKV_E_INVALID_ARG;
+  if (B == 0) return THINKV_OK;
+  if (!seq_ids || !checksum) return THINKV_E_INVALID_ARG;
+  // four waves to a workgroup, as many workgroups as fill the machine at the occupancy of the attention kernel
+  int64_t per_head = (int64_t)compute_units() * TKV_WAVES / ((int64_t)B * view->cfg.n_kv_heads);
+  if (per_head < 1) per_head = 1;
+  return launch_probe_stream(*view, layer, seq_ids, B, (int)per_head, checksum, (hipStream_t)stream);
 }
 
 const char* thinkv_status_string(int status) {

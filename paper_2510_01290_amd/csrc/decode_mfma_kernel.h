@@ -41,9 +41,6 @@
 #pragma once
 #include "decode_common.h"
 
-#ifndef TKV_ABL
-#define TKV_ABL 0
-#endif
 #ifndef TKV_CHUNK
 #define TKV_CHUNK 4
 #endif
@@ -343,7 +340,7 @@ struct ClassRunner {
         const int g = set * CS + gl;
         H8 ka;
 #pragma unroll
-        for (int vv = 0; vv < 4; ++vv) ka.u[vv] = (TKV_ABL & 16) ? r.kw[(4 * g + vv) % PageRegs<D, BITS, NSET>::CW] : F::get(r.kw, 4 * g + vv);
+        for (int vv = 0; vv < 4; ++vv) ka.u[vv] = F::get(r.kw, 4 * g + vv);
         c[set] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka.h, bq[g].h, gl == 0 ? zero : c[set], 0, 0, 0);
       }
     }
@@ -355,8 +352,8 @@ struct ClassRunner {
       const float t = fmaf(half_of<R>(r.km[set].x, r.km[set].y), c[set][R], z);                  \
       acc = set == 0 ? t : acc + t;                                                              \
     }                                                                                            \
-    if (!(TKV_ABL & 64)) { acc = add_row_ror<8>(acc);                                                                   \
-    if constexpr (GP == 4) acc = add_row_ror<4>(acc); }                                           \
+    acc = add_row_ror<8>(acc);                                                                   \
+    if constexpr (GP == 4) acc = add_row_ror<4>(acc);                                            \
     s[R] = acc;                                                                                  \
   }
     TKV_SCORE(0) TKV_SCORE(1) TKV_SCORE(2) TKV_SCORE(3)
@@ -364,23 +361,13 @@ struct ClassRunner {
   }
 
   __device__ __forceinline__ void compute(const Pair& r, const PairIds& id) {
-    if constexpr ((TKV_ABL & 128) != 0) {   // loads only: fold every loaded word into the denominator
-      uint32_t x = 0;
-      constexpr int CWx = PageRegs<D, BITS, NSET>::CW;
-#pragma unroll
-      for (int i = 0; i < CWx; ++i) x ^= r.a.kw[i] ^ r.a.vw[i] ^ r.b.kw[i] ^ r.b.vw[i];
-#pragma unroll
-      for (int s2 = 0; s2 < NSET; ++s2) x ^= r.a.km[s2].x ^ r.a.km[s2].w ^ r.a.vm[s2].y ^ r.a.vm[s2].z ^ r.b.km[s2].x ^ r.b.km[s2].w ^ r.b.vm[s2].y ^ r.b.vm[s2].z;
-      st.l += __builtin_bit_cast(float, x & 0x3F800000u);
-      return;
-    }
     const uint32_t live_a = id.live_a, live_b = id.live_b;
     float sa[4], sb[4];
     page_scores(r.a, sa);
     page_scores(r.b, sb);
     // ---------------- dead slots: score -inf, hence p = 0.  Their scales and zero-points are finite
     // (stale, or zero in a slot never written: arenas start zero-filled), so they drop out of every sum.
-    if (!(TKV_ABL & 1) && (live_a & live_b) != 0xFFFFu) {
+    if ((live_a & live_b) != 0xFFFFu) {
       const uint32_t la = (live_a >> (4 * qd)) & 0xFu, lb = (live_b >> (4 * qd)) & 0xFu;
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
@@ -428,8 +415,8 @@ struct ClassRunner {
     const float mref = st.m_sub - lift;
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
-      pa[r4] = (TKV_ABL & 2) ? fmaf(sa[r4], kappa, -mref) : __builtin_amdgcn_exp2f(fmaf(sa[r4], kappa, -mref));
-      pb[r4] = (TKV_ABL & 2) ? fmaf(sb[r4], kappa, -mref) : __builtin_amdgcn_exp2f(fmaf(sb[r4], kappa, -mref));
+      pa[r4] = __builtin_amdgcn_exp2f(fmaf(sa[r4], kappa, -mref));
+      pb[r4] = __builtin_amdgcn_exp2f(fmaf(sb[r4], kappa, -mref));
     }
     st.l += ((pa[0] + pa[1]) + (pa[2] + pa[3])) + ((pb[0] + pb[1]) + (pb[2] + pb[3]));
     // ---------------- values, per column set: B = two-term split of p * s_V, A = V codes
@@ -496,15 +483,12 @@ struct ClassRunner {
         const int mb = 2 * CS * set + mm;
         H8 va;
         // field f = u*NM + mb holds slots (2u, 2u+1) of the lane's slot quad
-        constexpr int CWv = PageRegs<D, BITS, NSET>::CW;
-        va.u[0] = (TKV_ABL & 8) ? r.a.vw[mb % CWv] : F::get(r.a.vw, 0 * NM + mb);
-        va.u[1] = (TKV_ABL & 8) ? r.a.vw[(mb + 1) % CWv] : F::get(r.a.vw, 1 * NM + mb);
-        va.u[2] = (TKV_ABL & 8) ? r.b.vw[mb % CWv] : F::get(r.b.vw, 0 * NM + mb);
-        va.u[3] = (TKV_ABL & 8) ? r.b.vw[(mb + 1) % CWv] : F::get(r.b.vw, 1 * NM + mb);
-        if (!(TKV_ABL & 32)) st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, hi.h, st.o[mb], 0, 0, 0);
-        else st.o[mb][0] += __builtin_bit_cast(float, va.u[0] ^ va.u[1] ^ va.u[2] ^ va.u[3] ^ hi.u[0] ^ hi.u[1] ^ hi.u[2] ^ hi.u[3]);
-        if (!(TKV_ABL & (4 | 32))) st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, lo.h, st.o[mb], 0, 0, 0);
-        else if (TKV_ABL & 32) st.o[mb][1] += __builtin_bit_cast(float, lo.u[0] ^ lo.u[1] ^ lo.u[2] ^ lo.u[3]);
+        va.u[0] = F::get(r.a.vw, 0 * NM + mb);
+        va.u[1] = F::get(r.a.vw, 1 * NM + mb);
+        va.u[2] = F::get(r.b.vw, 0 * NM + mb);
+        va.u[3] = F::get(r.b.vw, 1 * NM + mb);
+        st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, hi.h, st.o[mb], 0, 0, 0);
+        st.o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va.h, lo.h, st.o[mb], 0, 0, 0);
       }
     }
   }
