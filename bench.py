@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--ctx", type=int, default=32768, help="live tokens per sequence")
     ap.add_argument("--batch", type=int, default=16)
     ap.add_argument("--variant", default="fast", choices=["fast", "valu"])
+    ap.add_argument("--bits", default="8,2,4", help="bit widths of the thought types T,E,R of the default workload (BASELINE: 8,2,4); "
+                                                     "8,8,8 / 4,4,4 / 2,2,2 give caches of the same shape with a single width")
     ap.add_argument("--workload", default="cfg2-32k", choices=["cfg2-32k", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5"],
                     help="cfg2-32k (default): the headline step.  The others time decode attention alone on that "
                          "configuration's cache (a step = one attention call per built layer)")
@@ -72,6 +74,9 @@ def main():
     nsteps = args.steps + args.warmup + 2 * n_extra
     wl = synth.config_llama8b_layer(seed=1, n_seqs=args.batch, ctx=args.ctx, refill_chunk=64,
                                     name=f"cfg2-shape B={args.batch} ctx={args.ctx}")
+    bits = tuple(int(x) for x in args.bits.split(","))
+    assert len(bits) == 3 and all(b_ in (2, 4, 8) for b_ in bits)
+    wl.geom.bits_of_class = bits
     g = wl.geom
     # room for the timed appends
     arena = tuple(int(x + args.batch * (nsteps // 16 + 2)) for x in harness.arena_need(wl))
@@ -313,13 +318,13 @@ def main():
         "attn_with_sparsity_statistic_us_median": attn_sparsity_us, "tbe_select": tbe, "tbe_plan": plan, "bulk_append": bulk,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16" if args.variant == "fast" else "f32",
         "data": "synthetic",
-        "config": {"workload": wl.name + " (R1-Llama-8B layer: 32 q / 8 kv heads, head_dim 128, bf16; T8/R4/E2, 30% E + 10% R evicted and refilled)",
+        "config": {"workload": wl.name + f" (R1-Llama-8B layer: 32 q / 8 kv heads, head_dim 128, bf16; T{bits[0]}/R{bits[2]}/E{bits[1]}, 30% E + 10% R evicted and refilled)",
                    "batch": args.batch, "live_tokens_per_seq": int(sum(live_by_class) / args.batch), "page_size": 16,
                    "live_by_class_TER": live_by_class, "kernel": args.variant, "build_seconds": round(build_s, 1), "cache_replicas": len(gcs),
                    "step": "evict 1 + append 1 (one call, thinkv_evict_append) + decode attention, per sequence"},
         "roofline": {"bound": "hbm", "kernel": "decode attention (split-K kernel + merge)", "achieved": achieved, "peak": HBM_PEAK / 1e9,
                      "unit": "GB/s", "frac": achieved * 1e9 / HBM_PEAK,
-                     "traffic": TRAFFIC_DEFAULT_BYTES if (args.ctx == 32768 and args.batch == 16 and args.variant == "fast") else None,
+                     "traffic": TRAFFIC_DEFAULT_BYTES if (args.ctx == 32768 and args.batch == 16 and args.variant == "fast" and bits == (8, 2, 4)) else None,
                      "traffic_source": TRAFFIC_SOURCE, "algorithmic_bytes_per_launch": attn_bytes,
                      "stream_ceiling": {"GB/s": ceiling, "us": probe_us, "bytes": page_bytes_read, "frac_of_peak": ceiling * 1e9 / HBM_PEAK,
                                         "what": "the pages of the same launch read by a kernel that only loads (thinkv_probe_stream_pages)"},

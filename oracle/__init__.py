@@ -12,6 +12,8 @@ Pinning status (see tests/test_oracle_*.py):
   layout.pack_page_head ................. pinned (independent bit-by-bit unpacker, hand-written fixture)
   cache.OracleCache (bookkeeping) ....... pinned (walkthrough events of the paper's Sec. "ThinKV
                                           Walkthrough Example", brute-force dict model, invariants)
+  formats (E4M3 / E2M1 / ternary codes, group quantisers with E4M3 scales) ... pinned (every code against
+                                          hand-made tables and the library's 8-bit float type, rounding cases, brute force)
   attention.decode_attention ............ pinned (dense softmax on compacted tokens, Theorem 1
                                           permutation invariance, closed forms, library softmax)
 """
