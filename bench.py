@@ -21,7 +21,7 @@ HBM_PEAK = 8.0e12
 # HBM bytes of one decode-attention launch (split-K kernel + merge) on the default workload, from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a copy of known size
 # (profiles/decode_attention_cfg2_32k_hbm_traffic.txt); other workloads report null
-TRAFFIC_DEFAULT_BYTES = 734.7e6
+TRAFFIC_DEFAULT_BYTES = 753.7e6
 TRAFFIC_SOURCE = "profiles/decode_attention_cfg2_32k_hbm_traffic.txt (rocprofv3 counters of an earlier run of this command, not measured live)"
 
 
