@@ -42,8 +42,8 @@ def main():
                     help="identical copies of the cache the steps rotate over, so that the data of a step was last touched "
                          "replicas steps ago (3 x 0.75 GB is far beyond the 256 MB memory-side cache)")
     ap.add_argument("--contrast", action="store_true",
-                    help="also time what in-place slot reuse avoids: compaction of a contiguous binary16 cache by a gather "
-                         "after an eviction, alone and running beside decode attention on a second stream")
+                    help="also time what in-place slot reuse avoids: compaction of a contiguous binary16 cache by a gather kernel "
+                         "(thinkv_gather_rows) after an eviction, alone and running beside decode attention on a second stream")
     ap.add_argument("--e2e", action="store_true",
                     help="with --workload cfg5: the configuration as written -- 64 consecutive decode steps of {append one token "
                          "per sequence on every layer, an eviction pass every 16th step, attention on every layer}")
@@ -272,7 +272,7 @@ def main():
     torch.cuda.synchronize()
     contrast = None
     if args.contrast:
-        contrast = gather_contrast(args, np, torch, dev, g,
+        contrast = gather_contrast(args, np, torch, B, dev, g,
                                    lambda j: decode(gcs[j % len(gcs)], 0, q_all[nsteps - 1], out, lse, ev_seq, t_pos[nsteps - 1], 0, scale, max_ctx_pages))
     # what the memory system gives for this layout: the same (page, kv-head) blocks read by a kernel that does nothing else
     chk = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -346,22 +346,23 @@ def main():
     print(json.dumps(line))
 
 
-def gather_contrast(args, np, torch, dev, g, attention):
+def gather_contrast(args, np, torch, B, dev, g, attention):
     """What eviction costs when the cache is kept contiguous (Sec. 5.1 of the paper, its Observations on gather-based
     compaction): after an eviction the survivors of every sequence are gathered into a dense buffer.  Here: a binary16
     cache [batch * ctx][Hkv * D] for K and for V, 30 % of the tokens of every sequence evicted, the rest gathered row by
-    row (torch.index_select: plain device plumbing, 2 x Hkv * D * 2 bytes per token).  Timed alone, and looping on a second
-    stream while decode attention over the quantised paged cache runs on the first."""
+    row by thinkv_gather_rows (2 x Hkv * D * 2 bytes per token).  Timed alone (the sequential variant: the step waits
+    for it), and looping on a second stream of the same priority while decode attention over the quantised paged cache
+    runs on the first (the overlapped variant)."""
     n_tok, row = args.batch * args.ctx, g.n_kv_heads * g.head_dim
     gen = torch.Generator(device=dev).manual_seed(5)
     kv = [torch.empty((n_tok, row), dtype=torch.float16, device=dev).normal_(generator=gen) for _ in range(2)]
     keep = torch.rand(n_tok, device=dev, generator=gen) >= 0.3
-    rows = torch.nonzero(keep).flatten()
+    rows = torch.nonzero(keep).flatten().to(torch.int32)
     dst = [torch.empty((int(rows.numel()), row), dtype=torch.float16, device=dev) for _ in range(2)]
 
-    def gather():
+    def gather(stream=None):
         for a, b in zip(kv, dst):
-            torch.index_select(a, 0, rows, out=b)
+            B.thinkv_gather_rows(a, b, rows, stream=stream)
 
     def timed(fn, n, stream=None):
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
@@ -378,19 +379,20 @@ def gather_contrast(args, np, torch, dev, g, attention):
         gather()
         attention(j)
     torch.cuda.synchronize()
+    assert torch.equal(dst[0][:1000], kv[0][rows[:1000].long()])
     g_alone = timed(lambda j: gather(), 10)
     a_alone = timed(attention, 30)
     torch.cuda.synchronize()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        g_beside = timed(lambda j: gather(), 40, side)        # about 40 x the time of one attention call each
-    a_beside = timed(attention, 60)                            # all of them start while the gathers are still running
+    g_beside = timed(lambda j: gather(side), 40, side)           # about 40 x the time of one attention call each
+    a_beside = timed(attention, 60)                               # all of them start while the gathers are still running
     still_running = not g_beside[-1][1].query()
     torch.cuda.synchronize()
     moved = 2 * int(rows.numel()) * row * 2 * 2               # read + written
     ga, aa, gb, ab = med(g_alone), med(a_alone), med(g_beside), med(a_beside)
     return {"contiguous_f16_cache_GB": 2 * n_tok * row * 2 / 1e9, "evicted_fraction": 0.3, "bytes_moved_per_compaction": moved,
+            "gather_kernel": "thinkv_gather_rows",
             "gather_us_alone": ga, "gather_GB_per_s_alone": moved / ga / 1e3, "attention_us_alone": aa,
             "attention_us_beside_gather": ab, "attention_slowdown_beside_gather": ab / aa, "gather_us_beside_attention": gb,
             "gathers_outlasted_the_attention_calls": bool(still_running),

@@ -365,6 +365,16 @@ int thinkv_decode_attention_sparsity(const thinkv_view* view, int32_t layer, con
 int thinkv_probe_stream_pages(const thinkv_view* view, int32_t layer, const int32_t* seq_ids, int32_t B, uint32_t* checksum,
                               void* stream);
 
+/*
+ * Contrast, not part of the method: the gather a CONTIGUOUS cache needs after every eviction (Sec. 5.1
+ * "The Cost of Gather-Based Compaction", Observations 4a / 4b) -- the data movement that in-place slot
+ * reuse does without.  dst[i] = src[rows[i]] for i < n_rows, rows of row_bytes bytes.
+ *   src   DEVICE rows of row_bytes bytes (16-byte aligned; row_bytes a multiple of 16)
+ *   dst   DEVICE n_rows rows, must not overlap src
+ *   rows  DEVICE [n_rows] indices into src (for a compaction: the surviving rows, ascending)
+ */
+int thinkv_gather_rows(const void* src, void* dst, const int32_t* rows, int64_t n_rows, int32_t row_bytes, void* stream);
+
 const char* thinkv_status_string(int status);
 
 #ifdef __cplusplus

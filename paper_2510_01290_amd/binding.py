@@ -16,7 +16,7 @@ ST_NOPAGES, ST_BAD_CLASS, ST_BAD_SLOT, ST_EVICT_DEAD, ST_BAD_SEQ, ST_BAD_SEGMENT
 EXPORTS = ["thinkv_block_bytes", "thinkv_page_bytes", "thinkv_append_workspace_bytes",
            "thinkv_decode_workspace_bytes", "thinkv_init_view", "thinkv_append_quantized", "thinkv_evict", "thinkv_evict_append",
            "thinkv_decode_attention", "thinkv_decode_attention_noalloc", "thinkv_decode_attention_valu", "thinkv_decode_sparsity_workspace_bytes",
-           "thinkv_decode_attention_sparsity", "thinkv_tbe_workspace_bytes", "thinkv_tbe_select", "thinkv_tbe_plan_workspace_bytes", "thinkv_tbe_plan", "thinkv_probe_stream_pages",
+           "thinkv_decode_attention_sparsity", "thinkv_tbe_workspace_bytes", "thinkv_tbe_select", "thinkv_tbe_plan_workspace_bytes", "thinkv_tbe_plan", "thinkv_probe_stream_pages", "thinkv_gather_rows",
            "thinkv_status_string"]
 
 
@@ -79,6 +79,8 @@ def load():
     lib.thinkv_tbe_plan.argtypes = [C.POINTER(View), i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.thinkv_probe_stream_pages.restype = C.c_int
     lib.thinkv_probe_stream_pages.argtypes = [C.POINTER(View), i32, vp, i32, vp, vp]
+    lib.thinkv_gather_rows.restype = C.c_int
+    lib.thinkv_gather_rows.argtypes = [vp, vp, vp, C.c_int64, i32, vp]
     lib.thinkv_status_string.restype = C.c_char_p
     lib.thinkv_status_string.argtypes = [C.c_int]
     _lib = lib
@@ -296,6 +298,14 @@ def thinkv_decode_attention_sparsity(cache, layer, q, out, lse, sparsity, seq_id
         C.byref(cache.view), layer, _ptr(q), _ptr(out), _ptr(lse), _ptr(sparsity), _ptr(seq_ids), _ptr(q_pos), B, window,
         float(softmax_scale), _DT[q.dtype], _DT[out.dtype], int(max_ctx_pages), _ptr(ws), ws.numel(), _stream(stream)),
         "thinkv_decode_attention_sparsity")
+
+
+def thinkv_gather_rows(src, dst, rows, stream=None):
+    """contrast kernel: dst[i] = src[rows[i]] (2-D contiguous tensors of equal row size, rows int32)"""
+    assert src.is_contiguous() and dst.is_contiguous() and src.dim() == 2 and dst.dim() == 2 and src.dtype == dst.dtype
+    assert rows.dtype == torch.int32 and rows.is_contiguous() and dst.shape[0] == rows.numel() and dst.shape[1] == src.shape[1]
+    _check(load().thinkv_gather_rows(_ptr(src), _ptr(dst), _ptr(rows), int(rows.numel()), int(src.shape[1] * src.element_size()),
+                                     _stream(stream)), "thinkv_gather_rows")
 
 
 def thinkv_probe_stream_pages(cache, layer, seq_ids, checksum, stream=None):

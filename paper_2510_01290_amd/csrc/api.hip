@@ -27,6 +27,7 @@ int launch_stat_fill(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
 int launch_stat_count(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
 int launch_decode_merge(const thinkv_view& v, const DecodeArgs& a, hipStream_t st);
 int decode_mfma_supported(const thinkv_config& c);
+int launch_gather_rows(const void* src, void* dst, const int32_t* rows, int64_t n_rows, int row_bytes, int n_wg, hipStream_t st);
 int launch_probe_stream(const thinkv_view& v, int layer, const int32_t* seq_ids, int B, int per_head, uint32_t* checksum, hipStream_t st);
 
 
@@ -364,6 +365,18 @@ int thinkv_probe_stream_pages(const thinkv_view* view, int32_t layer, const int3
   int64_t per_head = (int64_t)compute_units() * TKV_WAVES / ((int64_t)B * view->cfg.n_kv_heads);
   if (per_head < 1) per_head = 1;
   return launch_probe_stream(*view, layer, seq_ids, B, (int)per_head, checksum, (hipStream_t)stream);
+}
+
+int thinkv_gather_rows(const void* src, void* dst, const int32_t* rows, int64_t n_rows, int32_t row_bytes, void* stream) {
+  if (n_rows < 0 || row_bytes <= 0 || row_bytes % 16) return THINKV_E_INVALID_ARG;
+  if (n_rows == 0) return THINKV_OK;
+  if (!src || !dst || !rows) return THINKV_E_INVALID_ARG;
+  if (((uintptr_t)src | (uintptr_t)dst) & 15) return THINKV_E_INVALID_ARG;
+  const int64_t pieces = n_rows * (row_bytes / 16);
+  int64_t n_wg = (pieces + 1023) / 1024;                      // four pieces a thread
+  const int64_t most = (int64_t)compute_units() * 16;        // a few rounds of workgroups at most: the loop does the rest
+  if (n_wg > most) n_wg = most;
+  return launch_gather_rows(src, dst, rows, n_rows, row_bytes, (int)n_wg, (hipStream_t)stream);
 }
 
 const char* thinkv_status_string(int status) {
