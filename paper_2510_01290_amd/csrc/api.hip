@@ -57,8 +57,8 @@ static int check_view(const thinkv_view* v) {
   return THINKV_OK;
 }
 
-// Work-item sizes.  The fast kernel's items are single waves (TKV_WAVES of them per SIMD); the
-// plain kernel's are workgroups of four waves, three to a compute unit.  An item pays a fixed
+// Work-item sizes.  The fast kernel's items are single waves; the
+// plain kernel's are workgroups of four waves, three to a compute unit (the fast kernel: two or three waves a SIMD, by head_dim).  An item pays a fixed
 // price (query set-up, three type switches, its partial row), so it is given at least a few page
 // pairs.  Where the launch has few (query, kv-head) pairs, the items of the longest sequence fill
 // the machine exactly once; where it has many, an item per so many pages, about sixteen rounds of
@@ -85,7 +85,7 @@ struct ItemSizing {
 
 static ItemSizing size_items(const thinkv_config& c, int B, int max_ctx_pages, int window, bool fast) {
   const int64_t heads = (int64_t)B * c.n_kv_heads;
-  const int64_t resident = fast ? (int64_t)compute_units() * 4 * TKV_WAVES : (int64_t)compute_units() * 3;
+  const int64_t resident = fast ? (int64_t)compute_units() * 4 * decode_waves_per_simd(c.head_dim) : (int64_t)compute_units() * 3;
   const int least = window > 0 ? (fast ? 64 : 256) : (fast ? 16 : 32);   // fewest pages worth an item
   int64_t cap = ((int64_t)max_ctx_pages + least - 1) / least;
   if (cap < 1) cap = 1;
@@ -362,7 +362,7 @@ int thinkv_probe_stream_pages(const thinkv_view* view, int32_t layer, const int3
   if (B == 0) return THINKV_OK;
   if (!seq_ids || !checksum) return THINKV_E_INVALID_ARG;
   // four waves to a workgroup, as many workgroups as fill the machine at the occupancy of the attention kernel
-  int64_t per_head = (int64_t)compute_units() * TKV_WAVES / ((int64_t)B * view->cfg.n_kv_heads);
+  int64_t per_head = (int64_t)compute_units() * decode_waves_per_simd(view->cfg.head_dim) / ((int64_t)B * view->cfg.n_kv_heads);
   if (per_head < 1) per_head = 1;
   return launch_probe_stream(*view, layer, seq_ids, B, (int)per_head, checksum, (hipStream_t)stream);
 }

@@ -14,10 +14,16 @@
 #pragma once
 #include "common.h"
 
-// waves per SIMD the fast kernel is built for (its register budget); the host sizes launches with the same number
-#ifndef TKV_WAVES
-#define TKV_WAVES 2
+// waves per SIMD the fast kernel is built for (its register budget: 256 registers a lane at head_dim 128, where a
+// pair of 8-bit pages alone takes 48 and two pairs are held; half the tiles and half the page bytes at head_dim 64
+// leave room for a third wave); the host sizes launches with the same numbers
+#ifndef TKV_WAVES_128
+#define TKV_WAVES_128 2
 #endif
+#ifndef TKV_WAVES_64
+#define TKV_WAVES_64 3
+#endif
+__host__ __device__ constexpr int decode_waves_per_simd(int head_dim) { return head_dim == 64 ? TKV_WAVES_64 : TKV_WAVES_128; }
 
 namespace thinkv {
 

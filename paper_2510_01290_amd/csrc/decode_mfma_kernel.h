@@ -664,7 +664,7 @@ struct ClassRunner {
 // four-wave workgroup as fast as a one-wave one, and a launch of thousands of single waves takes ten
 // microseconds to get going).  WIN: sliding-window layer (static shares).
 template <int D, int GP, bool WIN, bool STAT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TKV_WAVES, TKV_WAVES))) void decode_mfma_kernel(thinkv_view v, DecodeArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(decode_waves_per_simd(D), decode_waves_per_simd(D)))) void decode_mfma_kernel(thinkv_view v, DecodeArgs a) {
   using CL = Cols<D, GP>;
   constexpr int NG = D / 32, NM = D / 16, CS = CL::CS, NSET = CL::NSET;
   const thinkv_config& c = v.cfg;
