@@ -26,18 +26,18 @@
 // read back in the slice of its group.  The zero-point part of the output and the softmax
 // denominator are lane-local binary32 sums.
 //
-// One workgroup of four waves per (query, kv-head, item); the pages of every thought type are
-// walked type by type, so the bit width is a compile-time constant of each inner loop; the
-// four waves are merged through LDS into one partial (m, l, acc) per query head.
+// One wave per work item of a (query, kv-head); the pages of every thought type are walked type
+// by type, so the bit width is a compile-time constant of each inner loop; every item leaves one
+// partial (acc, m, l) per query head, which the merge kernel folds.
 //
 // Work distribution.  On sliding-window layers an item owns a fixed share of each type's page
-// list and a wave takes every fourth page pair of it.  On full-attention layers the launch is
-// sized so that all workgroups are resident at once, and the waves of all workgroups of one
-// (query, kv-head) draw chunks of page pairs from three shared counters (one per type) until
-// the lists are empty: the kernel is bound by memory there, compute units do not all see the
-// same bandwidth, and a fixed split would leave the fast ones idle for the last fifth of the
-// launch.  Which workgroup adds a pair to its partial does not matter: the merge kernel sums
-// the partials of a head whatever they hold.
+// list.  On full-attention layers the items of one (query, kv-head) draw chunks of page pairs
+// from three shared counters (one per type) until the lists are empty: compute units do not
+// all see the same bandwidth, and a fixed split would leave the fast ones idle for the last
+// fifth of the launch.  Which item adds a pair to its partial does not matter: the merge kernel
+// sums the partials of a head whatever they hold.  A wave keeps the loads of its next pair in
+// flight while it works on the current one, and learns the ids of its next chunk by scalar loads,
+// outside the vector-memory queue.
 #pragma once
 #include "decode_common.h"
 
@@ -684,11 +684,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(decode_wave
     a.alloc[2 * (b * c.n_kv_heads + hkv)] = it.row0;
     a.alloc[2 * (b * c.n_kv_heads + hkv) + 1] = it.n;
   }
-#ifdef TKV_STAMP
-  unsigned long long* stamps = (unsigned long long*)(a.alloc + 2 * a.B * c.n_kv_heads + 64) + (int64_t)item * 8;
-  const bool stamper = lane == 0;
-  if (stamper) { stamps[0] = wall_clock64(); stamps[6] = ((unsigned long long)b << 32) | (unsigned)(hkv * 1000 + it.j); }
-#endif
 
   // ---- the query: lane (slice gl, head, row quad qd) reads, per column set, the eight values of
   // channels 32g + 8qd .. of its head (g = the set's group of its slice), rounds them to binary16
@@ -731,9 +726,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(decode_wave
   st.m = -INFINITY;
   st.m_sub = 0.f;
   const int qpos = WIN ? a.q_pos[b] : 0;
-#ifdef TKV_STAMP
-  if (stamper) stamps[1] = wall_clock64();
-#endif
 
   // Items start on different types: a pair of 8-bit pages moves three times the bytes of a pair of
   // 2-bit pages for the same arithmetic, so if every wave walked the types in the same order the
@@ -765,9 +757,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(decode_wave
       if (bits == 2) TKV_RUN(2) else if (bits == 4) TKV_RUN(4) else TKV_RUN(8)
 #undef TKV_RUN
     }
-#ifdef TKV_STAMP
-    if (stamper) stamps[2 + kk] = wall_clock64();
-#endif
   }
 
   // ---- the item's partial row per query head.  The four lanes of a column (row quads) each hold a
@@ -817,9 +806,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(decode_wave
       }
     }
   }
-#ifdef TKV_STAMP
-  if (stamper) stamps[5] = wall_clock64();
-#endif
   // (direct) the work queues of this head are left empty for the next call: no other item shares them
   if (a.direct && lane < 4) v.work_counters[(((int64_t)a.layer * c.max_seqs + b) * c.n_kv_heads + hkv) * 4 + lane] = 0u;
 }
