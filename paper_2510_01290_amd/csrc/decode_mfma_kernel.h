@@ -502,6 +502,7 @@ struct ClassRunner {
   // flight while it computes.  When the stream ends the pair in flight is a repeat (a cache hit)
   // and is dropped.
   static constexpr int kChunkPairs = TKV_CHUNK;
+  static_assert(kChunkPairs == 4, "a chunk's page ids are fetched as eight-word vectors");
   static_assert(kChunkPairs <= 8, "a chunk's page ids are held in sixteen scalars");
   static constexpr int kChunkPages = 2 * kChunkPairs;
   typedef const int32_t __attribute__((address_space(4))) * ConstI32;   // read-only for the whole launch: scalar loads
@@ -517,9 +518,23 @@ struct ClassRunner {
     int nj;                       // first pair of the next chunk (>= n_pairs: none)
     int on_order;                 // lane 0: first pair of the chunk after that (atomic in flight)
   };
-  // ids and masks of the chunk that starts at pair j -> scalars; entries past the end of the list repeat its last page (never used)
+  // ids and masks of the chunk that starts at pair j -> scalars.  A chunk that lies inside the list is fetched by two
+  // eight-word scalar loads (page lists are only word-aligned: the scalar unit does not ask for more); the last chunk
+  // of a list word by word, entries past the end repeating the last page (never used).
+  typedef int32_t Words8 __attribute__((ext_vector_type(kChunkPages), aligned(4)));
+  typedef const Words8 __attribute__((address_space(4))) * ConstWords8;
   __device__ __forceinline__ void load_ids(Stream& q, int j) const {
     const int pg0 = 2 * j;
+    if (pg0 + kChunkPages <= q.n_pages) {
+      const Words8 a = *(ConstWords8)(q.tab + pg0);
+      const Words8 b = *(ConstWords8)(q.msk + pg0);
+#pragma unroll
+      for (int i = 0; i < kChunkPages; ++i) {
+        q.s_pid[i] = __builtin_amdgcn_readfirstlane(a[i]);
+        q.s_msk[i] = __builtin_amdgcn_readfirstlane(b[i]);
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < kChunkPages; ++i) {
       const int at = pg0 + i < q.n_pages ? pg0 + i : q.n_pages - 1;
