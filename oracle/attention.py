@@ -7,7 +7,8 @@ query head gets its own softmax -- the max-pool aggregation printed there is use
 paper for its sparsity statistic only).  Everything is binary64:
 
     live set   = slots whose live bit is set [and 0 <= q_pos - slot_pos < W on window layers]
-    k^_j, v^_j = zp + code * scale from the STORED binary16 scale / zero-point
+    k^_j, v^_j = the stored codes decoded with the STORED scales (zp + code * scale from the binary16 scale /
+                 zero-point of the integer formats; code value times E4M3 or tensor scale for the paper's formats)
     o_h        = sum_j softmax_j(scale * q_h . k^_j) v^_j ,  lse_h = log sum_j exp(scale * q_h . k^_j)
 
 Tokens are visited in ascending logical position (ties: table order), which makes the result
@@ -15,8 +16,6 @@ independent of where a token physically sits (Theorem "KV Permutation Invariance
 Attention").  An empty live set gives o = 0 and lse = -inf.
 """
 import numpy as np
-
-from . import quant
 
 
 def gather_live(cache, s, layer, q_pos=None, window=0):
@@ -37,8 +36,8 @@ def gather_live(cache, s, layer, q_pos=None, window=0):
         if sel.size == 0:
             continue
         p, sl = pid[sel], slot[sel]
-        k[sel] = quant.dequantize(cache.k_codes[c][p, :, sl, :], cache.k_scale[c][p, :, sl, :], cache.k_zp[c][p, :, sl, :])
-        v[sel] = quant.dequantize(cache.v_codes[c][p, :, sl, :], cache.v_scale[c][p, :, sl, :], cache.v_zp[c][p, :, sl, :])
+        k[sel] = cache.dequant(c, 0, p, sl)
+        v[sel] = cache.dequant(c, 1, p, sl)
     order = np.argsort(pos, kind="stable")
     return pos[order], k[order], v[order]
 

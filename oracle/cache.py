@@ -25,7 +25,7 @@ Thought types are numbered as in the paper's pseudocode: 0 = transition (T), 1 =
 from dataclasses import dataclass, field
 import numpy as np
 
-from . import layout, quant
+from . import formats, layout, quant
 
 PAGE = layout.PAGE
 ST_NOPAGES, ST_BAD_CLASS, ST_BAD_SLOT, ST_EVICT_DEAD, ST_BAD_SEQ = 1, 2, 4, 8, 16
@@ -52,11 +52,15 @@ class OracleConfig:
     arena_pages: tuple              # physical pages per class
     page_size: int = PAGE
     group_size: int = quant.GROUP
+    fmt: str = "int"                # "int": asymmetric integer codes, binary16 scale and zero-point per 32 (quant.py);
+                                    # "fp": the paper's formats (formats.py): 8 bits = E4M3 with one scale per tensor,
+                                    # 4 bits = E2M1 and 2 bits = ternary with an E4M3 scale per 16 channels of the token
+    fp8_scale: tuple = (1.0, 1.0)   # fmt "fp": the per-tensor binary32 scales of keys and of values (from calibration)
 
 
 class OracleCache:
     def __init__(self, cfg: OracleConfig, store_data=True):
-        assert cfg.page_size == PAGE and cfg.group_size == quant.GROUP
+        assert cfg.page_size == PAGE and cfg.group_size == quant.GROUP and cfg.fmt in ("int", "fp")
         self.cfg = cfg
         self.store_data = store_data
         S, L, MP = cfg.max_seqs, cfg.n_layers, cfg.max_pages
@@ -79,8 +83,14 @@ class OracleCache:
             nd = n if store_data else 0
             self.k_codes.append(np.zeros((nd, H, PAGE, D), dtype=np.uint8))
             self.v_codes.append(np.zeros((nd, H, PAGE, D), dtype=np.uint8))
-            for lst in (self.k_scale, self.k_zp, self.v_scale, self.v_zp):
-                lst.append(np.zeros((nd, H, PAGE, NG), dtype=np.float16))
+            if cfg.fmt == "int":
+                for lst in (self.k_scale, self.k_zp, self.v_scale, self.v_zp):
+                    lst.append(np.zeros((nd, H, PAGE, NG), dtype=np.float16))
+            else:   # E4M3 scale codes per 16 channels (unused by the 8-bit type); no zero-points
+                for lst in (self.k_scale, self.v_scale):
+                    lst.append(np.zeros((nd, H, PAGE, D // formats.GROUP16), dtype=np.uint8))
+                for lst in (self.k_zp, self.v_zp):
+                    lst.append(None)
 
     # ------------------------------------------------------------------ append
     def _select_slot(self, s, l, c):
@@ -124,8 +134,7 @@ class OracleCache:
                 idx = np.flatnonzero(tok_class == c)
                 if idx.size:
                     b = cfg.bits_of_class[c]
-                    q[c] = (dict(zip(idx.tolist(), range(idx.size))),
-                            quant.quantize_groups(k_new[idx], b), quant.quantize_groups(v_new[idx], b))
+                    q[c] = (dict(zip(idx.tolist(), range(idx.size))), self._quantize(k_new[idx], b, 0), self._quantize(v_new[idx], b, 1))
         for i in range(n_tok):
             s, pos, c = int(tok_seq[i]), int(tok_pos[i]), int(tok_class[i])
             if not 0 <= s < cfg.max_seqs:
@@ -152,13 +161,44 @@ class OracleCache:
             if self.store_data:
                 row, (kc, ks, kz), (vc, vs, vz) = q[c][0][i], q[c][1], q[c][2]
                 self.k_codes[c][pid, :, slot, :] = kc[row]
-                self.k_scale[c][pid, :, slot, :] = ks[row]
-                self.k_zp[c][pid, :, slot, :] = kz[row]
                 self.v_codes[c][pid, :, slot, :] = vc[row]
-                self.v_scale[c][pid, :, slot, :] = vs[row]
-                self.v_zp[c][pid, :, slot, :] = vz[row]
+                if ks is not None:
+                    self.k_scale[c][pid, :, slot, :] = ks[row]
+                    self.v_scale[c][pid, :, slot, :] = vs[row]
+                if kz is not None:
+                    self.k_zp[c][pid, :, slot, :] = kz[row]
+                    self.v_zp[c][pid, :, slot, :] = vz[row]
             handles[i] = make_handle(c, pi, slot)
         return handles
+
+    # --------------------------------------------------------- number formats
+    def _quantize(self, x, bits, kind):
+        """(codes, scales or None, zero-points or None) of rows x [n, Hkv, D]; kind 0 = keys, 1 = values"""
+        if self.cfg.fmt == "int":
+            return quant.quantize_groups(x, bits)
+        if bits == 8:
+            return formats.fp8_quantize(x, self.cfg.fp8_scale[kind]), None, None
+        codes, sc = (formats.nvfp4_quantize if bits == 4 else formats.ternary_quantize)(x)
+        return codes, sc, None
+
+    def dequant(self, c, kind, pids, slots):
+        """binary64 values [n, Hkv, D] of the listed (page, slot) pairs of class c; kind 0 = keys, 1 = values"""
+        codes = (self.v_codes if kind else self.k_codes)[c][pids, :, slots, :]
+        scale = (self.v_scale if kind else self.k_scale)[c][pids, :, slots, :]
+        if self.cfg.fmt == "int":
+            zp = (self.v_zp if kind else self.k_zp)[c][pids, :, slots, :]
+            return quant.dequantize(codes, scale, zp)
+        bits = self.cfg.bits_of_class[c]
+        if bits == 8:
+            return formats.fp8_dequantize(codes, self.cfg.fp8_scale[kind])
+        return (formats.nvfp4_dequantize if bits == 4 else formats.ternary_dequantize)(codes, scale)
+
+    def token_bytes(self, c):
+        """K + V bytes one token of class c occupies per kv-head"""
+        b, D = self.cfg.bits_of_class[c], self.cfg.head_dim
+        if self.cfg.fmt == "int":
+            return 2 * (D * b // 8 + D // quant.GROUP * 4)
+        return 2 * (D * b // 8 + (0 if b == 8 else D // formats.GROUP16))
 
     # ------------------------------------------------------------------- evict
     def evict_slots(self, layer, ev_seq, ev_handle):
@@ -199,18 +239,18 @@ class OracleCache:
 
     def arena_image(self, c, n_pages=None):
         """uint8 [n_pages, page_bytes] image of the first n_pages physical pages of class c."""
-        b = self.cfg.bits_of_class[c]
         n = self.k_codes[c].shape[0] if n_pages is None else n_pages
-        img = layout.pack_page_head(self.k_codes[c][:n], self.k_scale[c][:n], self.k_zp[c][:n],
-                                    self.v_codes[c][:n], self.v_scale[c][:n], self.v_zp[c][:n], b)
-        return img.reshape(n, -1)
+        return self.arena_image_pages(c, np.arange(n))
 
     def arena_image_pages(self, c, pids):
         """uint8 [len(pids), page_bytes] image of the listed physical pages of class c"""
         b = self.cfg.bits_of_class[c]
         p = np.asarray(pids, dtype=np.int64)
-        img = layout.pack_page_head(self.k_codes[c][p], self.k_scale[c][p], self.k_zp[c][p],
-                                    self.v_codes[c][p], self.v_scale[c][p], self.v_zp[c][p], b)
+        if self.cfg.fmt == "int":
+            img = layout.pack_page_head(self.k_codes[c][p], self.k_scale[c][p], self.k_zp[c][p],
+                                        self.v_codes[c][p], self.v_scale[c][p], self.v_zp[c][p], b)
+        else:
+            img = layout.pack_page_head_fp(self.k_codes[c][p], self.k_scale[c][p], self.v_codes[c][p], self.v_scale[c][p], b)
         return img.reshape(len(p), -1)
 
     def stored_bytes_live(self, s, layer):
@@ -219,6 +259,5 @@ class OracleCache:
         cfg = self.cfg
         tot = 0
         for _, c, _, _ in self.live_tokens(s, layer):
-            b = cfg.bits_of_class[c]
-            tot += cfg.n_kv_heads * 2 * (cfg.head_dim * b // 8 + cfg.head_dim // quant.GROUP * 4)
+            tot += cfg.n_kv_heads * self.token_bytes(c)
         return tot

@@ -17,9 +17,10 @@ Readings where the paper is silent:
     (0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives);
   * ternary code = sign bit, magnitude bit: 0 -> 0, 1 -> +1, 2 -> -0 (reads 0), 3 -> -1;
   * a group's scale is amax / qmax (qmax = 6 for E2M1, 1 for ternary) rounded UP to the next
-    E4M3 value, so that the largest element never saturates by more than rounding; a group of
-    zeros (or one whose scale would underflow E4M3) has scale 0 and decodes to zeros; no
-    second, per-tensor scale sits under the E4M3 group scales (the paper names one only for FP8);
+    E4M3 value (at least 2^-9, the smallest one, for any group that is not all zeros; 448 at
+    most, beyond which elements saturate), so that the largest element never saturates by more
+    than rounding; a group of zeros has scale 0 and decodes to zeros; no second, per-tensor
+    scale sits under the E4M3 group scales (the paper names one only for FP8);
   * the per-tensor binary32 scale of FP8 comes from calibration and is an input here;
   * groups run along head_dim inside one token, for keys and values alike (16 consecutive
     channels).  The paper quantises keys per channel over groups of g tokens held back in a

@@ -26,6 +26,11 @@ FPH = 16/b, where (chunk, f, h) are
 
 (bit offsets count from the least significant bit of the chunk read as a little-endian
 integer).  A page is n_kv_heads such blocks back to back; an arena is pages back to back.
+
+The paper's own formats (formats.py) keep the code regions exactly as above (an E2M1 nibble, a
+ternary code or an E4M3 byte is a 4-, 2- or 8-bit code like any other); only the meta regions
+differ: one E4M3 scale byte per (slot, group of 16 channels), at byte  group16*16 + slot  of the
+region (D/16 * 16 bytes), and no meta region at all for the 8-bit type, whose scale is per tensor.
 """
 import numpy as np
 
@@ -104,3 +109,26 @@ def pack_page_head(k_codes, k_scale, k_zp, v_codes, v_scale, v_zp, bits):
     return np.concatenate([
         _pack_codes(k_codes, bits, D, k_code_bit), _pack_meta(k_scale, k_zp),
         _pack_codes(v_codes, bits, D, v_code_bit), _pack_meta(v_scale, v_zp)], axis=-1)
+
+
+def block_bytes_fp(bits, D):
+    return 2 * (64 * chunk_bytes(bits, D) + (0 if bits == 8 else PAGE * (D // 16)))
+
+
+def _pack_meta_fp(scale_codes):
+    """E4M3 scale codes uint8 [..., 16, D/16] -> uint8 [..., D/16 * 16]: byte group16*16 + slot"""
+    sc = np.asarray(scale_codes, dtype=np.uint8)
+    return np.ascontiguousarray(np.swapaxes(sc, -1, -2)).reshape(sc.shape[:-2] + (sc.shape[-1] * PAGE,))
+
+
+def pack_page_head_fp(k_codes, k_scale_codes, v_codes, v_scale_codes, bits):
+    """the paper's formats: k_codes, v_codes uint8 [..., 16, D]; *_scale_codes uint8 [..., 16, D/16] (ignored at 8 bits).
+    Returns the uint8 [..., block_bytes_fp] image of each (page, kv-head)."""
+    D = k_codes.shape[-1]
+    parts = [_pack_codes(k_codes, bits, D, k_code_bit)]
+    if bits != 8:
+        parts.append(_pack_meta_fp(k_scale_codes))
+    parts.append(_pack_codes(v_codes, bits, D, v_code_bit))
+    if bits != 8:
+        parts.append(_pack_meta_fp(v_scale_codes))
+    return np.concatenate(parts, axis=-1)

@@ -96,8 +96,7 @@ def segment_keys(cache, layer, seq, handles):
     for i, h in enumerate(handles):
         c, pi, slot = split_handle(h)
         pid = int(cache.table[seq, layer, c, pi])
-        out[i] = quant.dequantize(cache.k_codes[c][pid, :, slot, :], cache.k_scale[c][pid, :, slot, :],
-                                  cache.k_zp[c][pid, :, slot, :]).reshape(-1)
+        out[i] = cache.dequant(c, 0, np.array([pid]), np.array([slot])).reshape(-1)
     return out
 
 

@@ -97,3 +97,99 @@ def test_scale_rounds_up_and_covers_the_group():
     back = F.fp8_dequantize(F.fp8_quantize(y, 0.05), 0.05)
     big = np.abs(y) > 0.05 * 2.0 ** -6
     assert np.all(np.abs(back[big] - y[big]) <= np.abs(y[big]) * 2.0 ** -4)
+
+
+# ------------------------------------------------- the formats inside the paged cache (layout, bookkeeping, attention)
+def _read_fp_block_bit_by_bit(img, bits, D):
+    """independent reader of a (page, kv-head) block in the paper's formats: code regions as for the integer formats
+    (the chunk formulas at the top of oracle/layout.py), one scale byte per (slot, group of 16) at group16*16 + slot"""
+    from oracle import layout
+    cb = layout.chunk_bytes(bits, D)
+    meta = 0 if bits == 8 else 16 * (D // 16)
+    offs = (0, 64 * cb, 64 * cb + meta, 2 * 64 * cb + meta)
+    fph = 16 // bits
+    kc = np.zeros((16, D), np.uint8)
+    vc = np.zeros((16, D), np.uint8)
+    for lane in range(64):
+        kchunk = int.from_bytes(img[offs[0] + lane * cb: offs[0] + (lane + 1) * cb].tobytes(), "little")
+        vchunk = int.from_bytes(img[offs[2] + lane * cb: offs[2] + (lane + 1) * cb].tobytes(), "little")
+        for f in range(cb * 8 // bits // 2):
+            for h in range(2):
+                off = 32 * (f // fph) + 16 * h + bits * (f % fph)
+                j, t = lane // 16, lane % 16
+                kc[t, 32 * (f // 4) + 8 * j + 2 * (f % 4) + h] = (kchunk >> off) & ((1 << bits) - 1)
+                q, m = lane // 16, lane % 16
+                u, mb = f // (D // 16), f % (D // 16)
+                vc[4 * q + 2 * u + h, 16 * mb + m] = (vchunk >> off) & ((1 << bits) - 1)
+    ks = vs = None
+    if bits != 8:
+        ks = np.array([[img[offs[1] + g * 16 + t] for g in range(D // 16)] for t in range(16)], np.uint8)
+        vs = np.array([[img[offs[3] + g * 16 + t] for g in range(D // 16)] for t in range(16)], np.uint8)
+    return kc, ks, vc, vs
+
+
+def test_fp_block_layout_round_trips_through_an_independent_reader():
+    from oracle import layout
+    for D in (64, 128):
+        for bits in (2, 4, 8):
+            rng = np.random.default_rng(bits * D + 1)
+            kc = rng.integers(0, 1 << bits, (16, D), dtype=np.uint8)
+            vc = rng.integers(0, 1 << bits, (16, D), dtype=np.uint8)
+            ks = rng.integers(0, 127, (16, D // 16), dtype=np.uint8)
+            vs = rng.integers(0, 127, (16, D // 16), dtype=np.uint8)
+            img = layout.pack_page_head_fp(kc, ks, vc, vs, bits)
+            assert img.size == layout.block_bytes_fp(bits, D) == 16 * 2 * (D * bits // 8 + (0 if bits == 8 else D // 16))
+            gk, gks, gv, gvs = _read_fp_block_bit_by_bit(img, bits, D)
+            assert np.array_equal(gk, kc) and np.array_equal(gv, vc)
+            if bits != 8:
+                assert np.array_equal(gks, ks) and np.array_equal(gvs, vs)
+
+
+def test_cache_in_the_papers_formats():
+    """the paged cache with fmt='fp': what it stores is the formats' quantiser output, what attention sees is its decode,
+    and attention over it equals dense softmax attention over those decoded tokens (evicted == absent)"""
+    from oracle import attention, cache as oc
+    cfg = oc.OracleConfig(1, 8, 2, 64, (2, 4, 8), 1, 16, (16, 16, 16), fmt="fp", fp8_scale=(0.04, 0.06))     # the paper's map: T2 / E4 / R8
+    c = oc.OracleCache(cfg)
+    rng = np.random.default_rng(3)
+    n = 90
+    k = rng.standard_normal((n, 2, 64)).astype(np.float16).astype(np.float32)
+    v = rng.standard_normal((n, 2, 64)).astype(np.float16).astype(np.float32)
+    v[:, :, 5] *= 8
+    cls = rng.integers(0, 3, n).astype(np.uint8)
+    h = c.append(0, k, v, np.zeros(n, np.int64), np.arange(n), cls)
+    assert (h >= 0).all()
+    c.evict_slots(0, [0] * 10, h[20:30])
+    # stored codes and scales are the formats' own
+    for i in (0, 7, 50, 89):
+        cc, pi, slot = oc.split_handle(h[i])
+        pid = int(c.table[0, 0, cc, pi])
+        bits = cfg.bits_of_class[cc]
+        if bits == 8:
+            want = F.fp8_quantize(v[i], 0.06)
+        else:
+            want, sc = (F.nvfp4_quantize if bits == 4 else F.ternary_quantize)(v[i])
+            assert np.array_equal(c.v_scale[cc][pid, :, slot, :], sc)
+        assert np.array_equal(c.v_codes[cc][pid, :, slot, :], want)
+    q = rng.standard_normal((1, 8, 64))
+    out, lse = attention.decode_attention(c, 0, q, [0], [n - 1], 0, 0.125)
+    keep = np.r_[0:20, 30:n]
+    kd = np.zeros((len(keep), 2, 64))
+    vd = np.zeros((len(keep), 2, 64))
+    for r, i in enumerate(keep):
+        bits = cfg.bits_of_class[cls[i]]
+        for src, dst, ts in ((k, kd, 0.04), (v, vd, 0.06)):
+            if bits == 8:
+                dst[r] = F.fp8_dequantize(F.fp8_quantize(src[i], ts), ts)
+            elif bits == 4:
+                dst[r] = F.nvfp4_dequantize(*F.nvfp4_quantize(src[i]))
+            else:
+                dst[r] = F.ternary_dequantize(*F.ternary_quantize(src[i]))
+    for hq in range(8):
+        sc = 0.125 * kd[:, hq // 4, :] @ q[0, hq]
+        p = np.exp(sc - sc.max())
+        assert np.allclose(out[0, hq], (p / p.sum()) @ vd[:, hq // 4, :], rtol=1e-12, atol=1e-12)
+    # bytes: 2-bit 2*(16+4), 4-bit 2*(32+4), 8-bit 2*64 per token and kv-head at D = 64
+    assert [c.token_bytes(t) for t in range(3)] == [40, 72, 128]
+    img = c.arena_image(1)
+    assert img.shape[1] == 2 * 16 * 72
