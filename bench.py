@@ -38,6 +38,9 @@ def main():
     ap.add_argument("--workload", default="cfg2-32k", choices=["cfg2-32k", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5"],
                     help="cfg2-32k (default): the headline step.  The others time decode attention alone on that "
                          "configuration's cache (a step = one attention call per built layer)")
+    ap.add_argument("--format", default="int", choices=["int", "fp"],
+                    help="number formats of the default workload's cache: int = integer codes with binary16 scale and zero-point per 32 "
+                         "(BASELINE.json); fp = the paper's FP8-E4M3 / NVFP4 / ternary with E4M3 scales per 16")
     ap.add_argument("--replicas", type=int, default=3,
                     help="identical copies of the cache the steps rotate over, so that the data of a step was last touched "
                          "replicas steps ago (3 x 0.75 GB is far beyond the 256 MB memory-side cache)")
@@ -77,7 +80,9 @@ def main():
     bits = tuple(int(x) for x in args.bits.split(","))
     assert len(bits) == 3 and all(b_ in (2, 4, 8) for b_ in bits)
     wl.geom.bits_of_class = bits
+    wl.geom.fmt = args.format
     g = wl.geom
+    tok_bytes = [2 * (g.head_dim * b_ // 8 + (g.head_dim // 32 * 4 if args.format == "int" else (0 if b_ == 8 else g.head_dim // 16))) for b_ in bits]
     # room for the timed appends
     arena = tuple(int(x + args.batch * (nsteps // 16 + 2)) for x in harness.arena_need(wl))
     maxp = harness.max_pages_need(wl) + nsteps // 16 + 2
@@ -173,7 +178,7 @@ def main():
     # decode attention with the attention-sparsity statistic riding on it
     sp = torch.empty(args.batch, dtype=torch.float32, device=dev)
     smarks = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_extra)]
-    if args.variant == "fast":
+    if args.variant == "fast" and args.format == "int":
         i = nsteps - 1
         for j in range(n_extra + 3):
             gc = gcs[j % len(gcs)]
@@ -285,7 +290,7 @@ def main():
         b_.record()
     torch.cuda.synchronize()
     probe_us = float(np.mean([a_.elapsed_time(b_) for a_, b_ in pm]) * 1e3)
-    attn_sparsity_us = float(np.median([a.elapsed_time(b) for a, b in smarks]) * 1e3) if args.variant == "fast" else None
+    attn_sparsity_us = float(np.median([a.elapsed_time(b) for a, b in smarks]) * 1e3) if (args.variant == "fast" and args.format == "int") else None
     evict_us = float(np.median([m[0].elapsed_time(m[1]) for m in marks]) * 1e3)
     append_us = float(np.median([m[1].elapsed_time(m[2]) for m in marks]) * 1e3)
     evict_append_us = float(np.median([a.elapsed_time(b) for a, b in fmarks]) * 1e3)
@@ -300,7 +305,7 @@ def main():
         live_by_class.append(int(sum(np.unpackbits(sm[s, c, :npg[s, c]].view(np.uint8)).sum() for s in range(args.batch))))
     pages_visited = int(gc.n_pages[:, 0].sum().item())
     H, D, Hq = g.n_kv_heads, g.head_dim, g.n_q_heads
-    kv_bytes = sum(n * H * 2 * (D * b // 8 + D // 32 * 4) for n, b in zip(live_by_class, g.bits_of_class))
+    kv_bytes = sum(n * H * tb for n, tb in zip(live_by_class, tok_bytes))
     attn_bytes = kv_bytes + pages_visited * 8 + args.batch * Hq * D * (2 + 2)
     append_bytes = args.batch * (2 * H * D * 2 + H * 2 * (D * 4 // 8 + D // 32 * 4) + 12)
     step_bytes = attn_bytes + append_bytes + args.batch * 12
@@ -316,15 +321,15 @@ def main():
         "us_per_step": ms_step * 1e3, "attn_us_mean": float(attn_ms.mean() * 1e3), "attn_us_min": float(attn_ms.min() * 1e3),
         "attn_us_median": float(np.median(attn_ms) * 1e3), "evict_us_median": evict_us, "append_us_median": append_us, "evict_append_us_median": evict_append_us,
         "attn_with_sparsity_statistic_us_median": attn_sparsity_us, "tbe_select": tbe, "tbe_plan": plan, "bulk_append": bulk,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16" if args.variant == "fast" else "f32",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16" if (args.variant == "fast" and args.format == "int") else "f32",
         "data": "synthetic",
         "config": {"workload": wl.name + f" (R1-Llama-8B layer: 32 q / 8 kv heads, head_dim 128, bf16; T{bits[0]}/R{bits[2]}/E{bits[1]}, 30% E + 10% R evicted and refilled)",
                    "batch": args.batch, "live_tokens_per_seq": int(sum(live_by_class) / args.batch), "page_size": 16,
-                   "live_by_class_TER": live_by_class, "kernel": args.variant, "build_seconds": round(build_s, 1), "cache_replicas": len(gcs),
+                   "live_by_class_TER": live_by_class, "kernel": args.variant, "format": args.format, "build_seconds": round(build_s, 1), "cache_replicas": len(gcs),
                    "step": "evict 1 + append 1 (one call, thinkv_evict_append) + decode attention, per sequence"},
         "roofline": {"bound": "hbm", "kernel": "decode attention (split-K kernel + merge)", "achieved": achieved, "peak": HBM_PEAK / 1e9,
                      "unit": "GB/s", "frac": achieved * 1e9 / HBM_PEAK,
-                     "traffic": TRAFFIC_DEFAULT_BYTES if (args.ctx == 32768 and args.batch == 16 and args.variant == "fast" and bits == (8, 2, 4)) else None,
+                     "traffic": TRAFFIC_DEFAULT_BYTES if (args.ctx == 32768 and args.batch == 16 and args.variant == "fast" and bits == (8, 2, 4) and args.format == "int") else None,
                      "traffic_source": TRAFFIC_SOURCE, "algorithmic_bytes_per_launch": attn_bytes,
                      "stream_ceiling": {"GB/s": ceiling, "us": probe_us, "bytes": page_bytes_read, "frac_of_peak": ceiling * 1e9 / HBM_PEAK,
                                         "what": "the pages of the same launch read by a kernel that only loads (thinkv_probe_stream_pages)"},

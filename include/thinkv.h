@@ -68,7 +68,28 @@ typedef struct {
   int32_t bits_of_class[3]; /* each 2, 4 or 8; index = thought type                          */
   int32_t max_seqs;
   int32_t max_pages;        /* capacity of each (sequence, layer, type) page list            */
+  int32_t format;           /* THINKV_FMT_INT (0) or THINKV_FMT_FP                           */
+  float fp8_scale[2];       /* THINKV_FMT_FP: the per-tensor scales of keys and of values of
+                               the 8-bit (E4M3) type, positive, from calibration             */
 } thinkv_config;
+
+/*
+ * Number formats of the cache.
+ *   THINKV_FMT_INT  asymmetric integer codes (appendix "Group Quantization"): groups of 32 channels of a
+ *                   token share a binary16 scale and zero-point; x^ = zp + code * scale.  The bench format.
+ *   THINKV_FMT_FP   the paper's own formats (Sec. 4.2, appendix "Quantization Data Formats"), chosen by the
+ *                   type's bit width: 8 = FP8 E4M3 (finite-only, bias 7) with the per-tensor scale above;
+ *                   4 = NVFP4: E2M1 codes (bias 1; sign in bit 3) with one E4M3 scale per 16 channels of
+ *                   the token; 2 = ternary (bit 1 sign, bit 0 magnitude; -0 never written) with one E4M3
+ *                   scale per 16 channels.  x^ = value(code) * scale; no zero-points.  Codes round to
+ *                   nearest, ties to the even code, and saturate; a group's scale is amax / qmax
+ *                   (qmax 6 / 1) rounded up to the next E4M3 value.  Code regions of a block are laid out
+ *                   as for THINKV_FMT_INT; a meta region is head_dim/16 * 16 scale bytes, byte
+ *                   group16 * 16 + slot (none for the 8-bit type).  Appends and decode attention take the
+ *                   plain vector-ALU kernels in this format (no matrix-core path, no sparsity statistic yet).
+ */
+#define THINKV_FMT_INT 0
+#define THINKV_FMT_FP 1
 
 /*
  * The cache.  The paper's block table (physical block #, # filled, thought type, eviction

@@ -23,7 +23,8 @@ EXPORTS = ["thinkv_block_bytes", "thinkv_page_bytes", "thinkv_append_workspace_b
 class Config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("page_size", C.c_int32), ("group_size", C.c_int32),
-                ("bits_of_class", C.c_int32 * 3), ("max_seqs", C.c_int32), ("max_pages", C.c_int32)]
+                ("bits_of_class", C.c_int32 * 3), ("max_seqs", C.c_int32), ("max_pages", C.c_int32),
+                ("format", C.c_int32), ("fp8_scale", C.c_float * 2)]
 
 
 class View(C.Structure):
@@ -101,8 +102,12 @@ def _stream(stream):
     return C.c_void_p(s.cuda_stream)
 
 
-def make_config(n_layers, n_q_heads, n_kv_heads, head_dim, bits_of_class, max_seqs, max_pages):
-    return Config(n_layers, n_q_heads, n_kv_heads, head_dim, 16, 32, (C.c_int32 * 3)(*bits_of_class), max_seqs, max_pages)
+FMT_INT, FMT_FP = 0, 1
+
+
+def make_config(n_layers, n_q_heads, n_kv_heads, head_dim, bits_of_class, max_seqs, max_pages, fmt=FMT_INT, fp8_scale=(1.0, 1.0)):
+    return Config(n_layers, n_q_heads, n_kv_heads, head_dim, 16, 32, (C.c_int32 * 3)(*bits_of_class), max_seqs, max_pages,
+                  fmt, (C.c_float * 2)(*fp8_scale))
 
 
 def thinkv_block_bytes(cfg, bits):
@@ -125,10 +130,10 @@ class Cache:
     """Device buffers of one cache (torch tensors) and the thinkv_view that points at them."""
 
     def __init__(self, n_layers, n_q_heads, n_kv_heads, head_dim, bits_of_class, max_seqs, max_pages,
-                 arena_pages, device="cuda:0"):
+                 arena_pages, device="cuda:0", fmt=FMT_INT, fp8_scale=(1.0, 1.0)):
         load()
         self.device = torch.device(device)
-        self.cfg = make_config(n_layers, n_q_heads, n_kv_heads, head_dim, bits_of_class, max_seqs, max_pages)
+        self.cfg = make_config(n_layers, n_q_heads, n_kv_heads, head_dim, bits_of_class, max_seqs, max_pages, fmt, fp8_scale)
         self.bits_of_class = tuple(bits_of_class)
         self.arena_pages = tuple(int(x) for x in arena_pages)
         d = self.device

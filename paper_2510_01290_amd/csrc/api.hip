@@ -41,6 +41,10 @@ static int check_config(const thinkv_config* c) {
   if (c->max_pages >= (1 << 24)) return THINKV_E_SHAPE;
   for (int k = 0; k < 3; ++k)
     if (!bits_ok(c->bits_of_class[k])) return THINKV_E_SHAPE;
+  if (c->format != THINKV_FMT_INT && c->format != THINKV_FMT_FP) return THINKV_E_UNSUPPORTED;
+  if (c->format == THINKV_FMT_FP)
+    for (int k = 0; k < 2; ++k)
+      if (!(c->fp8_scale[k] > 0.0f) || !(c->fp8_scale[k] < 3.0e38f)) return THINKV_E_INVALID_ARG;
   return THINKV_OK;
 }
 
@@ -187,7 +191,7 @@ extern "C" {
 
 size_t thinkv_block_bytes(const thinkv_config* cfg, int bits) {
   if (check_config(cfg) || !bits_ok(bits)) return 0;
-  return (size_t)block_geom(bits, cfg->head_dim).block_bytes;
+  return (size_t)block_geom(bits, cfg->head_dim, cfg->format).block_bytes;
 }
 
 size_t thinkv_page_bytes(const thinkv_config* cfg, int bits) {

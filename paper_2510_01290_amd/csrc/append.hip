@@ -29,6 +29,7 @@
 // appends one token per sequence, so the call is a chain of short dependent launches and one
 // launch less is a good part of its time.
 #include "common.h"
+#include "formats_dev.h"
 
 namespace thinkv {
 
@@ -253,6 +254,7 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
   __shared__ int s_place[7];            // type, page id, slot, ok, index in the page list, arrivals wanted, last to arrive
   __shared__ uint8_t s_codes[HP][2][D];
   __shared__ uint32_t s_meta[HP][2][NG];
+  __shared__ uint8_t s_scale8[HP][2][D / kGroupFp];   // THINKV_FMT_FP: the E4M3 scale codes of the row's groups of 16
   const thinkv_config& c = v.cfg;
   const int i = blockIdx.x, tid = threadIdx.x;
   // the first input value of this thread is requested before the slot is settled: the slot takes a
@@ -359,7 +361,8 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
   if (!s_place[3]) return;
   const int cls = s_place[0], pid = s_place[1], t = s_place[2];
   const int bits = c.bits_of_class[cls];
-  const BlockGeom g = block_geom(bits, D);
+  const bool fp = c.format == THINKV_FMT_FP;
+  const BlockGeom g = block_geom(bits, D, c.format);
   const int H = c.n_kv_heads;
   const float qmax = (float)((1 << bits) - 1);
   uint8_t* page = v.arena[cls] + (int64_t)pid * H * g.block_bytes;
@@ -370,6 +373,23 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
     if (h < h_end) {
       const void* src = kind ? v_new : k_new;
       const float x = h == h_first ? x_first : load_as_f32(src, ((int64_t)i * H + h) * D + ch, in_dtype);
+      if (fp) {
+        // the paper's formats: the ratio to the scale in binary64, as the formats are defined
+        uint32_t code;
+        if (bits == 8) {
+          code = e4m3_encode((double)x / (double)c.fp8_scale[kind]);
+        } else {
+          float amax = fabsf(x);
+#pragma unroll
+          for (int d = 8; d >= 1; d >>= 1) amax = fmaxf(amax, __shfl_xor(amax, d, 64));
+          const uint32_t sc8 = e4m3_code_up((double)amax / (bits == 4 ? 6.0 : 1.0));
+          const double sd = (double)e4m3_value(sc8);
+          const double r = sd > 0.0 ? (double)x / sd : 0.0;
+          code = bits == 4 ? e2m1_encode(r) : ternary_encode(r);
+          if ((ch & 15) == 0) s_scale8[hs][kind][ch >> 4] = (uint8_t)sc8;
+        }
+        s_codes[hs][kind][ch] = (uint8_t)code;
+      } else {
       float mn = x, mx = x;
 #pragma unroll
       for (int d = 16; d >= 1; d >>= 1) {
@@ -392,6 +412,7 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
       s_codes[hs][kind][ch] = (uint8_t)(int)code;
       if ((ch & 31) == 0)
         s_meta[hs][kind][ch >> 5] = (uint32_t)__builtin_bit_cast(uint16_t, sc) | ((uint32_t)__builtin_bit_cast(uint16_t, zp) << 16);
+      }
     }
     __syncthreads();
     // pack: every destination byte the slot owns is assembled by one thread
@@ -422,7 +443,13 @@ __global__ __launch_bounds__(256) void append_place_kernel(thinkv_view v, int la
         blk[g.v_codes + (16 * (t >> 2) + m) * CB + off] = (uint8_t)byte;
       }
     }
-    if (tid < HP * 2 * NG) {
+    if (fp) {
+      constexpr int NG16 = D / kGroupFp;
+      if (bits != 8 && tid < HP * 2 * NG16) {
+        const int mh = tid / (2 * NG16), mr = tid % (2 * NG16), mk = mr / NG16, mg = mr % NG16;
+        if (h0 + mh < H) (page + (int64_t)(h0 + mh) * g.block_bytes)[(mk ? g.v_meta : g.k_meta) + mg * kPage + t] = s_scale8[mh][mk][mg];
+      }
+    } else if (tid < HP * 2 * NG) {
       const int mh = tid / (2 * NG), mr = tid % (2 * NG), mk = mr / NG, mg = mr % NG;
       if (h0 + mh < H) {
         uint8_t* blk = page + (int64_t)(h0 + mh) * g.block_bytes;
@@ -825,7 +852,7 @@ int launch_append(const thinkv_view& v, int layer, const void* k_new, const void
   hipLaunchKernelGGL(append_plan_kernel, dim3(S), dim3(256), 0, st, v, layer, tok_seq, tok_class, n_tok, ws, ev_seq, ev_handle, n_ev);
   const int commit_here = n_tok <= kBulkFrom;   // else thousands of blocks would bump one sequence's counter
   const bool aligned = (((uintptr_t)k_new | (uintptr_t)v_new) & 15) == 0;
-  if (!commit_here && aligned) {
+  if (!commit_here && aligned && v.cfg.format == THINKV_FMT_INT) {   // the paper's formats go through the per-token kernel
     hipLaunchKernelGGL(append_grant_kernel, dim3(1), dim3(256), 0, st, v, ws);
     // enough blocks to fill the chip: a mid-sized call spreads the kv-heads of its token groups over blocks
     const int H = v.cfg.n_kv_heads, groups = (n_tok + kBulkTokens - 1) / kBulkTokens;

@@ -23,11 +23,14 @@ struct BlockGeom {
   int block_bytes;
 };
 
-__host__ __device__ inline BlockGeom block_geom(int bits, int D) {
+// fmt THINKV_FMT_FP: the code regions are the same; a meta region is one E4M3 scale byte per (slot, group
+// of 16 channels), byte group16 * 16 + slot, and there is none for the 8-bit type (per-tensor scale).
+constexpr int kGroupFp = 16;
+__host__ __device__ inline BlockGeom block_geom(int bits, int D, int fmt = THINKV_FMT_INT) {
   BlockGeom g;
   g.chunk_bytes = (D / kGroup) * bits;
   g.codes_bytes = 64 * g.chunk_bytes;
-  g.meta_bytes = kPage * (D / kGroup) * 4;
+  g.meta_bytes = fmt == THINKV_FMT_FP ? (bits == 8 ? 0 : kPage * (D / kGroupFp)) : kPage * (D / kGroup) * 4;
   g.k_codes = 0;
   g.k_meta = g.codes_bytes;
   g.v_codes = g.k_meta + g.meta_bytes;
@@ -41,6 +44,23 @@ __host__ __device__ inline BlockGeom block_geom(int bits, int D) {
 __host__ __device__ inline int meta_index(int t, int g) { return (g * 4 + (t >> 2)) * 8 + (t & 3); }
 
 __host__ __device__ inline bool bits_ok(int b) { return b == 2 || b == 4 || b == 8; }
+
+// Values of the codes of the paper's formats.  An IEEE-style format nests in a wider one: the magnitude bits of
+// an E4M3 or E2M1 code, placed under the exponent of a binary16 number, are that number up to a power of two
+// (subnormals included).
+__device__ inline float e4m3_value(uint32_t b) {
+  const uint16_t h = (uint16_t)(((b & 0x80u) << 8) | ((b & 0x7Fu) << 7));
+  return (float)__builtin_bit_cast(_Float16, h) * 256.0f;
+}
+__device__ inline float e2m1_value(uint32_t n) {
+  const uint16_t h = (uint16_t)(((n & 8u) << 12) | ((n & 7u) << 9));
+  return (float)__builtin_bit_cast(_Float16, h) * 16384.0f;
+}
+__device__ inline float ternary_value(uint32_t c) { return (c & 1u) ? ((c & 2u) ? -1.0f : 1.0f) : 0.0f; }
+// value of a code of the b-bit type of THINKV_FMT_FP, before its scale
+__device__ inline float fp_code_value(uint32_t code, int bits) {
+  return bits == 8 ? e4m3_value(code) : (bits == 4 ? e2m1_value(code) : ternary_value(code));
+}
 
 // index helpers for the per-(sequence, layer[, type]) tables
 __device__ inline int64_t table_base(const thinkv_config& c, int seq, int layer, int cls) {

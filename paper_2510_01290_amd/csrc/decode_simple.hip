@@ -51,7 +51,8 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
 
   for (int k = 0; k < 3; ++k) {
     const int bits = c.bits_of_class[k];
-    const BlockGeom geo = block_geom(bits, D);
+    const bool fp = c.format == THINKV_FMT_FP;
+    const BlockGeom geo = block_geom(bits, D, c.format);
     const int p0 = (int)((int64_t)it.j * np[k] / it.n), p1 = (int)((int64_t)(it.j + 1) * np[k] / it.n);
     const int32_t* tab = v.block_table + table_base(c, seq, a.layer, k);
     const uint32_t* msk = v.slot_mask + table_base(c, seq, a.layer, k);
@@ -74,10 +75,17 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
       float part[GMAX];
       for (int g = 0; g < GMAX; ++g) part[g] = 0.f;
       for (int grp = 0; grp < NG; ++grp) {
-        const float sc = (float)kmeta[meta_index(t, grp)];
-        const float zp = (float)kmeta[meta_index(t, grp) + 4];
+        float sc, zp = 0.f;
+        if (fp) {
+          // channels 32 grp + 8 j .. + 7 lie in the group of 16 number 2 grp + j / 2
+          sc = bits == 8 ? c.fp8_scale[0] : e4m3_value(((const uint8_t*)kmeta)[(2 * grp + (j >> 1)) * kPage + t]);
+        } else {
+          sc = (float)kmeta[meta_index(t, grp)];
+          zp = (float)kmeta[meta_index(t, grp) + 4];
+        }
         for (int e = 0; e < 8; ++e) {
-          const float kh = fmaf((float)field(kw, 4 * grp + (e >> 1), e & 1, bits), sc, zp);
+          const uint32_t code = field(kw, 4 * grp + (e >> 1), e & 1, bits);
+          const float kh = fp ? fp_code_value(code, bits) * sc : fmaf((float)code, sc, zp);
           const int ch = 32 * grp + 8 * j + e;
           for (int g = 0; g < GMAX; ++g)
             if (g < G) part[g] = fmaf(kh, s_q[g][ch], part[g]);
@@ -112,9 +120,15 @@ __global__ __launch_bounds__(256) void decode_simple_kernel(thinkv_view v, Decod
         float pr[GMAX];
         for (int g = 0; g < GMAX; ++g) pr[g] = (g < G) ? __shfl(p[g], tok, 64) : 0.f;
         for (int mb = 0; mb < NM; ++mb) {
-          const float sc = (float)vmeta[meta_index(tok, mb >> 1)];
-          const float zp = (float)vmeta[meta_index(tok, mb >> 1) + 4];
-          const float vh = fmaf((float)field(vw, (r >> 1) * NM + mb, r & 1, bits), sc, zp);
+          float sc, zp = 0.f;
+          if (fp) {   // channel block mb is a group of 16
+            sc = bits == 8 ? c.fp8_scale[1] : e4m3_value(((const uint8_t*)vmeta)[mb * kPage + tok]);
+          } else {
+            sc = (float)vmeta[meta_index(tok, mb >> 1)];
+            zp = (float)vmeta[meta_index(tok, mb >> 1) + 4];
+          }
+          const uint32_t code = field(vw, (r >> 1) * NM + mb, r & 1, bits);
+          const float vh = fp ? fp_code_value(code, bits) * sc : fmaf((float)code, sc, zp);
           for (int g = 0; g < GMAX; ++g)
             if (g < G) acc[g][mb] = fmaf(pr[g], vh, acc[g][mb]);
         }

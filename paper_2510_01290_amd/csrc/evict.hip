@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void arena_clear_kernel(uint4* p, int64_t n16)
 int launch_init(const thinkv_view& v, hipStream_t st) {
   hipLaunchKernelGGL(init_kernel, dim3(1024), dim3(256), 0, st, v);
   for (int k = 0; k < 3; ++k) {
-    const int64_t n16 = v.arena_pages[k] * (int64_t)v.cfg.n_kv_heads * block_geom(v.cfg.bits_of_class[k], v.cfg.head_dim).block_bytes / 16;
+    const int64_t n16 = v.arena_pages[k] * (int64_t)v.cfg.n_kv_heads * block_geom(v.cfg.bits_of_class[k], v.cfg.head_dim, v.cfg.format).block_bytes / 16;
     if (n16 > 0) hipLaunchKernelGGL(arena_clear_kernel, dim3(2048), dim3(256), 0, st, (uint4*)v.arena[k], n16);
   }
   return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;

@@ -21,7 +21,7 @@ __global__ __launch_bounds__(256) void probe_stream_kernel(thinkv_view v, int la
   uint32_t acc = 0;
   for (int k = 0; k < 3; ++k) {
     const int np = v.n_pages[npages_index(c, seq, layer, k)];
-    const int bb = block_geom(c.bits_of_class[k], c.head_dim).block_bytes;
+    const int bb = block_geom(c.bits_of_class[k], c.head_dim, c.format).block_bytes;
     const int32_t* tab = v.block_table + table_base(c, seq, layer, k);
     const int stride = 4 * per_head;
     // the wave's pages are first + i * stride; their ids are fetched 64 at a time (lane i: page i of the run), then

@@ -92,7 +92,8 @@ __global__ __launch_bounds__(256) void tbe_gather_kernel(thinkv_view v, TbeArgs 
     const int bits = c.bits_of_class[cls];
     const int lb = bits == 8 ? 3 : (bits == 4 ? 2 : 1), lf = 4 - lb;   // log2 of the bits per code and of the fields per half word
     const uint32_t mask = (1u << bits) - 1u;
-    const BlockGeom g = block_geom(bits, D);
+    const bool fp = c.format == THINKV_FMT_FP;
+    const BlockGeom g = block_geom(bits, D, c.format);
     const uint8_t* page = v.arena[cls] + (int64_t)s_pid[t] * H * g.block_bytes;
     for (int idx = tid; idx < a.dim; idx += 256) {
       const int hd = idx >> ld, ch = idx & (D - 1);
@@ -100,7 +101,13 @@ __global__ __launch_bounds__(256) void tbe_gather_kernel(thinkv_view v, TbeArgs 
       const int grp = ch >> 5, chunk = 16 * ((ch & 31) >> 3) + slot;
       const int f = 4 * grp + ((ch & 7) >> 1), bit = 32 * (f >> lf) + 16 * (ch & 1) + ((f & ((1 << lf) - 1)) << lb);
       const uint32_t word = ((const uint32_t*)(blk + g.k_codes + chunk * g.chunk_bytes))[bit >> 5];
-      const float code = (float)((word >> (bit & 31)) & mask);
+      const uint32_t raw = (word >> (bit & 31)) & mask;
+      if (fp) {   // the paper's formats: value of the code times the tensor's scale or the E4M3 scale of the channel's group of 16
+        const float sc = bits == 8 ? c.fp8_scale[0] : e4m3_value(blk[g.k_meta + (ch >> 4) * kPage + slot]);
+        row[idx] = fp_code_value(raw, bits) * sc;
+        continue;
+      }
+      const float code = (float)raw;
       const _Float16* meta = (const _Float16*)(blk + g.k_meta);
       row[idx] = fmaf(code, (float)meta[meta_index(slot, grp)], (float)meta[meta_index(slot, grp) + 4]);
     }

@@ -59,4 +59,5 @@ def make_gpu_cache(wl, max_seqs=None, arena_pages=None, max_pages=None, device="
     g = wl.geom
     return B.Cache(g.n_layers, g.n_q_heads, g.n_kv_heads, g.head_dim, g.bits_of_class,
                    max_seqs or wl.n_seqs, max_pages or max_pages_need(wl),
-                   arena_pages or arena_need(wl), device=device)
+                   arena_pages or arena_need(wl), device=device,
+                   fmt=B.FMT_FP if getattr(g, "fmt", "int") == "fp" else B.FMT_INT, fp8_scale=tuple(getattr(g, "fp8_scale", (1.0, 1.0))))

@@ -75,6 +75,8 @@ class Geometry:
     head_dim: int
     dtype: str = "bf16"                    # dtype of K/V rows and queries
     bits_of_class: tuple = (8, 2, 4)       # (T, E, R) -- BASELINE configs: T=8, R=4, E=2
+    fmt: str = "int"                       # "int": integer codes, group 32 (BASELINE); "fp": the paper's E4M3 / NVFP4 / ternary
+    fp8_scale: tuple = (0.05, 0.05)        # fmt "fp": per-tensor scales of keys and values of the 8-bit type
 
 
 def kv_rows(seed, layer, seq, kind, t0, t1, geom, device):

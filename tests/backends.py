@@ -24,4 +24,5 @@ class OracleBackend:
 
 def oracle_config(geom, max_seqs, max_pages, arena_pages):
     return ocache.OracleConfig(geom.n_layers, geom.n_q_heads, geom.n_kv_heads, geom.head_dim,
-                               tuple(geom.bits_of_class), max_seqs, max_pages, tuple(arena_pages))
+                               tuple(geom.bits_of_class), max_seqs, max_pages, tuple(arena_pages),
+                               fmt=getattr(geom, "fmt", "int"), fp8_scale=tuple(getattr(geom, "fp8_scale", (1.0, 1.0))))
