@@ -208,6 +208,202 @@ struct PairRegs {
   PageRegs<D, BITS, NSET> a, b;
 };
 
+// Walking the pages of one type: the part that does not depend on what is done with a pair.  Derived
+// supplies  void issue_loads(Pair&, const PairIds&)  and  void compute(const Pair&, const PairIds&).
+template <class Derived, class Pair>
+struct PairWalk {
+  const thinkv_view& v;
+  const DecodeArgs& a;
+  const int cls, hkv, qpos;
+  const int32_t* tab;
+  const int p0, p1;
+  int lane;
+  __device__ __forceinline__ PairWalk(const thinkv_view& v_, const DecodeArgs& a_, int cls_, int hkv_, int qpos_, const int32_t* tab_, int p0_, int p1_)
+      : v(v_), a(a_), cls(cls_), hkv(hkv_), qpos(qpos_), tab(tab_), p0(p0_), p1(p1_), lane(threadIdx.x & 63) {}
+  __device__ __forceinline__ Derived& self() { return *static_cast<Derived*>(this); }
+
+  // Shared queues: *counter hands out page pairs of the type's page list tab[0 .. n_pages) to every
+  // item of this (query, kv-head), kChunkPairs consecutive pairs per request.  A wave keeps the
+  // chunk it works on, the ids of the next one (requested when the current one was started, so
+  // they have long arrived when they are needed) and one more chunk on order; its pairs thus
+  // form one stream across chunk boundaries, and the loads of pair i + 1 are requested before
+  // pair i is worked on (two register sets, A and B, used in turn): a wave always has a pair in
+  // flight while it computes.  When the stream ends the pair in flight is a repeat (a cache hit)
+  // and is dropped.
+  static constexpr int kChunkPairs = TKV_CHUNK;
+  static_assert(kChunkPairs == 4, "a chunk's page ids are fetched as eight-word vectors");
+  static_assert(kChunkPairs <= 8, "a chunk's page ids are held in sixteen scalars");
+  static constexpr int kChunkPages = 2 * kChunkPairs;
+  typedef const int32_t __attribute__((address_space(4))) * ConstI32;   // read-only for the whole launch: scalar loads
+  struct Stream {
+    ConstI32 tab, msk;
+    uint32_t* counter;
+    int n_pages, n_pairs;
+    int pg0, cnt, pr;             // current chunk: first page, pages, next pair
+    int vpid;                     // lane L: id of page L of the current chunk
+    int vmask;                    // lane L: mask word of that page (live bits in the low half)
+    int s_pid[kChunkPages];       // the next chunk's ids and mask words: scalar loads requested when the
+    int s_msk[kChunkPages];       //   current chunk was started (no traffic in the vector-memory queue)
+    int nj;                       // first pair of the next chunk (>= n_pairs: none)
+    int on_order;                 // lane 0: first pair of the chunk after that (atomic in flight)
+  };
+  // ids and masks of the chunk that starts at pair j -> scalars.  A chunk that lies inside the list is fetched by two
+  // eight-word scalar loads (page lists are only word-aligned: the scalar unit does not ask for more); the last chunk
+  // of a list word by word, entries past the end repeating the last page (never used).
+  typedef int32_t Words8 __attribute__((ext_vector_type(kChunkPages), aligned(4)));
+  typedef const Words8 __attribute__((address_space(4))) * ConstWords8;
+  __device__ __forceinline__ void load_ids(Stream& q, int j) const {
+    const int pg0 = 2 * j;
+    if (pg0 + kChunkPages <= q.n_pages) {
+      const Words8 a = *(ConstWords8)(q.tab + pg0);
+      const Words8 b = *(ConstWords8)(q.msk + pg0);
+#pragma unroll
+      for (int i = 0; i < kChunkPages; ++i) {
+        q.s_pid[i] = __builtin_amdgcn_readfirstlane(a[i]);
+        q.s_msk[i] = __builtin_amdgcn_readfirstlane(b[i]);
+      }
+      return;
+    }
+#pragma unroll
+    for (int i = 0; i < kChunkPages; ++i) {
+      const int at = pg0 + i < q.n_pages ? pg0 + i : q.n_pages - 1;
+      q.s_pid[i] = __builtin_amdgcn_readfirstlane(q.tab[at]);
+      q.s_msk[i] = __builtin_amdgcn_readfirstlane(q.msk[at]);
+    }
+  }
+  __device__ __forceinline__ void spread_ids(Stream& q) const {
+#pragma unroll
+    for (int i = 0; i < kChunkPages; ++i) {
+      asm("v_writelane_b32 %0, %1, %2" : "+v"(q.vpid) : "s"(__builtin_amdgcn_readfirstlane(q.s_pid[i])), "n"(i));
+      asm("v_writelane_b32 %0, %1, %2" : "+v"(q.vmask) : "s"(__builtin_amdgcn_readfirstlane(q.s_msk[i])), "n"(i));
+    }
+  }
+  // asks for the next chunk
+  __device__ __forceinline__ void order_chunk(Stream& q) const {
+    int r = 0;
+    if (lane == 0) r = (int)atomicAdd(q.counter, (uint32_t)kChunkPairs);
+    q.on_order = r;   // valid in lane 0
+  }
+  __device__ __forceinline__ void set_chunk(Stream& q, int j) const {
+    q.pg0 = 2 * j;
+    q.cnt = q.n_pages - q.pg0 < kChunkPages ? q.n_pages - q.pg0 : kChunkPages;
+    q.pr = 0;
+  }
+  // the next pair of the stream; false (and a repeat of page 0 of the current chunk with no live slot) at its end
+  __device__ __forceinline__ bool next_pair(Stream& q, PairIds& id) const {
+    bool have = true;
+    if (2 * q.pr >= q.cnt) {
+      if (q.nj < q.n_pairs) {
+        spread_ids(q);
+        set_chunk(q, q.nj);
+        q.nj = __builtin_amdgcn_readfirstlane(q.on_order);
+        if (q.nj < q.n_pairs) load_ids(q, q.nj);
+        order_chunk(q);
+      } else {
+        have = false;
+      }
+    }
+    const int ia = have ? 2 * q.pr : 0;
+    const bool two = have && 2 * q.pr + 1 < q.cnt;
+    const int ib = two ? 2 * q.pr + 1 : ia;
+    id.pid_a = __builtin_amdgcn_readlane(q.vpid, ia);
+    id.live_a = have ? (uint32_t)__builtin_amdgcn_readlane(q.vmask, ia) & 0xFFFFu : 0u;
+    id.pid_b = __builtin_amdgcn_readlane(q.vpid, ib);
+    id.live_b = two ? (uint32_t)__builtin_amdgcn_readlane(q.vmask, ib) & 0xFFFFu : 0u;
+    id.idx_a = q.pg0 + ia;
+    id.idx_b = two ? q.pg0 + ib : -1;
+    q.pr += have ? 1 : 0;
+    return have;
+  }
+  __device__ __forceinline__ void run_dynamic(int n_pages, uint32_t* counter) {
+    Stream q;
+    q.tab = (ConstI32)(uintptr_t)tab;
+    q.msk = (ConstI32)(uintptr_t)(v.slot_mask + (tab - v.block_table));
+    q.counter = counter;
+    q.n_pages = n_pages;
+    q.n_pairs = (n_pages + 1) >> 1;
+    order_chunk(q);
+    const int j0 = __builtin_amdgcn_readfirstlane(q.on_order);
+    if (j0 >= q.n_pairs) return;
+    order_chunk(q);
+    load_ids(q, j0);
+    q.vpid = 0;
+    q.vmask = 0;
+    spread_ids(q);
+    set_chunk(q, j0);
+    q.nj = __builtin_amdgcn_readfirstlane(q.on_order);
+    if (q.nj < q.n_pairs) load_ids(q, q.nj);
+    order_chunk(q);
+    PairIds ida, idb;
+    Pair ra, rb;
+    next_pair(q, ida);   // the first chunk has at least one page
+    self().issue_loads(ra, ida);
+    while (true) {
+      const bool more_b = next_pair(q, idb);
+      self().issue_loads(rb, idb);
+      if ((ida.live_a | ida.live_b) != 0) self().compute(ra, ida);
+      if (!more_b) break;
+      const bool more_a = next_pair(q, ida);
+      self().issue_loads(ra, ida);
+      if ((idb.live_a | idb.live_b) != 0) self().compute(rb, idb);
+      if (!more_a) break;
+    }
+  }
+
+  // Static share (sliding-window layers): page ids and live masks of up to 64 pages are fetched
+  // with one vector load each (lane L holds page p0 + base + L).  A page can hold a visible
+  // token only if the largest position ever written into it lies inside the window, so one
+  // word per page (page_pos_max) settles most pages; a lane reads the 16 positions of its page
+  // only when that test passes.  The pages of a run of 64 that still have a visible slot are
+  // paired up, and ids and masks reach the pair code through v_readlane.
+  __device__ __forceinline__ void run() {
+    const int n_pages = p1 - p0;
+    for (int base = 0; base < n_pages; base += 64) {
+      const int cnt = n_pages - base < 64 ? n_pages - base : 64;
+      int vpid = 0;
+      uint32_t vmask = 0;
+      if (lane < cnt) {
+        vpid = tab[p0 + base + lane];
+        vmask = v.slot_mask[(tab - v.block_table) + p0 + base + lane] & 0xFFFFu;
+      }
+      if (a.window > 0) {
+        uint32_t vis = 0;
+        if (vmask != 0 && v.page_pos_max[cls][vpid] > qpos - a.window) {
+          const int4* sp = (const int4*)(v.slot_pos[cls] + (int64_t)vpid * kPage);
+#pragma unroll
+          for (int t4 = 0; t4 < kPage / 4; ++t4) {
+            const int4 pos = sp[t4];
+            const int d0 = qpos - pos.x, d1 = qpos - pos.y, d2 = qpos - pos.z, d3 = qpos - pos.w;
+            vis |= ((d0 >= 0 && d0 < a.window) ? 1u : 0u) << (4 * t4);
+            vis |= ((d1 >= 0 && d1 < a.window) ? 2u : 0u) << (4 * t4);
+            vis |= ((d2 >= 0 && d2 < a.window) ? 4u : 0u) << (4 * t4);
+            vis |= ((d3 >= 0 && d3 < a.window) ? 8u : 0u) << (4 * t4);
+          }
+        }
+        vmask &= vis;
+      }
+      uint64_t todo = __ballot(vmask != 0);
+      while (todo) {
+        const int ia = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        const bool two = todo != 0;
+        const int ib = two ? __builtin_ctzll(todo) : ia;
+        if (two) todo &= todo - 1;
+        PairIds id;
+        id.pid_a = __builtin_amdgcn_readlane(vpid, ia);
+        id.live_a = __builtin_amdgcn_readlane(vmask, ia);
+        id.pid_b = __builtin_amdgcn_readlane(vpid, ib);
+        id.live_b = two ? __builtin_amdgcn_readlane(vmask, ib) : 0u;
+        id.idx_a = p0 + base + ia;
+        id.idx_b = two ? p0 + base + ib : -1;
+        Pair r;
+        self().issue_loads(r, id);
+        self().compute(r, id);
+      }
+    }
+  }
+};
+
 // What a lane keeps of the query for the whole item: per column set the eight binary16 values of
 // (its head, its slice's group, channels 8qd .. 8qd+7) and the sum of the group's 32 values.
 template <int NSET>
@@ -221,18 +417,19 @@ struct QRegs {
 // the query heads of the group of the scaled score, log2 domain; -inf for a dead or invisible
 // slot) in a[.].stat, for the attention-sparsity statistic.
 template <int D, int BITS, int GP, bool STAT>
-struct ClassRunner {
+struct ClassRunner : PairWalk<ClassRunner<D, BITS, GP, STAT>, PairRegs<D, BITS, Cols<D, GP>::NSET>> {
   using CL = Cols<D, GP>;
   static constexpr int NG = D / 32, NM = D / 16, CS = CL::CS, NSET = CL::NSET;
   using F = Fld<BITS>;
   using Pair = PairRegs<D, BITS, NSET>;
+  using Walk = PairWalk<ClassRunner<D, BITS, GP, STAT>, Pair>;
+  using Walk::v;
+  using Walk::a;
+  using Walk::cls;
+  using Walk::hkv;
+  using Walk::lane;
   WaveState<D, NSET>& st;
-  const thinkv_view& v;
-  const DecodeArgs& a;
-  const int cls, hkv, qpos;
-  const int32_t* tab;
-  const int p0, p1;
-  int lane, qd, n;
+  int qd, n;
   int meta_off[NSET];  // byte offset, inside a meta region, of this lane's unit per column set
   H8 bq[NG];           // B operands of the score MFMAs: q of group g in slice g % CS, zeros elsewhere
   float qs[NSET];      // 2^(OMIN-24) * sum_{i in group} q_i of this lane's (slice group, head)
@@ -248,8 +445,7 @@ struct ClassRunner {
   __device__ __forceinline__ ClassRunner(WaveState<D, NSET>& st_, const thinkv_view& v_, const DecodeArgs& a_, int cls_,
                                          const int32_t* tab_, int p0_, int p1_, int hkv_, int G, const QRegs<NSET>& qr,
                                          int qpos_, float* stat_, int stat_room_)
-      : st(st_), v(v_), a(a_), cls(cls_), hkv(hkv_), qpos(qpos_), tab(tab_), p0(p0_), p1(p1_), stat(stat_), stat_room(stat_room_) {
-    lane = threadIdx.x & 63;
+      : Walk(v_, a_, cls_, hkv_, qpos_, tab_, p0_, p1_), st(st_), stat(stat_), stat_room(stat_room_) {
     qd = lane >> 4;
     n = lane & 15;
     const int gl = n / GP, head = n % GP;
@@ -493,186 +689,6 @@ struct ClassRunner {
     }
   }
 
-  // Shared queues: *counter hands out page pairs of the type's page list tab[0 .. n_pages) to every
-  // item of this (query, kv-head), kChunkPairs consecutive pairs per request.  A wave keeps the
-  // chunk it works on, the ids of the next one (requested when the current one was started, so
-  // they have long arrived when they are needed) and one more chunk on order; its pairs thus
-  // form one stream across chunk boundaries, and the loads of pair i + 1 are requested before
-  // pair i is worked on (two register sets, A and B, used in turn): a wave always has a pair in
-  // flight while it computes.  When the stream ends the pair in flight is a repeat (a cache hit)
-  // and is dropped.
-  static constexpr int kChunkPairs = TKV_CHUNK;
-  static_assert(kChunkPairs == 4, "a chunk's page ids are fetched as eight-word vectors");
-  static_assert(kChunkPairs <= 8, "a chunk's page ids are held in sixteen scalars");
-  static constexpr int kChunkPages = 2 * kChunkPairs;
-  typedef const int32_t __attribute__((address_space(4))) * ConstI32;   // read-only for the whole launch: scalar loads
-  struct Stream {
-    ConstI32 tab, msk;
-    uint32_t* counter;
-    int n_pages, n_pairs;
-    int pg0, cnt, pr;             // current chunk: first page, pages, next pair
-    int vpid;                     // lane L: id of page L of the current chunk
-    int vmask;                    // lane L: mask word of that page (live bits in the low half)
-    int s_pid[kChunkPages];       // the next chunk's ids and mask words: scalar loads requested when the
-    int s_msk[kChunkPages];       //   current chunk was started (no traffic in the vector-memory queue)
-    int nj;                       // first pair of the next chunk (>= n_pairs: none)
-    int on_order;                 // lane 0: first pair of the chunk after that (atomic in flight)
-  };
-  // ids and masks of the chunk that starts at pair j -> scalars.  A chunk that lies inside the list is fetched by two
-  // eight-word scalar loads (page lists are only word-aligned: the scalar unit does not ask for more); the last chunk
-  // of a list word by word, entries past the end repeating the last page (never used).
-  typedef int32_t Words8 __attribute__((ext_vector_type(kChunkPages), aligned(4)));
-  typedef const Words8 __attribute__((address_space(4))) * ConstWords8;
-  __device__ __forceinline__ void load_ids(Stream& q, int j) const {
-    const int pg0 = 2 * j;
-    if (pg0 + kChunkPages <= q.n_pages) {
-      const Words8 a = *(ConstWords8)(q.tab + pg0);
-      const Words8 b = *(ConstWords8)(q.msk + pg0);
-#pragma unroll
-      for (int i = 0; i < kChunkPages; ++i) {
-        q.s_pid[i] = __builtin_amdgcn_readfirstlane(a[i]);
-        q.s_msk[i] = __builtin_amdgcn_readfirstlane(b[i]);
-      }
-      return;
-    }
-#pragma unroll
-    for (int i = 0; i < kChunkPages; ++i) {
-      const int at = pg0 + i < q.n_pages ? pg0 + i : q.n_pages - 1;
-      q.s_pid[i] = __builtin_amdgcn_readfirstlane(q.tab[at]);
-      q.s_msk[i] = __builtin_amdgcn_readfirstlane(q.msk[at]);
-    }
-  }
-  __device__ __forceinline__ void spread_ids(Stream& q) const {
-#pragma unroll
-    for (int i = 0; i < kChunkPages; ++i) {
-      asm("v_writelane_b32 %0, %1, %2" : "+v"(q.vpid) : "s"(__builtin_amdgcn_readfirstlane(q.s_pid[i])), "n"(i));
-      asm("v_writelane_b32 %0, %1, %2" : "+v"(q.vmask) : "s"(__builtin_amdgcn_readfirstlane(q.s_msk[i])), "n"(i));
-    }
-  }
-  // asks for the next chunk
-  __device__ __forceinline__ void order_chunk(Stream& q) const {
-    int r = 0;
-    if (lane == 0) r = (int)atomicAdd(q.counter, (uint32_t)kChunkPairs);
-    q.on_order = r;   // valid in lane 0
-  }
-  __device__ __forceinline__ void set_chunk(Stream& q, int j) const {
-    q.pg0 = 2 * j;
-    q.cnt = q.n_pages - q.pg0 < kChunkPages ? q.n_pages - q.pg0 : kChunkPages;
-    q.pr = 0;
-  }
-  // the next pair of the stream; false (and a repeat of page 0 of the current chunk with no live slot) at its end
-  __device__ __forceinline__ bool next_pair(Stream& q, PairIds& id) const {
-    bool have = true;
-    if (2 * q.pr >= q.cnt) {
-      if (q.nj < q.n_pairs) {
-        spread_ids(q);
-        set_chunk(q, q.nj);
-        q.nj = __builtin_amdgcn_readfirstlane(q.on_order);
-        if (q.nj < q.n_pairs) load_ids(q, q.nj);
-        order_chunk(q);
-      } else {
-        have = false;
-      }
-    }
-    const int ia = have ? 2 * q.pr : 0;
-    const bool two = have && 2 * q.pr + 1 < q.cnt;
-    const int ib = two ? 2 * q.pr + 1 : ia;
-    id.pid_a = __builtin_amdgcn_readlane(q.vpid, ia);
-    id.live_a = have ? (uint32_t)__builtin_amdgcn_readlane(q.vmask, ia) & 0xFFFFu : 0u;
-    id.pid_b = __builtin_amdgcn_readlane(q.vpid, ib);
-    id.live_b = two ? (uint32_t)__builtin_amdgcn_readlane(q.vmask, ib) & 0xFFFFu : 0u;
-    id.idx_a = q.pg0 + ia;
-    id.idx_b = two ? q.pg0 + ib : -1;
-    q.pr += have ? 1 : 0;
-    return have;
-  }
-  __device__ __forceinline__ void run_dynamic(int n_pages, uint32_t* counter) {
-    Stream q;
-    q.tab = (ConstI32)(uintptr_t)tab;
-    q.msk = (ConstI32)(uintptr_t)(v.slot_mask + (tab - v.block_table));
-    q.counter = counter;
-    q.n_pages = n_pages;
-    q.n_pairs = (n_pages + 1) >> 1;
-    order_chunk(q);
-    const int j0 = __builtin_amdgcn_readfirstlane(q.on_order);
-    if (j0 >= q.n_pairs) return;
-    order_chunk(q);
-    load_ids(q, j0);
-    q.vpid = 0;
-    q.vmask = 0;
-    spread_ids(q);
-    set_chunk(q, j0);
-    q.nj = __builtin_amdgcn_readfirstlane(q.on_order);
-    if (q.nj < q.n_pairs) load_ids(q, q.nj);
-    order_chunk(q);
-    PairIds ida, idb;
-    Pair ra, rb;
-    next_pair(q, ida);   // the first chunk has at least one page
-    issue_loads(ra, ida);
-    while (true) {
-      const bool more_b = next_pair(q, idb);
-      issue_loads(rb, idb);
-      if ((ida.live_a | ida.live_b) != 0) compute(ra, ida);
-      if (!more_b) break;
-      const bool more_a = next_pair(q, ida);
-      issue_loads(ra, ida);
-      if ((idb.live_a | idb.live_b) != 0) compute(rb, idb);
-      if (!more_a) break;
-    }
-  }
-
-  // Static share (sliding-window layers): page ids and live masks of up to 64 pages are fetched
-  // with one vector load each (lane L holds page p0 + base + L).  A page can hold a visible
-  // token only if the largest position ever written into it lies inside the window, so one
-  // word per page (page_pos_max) settles most pages; a lane reads the 16 positions of its page
-  // only when that test passes.  The pages of a run of 64 that still have a visible slot are
-  // paired up, and ids and masks reach the pair code through v_readlane.
-  __device__ __forceinline__ void run() {
-    const int n_pages = p1 - p0;
-    for (int base = 0; base < n_pages; base += 64) {
-      const int cnt = n_pages - base < 64 ? n_pages - base : 64;
-      int vpid = 0;
-      uint32_t vmask = 0;
-      if (lane < cnt) {
-        vpid = tab[p0 + base + lane];
-        vmask = v.slot_mask[(tab - v.block_table) + p0 + base + lane] & 0xFFFFu;
-      }
-      if (a.window > 0) {
-        uint32_t vis = 0;
-        if (vmask != 0 && v.page_pos_max[cls][vpid] > qpos - a.window) {
-          const int4* sp = (const int4*)(v.slot_pos[cls] + (int64_t)vpid * kPage);
-#pragma unroll
-          for (int t4 = 0; t4 < kPage / 4; ++t4) {
-            const int4 pos = sp[t4];
-            const int d0 = qpos - pos.x, d1 = qpos - pos.y, d2 = qpos - pos.z, d3 = qpos - pos.w;
-            vis |= ((d0 >= 0 && d0 < a.window) ? 1u : 0u) << (4 * t4);
-            vis |= ((d1 >= 0 && d1 < a.window) ? 2u : 0u) << (4 * t4);
-            vis |= ((d2 >= 0 && d2 < a.window) ? 4u : 0u) << (4 * t4);
-            vis |= ((d3 >= 0 && d3 < a.window) ? 8u : 0u) << (4 * t4);
-          }
-        }
-        vmask &= vis;
-      }
-      uint64_t todo = __ballot(vmask != 0);
-      while (todo) {
-        const int ia = __builtin_ctzll(todo);
-        todo &= todo - 1;
-        const bool two = todo != 0;
-        const int ib = two ? __builtin_ctzll(todo) : ia;
-        if (two) todo &= todo - 1;
-        PairIds id;
-        id.pid_a = __builtin_amdgcn_readlane(vpid, ia);
-        id.live_a = __builtin_amdgcn_readlane(vmask, ia);
-        id.pid_b = __builtin_amdgcn_readlane(vpid, ib);
-        id.live_b = two ? __builtin_amdgcn_readlane(vmask, ib) : 0u;
-        id.idx_a = p0 + base + ia;
-        id.idx_b = two ? p0 + base + ib : -1;
-        Pair r;
-        issue_loads(r, id);
-        compute(r, id);
-      }
-    }
-  }
 };
 
 // One wave per item; a workgroup is four items that share nothing but the launch (the hardware starts a
