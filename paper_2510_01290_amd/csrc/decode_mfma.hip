@@ -7,7 +7,7 @@ namespace thinkv {
 
 int decode_mfma_supported(const thinkv_config& c) {
   const int G = c.n_q_heads / c.n_kv_heads;
-  return c.format == THINKV_FMT_INT && (c.head_dim == 64 || c.head_dim == 128) && G >= 1 && G <= 8;   // the paper's formats: plain kernel
+  return (c.head_dim == 64 || c.head_dim == 128) && G >= 1 && G <= 8;
 }
 
 int launch_decode_mfma(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) { return launch_decode_mfma_t<false>(v, a, st); }

@@ -691,13 +691,20 @@ struct ClassRunner : PairWalk<ClassRunner<D, BITS, GP, STAT>, PairRegs<D, BITS, 
 
 };
 
+}  // namespace thinkv
+#include "decode_mfma_fp.h"
+namespace thinkv {
+
 // One wave per item; a workgroup is four items that share nothing but the launch (the hardware starts a
 // four-wave workgroup as fast as a one-wave one, and a launch of thousands of single waves takes ten
 // microseconds to get going).  WIN: sliding-window layer (static shares).
-template <int D, int GP, bool WIN, bool STAT>
+// FP: the cache is in the paper's number formats (decode_mfma_fp.h), else in the integer formats.
+template <int D, int GP, bool WIN, bool STAT, bool FP>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(decode_waves_per_simd(D), decode_waves_per_simd(D)))) void decode_mfma_kernel(thinkv_view v, DecodeArgs a) {
-  using CL = Cols<D, GP>;
-  constexpr int NG = D / 32, NM = D / 16, CS = CL::CS, NSET = CL::NSET;
+  static_assert(!(FP && STAT), "the sparsity statistic rides on the integer-format kernel only");
+  constexpr int NM = D / 16;
+  constexpr int CS = FP ? ColsFp<D, GP>::CS : Cols<D, GP>::CS, NSET = FP ? ColsFp<D, GP>::NSET : Cols<D, GP>::NSET;
+  constexpr int GB = FP ? 1 : 2;   // 16-channel blocks per quantisation group
   const thinkv_config& c = v.cfg;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int item = blockIdx.x * 4 + wave;
@@ -719,8 +726,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(decode_wave
   // ---- the query: lane (slice gl, head, row quad qd) reads, per column set, the eight values of
   // channels 32g + 8qd .. of its head (g = the set's group of its slice), rounds them to binary16
   // and adds them up; the four row quads complete the group's sum
-  QRegs<NSET> qr;
-  {
+  QRegs<FP ? 1 : NSET> qr;
+  QRegsFp<FP ? NSET : 1> qf;
+  if constexpr (FP) {
+    // the paper's formats: a slice carries a group of 16 channels; the lane holds the eight values of channels
+    // 32 G + 8 qd .. of its head where those lie in its slice's group (qd / 2 = parity of the group), zeros otherwise
+    const bool used = gl < CS && head < G;
+    const int glc = gl < CS ? gl : CS - 1;
+#pragma unroll
+    for (int s = 0; s < NSET; ++s) {
+      const int g16 = s * CS + glc;
+      const bool mine = used && (g16 & 1) == (qd >> 1);
+      const int64_t at = ((int64_t)b * Hq + hkv * G + (used ? head : 0)) * D + 32 * (g16 >> 1) + 8 * qd;
+      H8 t;
+      if (a.q_dtype == THINKV_F16) {
+        const uint4 raw = *(const uint4*)((const _Float16*)a.q + at);
+        t.u[0] = raw.x; t.u[1] = raw.y; t.u[2] = raw.z; t.u[3] = raw.w;
+      } else {
+        const uint4 raw = *(const uint4*)((const uint16_t*)a.q + at);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t u = (e & 1) ? (w[e >> 1] & 0xFFFF0000u) : (w[e >> 1] << 16);
+          t.h[e] = (_Float16)__builtin_bit_cast(float, u);
+        }
+      }
+#pragma unroll
+      for (int w4 = 0; w4 < 4; ++w4) qf.q[s].u[w4] = mine ? t.u[w4] : 0u;
+    }
+  } else {
     const bool used = gl < CS && head < G;
     const int glc = gl < CS ? gl : CS - 1;
 #pragma unroll
@@ -779,7 +813,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(decode_wave
         stat_room = (int)(a.stat_stride / kPage) - before;
       }
 #define TKV_RUN(B_)                                                                                     \
-  {                                                                                                     \
+  if constexpr (FP) {                                                                                   \
+    ClassRunnerFp<D, B_, GP> cr(st, v, a, k, tab, p0, p1, hkv, G, qf, qpos);                             \
+    if constexpr (WIN) cr.run();                                                                        \
+    else cr.run_dynamic(npk, counter);                                                                  \
+    cr.leave();                                                                                         \
+  } else {                                                                                              \
     ClassRunner<D, B_, GP, STAT> cr(st, v, a, k, tab, p0, p1, hkv, G, qr, qpos, stat, stat_room);        \
     if constexpr (WIN) cr.run();                                                                        \
     else cr.run_dynamic(npk, counter);                                                                  \
@@ -799,9 +838,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(decode_wave
   float zsum[NSET];
 #pragma unroll
   for (int set = 0; set < NSET; ++set) {
-    float z = st.oz[set];
-    z += __shfl_xor(z, 16, 64);
-    z += __shfl_xor(z, 32, 64);
+    float z = FP ? 0.f : st.oz[set];   // the paper's formats have no zero-points
+    if constexpr (!FP) {
+      z += __shfl_xor(z, 16, 64);
+      z += __shfl_xor(z, 32, 64);
+    }
     zsum[set] = z;
   }
   if (head < G) {
@@ -809,7 +850,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(decode_wave
       const int64_t o_at = ((int64_t)b * Hq + hkv * G + head) * D;
 #pragma unroll
       for (int mb = 0; mb < NM; ++mb) {
-        const int g = mb >> 1, set = g / CS;
+        const int g = mb / GB, set = g / CS;
         if (gl == g % CS) {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
@@ -821,7 +862,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(decode_wave
       float* dst = partial_row(a, G, D, it.row0 + it.j, head);
 #pragma unroll
       for (int mb = 0; mb < NM; ++mb) {
-        const int g = mb >> 1, set = g / CS;
+        const int g = mb / GB, set = g / CS;
         if (gl == g % CS) {
           float4 o4;
           o4.x = st.o[mb][0] * 16777216.f + zsum[set];
@@ -845,12 +886,21 @@ template <int D, bool WIN, bool STAT>
 static int launch_dw(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) {
   const int G = v.cfg.n_q_heads / v.cfg.n_kv_heads;
   dim3 grid((a.n_rows + 3) / 4), blk(256);
-  if (G <= 4)
-    hipLaunchKernelGGL((decode_mfma_kernel<D, 4, WIN, STAT>), grid, blk, 0, st, v, a);
-  else if (G <= 8)
-    hipLaunchKernelGGL((decode_mfma_kernel<D, 8, WIN, STAT>), grid, blk, 0, st, v, a);
-  else
-    return THINKV_E_SHAPE;
+  if (G > 8) return THINKV_E_SHAPE;
+  if (v.cfg.format == THINKV_FMT_FP) {
+    if constexpr (STAT) {
+      return THINKV_E_UNSUPPORTED;
+    } else {
+      if (G <= 4)
+        hipLaunchKernelGGL((decode_mfma_kernel<D, 4, WIN, false, true>), grid, blk, 0, st, v, a);
+      else
+        hipLaunchKernelGGL((decode_mfma_kernel<D, 8, WIN, false, true>), grid, blk, 0, st, v, a);
+    }
+  } else if (G <= 4) {
+    hipLaunchKernelGGL((decode_mfma_kernel<D, 4, WIN, STAT, false>), grid, blk, 0, st, v, a);
+  } else {
+    hipLaunchKernelGGL((decode_mfma_kernel<D, 8, WIN, STAT, false>), grid, blk, 0, st, v, a);
+  }
   return hipGetLastError() == hipSuccess ? THINKV_OK : THINKV_E_HIP;
 }
 

@@ -36,6 +36,13 @@ def test_config2_headline_32k_as_benchmarked():
     _run(synth.config_llama8b_32k(seed=1, n_seqs=16, refill_chunk=64), [(s, 0) for s in (0, 1, 4, 6, 9, 10, 13, 14)])
 
 
+def test_config2_headline_32k_in_the_papers_formats():
+    """the bench workload with the cache in the paper's own formats (FP8-E4M3 / NVFP4 / ternary, the paper's map R8 / E4 / T2)"""
+    wl = synth.config_llama8b_32k(seed=1, n_seqs=16, refill_chunk=64)
+    wl.geom.bits_of_class, wl.geom.fmt, wl.geom.fp8_scale = (2, 4, 8), "fp", (0.05, 0.05)
+    _run(wl, [(s, 0) for s in (0, 2, 5, 7, 8, 11, 12, 15)])
+
+
 def test_config3_qwen14b_budgeted_decode():
     """config 3 at full size: 32 trajectories of 32,768 decode appends under a 2,048-token budget (G = 5)"""
     res = _run(synth.config_qwen14b_budget(), [(s, 0) for s in (0, 5, 9, 14, 18, 23, 27, 30)])

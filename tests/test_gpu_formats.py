@@ -1,6 +1,7 @@
 """The paper's number formats on the device (THINKV_FMT_FP: E4M3 with a per-tensor scale, E2M1 and ternary codes
 with an E4M3 scale per 16 channels) against the oracle (oracle/formats.py through the oracle cache): codes, scale
-bytes and every table bit for bit, attention within the tolerance of the other GPU tests (needs an MI355X)."""
+bytes and every table bit for bit, attention -- the matrix-core kernel and the plain one -- within the tolerance of
+the other GPU tests (needs an MI355X)."""
 import numpy as np
 import pytest
 import torch
@@ -24,7 +25,7 @@ def test_config1_tiny_in_the_papers_formats(bits, scale):
     _say(parity.run_case(case, out_dtypes=(torch.float32, torch.float16)))
 
 
-@pytest.mark.parametrize("D,dtype,G", [(128, "bf16", 4), (64, "f16", 8)])
+@pytest.mark.parametrize("D,dtype,G", [(128, "bf16", 4), (64, "f16", 8), (128, "f16", 5), (64, "bf16", 4), (128, "bf16", 1)])
 def test_ragged_multi_sequence_with_a_window_layer_in_the_papers_formats(D, dtype, G):
     _say(f"ragged multi-seq in the paper's formats, D={D} {dtype} G={G}, layer 1 with a window of 128")
     geom = synth.Geometry(2, 2 * G, 2, D, dtype, (2, 4, 8), "fp", (0.04, 0.06))
