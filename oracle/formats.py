@@ -8,8 +8,7 @@ zero and reads as 0) with one E4M3 scale per group of 16.
 
 This module is the definition of those formats written out (decode tables from the bit
 fields, encoders that round to the nearest representable value, ties to the even code, and
-saturate), plus the group quantisers built on them.  Nothing here is on the HIP path yet:
-it is the pinned starting point of the row that adds these formats to the cache.
+saturate), plus the group quantisers built on them.
 
 Readings where the paper is silent:
   * E4M3 is the finite-only variant used for FP8 inference (bias 7, largest value 448, the
