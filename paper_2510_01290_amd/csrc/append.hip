@@ -694,14 +694,15 @@ __global__ __launch_bounds__(256) void append_place_bulk_kernel(thinkv_view v, i
   const bool ok = s_ok[t] != 0;
   const int slot = s_slot[t];
   const int bits = c.bits_of_class[s_cls[t]];
-  const BlockGeom gm = block_geom(bits, D);
+  const bool fp = c.format == THINKV_FMT_FP;
+  const BlockGeom gm = block_geom(bits, D, c.format);
   uint8_t* const page = v.arena[s_cls[t]] + (int64_t)s_pid[t] * H * gm.block_bytes;
   const float qmax = (float)((1 << bits) - 1);
   // ... and its (token, chunk) as a thread that packs V codes
   const int tv = tid >> 4, m = tid & 15;
   const bool v_ok = s_ok[tv] != 0;
   const int bv = c.bits_of_class[s_cls[tv]], slv = s_slot[tv];
-  const BlockGeom gv = block_geom(bv, D);
+  const BlockGeom gv = block_geom(bv, D, c.format);
   uint8_t* const v_chunk = v.arena[s_cls[tv]] + (int64_t)s_pid[tv] * H * gv.block_bytes + gv.v_codes +
                            (16 * (slv >> 2) + m) * gv.chunk_bytes + 2 * (slv & 1);
   const int v_u = (slv >> 1) & 1;
@@ -725,6 +726,26 @@ __global__ __launch_bounds__(256) void append_place_bulk_kernel(thinkv_view v, i
           x[e] = in_dtype == THINKV_F16 ? (float)__builtin_bit_cast(_Float16, u) : __builtin_bit_cast(float, (uint32_t)u << 16);
         }
       }
+      uint32_t code[8];
+      if (fp) {
+        // the paper's formats: the eight channels of a thread lie in one group of 16 (number 2 grp + j / 2), which two
+        // neighbour threads share; ratios to the scale in binary64, as the formats are defined
+        double sd = (double)c.fp8_scale[kind];
+        if (bits != 8) {
+          float amax = fabsf(x[0]);
+#pragma unroll
+          for (int e = 1; e < 8; ++e) amax = fmaxf(amax, fabsf(x[e]));
+          amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
+          const uint32_t sc8 = e4m3_code_up((double)amax / (bits == 4 ? 6.0 : 1.0));
+          sd = (double)e4m3_value(sc8);
+          if ((j & 1) == 0) (blk + (kind ? gm.v_meta : gm.k_meta))[(2 * grp + (j >> 1)) * kPage + slot] = (uint8_t)sc8;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const double r = sd > 0.0 ? (double)x[e] / sd : 0.0;
+          code[e] = bits == 8 ? e4m3_encode(r) : (bits == 4 ? e2m1_encode(r) : ternary_encode(r));
+        }
+      } else {
       float mn = x[0], mx = x[0];
 #pragma unroll
       for (int e = 1; e < 8; ++e) {
@@ -744,7 +765,6 @@ __global__ __launch_bounds__(256) void append_place_bulk_kernel(thinkv_view v, i
         sc = __builtin_bit_cast(_Float16, (uint16_t)(u + 1));
       }
       const float sf = (float)sc, zf = (float)zp;
-      uint32_t code[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         float q = 0.0f;
@@ -758,6 +778,7 @@ __global__ __launch_bounds__(256) void append_place_bulk_kernel(thinkv_view v, i
         uint16_t* meta = (uint16_t*)(blk + (kind ? gm.v_meta : gm.k_meta));
         meta[meta_index(slot, grp)] = __builtin_bit_cast(uint16_t, sc);
         meta[meta_index(slot, grp) + 4] = __builtin_bit_cast(uint16_t, zp);
+      }
       }
       if (!kind) {
         // K: channel 32 grp + 8 j + e is field 4 grp + e / 2, half e % 2, of chunk 16 j + slot
@@ -852,7 +873,7 @@ int launch_append(const thinkv_view& v, int layer, const void* k_new, const void
   hipLaunchKernelGGL(append_plan_kernel, dim3(S), dim3(256), 0, st, v, layer, tok_seq, tok_class, n_tok, ws, ev_seq, ev_handle, n_ev);
   const int commit_here = n_tok <= kBulkFrom;   // else thousands of blocks would bump one sequence's counter
   const bool aligned = (((uintptr_t)k_new | (uintptr_t)v_new) & 15) == 0;
-  if (!commit_here && aligned && v.cfg.format == THINKV_FMT_INT) {   // the paper's formats go through the per-token kernel
+  if (!commit_here && aligned) {
     hipLaunchKernelGGL(append_grant_kernel, dim3(1), dim3(256), 0, st, v, ws);
     // enough blocks to fill the chip: a mid-sized call spreads the kv-heads of its token groups over blocks
     const int H = v.cfg.n_kv_heads, groups = (n_tok + kBulkTokens - 1) / kBulkTokens;

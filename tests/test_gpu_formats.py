@@ -34,8 +34,9 @@ def test_ragged_multi_sequence_with_a_window_layer_in_the_papers_formats(D, dtyp
     _say(parity.run_case(parity.Case(wl), out_dtypes=(torch.float32, torch.bfloat16)))
 
 
+@pytest.mark.parametrize("bulk", [True, False], ids=["bulk-kernel", "per-token-kernel"])
 @pytest.mark.parametrize("bits", [2, 4, 8])
-def test_encoders_on_every_binary16_value(bits):
+def test_encoders_on_every_binary16_value(bits, bulk):
     """all finite binary16 values as group members (groups of 16: two fixed members set the scale, fourteen vary) and as
     FP8 inputs: codes and scale bytes from the device equal the oracle's, byte for byte.  Scale-setting members are chosen so
     that ties, saturation (values up to 65504 against a scale of 448 at most) and the subnormal codes all occur."""
@@ -62,7 +63,12 @@ def test_encoders_on_every_binary16_value(bits):
     gc = parity.make_gpu_cache(wl)
     ob = parity.make_oracle(wl)
     ts, tp, tc = np.zeros(n_tok, np.int32), np.arange(n_tok, dtype=np.int32), np.ones(n_tok, np.uint8)
-    hg = parity.GpuBackend(gc).append(0, k.cuda(), v.cuda(), ts, tp, tc)
+    kd, vd = k.cuda(), v.cuda()
+    if not bulk:      # rows that are not 16-byte aligned take the per-token kernel
+        kd = torch.cat([kd.flatten()[:1], kd.flatten()])[1:].view(k.shape)
+        vd = torch.cat([vd.flatten()[:1], vd.flatten()])[1:].view(v.shape)
+        assert kd.data_ptr() % 16 and kd.is_contiguous()
+    hg = parity.GpuBackend(gc).append(0, kd, vd, ts, tp, tc)
     ho = ob.append(0, k, v, ts, tp, tc)
     assert np.array_equal(hg, ho)
     parity.compare_bookkeeping_full(ob.cache, gc)
