@@ -85,8 +85,7 @@ typedef struct {
  *                   nearest, ties to the even code, and saturate; a group's scale is amax / qmax
  *                   (qmax 6 / 1) rounded up to the next E4M3 value.  Code regions of a block are laid out
  *                   as for THINKV_FMT_INT; a meta region is head_dim/16 * 16 scale bytes, byte
- *                   group16 * 16 + slot (none for the 8-bit type).  Every call works in this format except
- *                   thinkv_decode_attention_sparsity, which answers THINKV_E_UNSUPPORTED.
+ *                   group16 * 16 + slot (none for the 8-bit type).  Every call works in either format.
  */
 #define THINKV_FMT_INT 0
 #define THINKV_FMT_FP 1

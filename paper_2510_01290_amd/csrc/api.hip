@@ -139,7 +139,7 @@ static int decode_common(const thinkv_view* view, int32_t layer, const void* q, 
   if (q_dtype != THINKV_F16 && q_dtype != THINKV_BF16) return THINKV_E_UNSUPPORTED;
   if (out_dtype != THINKV_F16 && out_dtype != THINKV_BF16 && out_dtype != THINKV_F32) return THINKV_E_UNSUPPORTED;
   fast = fast && decode_mfma_supported(view->cfg);
-  if (sparsity && (!fast || view->cfg.format != THINKV_FMT_INT)) return THINKV_E_UNSUPPORTED;   // the statistic rides on the integer-format kernel
+  if (sparsity && !fast) return THINKV_E_UNSUPPORTED;
   const size_t partial_bytes = thinkv_decode_workspace_bytes(&view->cfg, B, max_ctx_pages);
   if (workspace_bytes < (sparsity ? thinkv_decode_sparsity_workspace_bytes(&view->cfg, B, max_ctx_pages) : partial_bytes)) return THINKV_E_WORKSPACE;
   DecodeArgs a;

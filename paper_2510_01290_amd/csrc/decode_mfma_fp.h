@@ -69,14 +69,16 @@ __device__ __forceinline__ void scales_to_halves(uint32_t bytes, uint32_t& lo, u
   hi = __builtin_amdgcn_perm(0u, bytes, 0x0C030C02u) << 7;
 }
 
-template <int D, int BITS, int GP>
-struct ClassRunnerFp : PairWalk<ClassRunnerFp<D, BITS, GP>, PairRegsFp<D, BITS, ColsFp<D, GP>::NSET>> {
+// STAT: besides attending, leave the group-pooled score of every visited slot for the attention-sparsity statistic
+// (as the integer-format runner does).
+template <int D, int BITS, int GP, bool STAT>
+struct ClassRunnerFp : PairWalk<ClassRunnerFp<D, BITS, GP, STAT>, PairRegsFp<D, BITS, ColsFp<D, GP>::NSET>> {
   using CL = ColsFp<D, GP>;
   static constexpr int NG32 = D / 32, NM = D / 16, CS = CL::CS, NSET = CL::NSET;
   static constexpr int kLift = 14;   // 2^14 * 448 * 2^-8 < 65504: the lifted second operand of the value products cannot overflow
   using F = FldFp<BITS>;
   using Pair = PairRegsFp<D, BITS, NSET>;
-  using Walk = PairWalk<ClassRunnerFp<D, BITS, GP>, Pair>;
+  using Walk = PairWalk<ClassRunnerFp<D, BITS, GP, STAT>, Pair>;
   using Walk::v;
   using Walk::a;
   using Walk::cls;
@@ -89,13 +91,17 @@ struct ClassRunnerFp : PairWalk<ClassRunnerFp<D, BITS, GP>, PairRegsFp<D, BITS, 
   float kappa;          // MFMA score units -> log2 domain
   float tile_out;       // tiles -> absolute units / 2^24 when the type is left
   float neg1;
+  float* stat;          // STAT: pooled scores of this type's page list, 16 per page
+  int stat_room;        // STAT: pages of this list the buffer has room for
+  bool head_ok;         // this lane's column belongs to a query head of the group
 
   __device__ __forceinline__ ClassRunnerFp(WaveState<D, NSET>& st_, const thinkv_view& v_, const DecodeArgs& a_, int cls_, const int32_t* tab_,
-                                           int p0_, int p1_, int hkv_, int G, const QRegsFp<NSET>& qr, int qpos_)
-      : Walk(v_, a_, cls_, hkv_, qpos_, tab_, p0_, p1_), st(st_) {
+                                           int p0_, int p1_, int hkv_, int G, const QRegsFp<NSET>& qr, int qpos_, float* stat_, int stat_room_)
+      : Walk(v_, a_, cls_, hkv_, qpos_, tab_, p0_, p1_), st(st_), stat(stat_), stat_room(stat_room_) {
     qd = lane >> 4;
     n = lane & 15;
     const int gl = n / GP;
+    head_ok = n % GP < G;
     const int glc = gl < CS ? gl : CS - 1;
     neg1 = -1.0f;
     asm volatile("" : "+v"(neg1));
@@ -211,6 +217,22 @@ struct ClassRunnerFp : PairWalk<ClassRunnerFp<D, BITS, GP>, PairRegsFp<D, BITS, 
         sa[r4] = ((la >> r4) & 1u) ? sa[r4] : -INFINITY;
         sb[r4] = ((lb >> r4) & 1u) ? sb[r4] : -INFINITY;
       }
+    }
+    if constexpr (STAT) {
+      // pooled scores: maximum over the heads of the group, i.e. over the GP lanes of a slice (all slices hold the
+      // same totals); the lanes of column 0 store their four slots of each page
+      auto pooled = [&](const float* sc, int idx) {
+        float u[4];
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          u[r4] = head_ok ? sc[r4] * kappa : -INFINITY;
+          u[r4] = max_dpp<0x4E>(max_dpp<0xB1>(u[r4]));
+          if constexpr (GP == 8) u[r4] = max_dpp<0x124>(u[r4]);
+        }
+        if (n == 0 && idx >= 0 && idx < stat_room) *(float4*)(stat + (int64_t)idx * kPage + 4 * qd) = make_float4(u[0], u[1], u[2], u[3]);
+      };
+      pooled(sa, id.idx_a);
+      pooled(sb, id.idx_b);
     }
     const float mx = fmaxf(fmaxf(fmaxf(sa[0], sa[1]), fmaxf(sa[2], sa[3])), fmaxf(fmaxf(sb[0], sb[1]), fmaxf(sb[2], sb[3]))) * kappa;
     if (__any(mx > st.m)) {

@@ -701,7 +701,6 @@ namespace thinkv {
 // FP: the cache is in the paper's number formats (decode_mfma_fp.h), else in the integer formats.
 template <int D, int GP, bool WIN, bool STAT, bool FP>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(decode_waves_per_simd(D), decode_waves_per_simd(D)))) void decode_mfma_kernel(thinkv_view v, DecodeArgs a) {
-  static_assert(!(FP && STAT), "the sparsity statistic rides on the integer-format kernel only");
   constexpr int NM = D / 16;
   constexpr int CS = FP ? ColsFp<D, GP>::CS : Cols<D, GP>::CS, NSET = FP ? ColsFp<D, GP>::NSET : Cols<D, GP>::NSET;
   constexpr int GB = FP ? 1 : 2;   // 16-channel blocks per quantisation group
@@ -814,7 +813,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(decode_wave
       }
 #define TKV_RUN(B_)                                                                                     \
   if constexpr (FP) {                                                                                   \
-    ClassRunnerFp<D, B_, GP> cr(st, v, a, k, tab, p0, p1, hkv, G, qf, qpos);                             \
+    ClassRunnerFp<D, B_, GP, STAT> cr(st, v, a, k, tab, p0, p1, hkv, G, qf, qpos, stat, stat_room);      \
     if constexpr (WIN) cr.run();                                                                        \
     else cr.run_dynamic(npk, counter);                                                                  \
     cr.leave();                                                                                         \
@@ -888,14 +887,10 @@ static int launch_dw(const thinkv_view& v, const DecodeArgs& a, hipStream_t st) 
   dim3 grid((a.n_rows + 3) / 4), blk(256);
   if (G > 8) return THINKV_E_SHAPE;
   if (v.cfg.format == THINKV_FMT_FP) {
-    if constexpr (STAT) {
-      return THINKV_E_UNSUPPORTED;
-    } else {
-      if (G <= 4)
-        hipLaunchKernelGGL((decode_mfma_kernel<D, 4, WIN, false, true>), grid, blk, 0, st, v, a);
-      else
-        hipLaunchKernelGGL((decode_mfma_kernel<D, 8, WIN, false, true>), grid, blk, 0, st, v, a);
-    }
+    if (G <= 4)
+      hipLaunchKernelGGL((decode_mfma_kernel<D, 4, WIN, STAT, true>), grid, blk, 0, st, v, a);
+    else
+      hipLaunchKernelGGL((decode_mfma_kernel<D, 8, WIN, STAT, true>), grid, blk, 0, st, v, a);
   } else if (G <= 4) {
     hipLaunchKernelGGL((decode_mfma_kernel<D, 4, WIN, STAT, false>), grid, blk, 0, st, v, a);
   } else {

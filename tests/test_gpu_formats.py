@@ -75,9 +75,8 @@ def test_encoders_on_every_binary16_value(bits, bulk):
     parity.compare_sequences(ob.cache, gc, [(0, 0, 0)], check_bytes=True)
 
 
-def test_kmeans_survivors_and_unsupported_calls_in_the_papers_formats():
-    """thought-adaptive eviction clusters the stored keys, whatever their format; the sparsity statistic needs the
-    matrix-core kernel, which this format does not have yet: the call says so"""
+def test_kmeans_survivors_in_the_papers_formats():
+    """thought-adaptive eviction clusters the stored keys, whatever their format"""
     from paper_2510_01290_amd import binding as B
     from oracle import tbe as otbe
     geom = synth.Geometry(1, 8, 2, 64, "f16", (2, 4, 8), "fp", (0.05, 0.05))
@@ -107,8 +106,3 @@ def test_kmeans_survivors_and_unsupported_calls_in_the_papers_formats():
             n_clear += 1
             assert np.array_equal(got[a:b], want[a:b]), (sg, margins[sg])
     assert n_clear >= 1
-    q = torch.zeros((1, 8, 64), dtype=torch.float16, device=d)
-    out = torch.empty((1, 8, 64), dtype=torch.float32, device=d)
-    with pytest.raises(RuntimeError, match="unsupported"):
-        B.thinkv_decode_attention_sparsity(gc, 0, q, out, None, torch.zeros(1, dtype=torch.float32, device=d),
-                                           torch.zeros(1, dtype=torch.int32, device=d), None, 0, 0.125, 64)

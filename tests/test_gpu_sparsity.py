@@ -112,6 +112,15 @@ def test_sparsity_ragged_multi_sequence(D, dtype, G):
     _say(_run(wl))
 
 
+@pytest.mark.parametrize("D,G", [(128, 4), (64, 8)])
+def test_sparsity_in_the_papers_formats(D, G):
+    _say(f"sparsity statistic over a cache in FP8 / NVFP4 / ternary, D={D} G={G}, layer 1 with a window")
+    geom = synth.Geometry(2, 2 * G, 2, D, "bf16", (2, 4, 8), "fp", (0.05, 0.05))
+    wl = synth.bulk_evict_refill("ragged-fp", geom, 7, 3, np.array([500, 33, 1200]), {synth.E: 0.3, synth.R: 0.1}, refill_chunk=4,
+                                 window_of_layer=[0, 128])
+    _say(_run(wl))
+
+
 def test_sparsity_window_and_empty():
     _say("sparsity statistic on a sliding-window layer, and with nothing visible")
     geom = synth.Geometry(2, 16, 2, 64, "bf16", (8, 2, 4))
