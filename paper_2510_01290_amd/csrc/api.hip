@@ -95,8 +95,12 @@ static ItemSizing size_items(const thinkv_config& c, int B, int max_ctx_pages, i
   if (cap < 1) cap = 1;
   if (cap > kMaxRowsPerHead) cap = kMaxRowsPerHead;
   int64_t per_head;
-  if (heads * 2 <= resident || window > 0)
+  if (window > 0)
     per_head = resident / heads;
+  else if (heads * 2 <= resident)
+    // all items resident at once; twice as many for larger batches, which are rarely of one length: an item per so many
+    // pages then gives the longer contexts more workers than the shorter ones, and late items find what is left
+    per_head = (B > 32 ? 2 : 1) * resident / heads;
   else
     per_head = ((fast ? 16 : 4) * resident + heads - 1) / heads;
   if (per_head > cap) per_head = cap;
