@@ -466,3 +466,46 @@ def test_whole_decode_step_replays_correctly_from_a_captured_graph():
             assert torch.equal(eager.arena[c], graphed.arena[c]), ("arena", c, i)
             assert torch.equal(eager.slot_pos[c], graphed.slot_pos[c]), ("slot_pos", c, i)
     assert int(eager.dev_status.abs().sum().item()) == 0
+
+
+def test_context_bound_below_the_true_page_count_still_attends_everything():
+    """max_ctx_pages is the host's bound for sizing the launch; a sequence that holds more pages than the bound gets fewer
+    items than it would like, but every page is still attended (both kernels, full-attention and window layers)"""
+    _say("decode attention with a context bound that is too small")
+    from paper_2510_01290_amd import binding as B
+    geom = synth.Geometry(2, 8, 2, 64, "f16", (8, 2, 4))
+    wl = synth.bulk_evict_refill("short-bound", geom, 13, 3, np.array([2500, 40, 900]), {synth.E: 0.2}, refill_chunk=9, window_of_layer=[0, 128])
+    gc = parity.make_gpu_cache(wl)
+    synth.ScriptRunner(wl, parity.GpuBackend(gc)).run()
+    ob = parity.make_oracle(wl)
+    synth.ScriptRunner(wl, ob).run()
+    for layer in (0, 1):
+        ref, ref_lse = parity.oracle_attention(ob.cache, wl, layer, [0, 1, 2], [0, 1, 2])
+        true_pages = int(gc.n_pages[:, layer].sum(-1).max().item())
+        for bound in (true_pages // 3, 5, 1, 0):
+            for variant in ("fast", "valu"):
+                out, lse = parity.gpu_attention(gc, wl, None, layer, torch.float32, variant, max_ctx_pages=bound)
+                assert np.abs(out - ref).max() <= parity.TOL, (layer, bound, variant, float(np.abs(out - ref).max()))
+                assert np.abs(lse - ref_lse).max() <= 1e-3
+
+
+def test_measurement_aids_run_and_refuse_bad_arguments():
+    """thinkv_probe_stream_pages only reads; it must run on any cache (empty sequences, unknown ids) and leave the cache as it was"""
+    import ctypes as C
+    from paper_2510_01290_amd import binding as B
+    geom = synth.Geometry(2, 8, 2, 128, "bf16", (8, 2, 4))
+    wl = synth.bulk_evict_refill("probe", geom, 3, 3, np.array([700, 0, 33]), {synth.E: 0.5}, refill_chunk=5)
+    wl.classes[1] = np.zeros(0, np.uint8)
+    gc = parity.make_gpu_cache(wl)
+    synth.ScriptRunner(wl, parity.GpuBackend(gc)).run()
+    before = [a.clone() for a in gc.arena] + [gc.block_table.clone(), gc.slot_mask.clone(), gc.work_counters.clone()]
+    chk = torch.zeros(1, dtype=torch.int32, device=gc.device)
+    for layer in (0, 1):
+        B.thinkv_probe_stream_pages(gc, layer, torch.tensor([0, 1, 2, 7, -1], dtype=torch.int32, device=gc.device)[:3], chk)
+    torch.cuda.synchronize()
+    after = [a for a in gc.arena] + [gc.block_table, gc.slot_mask, gc.work_counters]
+    assert all(torch.equal(x, y) for x, y in zip(before, after))
+    lib = B.load()
+    assert lib.thinkv_probe_stream_pages(C.byref(gc.view), 5, C.c_void_p(chk.data_ptr()), 1, C.c_void_p(chk.data_ptr()), None) == 1
+    assert lib.thinkv_probe_stream_pages(C.byref(gc.view), 0, None, 1, C.c_void_p(chk.data_ptr()), None) == 1
+    assert lib.thinkv_probe_stream_pages(C.byref(gc.view), 0, None, 0, None, None) == 0
