@@ -155,7 +155,9 @@ size_t thinkv_page_bytes(const thinkv_config* cfg, int bits);  /* n_kv_heads blo
 /* Bytes of scratch thinkv_append_quantized needs for a call with n_tok tokens. */
 size_t thinkv_append_workspace_bytes(const thinkv_config* cfg, int32_t n_tok);
 /* Bytes of scratch thinkv_decode_attention needs for B queries when no sequence holds more
- * than max_ctx_pages pages (summed over the three types) in the layer attended. */
+ * than max_ctx_pages pages (summed over the three types) in the layer attended.  The launch is
+ * sized for the machine, so the answer depends on the compute-unit count of the CURRENT device
+ * (256 is assumed where there is none): ask with the device current on which the call will run. */
 size_t thinkv_decode_workspace_bytes(const thinkv_config* cfg, int32_t B, int32_t max_ctx_pages);
 
 /* Puts a view into the empty state: free stacks filled so that pages come out 0,1,2,...,
@@ -227,7 +229,8 @@ int thinkv_evict_append(const thinkv_view* view, int32_t layer, const int32_t* e
  *   lse      DEVICE [B][n_q_heads] float, may be NULL: log-sum-exp of the scaled scores
  *   seq_ids  DEVICE [B] which sequence each query belongs to; B <= max_seqs
  *   q_pos    DEVICE [B] logical position of the query (used only when window > 0)
- *   max_ctx_pages  host upper bound on pages (all types) any attended sequence holds
+ *   max_ctx_pages  host upper bound on pages (all types) any attended sequence holds; it sizes the launch and the
+ *                  workspace.  A sequence that holds more is still attended in full, by fewer workers than it would get.
  *
  * A query with no visible token gets out = 0 and lse = -inf.  Accumulation is binary32.
  */
