@@ -669,17 +669,25 @@ def cpu_baseline(wl, args, nsteps, ev_handles, new_cls, np, torch, synth):
     t0 = time.perf_counter()
     done = 0
     live = 0
+    t_ev = t_ap = t_at = 0.0
     while done < nsteps and (done < 1 or time.perf_counter() - t0 < args.cpu_seconds):
         i = done
+        ta = time.perf_counter()
         oc.evict_slots(0, [0], [ev_handles[i, 0]])
+        tb = time.perf_counter()
         oc.append(0, k[i:i + 1], v[i:i + 1], [0], [n0 + i], [new_cls[i, 0]])
+        tc = time.perf_counter()
         q = synth.query_rows(wl.seed, 0, 0, i, g, cpu).float().numpy().astype(np.float64)[None]
         oattn.decode_attention(oc, 0, q, [0], [n0 + i], 0, g.head_dim ** -0.5)
+        td = time.perf_counter()
+        t_ev, t_ap, t_at = t_ev + tb - ta, t_ap + tc - tb, t_at + td - tc
         live = oc.stored_bytes_live(0, 0)
         done += 1
     dt = time.perf_counter() - t0
     return {"value": live * done / dt / 1e9, "unit": "GB/s", "cores": cores, "blas_threads": blas_threads, "kind": "oracle",
             "seconds_per_sequence_step": dt / done,
+            "us_per_sequence_evict_1": t_ev / done * 1e6, "us_per_sequence_append_1": t_ap / done * 1e6,
+            "us_per_sequence_attention": t_at / done * 1e6,
             "sample": f"{done} whole steps (evict 1, append 1, binary64 attention) of sequence 0 of the same workload "
                       f"({int(oc.n_live[0, 0])} live tokens); a batch step costs {args.batch}x this"}
 
