@@ -75,6 +75,7 @@ template <int D, int BITS, int GP, bool STAT>
 struct ClassRunnerFp : PairWalk<ClassRunnerFp<D, BITS, GP, STAT>, PairRegsFp<D, BITS, ColsFp<D, GP>::NSET>> {
   using CL = ColsFp<D, GP>;
   static constexpr int NG32 = D / 32, NM = D / 16, CS = CL::CS, NSET = CL::NSET;
+  static constexpr bool kHalfPipe = false;
   static constexpr int kLift = 14;   // 2^14 * 448 * 2^-8 < 65504: the lifted second operand of the value products cannot overflow
   using F = FldFp<BITS>;
   using Pair = PairRegsFp<D, BITS, NSET>;

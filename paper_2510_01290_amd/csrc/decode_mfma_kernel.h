@@ -41,6 +41,9 @@
 #pragma once
 #include "decode_common.h"
 
+#ifndef TKV_HALF
+#define TKV_HALF 0
+#endif
 #ifndef TKV_CHUNK
 #define TKV_CHUNK 4
 #endif
@@ -148,33 +151,29 @@ template <bool NT> __device__ __forceinline__ uint2 ld8(const void* p) {
   else return *(const uint2*)p;
 }
 
-template <int D, int BITS, int NSET>
-__device__ __forceinline__ void load_page(PageRegs<D, BITS, NSET>& r, const uint8_t* blk, int lane, const int* meta_off) {
+// the K half (codes, scales, zero-points) or the V half of one page's block into the lane's registers
+template <int D, int BITS, int NSET, bool VHALF>
+__device__ __forceinline__ void load_half(PageRegs<D, BITS, NSET>& r, const uint8_t* blk, int lane, const int* meta_off) {
   constexpr int CW = PageRegs<D, BITS, NSET>::CW;
   constexpr bool NT = ((TKV_NT >> (BITS == 2 ? 0 : (BITS == 4 ? 1 : 2))) & 1) != 0;
   const BlockGeom g = block_geom(BITS, D);
-  const uint32_t* kc = (const uint32_t*)(blk + g.k_codes) + lane * CW;
-  const uint32_t* vc = (const uint32_t*)(blk + g.v_codes) + lane * CW;
+  const uint32_t* src = (const uint32_t*)(blk + (VHALF ? g.v_codes : g.k_codes)) + lane * CW;
+  uint32_t* w = VHALF ? r.vw : r.kw;
   if constexpr (CW == 1) {
-    r.kw[0] = kc[0];
-    r.vw[0] = vc[0];
+    w[0] = src[0];
   } else if constexpr (CW == 2) {
-    const uint2 a = ld8<NT>(kc), b = ld8<NT>(vc);
-    r.kw[0] = a.x; r.kw[1] = a.y;
-    r.vw[0] = b.x; r.vw[1] = b.y;
+    const uint2 a = ld8<NT>(src);
+    w[0] = a.x; w[1] = a.y;
   } else {
 #pragma unroll
     for (int i = 0; i < CW; i += 4) {
-      const uint4 a = ld16<NT>(kc + i), b = ld16<NT>(vc + i);
-      r.kw[i] = a.x; r.kw[i + 1] = a.y; r.kw[i + 2] = a.z; r.kw[i + 3] = a.w;
-      r.vw[i] = b.x; r.vw[i + 1] = b.y; r.vw[i + 2] = b.z; r.vw[i + 3] = b.w;
+      const uint4 a = ld16<NT>(src + i);
+      w[i] = a.x; w[i + 1] = a.y; w[i + 2] = a.z; w[i + 3] = a.w;
     }
   }
+  uint4* m = VHALF ? r.vm : r.km;
 #pragma unroll
-  for (int s = 0; s < NSET; ++s) {
-    r.km[s] = ld16<NT>(blk + g.k_meta + meta_off[s]);
-    r.vm[s] = ld16<NT>(blk + g.v_meta + meta_off[s]);
-  }
+  for (int s = 0; s < NSET; ++s) m[s] = ld16<NT>(blk + (VHALF ? g.v_meta : g.k_meta) + meta_off[s]);
 }
 
 template <int D, int NSET>
@@ -334,6 +333,38 @@ struct PairWalk {
     q.nj = __builtin_amdgcn_readfirstlane(q.on_order);
     if (q.nj < q.n_pairs) load_ids(q, q.nj);
     order_chunk(q);
+    if constexpr (Derived::kHalfPipe) {
+      // Two register sets, A and B, each a K half and a V half.  A half is asked for again as soon as it has been
+      // worked on: the K half of pair i + 2 goes out right after the scores of pair i, its V half right after the
+      // values of pair i, so one and a half to two pairs are in flight for the registers of two.
+      PairIds id0, id1, id2;
+      Pair ra, rb;
+      next_pair(q, id0);   // the first chunk has at least one page
+      bool have1 = next_pair(q, id1);
+      self().issue_loads(ra, id0);
+      self().issue_loads(rb, id1);
+      float pa[4], pb[4];
+      while (true) {
+        const bool have2 = next_pair(q, id2);
+        const bool on0 = (id0.live_a | id0.live_b) != 0;
+        if (on0) self().scores(ra, id0, pa, pb);
+        self().template issue_half<false>(ra, id2);
+        if (on0) self().values(ra, pa, pb);
+        self().template issue_half<true>(ra, id2);
+        if (!have1) break;
+        const bool have3 = next_pair(q, id0);
+        const bool on1 = (id1.live_a | id1.live_b) != 0;
+        if (on1) self().scores(rb, id1, pa, pb);
+        self().template issue_half<false>(rb, id0);
+        if (on1) self().values(rb, pa, pb);
+        self().template issue_half<true>(rb, id0);
+        if (!have2) break;
+        id1 = id0;
+        id0 = id2;
+        have1 = have3;
+      }
+      return;
+    }
     PairIds ida, idb;
     Pair ra, rb;
     next_pair(q, ida);   // the first chunk has at least one page
@@ -423,6 +454,7 @@ struct ClassRunner : PairWalk<ClassRunner<D, BITS, GP, STAT>, PairRegs<D, BITS, 
   using F = Fld<BITS>;
   using Pair = PairRegs<D, BITS, NSET>;
   using Walk = PairWalk<ClassRunner<D, BITS, GP, STAT>, Pair>;
+  static constexpr bool kHalfPipe = TKV_HALF != 0;
   using Walk::v;
   using Walk::a;
   using Walk::cls;
@@ -521,8 +553,19 @@ struct ClassRunner : PairWalk<ClassRunner<D, BITS, GP, STAT>, PairRegs<D, BITS, 
     const BlockGeom geo = block_geom(BITS, D);
     const uint8_t* blk_a = v.arena[cls] + ((int64_t)id.pid_a * H + hkv) * geo.block_bytes;
     const uint8_t* blk_b = v.arena[cls] + ((int64_t)id.pid_b * H + hkv) * geo.block_bytes;
-    load_page<D, BITS, NSET>(r.a, blk_a, lane, meta_off);
-    load_page<D, BITS, NSET>(r.b, blk_b, lane, meta_off);
+    load_half<D, BITS, NSET, false>(r.a, blk_a, lane, meta_off);
+    load_half<D, BITS, NSET, false>(r.b, blk_b, lane, meta_off);
+    load_half<D, BITS, NSET, true>(r.a, blk_a, lane, meta_off);
+    load_half<D, BITS, NSET, true>(r.b, blk_b, lane, meta_off);
+  }
+  template <bool VHALF>
+  __device__ __forceinline__ void issue_half(Pair& r, const PairIds& id) const {
+    const int H = v.cfg.n_kv_heads;
+    const BlockGeom geo = block_geom(BITS, D);
+    const uint8_t* blk_a = v.arena[cls] + ((int64_t)id.pid_a * H + hkv) * geo.block_bytes;
+    const uint8_t* blk_b = v.arena[cls] + ((int64_t)id.pid_b * H + hkv) * geo.block_bytes;
+    load_half<D, BITS, NSET, VHALF>(r.a, blk_a, lane, meta_off);
+    load_half<D, BITS, NSET, VHALF>(r.b, blk_b, lane, meta_off);
   }
 
   // scores of one page for this lane's four tokens, in MFMA units (times kappa = log2 domain)
@@ -557,6 +600,11 @@ struct ClassRunner : PairWalk<ClassRunner<D, BITS, GP, STAT>, PairRegs<D, BITS, 
   }
 
   __device__ __forceinline__ void compute(const Pair& r, const PairIds& id) {
+    float pa[4], pb[4];
+    scores(r, id, pa, pb);
+    values(r, pa, pb);
+  }
+  __device__ __forceinline__ void scores(const Pair& r, const PairIds& id, float* pa, float* pb) {
     const uint32_t live_a = id.live_a, live_b = id.live_b;
     float sa[4], sb[4];
     page_scores(r.a, sa);
@@ -607,7 +655,6 @@ struct ClassRunner : PairWalk<ClassRunner<D, BITS, GP, STAT>, PairRegs<D, BITS, 
     }
     // p = 2^(score - m + lift): the weights are lifted by a power of two (see kLift), and with them
     // the denominator, the zero-point sums and the value tiles of this type
-    float pa[4], pb[4];
     const float mref = st.m_sub - lift;
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
@@ -615,7 +662,9 @@ struct ClassRunner : PairWalk<ClassRunner<D, BITS, GP, STAT>, PairRegs<D, BITS, 
       pb[r4] = __builtin_amdgcn_exp2f(fmaf(sb[r4], kappa, -mref));
     }
     st.l += ((pa[0] + pa[1]) + (pa[2] + pa[3])) + ((pb[0] + pb[1]) + (pb[2] + pb[3]));
-    // ---------------- values, per column set: B = two-term split of p * s_V, A = V codes
+  }
+  // ---------------- values, per column set: B = two-term split of p * s_V, A = V codes
+  __device__ __forceinline__ void values(const Pair& r, float* pa, float* pb) {
     float xa[NSET][4], xb[NSET][4];
 #pragma unroll
     for (int set = 0; set < NSET; ++set) {
